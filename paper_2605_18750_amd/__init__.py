@@ -1,0 +1,140 @@
+"""Thin ctypes binding of librrfp_stage.so: the same names as include/rrfp_stage.h and
+argument marshalling only.  Every step of the F/B/W path runs in the library's HIP kernels;
+this module fails loudly if the library is missing."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "librrfp_stage.so")
+
+STAGE_OK, STAGE_EINVAL, STAGE_ENOTREADY, STAGE_ENOMEM, STAGE_EHIP = 0, -1, -2, -3, -4
+STAGE_DTYPE_FP32, STAGE_DTYPE_BF16 = 0, 1
+STAGE_MLP_SWIGLU, STAGE_MLP_GELU = 0, 1
+STAGE_P_G1, STAGE_P_WQKV, STAGE_P_WO, STAGE_P_G2, STAGE_P_WUP, STAGE_P_WD, STAGE_P_COUNT = range(7)
+
+
+class stage_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "max_tokens",
+        "n_microbatches", "max_segments", "dtype", "mlp_kind", "causal", "norm_kind")] + [
+        ("norm_eps", C.c_float)]
+
+
+class StageError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"stage error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the library (built by `python -m paper_2605_18750_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2605_18750_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, sz = C.c_void_p, C.c_size_t
+        cfgp = C.POINTER(stage_config)
+        L.stage_query.argtypes = [cfgp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+        L.stage_param_layout.argtypes = [cfgp, C.c_int, C.c_int, C.POINTER(sz), C.POINTER(C.c_int64)]
+        L.stage_create.argtypes = [cfgp, vp, vp, sz, C.POINTER(vp)]
+        L.stage_create_dry.argtypes = [cfgp, C.POINTER(vp)]
+        L.stage_F.argtypes = [vp, C.c_int, vp, C.POINTER(C.c_int32), C.c_int, vp, vp]
+        L.stage_B.argtypes = [vp, C.c_int, vp, vp, vp]
+        L.stage_W.argtypes = [vp, C.c_int, vp]
+        L.stage_grad_reduce.argtypes = [vp, vp, vp]
+        L.stage_grad_slot.argtypes = [vp, C.c_int, C.POINTER(vp)]
+        L.stage_destroy.argtypes = [vp]
+        L.stage_last_error.argtypes = [vp]
+        L.stage_last_error.restype = C.c_char_p
+        for f in ("stage_query", "stage_param_layout", "stage_create", "stage_create_dry", "stage_F",
+                  "stage_B", "stage_W", "stage_grad_reduce", "stage_grad_slot", "stage_destroy"):
+            getattr(L, f).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(t) -> int:
+    """Device/host address of a torch tensor, or an int address, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(s) -> int:
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream
+
+
+def _check(rc: int, st=None):
+    if rc != STAGE_OK:
+        raise StageError(rc, stage_last_error(st))
+
+
+def stage_last_error(st=None) -> str:
+    return lib().stage_last_error(st).decode()
+
+
+def stage_query(cfg: stage_config):
+    """-> (param_bytes, grad_bytes, arena_bytes)"""
+    a, b, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(lib().stage_query(C.byref(cfg), C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+def stage_param_layout(cfg: stage_config, layer: int, which: int):
+    """-> (offset_elems, (rows, cols))"""
+    off = C.c_size_t()
+    shape = (C.c_int64 * 2)()
+    _check(lib().stage_param_layout(C.byref(cfg), layer, which, C.byref(off), shape))
+    return off.value, (shape[0], shape[1])
+
+
+def stage_create(cfg: stage_config, params_dev, arena_dev, arena_bytes: int):
+    h = C.c_void_p()
+    _check(lib().stage_create(C.byref(cfg), _ptr(params_dev), _ptr(arena_dev), arena_bytes, C.byref(h)))
+    return h
+
+
+def stage_create_dry(cfg: stage_config):
+    h = C.c_void_p()
+    _check(lib().stage_create_dry(C.byref(cfg), C.byref(h)))
+    return h
+
+
+def stage_F(st, mb: int, x_dev, cu_seqlens, y_dev, stream=None):
+    n = len(cu_seqlens) - 1
+    cu = (C.c_int32 * (n + 1))(*[int(v) for v in cu_seqlens])
+    _check(lib().stage_F(st, mb, _ptr(x_dev), cu, n, _ptr(y_dev), _stream(stream)), st)
+
+
+def stage_B(st, mb: int, dy_dev, dx_dev, stream=None):
+    _check(lib().stage_B(st, mb, _ptr(dy_dev), _ptr(dx_dev), _stream(stream)), st)
+
+
+def stage_W(st, mb: int, stream=None):
+    _check(lib().stage_W(st, mb, _stream(stream)), st)
+
+
+def stage_grad_reduce(st, grad_out_dev, stream=None):
+    _check(lib().stage_grad_reduce(st, _ptr(grad_out_dev), _stream(stream)), st)
+
+
+def stage_grad_slot(st, mb: int) -> int:
+    p = C.c_void_p()
+    _check(lib().stage_grad_slot(st, mb, C.byref(p)), st)
+    return p.value
+
+
+def stage_destroy(st):
+    _check(lib().stage_destroy(st))

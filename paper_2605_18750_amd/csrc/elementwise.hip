@@ -1,0 +1,298 @@
+// HBM-bound kernels of the stage tasks: RMSNorm forward/backward, SwiGLU and GELU
+// forward/backward, the fixed-order column sum for norm-gain gradients and the
+// index-ordered gradient reduction.  All arithmetic is fp32; storage is fp32 or bf16.
+// None of these kernels uses atomics: every sum has one fixed order.
+#include "kernels.h"
+#include "numeric.h"
+
+namespace rrfp {
+namespace {
+
+constexpr int WAVE = 64;
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+
+// ---------------------------------------------------------------- RMSNorm forward
+// One wavefront per row; 4 rows per workgroup.  Two sweeps over the row (the second is
+// served by cache): sum of squares, then scale.
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ g,
+                                                          T* __restrict__ h, float* __restrict__ r_out,
+                                                          int Tn, int H, float eps) {
+  constexpr int V = Vec<T>::N;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= Tn) return;
+  const T* xr = x + (size_t)row * H;
+  T* hr = h + (size_t)row * H;
+  float ss = 0.f;
+  const bool vec = (H % V) == 0;
+  if (vec) {
+    for (int c = lane * V; c < H; c += WAVE * V) {
+      float v[V];
+      load_vec<T>(xr + c, v);
+#pragma unroll
+      for (int i = 0; i < V; ++i) ss += v[i] * v[i];
+    }
+  } else {
+    for (int c = lane; c < H; c += WAVE) { float v = to_float(xr[c]); ss += v * v; }
+  }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)H + eps);
+  if (lane == 0) r_out[row] = r;
+  if (vec) {
+    for (int c = lane * V; c < H; c += WAVE * V) {
+      float v[V], gv[V];
+      load_vec<T>(xr + c, v);
+      load_vec<T>(g + c, gv);
+#pragma unroll
+      for (int i = 0; i < V; ++i) v[i] = v[i] * r * gv[i];
+      store_vec<T>(hr + c, v);
+    }
+  } else {
+    for (int c = lane; c < H; c += WAVE) hr[c] = from_float<T>(to_float(xr[c]) * r * to_float(g[c]));
+  }
+}
+
+// ---------------------------------------------------------------- RMSNorm backward, rows
+// dx = add_in + r * (w - xhat * mean(w * xhat)),  w = dh * g,  xhat = x * r.
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_rows_kernel(const T* __restrict__ dh, const T* __restrict__ x,
+                                                               const float* __restrict__ r, const T* __restrict__ g,
+                                                               const T* __restrict__ add_in, T* __restrict__ dx,
+                                                               int Tn, int H) {
+  constexpr int V = Vec<T>::N;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= Tn) return;
+  const size_t off = (size_t)row * H;
+  const float rr = r[row];
+  float dot = 0.f;
+  const bool vec = (H % V) == 0;
+  if (vec) {
+    for (int c = lane * V; c < H; c += WAVE * V) {
+      float a[V], b[V], gv[V];
+      load_vec<T>(dh + off + c, a);
+      load_vec<T>(x + off + c, b);
+      load_vec<T>(g + c, gv);
+#pragma unroll
+      for (int i = 0; i < V; ++i) dot += a[i] * gv[i] * (b[i] * rr);
+    }
+  } else {
+    for (int c = lane; c < H; c += WAVE) dot += to_float(dh[off + c]) * to_float(g[c]) * (to_float(x[off + c]) * rr);
+  }
+  dot = wave_sum(dot) / (float)H;
+  if (vec) {
+    for (int c = lane * V; c < H; c += WAVE * V) {
+      float a[V], b[V], gv[V], ad[V];
+      load_vec<T>(dh + off + c, a);
+      load_vec<T>(x + off + c, b);
+      load_vec<T>(g + c, gv);
+      load_vec<T>(add_in + off + c, ad);
+#pragma unroll
+      for (int i = 0; i < V; ++i) a[i] = ad[i] + rr * (a[i] * gv[i] - (b[i] * rr) * dot);
+      store_vec<T>(dx + off + c, a);
+    }
+  } else {
+    for (int c = lane; c < H; c += WAVE) {
+      float w = to_float(dh[off + c]) * to_float(g[c]);
+      dx[off + c] = from_float<T>(to_float(add_in[off + c]) + rr * (w - (to_float(x[off + c]) * rr) * dot));
+    }
+  }
+}
+
+// ---------------------------------------------------------------- RMSNorm backward, gain partials
+// partial[chunk][c] = sum over the chunk's rows (ascending) of dh[t][c] * x[t][c] * r[t].
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_gain_kernel(const T* __restrict__ dh, const T* __restrict__ x,
+                                                               const float* __restrict__ r, float* __restrict__ partial,
+                                                               int Tn, int H) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  const int chunk = blockIdx.y;
+  if (c >= H) return;
+  const int t0 = chunk * NORM_BWD_ROWS;
+  const int t1 = min(t0 + NORM_BWD_ROWS, Tn);
+  float acc = 0.f;
+  for (int t = t0; t < t1; ++t) acc += to_float(dh[(size_t)t * H + c]) * (to_float(x[(size_t)t * H + c]) * r[t]);
+  partial[(size_t)chunk * H + c] = acc;
+}
+
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ partial, int n_partial, int H,
+                                                     float* __restrict__ out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= H) return;
+  float acc = 0.f;
+  for (int p = 0; p < n_partial; ++p) acc += partial[(size_t)p * H + c];
+  out[c] = acc;
+}
+
+// ---------------------------------------------------------------- SwiGLU / GELU
+__device__ inline float sigmoidf_(float z) { return 1.0f / (1.0f + __expf(-z)); }
+
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T* __restrict__ gu, T* __restrict__ m, int Tn, int F) {
+  constexpr int V = Vec<T>::N;
+  const int fv = F / V;
+  const size_t n = (size_t)Tn * fv;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const size_t t = i / fv;
+    const int f = (int)(i % fv) * V;
+    float a[V], b[V];
+    load_vec<T>(gu + t * 2 * F + f, a);
+    load_vec<T>(gu + t * 2 * F + F + f, b);
+#pragma unroll
+    for (int k = 0; k < V; ++k) a[k] = a[k] * sigmoidf_(a[k]) * b[k];
+    store_vec<T>(m + t * F + f, a);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ dm, const T* __restrict__ gu,
+                                                         T* __restrict__ dgu, int Tn, int F) {
+  constexpr int V = Vec<T>::N;
+  const int fv = F / V;
+  const size_t n = (size_t)Tn * fv;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const size_t t = i / fv;
+    const int f = (int)(i % fv) * V;
+    float a[V], b[V], d[V], da[V], db[V];
+    load_vec<T>(gu + t * 2 * F + f, a);
+    load_vec<T>(gu + t * 2 * F + F + f, b);
+    load_vec<T>(dm + t * F + f, d);
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      const float sg = sigmoidf_(a[k]);
+      da[k] = d[k] * b[k] * sg * (1.0f + a[k] * (1.0f - sg));
+      db[k] = d[k] * a[k] * sg;
+    }
+    store_vec<T>(dgu + t * 2 * F + f, da);
+    store_vec<T>(dgu + t * 2 * F + F + f, db);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_fwd_kernel(const T* __restrict__ u, T* __restrict__ m, size_t nv) {
+  constexpr int V = Vec<T>::N;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
+    float a[V];
+    load_vec<T>(u + i * V, a);
+#pragma unroll
+    for (int k = 0; k < V; ++k) a[k] = 0.5f * a[k] * (1.0f + erff(a[k] * 0.70710678118654752f));
+    store_vec<T>(m + i * V, a);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* __restrict__ dm, const T* __restrict__ u,
+                                                       T* __restrict__ du, size_t nv) {
+  constexpr int V = Vec<T>::N;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
+    float a[V], d[V];
+    load_vec<T>(u + i * V, a);
+    load_vec<T>(dm + i * V, d);
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      const float Phi = 0.5f * (1.0f + erff(a[k] * 0.70710678118654752f));
+      const float phi = 0.39894228040143268f * __expf(-0.5f * a[k] * a[k]);
+      d[k] = d[k] * (Phi + a[k] * phi);
+    }
+    store_vec<T>(du + i * V, d);
+  }
+}
+
+// ---------------------------------------------------------------- gradient reduction
+__global__ __launch_bounds__(256) void grad_reduce_kernel(const float4* __restrict__ slots, size_t stride4, int M,
+                                                          float4* __restrict__ out, size_t n4) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+    float4 acc = slots[i];
+    for (int j = 1; j < M; ++j) {
+      const float4 v = slots[(size_t)j * stride4 + i];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    out[i] = acc;
+  }
+}
+
+inline int grid_for(size_t n, int cap = 256 * 32) {
+  size_t b = (n + 255) / 256;
+  return (int)(b < 1 ? 1 : (b > (size_t)cap ? cap : b));
+}
+
+}  // namespace
+
+#define DISPATCH_T(dtype, ...)                       \
+  if ((dtype) == F32) { using T = float; __VA_ARGS__; } \
+  else { using T = bf16_t; __VA_ARGS__; }
+
+hipError_t launch_rmsnorm_fwd(const void* x, const void* g, void* h, float* r_out, int Tn, int H, float eps,
+                              int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_fwd_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, (const T*)x,
+                                       (const T*)g, (T*)h, r_out, Tn, H, eps));
+  return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_bwd(const void* dh, const void* x, const float* r, const void* g, const void* add_in,
+                              void* dx, float* dg_partial, int Tn, int H, int dtype, hipStream_t s) {
+  const int chunks = (Tn + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS;
+  DISPATCH_T(dtype, {
+    hipLaunchKernelGGL(rmsnorm_bwd_gain_kernel<T>, dim3((H + 255) / 256, chunks), dim3(256), 0, s, (const T*)dh,
+                       (const T*)x, r, dg_partial, Tn, H);
+    hipLaunchKernelGGL(rmsnorm_bwd_rows_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, (const T*)dh, (const T*)x, r,
+                       (const T*)g, (const T*)add_in, (T*)dx, Tn, H);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum(const float* partial, int n_partial, int H, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(colsum_kernel, dim3((H + 255) / 256), dim3(256), 0, s, partial, n_partial, H, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_fwd(const void* gu, void* m, int Tn, int F, int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, {
+    if (F % Vec<T>::N) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(swiglu_fwd_kernel<T>, dim3(grid_for((size_t)Tn * F / Vec<T>::N)), dim3(256), 0, s, (const T*)gu,
+                       (T*)m, Tn, F);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_bwd(const void* dm, const void* gu, void* dgu, int Tn, int F, int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, {
+    if (F % Vec<T>::N) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(swiglu_bwd_kernel<T>, dim3(grid_for((size_t)Tn * F / Vec<T>::N)), dim3(256), 0, s, (const T*)dm,
+                       (const T*)gu, (T*)dgu, Tn, F);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_fwd(const void* u, void* m, int Tn, int F, int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, {
+    if (F % Vec<T>::N) return hipErrorInvalidValue;
+    const size_t nv = (size_t)Tn * F / Vec<T>::N;
+    hipLaunchKernelGGL(gelu_fwd_kernel<T>, dim3(grid_for(nv)), dim3(256), 0, s, (const T*)u, (T*)m, nv);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_bwd(const void* dm, const void* u, void* du, int Tn, int F, int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, {
+    if (F % Vec<T>::N) return hipErrorInvalidValue;
+    const size_t nv = (size_t)Tn * F / Vec<T>::N;
+    hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for(nv)), dim3(256), 0, s, (const T*)dm, (const T*)u, (T*)du, nv);
+  });
+  return hipGetLastError();
+}
+
+hipError_t launch_grad_reduce(const float* slots, size_t slot_stride, int M, float* out, size_t n, hipStream_t s) {
+  if (n % 4 || slot_stride % 4) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(grad_reduce_kernel, dim3(grid_for(n / 4)), dim3(256), 0, s, (const float4*)slots, slot_stride / 4,
+                     M, (float4*)out, n / 4);
+  return hipGetLastError();
+}
+
+}  // namespace rrfp

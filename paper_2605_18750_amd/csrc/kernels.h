@@ -1,0 +1,76 @@
+// Internal launcher interface between the stage host code and the gfx950 kernels.
+// Every launcher only enqueues on the given stream and returns the launch status.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rrfp {
+
+enum DType : int { F32 = 0, BF16 = 1 };
+
+static inline size_t dtype_size(int dt) { return dt == F32 ? 4 : 2; }
+
+// C[M,N] = A(m,k) * B(k,n) (+ R[M,N]), fp32 accumulation.
+//   transA == false: A stored [M,K] (lda), true: stored [K,M] (lda).
+//   transB == false: B stored [K,N] (ldb), true: stored [N,K] (ldb).
+// in_dtype is the type of A, B and R; out_dtype the type of C (F32 for weight gradients).
+struct GemmArgs {
+  const void* A; const void* B; void* C; const void* R;
+  int M, N, K;
+  int lda, ldb, ldc, ldr;
+  bool transA, transB;
+  int in_dtype, out_dtype;
+};
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);       // picks the kernel family
+hipError_t launch_gemm_simt(const GemmArgs& g, hipStream_t s);  // fp32-FMA tiles, any shape
+
+// One attention work item: a tile of rows [r0, r1) inside the segment [s0, s1).
+struct AttnTile { int32_t r0, r1, s0, s1; };
+
+constexpr int ATTN_TILE_Q = 64;    // rows per query tile (forward and dQ kernels)
+constexpr int ATTN_TILE_KV = 64;   // rows per key tile (dK/dV kernel)
+
+struct AttnArgs {
+  const void* qkv;      // [T, (nq + 2 nkv) d]: Q heads, K heads, V heads
+  void* o;              // [T, nq d]
+  float* lse;           // [nq, T]   log-sum-exp of the scaled, masked scores (natural log)
+  const AttnTile* q_tiles; int n_q_tiles;     // device pointers to the tile lists
+  const AttnTile* kv_tiles; int n_kv_tiles;
+  int T, nq, nkv, d, causal, dtype;
+  // backward only
+  const void* d_o;      // [T, nq d]
+  void* dqkv;           // [T, (nq + 2 nkv) d]
+  float* delta;         // [nq, T]   rowsum(dO * O)
+};
+hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_fwd_simt(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_bwd_simt(const AttnArgs& a, hipStream_t s);
+
+// h = x * r * g, r = rsqrt(mean(x^2) + eps); r_out [T] fp32.
+hipError_t launch_rmsnorm_fwd(const void* x, const void* g, void* h, float* r_out,
+                              int T, int H, float eps, int dtype, hipStream_t s);
+
+constexpr int NORM_BWD_ROWS = 64;  // rows per partial of the gain-gradient column sum
+// dx = add_in + r * (w - xhat * mean(w * xhat)), w = dh * g, xhat = x * r.
+// dg_partial [ceil(T / NORM_BWD_ROWS), H] fp32 receives per-row-chunk sums of dh * xhat;
+// launch_colsum then adds the partials in chunk order into dg [H].
+hipError_t launch_rmsnorm_bwd(const void* dh, const void* x, const float* r, const void* g,
+                              const void* add_in, void* dx, float* dg_partial,
+                              int T, int H, int dtype, hipStream_t s);
+hipError_t launch_colsum(const float* partial, int n_partial, int H, float* out, hipStream_t s);
+
+// SwiGLU on gu [T, 2F] (gate columns then up columns): m = silu(gate) * up.
+hipError_t launch_swiglu_fwd(const void* gu, void* m, int T, int F, int dtype, hipStream_t s);
+hipError_t launch_swiglu_bwd(const void* dm, const void* gu, void* dgu, int T, int F, int dtype,
+                             hipStream_t s);
+// GELU (erf form) on u [T, F].
+hipError_t launch_gelu_fwd(const void* u, void* m, int T, int F, int dtype, hipStream_t s);
+hipError_t launch_gelu_bwd(const void* dm, const void* u, void* du, int T, int F, int dtype,
+                           hipStream_t s);
+
+// out[i] = ((slot_0[i] + slot_1[i]) + ...) + slot_{M-1}[i], slots spaced slot_stride floats apart.
+hipError_t launch_grad_reduce(const float* slots, size_t slot_stride, int M, float* out, size_t n,
+                              hipStream_t s);
+
+}  // namespace rrfp

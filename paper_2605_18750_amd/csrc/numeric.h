@@ -1,0 +1,68 @@
+// Storage-type helpers shared by the device kernels: bf16 <-> fp32 conversion
+// (round-to-nearest-even) and 16-byte vector loads/stores converted to fp32.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rrfp {
+
+struct bf16_t { uint16_t bits; };
+
+__device__ __host__ inline float bf16_bits_to_float(uint32_t b) {
+  union { uint32_t u; float f; } v;
+  v.u = b << 16;
+  return v.f;
+}
+
+__device__ __host__ inline uint16_t float_to_bf16_bits(float f) {
+  union { uint32_t u; float f; } v;
+  v.f = f;
+  if ((v.u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((v.u >> 16) | 0x40u);  // NaN stays NaN
+  return (uint16_t)((v.u + 0x7fffu + ((v.u >> 16) & 1u)) >> 16);
+}
+
+__device__ inline float to_float(float v) { return v; }
+__device__ inline float to_float(bf16_t v) { return bf16_bits_to_float(v.bits); }
+
+template <typename T> __device__ inline T from_float(float f);
+template <> __device__ inline float from_float<float>(float f) { return f; }
+template <> __device__ inline bf16_t from_float<bf16_t>(float f) { return bf16_t{float_to_bf16_bits(f)}; }
+
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+}
+
+template <typename T> struct Vec;
+template <> struct Vec<float> { static constexpr int N = 4; };
+template <> struct Vec<bf16_t> { static constexpr int N = 8; };
+
+// 16-byte aligned vector load of Vec<T>::N elements, widened to fp32.
+template <typename T> __device__ inline void load_vec(const T* p, float* out);
+template <> __device__ inline void load_vec<float>(const float* p, float* out) {
+  const float4 v = *reinterpret_cast<const float4*>(p);
+  out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+template <> __device__ inline void load_vec<bf16_t>(const bf16_t* p, float* out) {
+  const uint4 v = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(w[i] << 16);
+    out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+
+template <typename T> __device__ inline void store_vec(T* p, const float* in);
+template <> __device__ inline void store_vec<float>(float* p, const float* in) {
+  *reinterpret_cast<float4*>(p) = make_float4(in[0], in[1], in[2], in[3]);
+}
+template <> __device__ inline void store_vec<bf16_t>(bf16_t* p, const float* in) {
+  uint4 v;
+  v.x = pack_bf16x2(in[0], in[1]);
+  v.y = pack_bf16x2(in[2], in[3]);
+  v.z = pack_bf16x2(in[4], in[5]);
+  v.w = pack_bf16x2(in[6], in[7]);
+  *reinterpret_cast<uint4*>(p) = v;
+}
+
+}  // namespace rrfp

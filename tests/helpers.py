@@ -1,0 +1,139 @@
+"""Shared by the tests: runs the same seeded workload through the oracle and through the
+HIP library (via the C ABI binding) and compares them with the max-norm relative error."""
+from __future__ import annotations
+
+import numpy as np
+
+import stage_inputs as SI
+from oracle import stage_oracle as O
+
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+
+
+def oracle_config(shape: SI.StageShape) -> O.OracleConfig:
+    return O.OracleConfig(n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
+                          n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
+                          mlp_kind=shape.mlp_kind, causal=shape.causal, norm_eps=shape.norm_eps)
+
+
+def max_norm_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max|got - ref| / max|ref| over one tensor."""
+    den = float(np.max(np.abs(ref)))
+    num = float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)))
+    return num / den if den > 0 else num
+
+
+class Workload:
+    """Seeded inputs of one stage: parameters, and x / dy / cu_seqlens per microbatch."""
+
+    def __init__(self, shape: SI.StageShape, cus: list, seed: int = SI.BASE_SEED):
+        self.shape = shape
+        self.cus = [np.asarray(c, dtype=np.int32) for c in cus]
+        self.M = len(cus)
+        self.layers = SI.make_stage_params(shape, seed)
+        self.x = [SI.make_x(shape, j, int(c[-1]), seed) for j, c in enumerate(self.cus)]
+        self.dy = [SI.make_dy(shape, j, int(c[-1]), seed) for j, c in enumerate(self.cus)]
+
+    def oracle_params(self):
+        return [{k: v.f64 for k, v in layer.items()} for layer in self.layers]
+
+
+def run_oracle(w: Workload):
+    """-> dict(y=[...], dx=[...], grads=[per-mb list of per-layer dicts], reduced=[per-layer dicts])"""
+    cfg = oracle_config(w.shape)
+    params = w.oracle_params()
+    ys, dxs, per_mb = [], [], []
+    for j in range(w.M):
+        y, caches = O.stage_F(w.x[j].f64, params, w.cus[j], cfg)
+        dx, gains, wst = O.stage_B(w.dy[j].f64, caches, params, cfg)
+        per_mb.append(O.merge_B_W(gains, O.stage_W(caches, wst, cfg)))
+        ys.append(y)
+        dxs.append(dx)
+    return {"y": ys, "dx": dxs, "grads": per_mb, "reduced": O.grad_reduce(per_mb)}
+
+
+def canonical_order(M: int):
+    return [("F", j) for j in range(M)] + [("B", j) for j in range(M)] + [("W", j) for j in range(M)]
+
+
+def run_gpu(w: Workload, order=None, n_streams: int = 1, max_tokens=None, keep_raw: bool = False):
+    """Runs the workload through the HIP library in the given task order (default canonical),
+    round-robin over n_streams streams.  Returns the same dict as run_oracle (fp64 numpy), plus
+    raw bit-level copies when keep_raw is set."""
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+
+    shape = w.shape
+    T_max = max(int(c[-1]) for c in w.cus) if max_tokens is None else max_tokens
+    cfg = Hn.make_config(shape, T_max, max(len(c) - 1 for c in w.cus), n_microbatches=w.M)
+    stage = Hn.Stage(cfg, Hn.pack_params(cfg, w.layers))
+    tdt = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
+    xs = [Hn.to_device(t.storage, shape.dtype) for t in w.x]
+    dys = [Hn.to_device(t.storage, shape.dtype) for t in w.dy]
+    ys = [torch.empty_like(x) for x in xs]
+    dxs = [torch.empty_like(x) for x in xs]
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    torch.cuda.synchronize()
+    order = canonical_order(w.M) if order is None else order
+    for i, (kind, j) in enumerate(order):
+        s = streams[i % n_streams]
+        if kind == "F":
+            R.stage_F(stage.handle, j, xs[j], w.cus[j], ys[j], s)
+        elif kind == "B":
+            R.stage_B(stage.handle, j, dys[j], dxs[j], s)
+        else:
+            R.stage_W(stage.handle, j, s)
+    R.stage_grad_reduce(stage.handle, stage.grad_out, streams[0])
+    torch.cuda.synchronize()
+    out = {"y": [Hn.to_f64(t) for t in ys], "dx": [Hn.to_f64(t) for t in dxs]}
+    slots = [stage.slot(j).cpu().numpy() for j in range(w.M)]
+    red = stage.grad_out.cpu().numpy()
+    out["grads"] = [Hn.unpack_grads(cfg, s) for s in slots]
+    out["reduced"] = Hn.unpack_grads(cfg, red)
+    if keep_raw:   # bit patterns, for order-independence checks (tensor regions only, no padding)
+        bits = torch.int16 if tdt == torch.bfloat16 else torch.int32
+        out["raw"] = {"y": [t.cpu().view(bits).numpy() for t in ys],
+                      "dx": [t.cpu().view(bits).numpy() for t in dxs],
+                      "grads": [Hn.unpack_grads(cfg, s.view(np.int32)) for s in slots],
+                      "reduced": Hn.unpack_grads(cfg, red.view(np.int32))}
+    stage.close()
+    return out
+
+
+def assert_bit_identical(a: dict, b: dict):
+    """Every output of two runs (raw bit patterns) must agree exactly."""
+    ra, rb = a["raw"], b["raw"]
+    for key in ("y", "dx"):
+        for j, (u, v) in enumerate(zip(ra[key], rb[key])):
+            assert np.array_equal(u, v), f"{key}[mb {j}] differs between dispatch orders"
+    for j, (gm, hm) in enumerate(zip(ra["grads"], rb["grads"])):
+        for l, (gl, hl) in enumerate(zip(gm, hm)):
+            for k in gl:
+                assert np.array_equal(gl[k], hl[k]), f"grad {k} layer {l} mb {j} differs between dispatch orders"
+    for l, (gl, hl) in enumerate(zip(ra["reduced"], rb["reduced"])):
+        for k in gl:
+            assert np.array_equal(gl[k], hl[k]), f"reduced grad {k} layer {l} differs between dispatch orders"
+
+
+def compare(got: dict, ref: dict, tol: float, what: str = ""):
+    """Asserts the max-norm relative error bound for y, dx, every per-microbatch gradient
+    tensor and the reduced gradients.  Returns the worst error seen."""
+    worst = 0.0
+    for key in ("y", "dx"):
+        for j, (g, r) in enumerate(zip(got[key], ref[key])):
+            e = max_norm_rel_err(g, r)
+            worst = max(worst, e)
+            assert e <= tol, f"{what} {key}[mb {j}]: rel err {e:.3e} > {tol}"
+    for j, (gm, rm) in enumerate(zip(got["grads"], ref["grads"])):
+        for l, (gl, rl) in enumerate(zip(gm, rm)):
+            for k in rl:
+                e = max_norm_rel_err(gl[k], rl[k])
+                worst = max(worst, e)
+                assert e <= tol, f"{what} grad {k} layer {l} mb {j}: rel err {e:.3e} > {tol}"
+    for l, (gl, rl) in enumerate(zip(got["reduced"], ref["reduced"])):
+        for k in rl:
+            e = max_norm_rel_err(gl[k], rl[k])
+            worst = max(worst, e)
+            assert e <= tol, f"{what} reduced grad {k} layer {l}: rel err {e:.3e} > {tol}"
+    return worst

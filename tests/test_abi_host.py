@@ -1,0 +1,130 @@
+"""Host-side checks that need no GPU: the library loads and exports every symbol the header
+declares; configuration validation; parameter layout; the per-microbatch dependency state
+machine (paper Section 3.1 / 4.1 / 7.1 ordering rules) through stage_create_dry."""
+import os
+import re
+import ctypes
+
+import pytest
+
+import paper_2605_18750_amd as R
+from paper_2605_18750_amd import harness as Hn
+import stage_inputs as SI
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _cfg(**kw):
+    base = dict(n_layers=2, hidden=128, n_q_heads=4, n_kv_heads=2, head_dim=32, ffn=192, max_tokens=64,
+                n_microbatches=3, max_segments=2, dtype=0, mlp_kind=0, causal=1, norm_kind=0, norm_eps=1e-5)
+    base.update(kw)
+    return R.stage_config(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "rrfp_stage.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(stage_[A-Za-z_]+)\s*\(", hdr))
+    assert {"stage_create", "stage_F", "stage_B", "stage_W", "stage_grad_reduce"} <= names
+    L = ctypes.CDLL(R.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_config_validation():
+    R.stage_query(_cfg())
+    bad = [dict(n_kv_heads=3), dict(hidden=0), dict(head_dim=24), dict(head_dim=144), dict(dtype=2),
+           dict(mlp_kind=5), dict(causal=2), dict(norm_kind=1), dict(norm_eps=-1.0), dict(ffn=190),
+           dict(dtype=1, head_dim=32), dict(dtype=1, head_dim=64, hidden=96), dict(n_layers=65)]
+    for kw in bad:
+        with pytest.raises(R.StageError) as e:
+            R.stage_query(_cfg(**kw))
+        assert e.value.code == R.STAGE_EINVAL, kw
+        assert len(str(e.value)) > 20
+
+
+def test_layout_is_disjoint_aligned_and_sized():
+    for shape, T in ((SI.TINY, 128), (SI.LANGUAGE, 4096), (SI.WIDE_GQA, 4096), (SI.VISION, 6272)):
+        cfg = Hn.make_config(shape, T, 8)
+        pb, gb, ab = R.stage_query(cfg)
+        esz = 4 if shape.dtype == "fp32" else 2
+        spans = []
+        for l in range(cfg.n_layers):
+            for w in range(R.STAGE_P_COUNT):
+                off, (r, c) = R.stage_param_layout(cfg, l, w)
+                assert off % 128 == 0
+                spans.append((off, off + r * c))
+        spans.sort()
+        assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
+        assert spans[-1][1] * esz <= pb and gb == pb // esz * 4 and ab > 0
+    cfg = Hn.make_config(SI.WIDE_GQA, 4096)
+    assert R.stage_param_layout(cfg, 0, R.STAGE_P_WQKV)[1] == (8192, (64 + 16) * 128)
+    assert R.stage_param_layout(cfg, 1, R.STAGE_P_WUP)[1] == (8192, 2 * 28672)
+    assert R.stage_param_layout(Hn.make_config(SI.VISION, 6272, 8), 0, R.STAGE_P_WUP)[1] == (1280, 5120)
+    with pytest.raises(R.StageError):
+        R.stage_param_layout(cfg, 2, 0)
+    with pytest.raises(R.StageError):
+        R.stage_param_layout(cfg, 0, 6)
+
+
+def test_language_arena_fits_one_gpu():
+    for shape, T, nseg in ((SI.LANGUAGE, 4096, 1), (SI.WIDE_GQA, 4096, 1), (SI.MULTIMODAL, 6144, 2), (SI.VISION, 6272, 8)):
+        pb, gb, ab = R.stage_query(Hn.make_config(shape, T, nseg))
+        assert pb + gb + ab < 250 * 2 ** 30, (shape.name, (pb + gb + ab) / 2 ** 30)
+
+
+def _expect(code, fn, *a):
+    with pytest.raises(R.StageError) as e:
+        fn(*a)
+    assert e.value.code == code, str(e.value)
+
+
+def test_dependency_state_machine():
+    st = R.stage_create_dry(_cfg())
+    cu = [0, 40, 64]
+    _expect(R.STAGE_ENOTREADY, R.stage_B, st, 0, None, None)          # B before F
+    _expect(R.STAGE_ENOTREADY, R.stage_W, st, 0)                      # W before B
+    _expect(R.STAGE_ENOTREADY, R.stage_grad_reduce, st, None)         # reduce before all W
+    R.stage_F(st, 0, None, cu, None)
+    _expect(R.STAGE_ENOTREADY, R.stage_F, st, 0, None, cu, None)      # slot busy
+    _expect(R.STAGE_ENOTREADY, R.stage_W, st, 0)
+    R.stage_F(st, 2, None, [0, 10], None)                             # any ready order
+    R.stage_B(st, 2, None, None)
+    _expect(R.STAGE_ENOTREADY, R.stage_B, st, 2, None, None)          # double issue
+    R.stage_B(st, 0, None, None)
+    R.stage_F(st, 1, None, cu, None)
+    R.stage_W(st, 0)
+    _expect(R.STAGE_ENOTREADY, R.stage_W, st, 0)
+    _expect(R.STAGE_ENOTREADY, R.stage_F, st, 0, None, cu, None)      # busy until the reduce
+    R.stage_B(st, 1, None, None)
+    R.stage_W(st, 1)                                                  # W may trail other microbatches' work
+    _expect(R.STAGE_ENOTREADY, R.stage_grad_reduce, st, None)
+    R.stage_W(st, 2)
+    R.stage_grad_reduce(st, None)
+    R.stage_F(st, 0, None, cu, None)                                  # slots are free again
+    R.stage_destroy(st)
+
+
+def test_argument_validation_has_no_side_effect():
+    st = R.stage_create_dry(_cfg())
+    _expect(R.STAGE_EINVAL, R.stage_F, st, 3, None, [0, 8], None)     # mb out of range
+    _expect(R.STAGE_EINVAL, R.stage_F, st, -1, None, [0, 8], None)
+    _expect(R.STAGE_EINVAL, R.stage_F, st, 0, None, [1, 8], None)     # cu[0] != 0
+    _expect(R.STAGE_EINVAL, R.stage_F, st, 0, None, [0, 8, 8], None)  # empty segment
+    _expect(R.STAGE_EINVAL, R.stage_F, st, 0, None, [0, 9, 5], None)  # not monotone
+    _expect(R.STAGE_EINVAL, R.stage_F, st, 0, None, [0, 65], None)    # T > max_tokens
+    _expect(R.STAGE_EINVAL, R.stage_F, st, 0, None, [0, 1, 2, 3], None)  # too many segments
+    _expect(R.STAGE_EINVAL, R.stage_F, st, 0, None, [0], None)        # no segment
+    assert "max_tokens" in R.stage_last_error(st) or len(R.stage_last_error(st)) > 0
+    R.stage_F(st, 0, None, [0, 64], None)                             # still free after the failures
+    _expect(R.STAGE_EINVAL, R.stage_B, st, 7, None, None)
+    _expect(R.STAGE_EINVAL, R.stage_W, st, 7)
+    R.stage_destroy(st)
+
+
+def test_real_create_rejects_bad_buffers_before_any_hip_call():
+    cfg = _cfg()
+    _, _, ab = R.stage_query(cfg)
+    _expect(R.STAGE_EINVAL, R.stage_create, cfg, None, None, ab)
+    _expect(R.STAGE_EINVAL, R.stage_create, cfg, 256 + 8, 4096, ab)     # misaligned
+    _expect(R.STAGE_ENOMEM, R.stage_create, cfg, 256, 4096, ab - 1)     # arena too small
