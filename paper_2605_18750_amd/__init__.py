@@ -52,6 +52,8 @@ def lib() -> C.CDLL:
         L.stage_destroy.argtypes = [vp]
         L.stage_last_error.argtypes = [vp]
         L.stage_last_error.restype = C.c_char_p
+        L.rrfp_gemm.argtypes = [vp, vp, vp, vp] + [C.c_int] * 12 + [vp]
+        L.rrfp_gemm.restype = C.c_int
         for f in ("stage_query", "stage_param_layout", "stage_create", "stage_create_dry", "stage_F",
                   "stage_B", "stage_W", "stage_grad_reduce", "stage_grad_slot", "stage_destroy"):
             getattr(L, f).restype = C.c_int
@@ -134,6 +136,17 @@ def stage_grad_slot(st, mb: int) -> int:
     p = C.c_void_p()
     _check(lib().stage_grad_slot(st, mb, C.byref(p)), st)
     return p.value
+
+
+RRFP_GEMM_AUTO, RRFP_GEMM_SIMT, RRFP_GEMM_MFMA = 0, 1, 2
+
+
+def rrfp_gemm(A, B, Cout, R, M, N, K, lda, ldb, ldc, ldr, trans_a, trans_b, in_dtype, out_dtype,
+              family=RRFP_GEMM_AUTO, stream=None):
+    rc = lib().rrfp_gemm(_ptr(A), _ptr(B), _ptr(Cout), _ptr(R), M, N, K, lda, ldb, ldc, ldr,
+                         int(trans_a), int(trans_b), in_dtype, out_dtype, family, _stream(stream))
+    if rc != STAGE_OK:
+        raise StageError(rc, "rrfp_gemm rejected its arguments" if rc == STAGE_EINVAL else "HIP launch failed")
 
 
 def stage_destroy(st):

@@ -4,7 +4,9 @@
 
 namespace rrfp {
 
-hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) { return launch_gemm_simt(g, s); }
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
+  return gemm_mfma_supports(g) ? launch_gemm_mfma(g, s) : launch_gemm_simt(g, s);
+}
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) { return launch_attn_fwd_simt(a, s); }
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) { return launch_attn_bwd_simt(a, s); }
 

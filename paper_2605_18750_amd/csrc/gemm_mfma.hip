@@ -1,0 +1,252 @@
+// bf16 MFMA GEMM for gfx950: C[M,N] = A(m,k) B(k,n) (+R), fp32 accumulation, bf16 or fp32 out.
+//
+// One workgroup (4 wavefronts, one per SIMD) owns a 256x256 tile of C and walks K in steps of
+// 64 with two LDS stages (2 x 64 KB): while the MFMAs of step k run from one stage, the global
+// loads of step k+1 are in flight into registers and are written to the other stage afterwards.
+// Each wavefront owns a 128x128 quadrant as 4x4 v_mfma_f32_32x32x16_bf16 accumulators.
+//
+// Operand tiles sit in LDS in their memory orientation, so every global load is a coalesced
+// 16-byte access:
+//   K-contiguous operand ([rows][K] in memory): LDS [256 rows][64 k], 16-byte chunks XOR-swizzled
+//     by (row & 7); a fragment (8 consecutive k of one row) is one ds_read_b128.
+//   K-strided operand ([K][rows] in memory): LDS [64 k][256 rows], 64-byte units XOR-swizzled by
+//     k; a fragment is two ds_read_b64_tr_b16, the LDS transpose read of gfx950 that hands each
+//     lane 4 consecutive k of one row out of a 4(k) x 16(rows) block.
+// The forward GEMMs use (A K-contiguous, B K-strided), the input-gradient GEMMs (both
+// K-contiguous), the weight-gradient GEMMs (both K-strided, K = tokens).
+//
+// The MFMA is issued with the B fragment as its first operand, so a lane's four consecutive
+// accumulator values are four consecutive columns of one row of C: 8-byte (bf16) or 16-byte
+// (fp32) stores.  Rows beyond M, columns beyond N and k beyond K are zero-filled on load and
+// masked on store.  The k loop order and the tile partition depend only on the shape, so the
+// result does not depend on how many CUs were free.
+#include "kernels.h"
+#include "numeric.h"
+
+namespace rrfp {
+namespace {
+
+constexpr int BM = 256, BN = 256, BK = 64, NTHREADS = 256;
+constexpr int TILE_BYTES = 256 * 64 * 2;          // one operand tile
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // A + B
+constexpr int SMEM_BYTES = 2 * STAGE_BYTES;       // two stages
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+
+// Byte offset of the 16-byte chunk (row, c) of a K-contiguous tile [256][64].
+__device__ __forceinline__ int kc_off(int row, int c) { return row * 128 + ((c ^ (row & 7)) << 4); }
+// Byte offset of the 16-byte chunk (k, c) of a K-strided tile [64][256]; c in 0..31.
+__device__ __forceinline__ int ks_off(int k, int c) {
+  const int f = (k & 3) | (((k >> 3) & 1) << 2);
+  return k * 512 + (((((c >> 2) ^ f) << 2) | (c & 3)) << 4);
+}
+
+// Global -> registers for one operand tile: 8 chunks of 16 bytes per thread.
+template <bool KC>
+__device__ __forceinline__ void load_tile(uint4 (&r)[8], const bf16_t* __restrict__ base, int ld, int outer0,
+                                          int outer_n, int k0, int K) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int q = i * NTHREADS + t;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (KC) {
+      const int row = q >> 3, c = q & 7;
+      const int go = outer0 + row, gk = k0 + c * 8;
+      if (go < outer_n && gk < K) v = *reinterpret_cast<const uint4*>(base + (size_t)go * ld + gk);
+    } else {
+      const int k = q >> 5, c = q & 31;
+      const int gk = k0 + k, go = outer0 + c * 8;
+      if (gk < K && go < outer_n) v = *reinterpret_cast<const uint4*>(base + (size_t)gk * ld + go);
+    }
+    r[i] = v;
+  }
+}
+
+template <bool KC>
+__device__ __forceinline__ void store_tile(const uint4 (&r)[8], char* tile) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int q = i * NTHREADS + t;
+    const int off = KC ? kc_off(q >> 3, q & 7) : ks_off(q >> 5, q & 31);
+    *reinterpret_cast<uint4*>(tile + off) = r[i];
+  }
+}
+
+// Fragment of 32 rows starting at row0 (multiple of 32), k-step ks (16 k): lane l gets row
+// row0 + (l & 31), k = ks*16 + (l >> 5)*8 + 0..7.
+template <bool KC>
+__device__ __forceinline__ bf16x8 read_frag(const char* tile, int row0, int ks, int lane) {
+  if (KC) {
+    const int row = row0 + (lane & 31);
+    const uint4 v = *reinterpret_cast<const uint4*>(tile + kc_off(row, ks * 2 + (lane >> 5)));
+    return __builtin_bit_cast(bf16x8, v);
+  } else {
+    const int kb = ks * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
+    const int c = (row0 >> 3) + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+    const int sub = (lane & 1) * 8;
+    union { short4v h[2]; bf16x8 v; } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + ks_off(kb, c) + sub));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + ks_off(kb + 4, c) + sub));
+    return u.v;
+  }
+}
+
+// Output tile index from the hardware workgroup id.  Workgroups are dealt round-robin to the
+// 8 XCDs, each with its own L2; give every XCD a contiguous run of tiles, and order tiles in
+// groups of 8 tile-rows so that the tiles resident on an XCD together share A and B panels.
+__device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int nt = tiles_m * tiles_n;
+  const int b = blockIdx.x;
+  const int q = nt >> 3, r = nt & 7, xcd = b & 7, i = b >> 3;
+  const int pid = xcd < r ? xcd * (q + 1) + i : r * (q + 1) + (xcd - r) * q + i;
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int g = pid / per_group;
+  const int first_m = g * GM;
+  const int gsize = min(tiles_m - first_m, GM);
+  const int in_g = pid - g * per_group;
+  tm = first_m + in_g % gsize;
+  tn = in_g / gsize;
+}
+
+template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
+__global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                             TO* __restrict__ C, const bf16_t* __restrict__ R, int M,
+                                                             int N, int K, int lda, int ldb, int ldc, int ldr,
+                                                             int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int tm, tn;
+  tile_coords(tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+
+  floatx16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  uint4 ra[8], rb[8];
+  const int nk = (K + BK - 1) / BK;
+  load_tile<A_KC>(ra, A, lda, m0, M, 0, K);
+  load_tile<B_KC>(rb, B, ldb, n0, N, 0, K);
+  store_tile<A_KC>(ra, smem);
+  store_tile<B_KC>(rb, smem + TILE_BYTES);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const char* sa = smem + (kt & 1) * STAGE_BYTES;
+    const char* sb = sa + TILE_BYTES;
+    const bool more = kt + 1 < nk;
+    if (more) {
+      load_tile<A_KC>(ra, A, lda, m0, M, (kt + 1) * BK, K);
+      load_tile<B_KC>(rb, B, ldb, n0, N, (kt + 1) * BK, K);
+    }
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[4], fb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[i] = read_frag<A_KC>(sa, wm + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) fb[j] = read_frag<B_KC>(sb, wn + j * 32, ks, lane);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      char* na = smem + ((kt + 1) & 1) * STAGE_BYTES;
+      store_tile<A_KC>(ra, na);
+      store_tile<B_KC>(rb, na + TILE_BYTES);
+    }
+    __syncthreads();
+  }
+
+  // Epilogue.  acc[i][j][g*4 + e] = C[m0 + wm + i*32 + (lane & 31)][n0 + wn + j*32 + g*8 + (lane >> 5)*4 + e].
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + wm + i * 32 + (lane & 31);
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = n0 + wn + j * 32 + g * 8 + (lane >> 5) * 4;
+        if (n >= N) continue;     // N is a multiple of 8: the four columns are in or out together
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e];
+        if (HAS_R) {
+          const uint2 rr = *reinterpret_cast<const uint2*>(R + (size_t)m * ldr + n);
+          v[0] += __uint_as_float(rr.x << 16); v[1] += __uint_as_float(rr.x & 0xffff0000u);
+          v[2] += __uint_as_float(rr.y << 16); v[3] += __uint_as_float(rr.y & 0xffff0000u);
+        }
+        if (sizeof(TO) == 4) {
+          *reinterpret_cast<float4*>((float*)C + (size_t)m * ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+          uint2 o;
+          o.x = pack_bf16x2(v[0], v[1]);
+          o.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>((bf16_t*)C + (size_t)m * ldc + n) = o;
+        }
+      }
+    }
+  }
+}
+
+template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
+hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
+  auto kern = gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>;
+  static bool configured = false;   // per instantiation; the attribute is process-wide for the function
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(NTHREADS), SMEM_BYTES, s, (const bf16_t*)g.A,
+                     (const bf16_t*)g.B, (TO*)g.C, (const bf16_t*)g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, g.ldr,
+                     tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+template <bool A_KC, bool B_KC>
+hipError_t launch_orient(const GemmArgs& g, hipStream_t s) {
+  if (g.out_dtype == F32) return g.R ? launch_one<A_KC, B_KC, float, true>(g, s) : launch_one<A_KC, B_KC, float, false>(g, s);
+  return g.R ? launch_one<A_KC, B_KC, bf16_t, true>(g, s) : launch_one<A_KC, B_KC, bf16_t, false>(g, s);
+}
+
+}  // namespace
+
+bool gemm_mfma_supports(const GemmArgs& g) {
+  if (g.in_dtype != BF16) return false;
+  if (g.M < 1 || g.N < 1 || g.K < 1) return false;
+  if ((g.lda | g.ldb | g.ldc) & 7) return false;
+  if (g.R && (g.ldr & 7)) return false;
+  if (g.N & 7) return false;
+  const bool a_kc = !g.transA, b_kc = g.transB;
+  if ((a_kc || b_kc) && (g.K & 7)) return false;      // K-contiguous chunks must be whole
+  if (!a_kc && (g.M & 7)) return false;               // K-strided A: rows of C come in chunks of 8
+  auto aligned = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  return aligned(g.A) && aligned(g.B) && aligned(g.C) && (!g.R || aligned(g.R));
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
+  if (!gemm_mfma_supports(g)) return hipErrorInvalidValue;
+  const bool a_kc = !g.transA, b_kc = g.transB;
+  if (a_kc && !b_kc) return launch_orient<true, false>(g, s);
+  if (a_kc && b_kc) return launch_orient<true, true>(g, s);
+  if (!a_kc && !b_kc) return launch_orient<false, false>(g, s);
+  return launch_orient<false, true>(g, s);
+}
+
+}  // namespace rrfp

@@ -1,0 +1,28 @@
+// Kernel-level C entry points (include/rrfp_kernels.h): thin argument checks around the
+// launchers the stage tasks use.
+#include "../../include/rrfp_kernels.h"
+#include "../../include/rrfp_stage.h"
+#include "kernels.h"
+
+using namespace rrfp;
+
+extern "C" int rrfp_gemm(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
+                         int ldc, int ldr, int trans_a, int trans_b, int in_dtype, int out_dtype, int family,
+                         void* stream) {
+  if (!A || !B || !C || M < 1 || N < 1 || K < 1) return STAGE_EINVAL;
+  if (in_dtype != F32 && in_dtype != BF16) return STAGE_EINVAL;
+  if (out_dtype != F32 && !(out_dtype == BF16 && in_dtype == BF16)) return STAGE_EINVAL;
+  if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N || (R && ldr < N)) return STAGE_EINVAL;
+  GemmArgs g{};
+  g.A = A; g.B = B; g.C = C; g.R = R; g.M = M; g.N = N; g.K = K;
+  g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ldr = ldr;
+  g.transA = trans_a != 0; g.transB = trans_b != 0; g.in_dtype = in_dtype; g.out_dtype = out_dtype;
+  hipError_t e;
+  if (family == RRFP_GEMM_AUTO) e = launch_gemm(g, (hipStream_t)stream);
+  else if (family == RRFP_GEMM_SIMT) e = launch_gemm_simt(g, (hipStream_t)stream);
+  else if (family == RRFP_GEMM_MFMA) {
+    if (!gemm_mfma_supports(g)) return STAGE_EINVAL;
+    e = launch_gemm_mfma(g, (hipStream_t)stream);
+  } else return STAGE_EINVAL;
+  return e == hipSuccess ? STAGE_OK : STAGE_EHIP;
+}

@@ -23,6 +23,8 @@ struct GemmArgs {
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);       // picks the kernel family
 hipError_t launch_gemm_simt(const GemmArgs& g, hipStream_t s);  // fp32-FMA tiles, any shape
+hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);  // bf16 MFMA 256x256x64 tiles
+bool gemm_mfma_supports(const GemmArgs& g);                     // alignment / divisibility rules
 
 // One attention work item: a tile of rows [r0, r1) inside the segment [s0, s1).
 struct AttnTile { int32_t r0, r1, s0, s1; };

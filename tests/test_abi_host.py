@@ -22,9 +22,9 @@ def _cfg(**kw):
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "rrfp_stage.h")).read()
+    hdr = open(os.path.join(ROOT, "include", "rrfp_stage.h")).read() + open(os.path.join(ROOT, "include", "rrfp_kernels.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(stage_[A-Za-z_]+)\s*\(", hdr))
+    names = set(re.findall(r"\b((?:stage|rrfp)_[A-Za-z_]+)\s*\(", hdr))
     assert {"stage_create", "stage_F", "stage_B", "stage_W", "stage_grad_reduce"} <= names
     L = ctypes.CDLL(R.LIB_PATH)
     for n in names:

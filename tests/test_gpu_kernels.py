@@ -1,0 +1,103 @@
+"""Kernel-level GPU parity (through the C ABI of rrfp_kernels.h) against fp64 definitions."""
+import sys
+
+import numpy as np
+import pytest
+
+import stage_inputs as SI
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _gemm_case(M, N, K, ta, tb, out_fp32, with_r, family, in_dtype="bf16", seed=5):
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+    from tests.helpers import max_norm_rel_err
+    name = f"gemm M{M} N{N} K{K} ta{ta} tb{tb} f32out{out_fp32} r{with_r} fam{family} {in_dtype}"
+    _say(f"[kernel] {name}")
+    A = SI.make_tensor(seed, name + "A", (K, M) if ta else (M, K), 1.0, in_dtype)
+    B = SI.make_tensor(seed, name + "B", (N, K) if tb else (K, N), 1.0, in_dtype)
+    Rr = SI.make_tensor(seed, name + "R", (M, N), 4.0, in_dtype) if with_r else None
+    ref = (A.f64.T if ta else A.f64) @ (B.f64.T if tb else B.f64)     # the definition, fp64
+    if with_r:
+        ref = ref + Rr.f64
+    dA, dB = Hn.to_device(A.storage, in_dtype), Hn.to_device(B.storage, in_dtype)
+    dR = Hn.to_device(Rr.storage, in_dtype) if with_r else None
+    odt = torch.float32 if (out_fp32 or in_dtype == "fp32") else torch.bfloat16
+    dC = torch.full((M, N), float("nan"), dtype=odt, device="cuda:0")
+    idt = R.STAGE_DTYPE_FP32 if in_dtype == "fp32" else R.STAGE_DTYPE_BF16
+    R.rrfp_gemm(dA, dB, dC, dR, M, N, K, dA.shape[1], dB.shape[1], N, N, ta, tb, idt,
+                R.STAGE_DTYPE_FP32 if odt == torch.float32 else R.STAGE_DTYPE_BF16, family)
+    torch.cuda.synchronize()
+    got = dC.cpu().to(torch.float64).numpy()
+    assert np.all(np.isfinite(got)), name + ": unwritten or non-finite outputs"
+    tol = 1e-4 if odt == torch.float32 and in_dtype == "fp32" else (2e-5 if odt == torch.float32 else 1e-2)
+    # fp32 accumulation of exact bf16 products: error ~ sqrt(K) * 2^-24 relative to the max; bf16 output adds 2^-9
+    err = max_norm_rel_err(got, ref)
+    _say(f"[kernel] {name}: rel err {err:.3e} (tol {tol})")
+    assert err <= tol, name
+
+
+ORIENT = [(0, 0), (0, 1), (1, 0), (1, 1)]
+
+
+@pytest.mark.parametrize("ta,tb", ORIENT)
+def test_mfma_gemm_small_ragged(ta, tb):
+    # several tiles in M and N with ragged tails, K with a ragged last step
+    _gemm_case(264, 520, 200, ta, tb, out_fp32=False, with_r=False, family=2)
+    _gemm_case(520, 264, 328, ta, tb, out_fp32=True, with_r=False, family=2)
+    _gemm_case(40, 72, 64, ta, tb, out_fp32=False, with_r=True, family=2)
+
+
+def test_mfma_gemm_ragged_token_counts():
+    # forward / input-gradient forms with T not a multiple of anything; weight-gradient form with K = T odd
+    _gemm_case(777, 512, 256, 0, 0, False, True, 2)
+    _gemm_case(777, 256, 512, 0, 1, False, False, 2)
+    _gemm_case(256, 512, 777, 1, 0, True, False, 2)
+    _gemm_case(1, 8, 8, 0, 0, False, False, 2)
+
+
+@pytest.mark.parametrize("ta,tb", ORIENT)
+def test_simt_gemm(ta, tb):
+    _gemm_case(70, 45, 33, ta, tb, out_fp32=True, with_r=True, family=1, in_dtype="fp32")
+    _gemm_case(130, 65, 100, ta, tb, out_fp32=False, with_r=False, family=1)
+
+
+def test_mfma_rejects_unsupported_shapes():
+    import torch
+    import paper_2605_18750_amd as R
+    a = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(R.StageError):
+        R.rrfp_gemm(a, a, a, None, 64, 60, 64, 64, 64, 64, 64, 0, 0, 1, 1, R.RRFP_GEMM_MFMA)   # N % 8
+    with pytest.raises(R.StageError):
+        R.rrfp_gemm(a, a, a, None, 64, 64, 60, 64, 64, 64, 64, 0, 0, 1, 1, R.RRFP_GEMM_MFMA)   # K % 8, A K-contiguous
+    with pytest.raises(R.StageError):
+        R.rrfp_gemm(a, a, a, None, 64, 64, 64, 32, 64, 64, 64, 0, 0, 1, 1, R.RRFP_GEMM_MFMA)   # lda < K
+
+
+def test_mfma_gemm_full_size_sampled_rows():
+    """Language-stage QKV projection at full size (4096 x 12288 x 4096): rows sampled across
+    tiles are compared with the fp64 definition row by row."""
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+    from tests.helpers import max_norm_rel_err
+    M, N, K = 4096, 12288, 4096
+    _say("[kernel] full-size NN gemm, sampled rows")
+    A = SI.make_tensor(1, "fullA", (M, K), 1.0, "bf16")
+    B = SI.make_tensor(1, "fullB", (K, N), 0.02, "bf16")
+    dA, dB = Hn.to_device(A.storage, "bf16"), Hn.to_device(B.storage, "bf16")
+    dC = torch.empty((M, N), dtype=torch.bfloat16, device="cuda:0")
+    R.rrfp_gemm(dA, dB, dC, None, M, N, K, K, N, N, N, 0, 0, 1, 1, R.RRFP_GEMM_MFMA)
+    torch.cuda.synchronize()
+    rows = [0, 1, 31, 32, 255, 256, 1000, 2047, 2048, 3333, 4095]
+    got = dC[rows].cpu().to(torch.float64).numpy()
+    ref = A.f64[rows] @ B.f64
+    err = max_norm_rel_err(got, ref)
+    _say(f"[kernel] full-size NN gemm: rel err {err:.3e}")
+    assert err <= 1e-2
