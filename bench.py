@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""bench.py -- throughput of the F/B/W stage tasks on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: F, B and W of every microbatch of
+the stage plus stage_grad_reduce, inputs resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload language|wide|vision|multimodal|tiny]
+
+value     = algorithmic TFLOP of the step / wall time (GEMM 2*T*P per layer per task kind,
+            attention forward 4*d*n_q*pairs with pairs = s^2/2 causal or s^2 bidirectional,
+            attention backward counted as twice the forward, no recompute, no elementwise flops).
+roofline  = the dominant kernel (the bf16 MFMA GEMM, timed alone on its largest forward shape
+            with HIP events on its stream) against the dense bf16 MFMA peak of 2.5 PFLOP/s.
+cpu_baseline = the fp64 oracle, as it stands, timed on this machine's host cores on a bounded
+            sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA: 256 CUs x 4096 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def task_flops(shape, cu):
+    """Algorithmic flops of F, B, W for one microbatch with segment boundaries cu."""
+    H, d, F = shape.hidden, shape.head_dim, shape.ffn
+    nq, nkv = shape.n_q_heads, shape.n_kv_heads
+    c = 3 if shape.mlp_kind == "swiglu" else 2
+    P = H * nq * d + 2 * H * nkv * d + nq * d * H + c * H * F
+    T = int(cu[-1])
+    pairs = sum(((int(b) - int(a)) ** 2) / (2.0 if shape.causal else 1.0) for a, b in zip(cu[:-1], cu[1:]))
+    A = 4.0 * d * nq * pairs
+    L = shape.n_layers
+    return {"F": L * (2.0 * T * P + A), "B": L * (2.0 * T * P + 2 * A), "W": L * 2.0 * T * P}
+
+
+def cpu_baseline(shape, T_sample: int):
+    """The oracle on one layer, one microbatch of T_sample tokens of the same shape."""
+    import numpy as np
+    import stage_inputs as SI
+    from oracle import stage_oracle as O
+    one = shape.replace(n_layers=1, name=shape.name + "/cpu_sample")
+    cfg = O.OracleConfig(n_layers=1, hidden=one.hidden, n_q_heads=one.n_q_heads, n_kv_heads=one.n_kv_heads,
+                         head_dim=one.head_dim, ffn=one.ffn, mlp_kind=one.mlp_kind, causal=one.causal,
+                         norm_eps=one.norm_eps)
+    if shape.name.startswith("vision"):
+        cu = np.arange(0, T_sample + 1, SI.VISION_TOKENS_PER_IMAGE)
+    else:
+        cu = np.array([0, T_sample])
+    T_sample = int(cu[-1])
+    params = [{k: v.f64 for k, v in SI.make_layer_params(one, 0).items()}]
+    x = SI.make_x(one, 0, T_sample).f64
+    dy = SI.make_dy(one, 0, T_sample).f64
+    t0 = time.perf_counter()
+    _, caches = O.stage_F(x, params, cu, cfg)
+    _, gains, wst = O.stage_B(dy, caches, params, cfg)
+    O.stage_W(caches, wst, cfg)
+    dt = time.perf_counter() - t0
+    fl = task_flops(one, cu)
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count()
+    env = os.environ.get("OMP_NUM_THREADS")
+    threads = min(cores, int(env)) if env and env.isdigit() else cores
+    return {"value": (fl["F"] + fl["B"] + fl["W"]) / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"fp64 numpy oracle, F+B+W of 1 layer of the {shape.name} shape, 1 microbatch, T={T_sample}, "
+                      f"{dt:.1f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="language")
+    ap.add_argument("--streams", type=int, default=1, help="streams the tasks are dealt to (B/F/W order)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+    import stage_inputs as SI
+
+    R.lib()   # fails loudly if the HIP library is not built
+    shape = {"language": SI.LANGUAGE, "wide": SI.WIDE_GQA, "vision": SI.VISION, "multimodal": SI.MULTIMODAL,
+             "tiny": SI.TINY}[args.workload]
+    M = shape.n_microbatches
+    cus = [SI.default_cu_seqlens(shape, j) for j in range(M)]
+    T_max = max(int(c[-1]) for c in cus)
+    cfg = Hn.make_config(shape, T_max, max(len(c) - 1 for c in cus))
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    tdt = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
+
+    # Synthetic inputs, generated on the device from a fixed seed: weights N(0, w_std), gains
+    # 1 + N(0, w_std), x N(0, x_std), dy N(0, dy_std).
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SI.BASE_SEED)
+    pb, gb, ab = R.stage_query(cfg)
+    esz = 4 if shape.dtype == "fp32" else 2
+    params = torch.empty(pb // esz, dtype=tdt, device=dev)
+    params.normal_(0.0, shape.w_std, generator=gen)
+    for l in range(cfg.n_layers):
+        for which in (R.STAGE_P_G1, R.STAGE_P_G2):
+            off, (r, _) = R.stage_param_layout(cfg, l, which)
+            params[off:off + r] += 1.0
+    arena = torch.empty(ab, dtype=torch.uint8, device=dev)
+    grad_out = torch.empty(gb // 4, dtype=torch.float32, device=dev)
+    st = R.stage_create(cfg, params, arena, ab)
+    xs = [torch.empty((int(c[-1]), shape.hidden), dtype=tdt, device=dev).normal_(0.0, shape.x_std, generator=gen) for c in cus]
+    dys = [torch.empty((int(c[-1]), shape.hidden), dtype=tdt, device=dev).normal_(0.0, shape.dy_std, generator=gen) for c in cus]
+    ys = [torch.empty_like(x) for x in xs]
+    dxs = [torch.empty_like(x) for x in xs]
+    streams = [torch.cuda.Stream() for _ in range(max(1, args.streams))]
+
+    fl = [task_flops(shape, c) for c in cus]
+    step_flops = sum(f["F"] + f["B"] + f["W"] for f in fl)
+
+    # Issue order: all F, then for each microbatch B then W (a B/F/W-style drain), dealt to streams.
+    order = [("F", j) for j in range(M)]
+    for j in range(M):
+        order += [("B", j), ("W", j)]
+
+    def step(events=None):
+        for i, (kind, j) in enumerate(order):
+            s = streams[i % len(streams)]
+            if events is not None:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e0.record(s)
+            if kind == "F":
+                R.stage_F(st, j, xs[j], cus[j], ys[j], s)
+            elif kind == "B":
+                R.stage_B(st, j, dys[j], dxs[j], s)
+            else:
+                R.stage_W(st, j, s)
+            if events is not None:
+                e1 = torch.cuda.Event(enable_timing=True)
+                e1.record(s)
+                events.append((kind, j, e0, e1))
+        R.stage_grad_reduce(st, grad_out, streams[0])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    # Per-task times (one stream, events around every task), outside the timed region.
+    saved = streams
+    streams = streams[:1]
+    per_kind = {"F": [], "B": [], "W": []}
+    for _ in range(2):
+        ev = []
+        step(ev)
+        torch.cuda.synchronize()
+        for kind, j, e0, e1 in ev:
+            per_kind[kind].append((j, e0.elapsed_time(e1)))
+    streams = saved
+    tasks = {}
+    for kind, lst in per_kind.items():
+        ms = float(np.median([t for _, t in lst]))
+        tf = float(np.median([fl[j][kind] / (t * 1e-3) / 1e12 for j, t in lst]))
+        tasks[kind] = {"ms_per_microbatch": round(ms, 4), "tflops": round(tf, 1),
+                       "frac_of_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    # Roofline of the dominant kernel: the MFMA GEMM on the largest forward shape of this stage
+    # (the MLP up projection), timed alone with HIP events on its stream.
+    roof = None
+    if shape.dtype == "bf16":
+        T = T_max
+        N_up = (2 if shape.mlp_kind == "swiglu" else 1) * shape.ffn
+        A = torch.empty((T, shape.hidden), dtype=tdt, device=dev).normal_(0.0, 1.0, generator=gen)
+        off, (r, c) = R.stage_param_layout(cfg, 0, R.STAGE_P_WUP)
+        Bw = params[off:off + r * c].view(r, c)
+        Cc = torch.empty((T, N_up), dtype=tdt, device=dev)
+        s = streams[0]
+        n_launch = 20
+        with torch.cuda.stream(s):
+            for _ in range(3):
+                R.rrfp_gemm(A, Bw, Cc, None, T, N_up, shape.hidden, shape.hidden, N_up, N_up, N_up, 0, 0, 1, 1,
+                            R.RRFP_GEMM_MFMA, s)
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record(s)
+            for _ in range(n_launch):
+                R.rrfp_gemm(A, Bw, Cc, None, T, N_up, shape.hidden, shape.hidden, N_up, N_up, N_up, 0, 0, 1, 1,
+                            R.RRFP_GEMM_MFMA, s)
+            g1.record(s)
+        torch.cuda.synchronize()
+        g_ms = g0.elapsed_time(g1) / n_launch
+        g_fl = 2.0 * T * N_up * shape.hidden
+        ach = g_fl / (g_ms * 1e-3) / 1e12
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "gemm_mfma_traffic.json")
+        if os.path.exists(tpath):
+            try:
+                traffic = json.load(open(tpath)).get(f"{T}x{N_up}x{shape.hidden}")
+            except Exception:
+                traffic = None
+        roof = {"bound": "mfma", "kernel": f"gemm_mfma_kernel NN {T}x{N_up}x{shape.hidden} bf16", "achieved": round(ach, 1),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic}
+
+    torch.cuda.synchronize()
+    R.stage_destroy(st)
+    del arena
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(shape, args.cpu_sample_tokens)
+
+    value = step_flops / wall * args.steps / 1e12
+    out = {
+        "metric": "F/B/W task TFLOP/s per stage (bf16), % of MFMA peak; ms per microbatch",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{shape.name}: {shape.n_layers} layers, hidden {shape.hidden}, {shape.n_q_heads} q heads / "
+                               f"{shape.n_kv_heads} kv heads x {shape.head_dim}, ffn {shape.ffn} {shape.mlp_kind}, "
+                               f"{'causal' if shape.causal else 'bidirectional'}, T per microbatch "
+                               f"{sorted(set(int(c[-1]) for c in cus))}, {M} microbatches",
+                   "step": "F, B, W of every microbatch + stage_grad_reduce", "streams": len(streams),
+                   "step_tflop": round(step_flops / 1e12, 3)},
+        "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "tasks": tasks,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
