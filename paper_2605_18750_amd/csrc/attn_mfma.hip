@@ -1,0 +1,278 @@
+// bf16 MFMA attention for gfx950: tiled online-softmax forward over packed segments with GQA,
+// causal or bidirectional masks and head_dim 64 / 80 / 128.
+//
+// Forward.  A workgroup (4 wavefronts) owns one query tile (up to 256 rows inside one segment)
+// of one query head; each wavefront owns 64 query rows.  Keys and values stream through LDS in
+// steps of 64 rows with two stages (global loads of step k+1 are in flight while step k runs).
+// Scores are computed TRANSPOSED, S^T[key, query] = K Q^T with v_mfma_f32_32x32x16_bf16, so
+// that a lane holds one query column: the softmax row statistics are lane-local except one
+// exchange between the two halves of the wavefront, and the probabilities, rounded to bf16, are
+// already in the B-operand layout of the second product O^T[d, query] += V^T P^T.  V stays in
+// LDS in its memory orientation and its fragments come from the LDS transpose read.
+// Exponentials are base 2 (scores pre-multiplied by log2 e / sqrt(d)); the saved log-sum-exp
+// is in natural-log units.
+#include "kernels.h"
+#include "numeric.h"
+
+namespace rrfp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+
+constexpr int BKV = 64;        // keys per step
+constexpr int WQ = 64;         // query rows per wavefront
+
+template <int D>
+struct FwdCfg {
+  static constexpr int DP = (D + 31) / 32 * 32;      // value columns padded to whole 32-wide MFMA blocks
+  static constexpr int KP = D * 2 + 16;              // K row pitch in bytes: 16-byte skew per row
+  static constexpr int VP = DP * 2 + 32;             // V row pitch in bytes: 32 or 96 (mod 128)
+  static constexpr int K_BYTES = BKV * KP;
+  static constexpr int V_BYTES = BKV * VP;
+  static constexpr int STAGE = (K_BYTES + V_BYTES + 255) / 256 * 256;
+  static constexpr int SMEM = 2 * STAGE;
+  static constexpr int CH = D / 8;                   // 16-byte chunks per row
+  static constexpr int NCHUNK = BKV * CH;            // chunks per K (or V) tile
+  static constexpr int PER_THREAD = (NCHUNK + 255) / 256;
+};
+
+template <int D>
+__device__ __forceinline__ void kv_load(uint4 (&rk)[FwdCfg<D>::PER_THREAD], uint4 (&rv)[FwdCfg<D>::PER_THREAD],
+                                        const bf16_t* __restrict__ qkv, int ld, int kcol, int vcol, int k0, int k_end) {
+  using C = FwdCfg<D>;
+#pragma unroll
+  for (int i = 0; i < C::PER_THREAD; ++i) {
+    const int q = i * 256 + threadIdx.x;
+    const int row = q / C::CH, c = q - row * C::CH;
+    uint4 a = make_uint4(0, 0, 0, 0), b = a;
+    if (q < C::NCHUNK && k0 + row < k_end) {
+      const bf16_t* p = qkv + (size_t)(k0 + row) * ld + c * 8;
+      a = *reinterpret_cast<const uint4*>(p + kcol);
+      b = *reinterpret_cast<const uint4*>(p + vcol);
+    }
+    rk[i] = a;
+    rv[i] = b;
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void kv_store(const uint4 (&rk)[FwdCfg<D>::PER_THREAD], const uint4 (&rv)[FwdCfg<D>::PER_THREAD],
+                                         char* stage) {
+  using C = FwdCfg<D>;
+#pragma unroll
+  for (int i = 0; i < C::PER_THREAD; ++i) {
+    const int q = i * 256 + threadIdx.x;
+    const int row = q / C::CH, c = q - row * C::CH;
+    if (q < C::NCHUNK) {
+      *reinterpret_cast<uint4*>(stage + row * C::KP + c * 16) = rk[i];
+      *reinterpret_cast<uint4*>(stage + C::K_BYTES + row * C::VP + c * 16) = rv[i];
+    }
+  }
+  if (C::DP != D) {   // zero the padded value columns so that the unused output rows stay finite
+    constexpr int PADCH = (C::DP - D) / 8;
+    for (int q = threadIdx.x; q < BKV * PADCH; q += 256) {
+      const int row = q / PADCH, c = q - row * PADCH;
+      *reinterpret_cast<uint4*>(stage + C::K_BYTES + row * C::VP + (C::CH + c) * 16) = make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+                                                            float* __restrict__ lse, const AttnTile* __restrict__ tiles,
+                                                            int Tn, int nq, int nkv, int causal, float scale_log2e) {
+  using C = FwdCfg<D>;
+  constexpr int NDS = D / 16;        // contraction steps of Q K^T
+  constexpr int NDB = C::DP / 32;    // 32-row blocks of O^T
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const AttnTile tl = tiles[blockIdx.x];
+  const int a = blockIdx.y, b = a / (nq / nkv);
+  const int ld = (nq + 2 * nkv) * D;
+  const int qcol = a * D, kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = lane >> 5, li = lane & 31;
+  const int wq0 = tl.r0 + wave * WQ;
+  const bool wave_has_rows = wq0 < tl.r1;
+
+  // Q fragments (B operand): column = query wq0 + ib*32 + li, k = ds*16 + h*8 .. +8.
+  bf16x8 qf[2][NDS];
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib) {
+    const int i = wq0 + ib * 32 + li;
+#pragma unroll
+    for (int ds = 0; ds < NDS; ++ds) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (i < tl.r1) v = *reinterpret_cast<const uint4*>(qkv + (size_t)i * ld + qcol + ds * 16 + h * 8);
+      qf[ib][ds] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  floatx16 oacc[NDB][2];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[db][ib][e] = 0.f;
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+
+  const int kv_end = causal ? tl.r1 : tl.s1;
+  const int nsteps = (kv_end - tl.s0 + BKV - 1) / BKV;
+  uint4 rk[C::PER_THREAD], rv[C::PER_THREAD];
+  kv_load<D>(rk, rv, qkv, ld, kcol, vcol, tl.s0, kv_end);
+  kv_store<D>(rk, rv, smem);
+  __syncthreads();
+
+  for (int st = 0; st < nsteps; ++st) {
+    const int k0 = tl.s0 + st * BKV;
+    const char* sk = smem + (st & 1) * C::STAGE;
+    const char* sv = sk + C::K_BYTES;
+    const bool more = st + 1 < nsteps;
+    if (more) kv_load<D>(rk, rv, qkv, ld, kcol, vcol, k0 + BKV, kv_end);
+
+    const bool active = wave_has_rows && (!causal || k0 <= wq0 + WQ - 1);
+    if (active) {
+      // S^T[jb][ib]: rows = keys k0 + jb*32 + .., columns = queries
+      floatx16 s[2][2];
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) s[jb][ib][e] = 0.f;
+#pragma unroll
+      for (int ds = 0; ds < NDS; ++ds) {
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) {
+          const uint4 kv4 = *reinterpret_cast<const uint4*>(sk + (jb * 32 + li) * C::KP + (ds * 2 + h) * 16);
+          const bf16x8 kf = __builtin_bit_cast(bf16x8, kv4);
+#pragma unroll
+          for (int ib = 0; ib < 2; ++ib) s[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ib][ds], s[jb][ib], 0, 0, 0);
+        }
+      }
+      const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
+      bf16x8 pf[2][2][2];   // [ib][jb][u]: probabilities of 16 keys as a B operand
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib) {
+        const int i = wq0 + ib * 32 + li;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            float v = s[jb][ib][e] * scale_log2e;
+            if (need_mask) {
+              const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+              if (j >= kv_end || (causal && j > i)) v = -INFINITY;
+            }
+            s[jb][ib][e] = v;
+            mx = fmaxf(mx, v);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run[ib], mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[ib] - m_new);
+        m_run[ib] = m_new;
+        float ps = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) {
+          float p[16];
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(s[jb][ib][e] - m_new);
+            ps += p[e];
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            uint4 w;
+            w.x = pack_bf16x2(p[u * 8 + 0], p[u * 8 + 1]);
+            w.y = pack_bf16x2(p[u * 8 + 2], p[u * 8 + 3]);
+            w.z = pack_bf16x2(p[u * 8 + 4], p[u * 8 + 5]);
+            w.w = pack_bf16x2(p[u * 8 + 6], p[u * 8 + 7]);
+            pf[ib][jb][u] = __builtin_bit_cast(bf16x8, w);
+          }
+        }
+        l_run[ib] = l_run[ib] * alpha + ps;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[db][ib][e] *= alpha;
+      }
+      // O^T[db][ib] += V^T P^T.  B-operand slot s of half h is key 16u + (s/4)*8 + h*4 + s%4 of the
+      // 32-key block, so the matching V fragment is two transpose reads starting at keys h*4 and 8 + h*4.
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int krow = jb * 32 + u * 16 + h * 4 + ((lane & 15) >> 2);
+#pragma unroll
+          for (int db = 0; db < NDB; ++db) {
+            const int col = db * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+            union { short4v hh[2]; bf16x8 v; } vf;
+            vf.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(sv + krow * C::VP + col * 2));
+            vf.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(sv + (krow + 8) * C::VP + col * 2));
+#pragma unroll
+            for (int ib = 0; ib < 2; ++ib)
+              oacc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[ib][jb][u], oacc[db][ib], 0, 0, 0);
+          }
+        }
+    }
+    if (more) kv_store<D>(rk, rv, smem + ((st + 1) & 1) * C::STAGE);
+    __syncthreads();
+  }
+
+  // Finalise: the two halves of the wavefront hold disjoint key subsets of every query column.
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib) {
+    const int i = wq0 + ib * 32 + li;
+    const float l_tot = l_run[ib] + __shfl_xor(l_run[ib], 32, 64);
+    if (i >= tl.r1) continue;
+    const float inv = 1.0f / l_tot;
+    if (h == 0) lse[(size_t)a * Tn + i] = (m_run[ib] + log2f(l_tot)) * 0.69314718055994531f;
+    bf16_t* orow = o + (size_t)i * nq * D + qcol;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int dd = db * 32 + g * 8 + h * 4;
+        if (dd >= D) continue;
+        uint2 w;
+        w.x = pack_bf16x2(oacc[db][ib][g * 4 + 0] * inv, oacc[db][ib][g * 4 + 1] * inv);
+        w.y = pack_bf16x2(oacc[db][ib][g * 4 + 2] * inv, oacc[db][ib][g * 4 + 3] * inv);
+        *reinterpret_cast<uint2*>(orow + dd) = w;
+      }
+  }
+}
+
+template <int D>
+hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
+  using C = FwdCfg<D>;
+  auto kern = attn_fwd_mfma_kernel<D>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  hipLaunchKernelGGL(kern, dim3(a.n_q_tiles, a.nq), dim3(256), C::SMEM, s, (const bf16_t*)a.qkv, (bf16_t*)a.o, a.lse,
+                     a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale_log2e);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool attn_mfma_supports(const AttnArgs& a) {
+  return a.dtype == BF16 && (a.d == 64 || a.d == 80 || a.d == 128) && a.n_q_tiles >= 1;
+}
+
+hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
+  if (!attn_mfma_supports(a)) return hipErrorInvalidValue;
+  if (a.d == 64) return fwd_launch<64>(a, s);
+  if (a.d == 80) return fwd_launch<80>(a, s);
+  return fwd_launch<128>(a, s);
+}
+
+}  // namespace rrfp

@@ -29,8 +29,8 @@ bool gemm_mfma_supports(const GemmArgs& g);                     // alignment / d
 // One attention work item: a tile of rows [r0, r1) inside the segment [s0, s1).
 struct AttnTile { int32_t r0, r1, s0, s1; };
 
-constexpr int ATTN_TILE_Q = 64;    // rows per query tile (forward and dQ kernels)
-constexpr int ATTN_TILE_KV = 64;   // rows per key tile (dK/dV kernel)
+constexpr int ATTN_TILE_Q = 256;   // rows per query tile (forward and dQ kernels)
+constexpr int ATTN_TILE_KV = 128;  // rows per key tile (dK/dV kernel)
 
 struct AttnArgs {
   const void* qkv;      // [T, (nq + 2 nkv) d]: Q heads, K heads, V heads
@@ -48,6 +48,8 @@ hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_fwd_simt(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd_simt(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s);
+bool attn_mfma_supports(const AttnArgs& a);
 
 // h = x * r * g, r = rsqrt(mean(x^2) + eps); r_out [T] fp32.
 hipError_t launch_rmsnorm_fwd(const void* x, const void* g, void* h, float* r_out,
