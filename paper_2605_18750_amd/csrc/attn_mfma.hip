@@ -246,6 +246,411 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
   }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Backward.  Three kernels, no atomics:
+//   delta:  delta[a][i] = sum_d dO[i,a,d] * O[i,a,d]
+//   dQ:     same tiling as the forward; per key step recompute S^T and dP^T = V dO^T, form
+//           dS^T = P^T * (dP^T - delta) in registers (already a B operand), dQ^T += K^T dS^T.
+//   dK/dV:  a workgroup owns 128 keys of one KV head (32 per wavefront, K and V fragments held
+//           in registers) and walks the query heads of its group and the query rows in ascending
+//           order; S = Q K^T and dP = dO V^T are computed UNtransposed so that a lane holds one
+//           key column and P, dS are B operands of dV^T += dO^T P and dK^T += Q^T dS.
+// ------------------------------------------------------------------------------------------
+
+// Generic tile movers: ROWS x D bf16 from global rows [row0, row_end) into registers, then into
+// LDS with a row pitch of PITCH bytes; columns D .. DPAD-1 are zero-filled.
+template <int D, int ROWS>
+struct TileRegs { static constexpr int N = (ROWS * (D / 8) + 255) / 256; };
+template <int D, int ROWS>
+using TileArr = uint4[TileRegs<D, ROWS>::N];
+
+template <int D, int ROWS>
+__device__ __forceinline__ void tile_load(TileArr<D, ROWS>& r, const bf16_t* __restrict__ base, int ld,
+                                          int row0, int row_end) {
+  constexpr int CH = D / 8;
+#pragma unroll
+  for (int i = 0; i < TileRegs<D, ROWS>::N; ++i) {
+    const int q = i * 256 + threadIdx.x;
+    const int row = q / CH, c = q - row * CH;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (q < ROWS * CH && row0 + row < row_end) v = *reinterpret_cast<const uint4*>(base + (size_t)(row0 + row) * ld + c * 8);
+    r[i] = v;
+  }
+}
+
+template <int D, int ROWS, int PITCH, int DPAD>
+__device__ __forceinline__ void tile_store(const TileArr<D, ROWS>& r, char* lds) {
+  constexpr int CH = D / 8;
+#pragma unroll
+  for (int i = 0; i < TileRegs<D, ROWS>::N; ++i) {
+    const int q = i * 256 + threadIdx.x;
+    const int row = q / CH, c = q - row * CH;
+    if (q < ROWS * CH) *reinterpret_cast<uint4*>(lds + row * PITCH + c * 16) = r[i];
+  }
+  if (DPAD != D) {
+    constexpr int PADCH = (DPAD - D) / 8;
+    for (int q = threadIdx.x; q < ROWS * PADCH; q += 256) {
+      const int row = q / PADCH, c = q - row * PADCH;
+      *reinterpret_cast<uint4*>(lds + row * PITCH + (CH + c) * 16) = make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
+// Fragment of a tile stored [row][k] (pitch bytes): lane gets row row0 + (lane & 31), k = ks*16 + h*8 .. +8.
+__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int pitch, int row0, int ks, int lane) {
+  const uint4 v = *reinterpret_cast<const uint4*>(tile + (row0 + (lane & 31)) * pitch + (ks * 2 + (lane >> 5)) * 16);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Transposed fragment of a tile stored [k][col] (pitch bytes): lane gets column col0 + (lane & 31) and
+// the eight k values kstart + {0..3} and kstart + 8 + {0..3}, kstart = k0 + (lane >> 5) * 4.  This is the
+// k order in which a 32x32 accumulator block, packed to bf16, serves as the other MFMA operand.
+__device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int pitch, int k0, int col0, int lane) {
+  const int krow = k0 + (lane >> 5) * 4 + ((lane & 15) >> 2);
+  const int col = col0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  union { short4v hh[2]; bf16x8 v; } f;
+  f.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + krow * pitch + col * 2));
+  f.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + (krow + 8) * pitch + col * 2));
+  return f.v;
+}
+
+__device__ __forceinline__ bf16x8 pack8(const float* p) {
+  uint4 w;
+  w.x = pack_bf16x2(p[0], p[1]); w.y = pack_bf16x2(p[2], p[3]);
+  w.z = pack_bf16x2(p[4], p[5]); w.w = pack_bf16x2(p[6], p[7]);
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
+                                                              float* __restrict__ delta, int Tn, int nq) {
+  // 16 lanes per (token, head) pair, 8 elements per lane.
+  const int pair = blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int c = threadIdx.x & 15;
+  float s = 0.f;
+  if (pair < Tn * nq && c < D / 8) {
+    float x[8], y[8];
+    load_vec<bf16_t>(o + (size_t)pair * D + c * 8, x);
+    load_vec<bf16_t>(d_o + (size_t)pair * D + c * 8, y);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += x[e] * y[e];
+  }
+#pragma unroll
+  for (int off = 1; off < 16; off <<= 1) s += __shfl_xor(s, off, 64);
+  if (c == 0 && pair < Tn * nq) {
+    const int i = pair / nq, a = pair - i * nq;
+    delta[(size_t)a * Tn + i] = s;
+  }
+}
+
+template <int D>
+struct DqCfg {
+  static constexpr int DP = (D + 31) / 32 * 32;
+  static constexpr int KP = DP * 2 + 32;             // K tile: row fragments and transposed fragments
+  static constexpr int VP = D * 2 + 16;              // V tile: row fragments only
+  static constexpr int K_BYTES = BKV * KP;
+  static constexpr int STAGE = (K_BYTES + BKV * VP + 255) / 256 * 256;
+  static constexpr int SMEM = 2 * STAGE;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+                                                           const float* __restrict__ lse, const float* __restrict__ delta,
+                                                           bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
+                                                           int Tn, int nq, int nkv, int causal, float scale) {
+  using C = DqCfg<D>;
+  constexpr int NDS = D / 16, NDB = C::DP / 32;
+  constexpr float LOG2E = 1.4426950408889634f;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const AttnTile tl = tiles[blockIdx.x];
+  const int a = blockIdx.y, b = a / (nq / nkv);
+  const int ld = (nq + 2 * nkv) * D;
+  const int qcol = a * D, kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = lane >> 5, li = lane & 31;
+  const int wq0 = tl.r0 + wave * WQ;
+  const bool wave_has_rows = wq0 < tl.r1;
+  const float scale_log2e = scale * LOG2E;
+
+  bf16x8 qf[2][NDS], dof[2][NDS];
+  float lse2[2], dl[2];
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib) {
+    const int i = wq0 + ib * 32 + li;
+    const bool ok = i < tl.r1;
+    lse2[ib] = ok ? lse[(size_t)a * Tn + i] * LOG2E : 0.f;
+    dl[ib] = ok ? delta[(size_t)a * Tn + i] : 0.f;
+#pragma unroll
+    for (int ds = 0; ds < NDS; ++ds) {
+      uint4 v = make_uint4(0, 0, 0, 0), w = v;
+      if (ok) {
+        v = *reinterpret_cast<const uint4*>(qkv + (size_t)i * ld + qcol + ds * 16 + h * 8);
+        w = *reinterpret_cast<const uint4*>(d_o + (size_t)i * nq * D + qcol + ds * 16 + h * 8);
+      }
+      qf[ib][ds] = __builtin_bit_cast(bf16x8, v);
+      dof[ib][ds] = __builtin_bit_cast(bf16x8, w);
+    }
+  }
+  floatx16 acc[NDB][2];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[db][ib][e] = 0.f;
+
+  const int kv_end = causal ? tl.r1 : tl.s1;
+  const int nsteps = (kv_end - tl.s0 + BKV - 1) / BKV;
+  uint4 rk[TileRegs<D, BKV>::N], rv[TileRegs<D, BKV>::N];
+  tile_load<D, BKV>(rk, qkv + kcol, ld, tl.s0, kv_end);
+  tile_load<D, BKV>(rv, qkv + vcol, ld, tl.s0, kv_end);
+  tile_store<D, BKV, C::KP, C::DP>(rk, smem);
+  tile_store<D, BKV, C::VP, D>(rv, smem + C::K_BYTES);
+  __syncthreads();
+
+  for (int st = 0; st < nsteps; ++st) {
+    const int k0 = tl.s0 + st * BKV;
+    const char* sk = smem + (st & 1) * C::STAGE;
+    const char* sv = sk + C::K_BYTES;
+    const bool more = st + 1 < nsteps;
+    if (more) {
+      tile_load<D, BKV>(rk, qkv + kcol, ld, k0 + BKV, kv_end);
+      tile_load<D, BKV>(rv, qkv + vcol, ld, k0 + BKV, kv_end);
+    }
+    const bool active = wave_has_rows && (!causal || k0 <= wq0 + WQ - 1);
+    if (active) {
+      const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib) {
+        const int i = wq0 + ib * 32 + li;
+        floatx16 s[2], dp[2];
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) { s[jb][e] = 0.f; dp[jb][e] = 0.f; }
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds)
+#pragma unroll
+          for (int jb = 0; jb < 2; ++jb) {
+            s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sk, C::KP, jb * 32, ds, lane), qf[ib][ds], s[jb], 0, 0, 0);
+            dp[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sv, C::VP, jb * 32, ds, lane), dof[ib][ds], dp[jb], 0, 0, 0);
+          }
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) {
+          float dsv[16];
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            float p = __builtin_amdgcn_exp2f(s[jb][e] * scale_log2e - lse2[ib]);
+            if (need_mask) {
+              const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+              if (j >= kv_end || (causal && j > i)) p = 0.f;
+            }
+            dsv[e] = p * (dp[jb][e] - dl[ib]);
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const bf16x8 dsf = pack8(dsv + u * 8);
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+              acc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(sk, C::KP, jb * 32 + u * 16, db * 32, lane), dsf,
+                                                                    acc[db][ib], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (more) {
+      char* nk = smem + ((st + 1) & 1) * C::STAGE;
+      tile_store<D, BKV, C::KP, C::DP>(rk, nk);
+      tile_store<D, BKV, C::VP, D>(rv, nk + C::K_BYTES);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib) {
+    const int i = wq0 + ib * 32 + li;
+    if (i >= tl.r1) continue;
+    bf16_t* row = dqkv + (size_t)i * ld + qcol;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int dd = db * 32 + g * 8 + h * 4;
+        if (dd >= D) continue;
+        uint2 w;
+        w.x = pack_bf16x2(acc[db][ib][g * 4 + 0] * scale, acc[db][ib][g * 4 + 1] * scale);
+        w.y = pack_bf16x2(acc[db][ib][g * 4 + 2] * scale, acc[db][ib][g * 4 + 3] * scale);
+        *reinterpret_cast<uint2*>(row + dd) = w;
+      }
+  }
+}
+
+constexpr int BQ_KV = 64;      // query rows per step of the dK/dV kernel
+constexpr int WK = 32;         // keys per wavefront of the dK/dV kernel
+
+template <int D>
+struct DkvCfg {
+  static constexpr int DP = (D + 31) / 32 * 32;
+  static constexpr int QP = DP * 2 + 32;             // Q and dO tiles: row and transposed fragments
+  static constexpr int T_BYTES = BQ_KV * QP;
+  static constexpr int STAGE = (2 * T_BYTES + 2 * BQ_KV * 4 + 255) / 256 * 256;   // Q, dO, lse2[64], delta[64]
+  static constexpr int SMEM = 2 * STAGE;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+                                                            const float* __restrict__ lse, const float* __restrict__ delta,
+                                                            bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
+                                                            int Tn, int nq, int nkv, int causal, float scale) {
+  using C = DkvCfg<D>;
+  constexpr int NDS = D / 16, NDB = C::DP / 32;
+  constexpr float LOG2E = 1.4426950408889634f;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const AttnTile tl = tiles[blockIdx.x];
+  const int b = blockIdx.y, G = nq / nkv;
+  const int ld = (nq + 2 * nkv) * D;
+  const int kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = lane >> 5, li = lane & 31;
+  const int wj0 = tl.r0 + wave * WK;
+  const int j = wj0 + li;                       // this lane's key column
+  const bool wave_has_keys = wj0 < tl.r1;
+  const float scale_log2e = scale * LOG2E;
+
+  bf16x8 kf[NDS], vf[NDS];
+#pragma unroll
+  for (int ds = 0; ds < NDS; ++ds) {
+    uint4 v = make_uint4(0, 0, 0, 0), w = v;
+    if (j < tl.r1) {
+      v = *reinterpret_cast<const uint4*>(qkv + (size_t)j * ld + kcol + ds * 16 + h * 8);
+      w = *reinterpret_cast<const uint4*>(qkv + (size_t)j * ld + vcol + ds * 16 + h * 8);
+    }
+    kf[ds] = __builtin_bit_cast(bf16x8, v);
+    vf[ds] = __builtin_bit_cast(bf16x8, w);
+  }
+  floatx16 dk[NDB], dv[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dk[db][e] = 0.f; dv[db][e] = 0.f; }
+
+  const int q_begin = causal ? tl.r0 : tl.s0;
+  const int nq_steps = (tl.s1 - q_begin + BQ_KV - 1) / BQ_KV;
+  const int nsteps = G * nq_steps;
+  uint4 rq[TileRegs<D, BQ_KV>::N], rd[TileRegs<D, BQ_KV>::N];
+  float r_lse = 0.f, r_dl = 0.f;
+
+  auto fetch = [&](int step) {
+    const int a = b * G + step / nq_steps;
+    const int q0 = q_begin + (step % nq_steps) * BQ_KV;
+    tile_load<D, BQ_KV>(rq, qkv + a * D, ld, q0, tl.s1);
+    tile_load<D, BQ_KV>(rd, d_o + a * D, nq * D, q0, tl.s1);
+    if (threadIdx.x < BQ_KV) {
+      const int i = q0 + threadIdx.x;
+      r_lse = i < tl.s1 ? lse[(size_t)a * Tn + i] * LOG2E : 0.f;
+      r_dl = i < tl.s1 ? delta[(size_t)a * Tn + i] : 0.f;
+    }
+  };
+  auto commit = [&](char* stage) {
+    tile_store<D, BQ_KV, C::QP, C::DP>(rq, stage);
+    tile_store<D, BQ_KV, C::QP, C::DP>(rd, stage + C::T_BYTES);
+    if (threadIdx.x < BQ_KV) {
+      reinterpret_cast<float*>(stage + 2 * C::T_BYTES)[threadIdx.x] = r_lse;
+      reinterpret_cast<float*>(stage + 2 * C::T_BYTES)[BQ_KV + threadIdx.x] = r_dl;
+    }
+  };
+  fetch(0);
+  commit(smem);
+  __syncthreads();
+
+  for (int st = 0; st < nsteps; ++st) {
+    const int q0 = q_begin + (st % nq_steps) * BQ_KV;
+    const char* sq = smem + (st & 1) * C::STAGE;
+    const char* sd = sq + C::T_BYTES;
+    const float* s_lse = reinterpret_cast<const float*>(sq + 2 * C::T_BYTES);
+    const float* s_dl = s_lse + BQ_KV;
+    const bool more = st + 1 < nsteps;
+    if (more) fetch(st + 1);
+    const bool active = wave_has_keys && (!causal || q0 + BQ_KV - 1 >= wj0);
+    if (active) {
+      const bool need_mask = (causal && q0 < wj0 + WK - 1) || (q0 + BQ_KV > tl.s1) || (wj0 + WK > tl.r1);
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib) {
+        floatx16 s, dp;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sq, C::QP, ib * 32, ds, lane), kf[ds], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sd, C::QP, ib * 32, ds, lane), vf[ds], dp, 0, 0, 0);
+        }
+        float pv[16], dsv[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int il = ib * 32 + (e >> 2) * 8 + h * 4 + (e & 3);     // row of this accumulator value
+          float p = __builtin_amdgcn_exp2f(s[e] * scale_log2e - s_lse[il]);
+          if (need_mask) {
+            const int i = q0 + il;
+            if (i >= tl.s1 || j >= tl.r1 || (causal && j > i)) p = 0.f;
+          }
+          pv[e] = p;
+          dsv[e] = p * (dp[e] - s_dl[il]);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const bf16x8 pf = pack8(pv + u * 8), dsf = pack8(dsv + u * 8);
+#pragma unroll
+          for (int db = 0; db < NDB; ++db) {
+            dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(sd, C::QP, ib * 32 + u * 16, db * 32, lane), pf, dv[db], 0, 0, 0);
+            dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(sq, C::QP, ib * 32 + u * 16, db * 32, lane), dsf, dk[db], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (more) commit(smem + ((st + 1) & 1) * C::STAGE);
+    __syncthreads();
+  }
+  if (j < tl.r1) {
+    bf16_t* krow = dqkv + (size_t)j * ld + kcol;
+    bf16_t* vrow = dqkv + (size_t)j * ld + vcol;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int dd = db * 32 + g * 8 + h * 4;
+        if (dd >= D) continue;
+        uint2 w;
+        w.x = pack_bf16x2(dk[db][g * 4 + 0] * scale, dk[db][g * 4 + 1] * scale);
+        w.y = pack_bf16x2(dk[db][g * 4 + 2] * scale, dk[db][g * 4 + 3] * scale);
+        *reinterpret_cast<uint2*>(krow + dd) = w;
+        w.x = pack_bf16x2(dv[db][g * 4 + 0], dv[db][g * 4 + 1]);
+        w.y = pack_bf16x2(dv[db][g * 4 + 2], dv[db][g * 4 + 3]);
+        *reinterpret_cast<uint2*>(vrow + dd) = w;
+      }
+  }
+}
+
+template <int D>
+hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
+  auto kq = attn_dq_mfma_kernel<D>;
+  auto kkv = attn_dkv_mfma_kernel<D>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kq, hipFuncAttributeMaxDynamicSharedMemorySize, DqCfg<D>::SMEM);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)kkv, hipFuncAttributeMaxDynamicSharedMemorySize, DkvCfg<D>::SMEM);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const float scale = 1.0f / sqrtf((float)D);
+  hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((a.T * a.nq + 15) / 16), dim3(256), 0, s, (const bf16_t*)a.o,
+                     (const bf16_t*)a.d_o, a.delta, a.T, a.nq);
+  hipLaunchKernelGGL(kkv, dim3(a.n_kv_tiles, a.nkv), dim3(256), DkvCfg<D>::SMEM, s, (const bf16_t*)a.qkv,
+                     (const bf16_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale);
+  hipLaunchKernelGGL(kq, dim3(a.n_q_tiles, a.nq), dim3(256), DqCfg<D>::SMEM, s, (const bf16_t*)a.qkv, (const bf16_t*)a.d_o,
+                     a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale);
+  return hipGetLastError();
+}
+
 template <int D>
 hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
   using C = FwdCfg<D>;
@@ -273,6 +678,13 @@ hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
   if (a.d == 64) return fwd_launch<64>(a, s);
   if (a.d == 80) return fwd_launch<80>(a, s);
   return fwd_launch<128>(a, s);
+}
+
+hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
+  if (!attn_mfma_supports(a) || a.n_kv_tiles < 1) return hipErrorInvalidValue;
+  if (a.d == 64) return bwd_launch<64>(a, s);
+  if (a.d == 80) return bwd_launch<80>(a, s);
+  return bwd_launch<128>(a, s);
 }
 
 }  // namespace rrfp

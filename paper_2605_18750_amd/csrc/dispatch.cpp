@@ -10,6 +10,8 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   return attn_mfma_supports(a) ? launch_attn_fwd_mfma(a, s) : launch_attn_fwd_simt(a, s);
 }
-hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) { return launch_attn_bwd_simt(a, s); }
+hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
+  return attn_mfma_supports(a) ? launch_attn_bwd_mfma(a, s) : launch_attn_bwd_simt(a, s);
+}
 
 }  // namespace rrfp

@@ -49,6 +49,7 @@ hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_fwd_simt(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd_simt(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s);
 bool attn_mfma_supports(const AttnArgs& a);
 
 // h = x * r * g, r = rsqrt(mean(x^2) + eps); r_out [T] fp32.
