@@ -22,6 +22,13 @@ typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
 
+__device__ __forceinline__ bf16x8 pack8(const float* p) {
+  uint4 w;
+  w.x = pack_bf16x2(p[0], p[1]); w.y = pack_bf16x2(p[2], p[3]);
+  w.z = pack_bf16x2(p[4], p[5]); w.w = pack_bf16x2(p[6], p[7]);
+  return __builtin_bit_cast(bf16x8, w);
+}
+
 constexpr int BKV = 64;        // keys per step
 constexpr int WQ = 64;         // query rows per wavefront
 
@@ -88,8 +95,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
   constexpr int NDS = D / 16;        // contraction steps of Q K^T
   constexpr int NDB = C::DP / 32;    // 32-row blocks of O^T
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const AttnTile tl = tiles[blockIdx.x];
-  const int a = blockIdx.y, b = a / (nq / nkv);
+  const AttnTile tl = tiles[blockIdx.y];
+  const int a = blockIdx.x, b = a / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
   const int qcol = a * D, kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -158,21 +165,22 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
 #pragma unroll
       for (int ib = 0; ib < 2; ++ib) {
         const int i = wq0 + ib * 32 + li;
-        float mx = -INFINITY;
+        if (need_mask) {
+#pragma unroll
+          for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+              s[jb][ib][e] = (j >= kv_end || (causal && j > i)) ? -INFINITY : s[jb][ib][e];
+            }
+        }
+        float mx = -INFINITY;   // maximum of the raw scores (the scale is positive)
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            float v = s[jb][ib][e] * scale_log2e;
-            if (need_mask) {
-              const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-              if (j >= kv_end || (causal && j > i)) v = -INFINITY;
-            }
-            s[jb][ib][e] = v;
-            mx = fmaxf(mx, v);
-          }
+          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[jb][ib][e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[ib], mx);
+        const float m_new = fmaxf(m_run[ib], mx * scale_log2e);
         const float alpha = __builtin_amdgcn_exp2f(m_run[ib] - m_new);
         m_run[ib] = m_new;
         float ps = 0.f;
@@ -181,24 +189,19 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
           float p[16];
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
-            p[e] = __builtin_amdgcn_exp2f(s[jb][ib][e] - m_new);
+            p[e] = __builtin_amdgcn_exp2f(fmaf(s[jb][ib][e], scale_log2e, -m_new));
             ps += p[e];
           }
 #pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            uint4 w;
-            w.x = pack_bf16x2(p[u * 8 + 0], p[u * 8 + 1]);
-            w.y = pack_bf16x2(p[u * 8 + 2], p[u * 8 + 3]);
-            w.z = pack_bf16x2(p[u * 8 + 4], p[u * 8 + 5]);
-            w.w = pack_bf16x2(p[u * 8 + 6], p[u * 8 + 7]);
-            pf[ib][jb][u] = __builtin_bit_cast(bf16x8, w);
-          }
+          for (int u = 0; u < 2; ++u) pf[ib][jb][u] = pack8(p + u * 8);
         }
         l_run[ib] = l_run[ib] * alpha + ps;
+        if (__any(alpha != 1.0f)) {   // the running maximum moved for some query of this wavefront
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
+          for (int db = 0; db < NDB; ++db)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) oacc[db][ib][e] *= alpha;
+            for (int e = 0; e < 16; ++e) oacc[db][ib][e] *= alpha;
+        }
       }
       // O^T[db][ib] += V^T P^T.  B-operand slot s of half h is key 16u + (s/4)*8 + h*4 + s%4 of the
       // 32-key block, so the matching V fragment is two transpose reads starting at keys h*4 and 8 + h*4.
@@ -315,13 +318,6 @@ __device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int pitch, int 
   return f.v;
 }
 
-__device__ __forceinline__ bf16x8 pack8(const float* p) {
-  uint4 w;
-  w.x = pack_bf16x2(p[0], p[1]); w.y = pack_bf16x2(p[2], p[3]);
-  w.z = pack_bf16x2(p[4], p[5]); w.w = pack_bf16x2(p[6], p[7]);
-  return __builtin_bit_cast(bf16x8, w);
-}
-
 template <int D>
 __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
                                                               float* __restrict__ delta, int Tn, int nq) {
@@ -363,8 +359,8 @@ __global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restr
   constexpr int NDS = D / 16, NDB = C::DP / 32;
   constexpr float LOG2E = 1.4426950408889634f;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const AttnTile tl = tiles[blockIdx.x];
-  const int a = blockIdx.y, b = a / (nq / nkv);
+  const AttnTile tl = tiles[blockIdx.y];
+  const int a = blockIdx.x, b = a / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
   const int qcol = a * D, kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -506,8 +502,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
   constexpr int NDS = D / 16, NDB = C::DP / 32;
   constexpr float LOG2E = 1.4426950408889634f;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const AttnTile tl = tiles[blockIdx.x];
-  const int b = blockIdx.y, G = nq / nkv;
+  const AttnTile tl = tiles[blockIdx.y];
+  const int b = blockIdx.x, G = nq / nkv;
   const int ld = (nq + 2 * nkv) * D;
   const int kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -644,9 +640,9 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)D);
   hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((a.T * a.nq + 15) / 16), dim3(256), 0, s, (const bf16_t*)a.o,
                      (const bf16_t*)a.d_o, a.delta, a.T, a.nq);
-  hipLaunchKernelGGL(kkv, dim3(a.n_kv_tiles, a.nkv), dim3(256), DkvCfg<D>::SMEM, s, (const bf16_t*)a.qkv,
+  hipLaunchKernelGGL(kkv, dim3(a.nkv, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const bf16_t*)a.qkv,
                      (const bf16_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale);
-  hipLaunchKernelGGL(kq, dim3(a.n_q_tiles, a.nq), dim3(256), DqCfg<D>::SMEM, s, (const bf16_t*)a.qkv, (const bf16_t*)a.d_o,
+  hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(256), DqCfg<D>::SMEM, s, (const bf16_t*)a.qkv, (const bf16_t*)a.d_o,
                      a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale);
   return hipGetLastError();
 }
@@ -662,7 +658,7 @@ hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
     configured = true;
   }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL(kern, dim3(a.n_q_tiles, a.nq), dim3(256), C::SMEM, s, (const bf16_t*)a.qkv, (bf16_t*)a.o, a.lse,
+  hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(256), C::SMEM, s, (const bf16_t*)a.qkv, (bf16_t*)a.o, a.lse,
                      a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale_log2e);
   return hipGetLastError();
 }

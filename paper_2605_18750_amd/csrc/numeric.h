@@ -26,11 +26,15 @@ __device__ inline float to_float(bf16_t v) { return bf16_bits_to_float(v.bits); 
 
 template <typename T> __device__ inline T from_float(float f);
 template <> __device__ inline float from_float<float>(float f) { return f; }
-template <> __device__ inline bf16_t from_float<bf16_t>(float f) { return bf16_t{float_to_bf16_bits(f)}; }
+// On the device the conversion is the hardware one (v_cvt_pk_bf16_f32: round-to-nearest-even).
+typedef __bf16 bf16x2_native __attribute__((ext_vector_type(2)));
+typedef float floatx2_native __attribute__((ext_vector_type(2)));
 
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+  const floatx2_native v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_native));
 }
+template <> __device__ inline bf16_t from_float<bf16_t>(float f) { return bf16_t{(uint16_t)(pack_bf16x2(f, 0.f) & 0xffffu)}; }
 
 template <typename T> struct Vec;
 template <> struct Vec<float> { static constexpr int N = 4; };
