@@ -203,17 +203,192 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __res
   }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Direct-to-LDS variant (the one the stage tasks run): global -> LDS copies are
+// buffer_load ... lds instructions, 16 bytes per lane, which land in LDS at
+// base + lane * 16 without passing through registers.  The XOR swizzles of the tile layouts
+// are therefore applied on the GLOBAL side: lane p of a 1 KB block fetches the chunk that
+// belongs at LDS position p.  Buffer descriptors bound every operand, so rows past the end
+// of an operand read as zero (that is what zero-fills the ragged K tail of the
+// weight-gradient GEMMs, K = tokens).  Fragment reads are software-pipelined one 16-wide
+// k-step ahead of the MFMAs that consume them.
+// Requires K % 64 == 0 when an operand is K-contiguous (a K tail would wrap into the next row).
+// ------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+template <bool KC>
+struct DirectLoader {
+  __amdgpu_buffer_rsrc_t rsrc;
+  int voff[8];
+  int k_stride;     // bytes per k-tile
+  __device__ __forceinline__ void init(const bf16_t* base, int ld, int outer0, int outer_n, int K, int wave, int lane) {
+    const size_t bytes = KC ? ((size_t)(outer_n - 1) * ld + K) * 2 : ((size_t)(K - 1) * ld + outer_n) * 2;
+    rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+    k_stride = KC ? BK * 2 : BK * ld * 2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int blk = i * 4 + wave;
+      if (KC) {
+        const int r = lane >> 3, row = blk * 8 + r, c = (lane & 7) ^ r;
+        voff[i] = (outer0 + row < outer_n) ? ((outer0 + row) * ld + c * 8) * 2 : (int)0x80000000;
+      } else {
+        const int k = blk * 2 + (lane >> 5), cp = lane & 31;
+        const int f = (k & 3) | (((k >> 3) & 1) << 2);
+        const int c = ((((cp >> 2) ^ f) << 2) | (cp & 3));
+        voff[i] = (k * ld + outer0 + c * 8) * 2;
+      }
+    }
+  }
+  __device__ __forceinline__ void issue(char* tile, int kt, int wave) const {
+    const int soff = kt * k_stride;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * 4 + wave) * 1024), 16, voff[i], soff, 0, 0);
+  }
+};
+
+// One 64-deep k-tile of MFMAs from one LDS stage; fragment reads run one 16-wide k-step ahead.
+template <bool A_KC, bool B_KC>
+__device__ __forceinline__ void compute_stage(floatx16 (&acc)[4][4], const char* sa, int wm, int wn, int lane) {
+  constexpr int DS_PER_KS = (A_KC ? 4 : 8) + (B_KC ? 4 : 8);
+  const char* sb = sa + TILE_BYTES;
+  bf16x8 fa[2][4], fb[2][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fa[0][i] = read_frag<A_KC>(sa, wm + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) fb[0][j] = read_frag<B_KC>(sb, wn + j * 32, 0, lane);
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) {
+    const int cur = ks & 1, nxt = cur ^ 1;
+    if (ks + 1 < BK / 16) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[nxt][i] = read_frag<A_KC>(sa, wm + i * 32, ks + 1, lane);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) fb[nxt][j] = read_frag<B_KC>(sb, wn + j * 32, ks + 1, lane);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+    if (ks + 1 < BK / 16) {
+      // interleave the next step's fragment reads with this step's MFMAs
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_KS / 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      }
+    }
+  }
+}
+
+template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
+__global__ __launch_bounds__(NTHREADS) void gemm_mfma_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                                TO* __restrict__ C, const bf16_t* __restrict__ R, int M,
+                                                                int N, int K, int lda, int ldb, int ldc, int ldr,
+                                                                int tiles_m, int tiles_n) {
+  // Two separate LDS arrays (not one buffer with an offset): the compiler can then prove that the
+  // fragment reads of one stage do not alias the in-flight direct loads into the other, and does not
+  // wait for them.
+  __shared__ __attribute__((aligned(1024))) char stage0[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char stage1[STAGE_BYTES];
+  int tm, tn;
+  tile_coords(tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+
+  floatx16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  DirectLoader<A_KC> la;
+  DirectLoader<B_KC> lb;
+  la.init(A, lda, m0, M, K, wave, lane);
+  lb.init(B, ldb, n0, N, K, wave, lane);
+  const int nk = (K + BK - 1) / BK;
+  la.issue(stage0, 0, wave);
+  lb.issue(stage0 + TILE_BYTES, 0, wave);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  for (int kt = 0; kt + 1 < nk; kt += 2) {
+    la.issue(stage1, kt + 1, wave);
+    lb.issue(stage1 + TILE_BYTES, kt + 1, wave);
+    compute_stage<A_KC, B_KC>(acc, stage0, wm, wn, lane);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (kt + 2 < nk) {
+      la.issue(stage0, kt + 2, wave);
+      lb.issue(stage0 + TILE_BYTES, kt + 2, wave);
+    }
+    compute_stage<A_KC, B_KC>(acc, stage1, wm, wn, lane);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  }
+  if (nk & 1) compute_stage<A_KC, B_KC>(acc, stage0, wm, wn, lane);
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + wm + i * 32 + (lane & 31);
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = n0 + wn + j * 32 + g * 8 + (lane >> 5) * 4;
+        if (n >= N) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e];
+        if (HAS_R) {
+          const uint2 rr = *reinterpret_cast<const uint2*>(R + (size_t)m * ldr + n);
+          v[0] += __uint_as_float(rr.x << 16); v[1] += __uint_as_float(rr.x & 0xffff0000u);
+          v[2] += __uint_as_float(rr.y << 16); v[3] += __uint_as_float(rr.y & 0xffff0000u);
+        }
+        if (sizeof(TO) == 4) {
+          *reinterpret_cast<float4*>((float*)C + (size_t)m * ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+          uint2 o;
+          o.x = pack_bf16x2(v[0], v[1]);
+          o.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>((bf16_t*)C + (size_t)m * ldc + n) = o;
+        }
+      }
+    }
+  }
+}
+
+// True when the direct-to-LDS kernel can take the call (else the register-staged one does).
+inline bool direct_ok(const GemmArgs& g) {
+  const bool a_kc = !g.transA, b_kc = g.transB;
+  if ((a_kc || b_kc) && (g.K % BK)) return false;
+  const size_t lim = (size_t)1 << 31;
+  const size_t a_bytes = (size_t)(a_kc ? g.M + BM : g.K + BK) * g.lda * 2;
+  const size_t b_bytes = (size_t)(b_kc ? g.N + BN : g.K + BK) * g.ldb * 2;
+  return a_bytes < lim && b_bytes < lim;
+}
+
 template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
 hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
-  auto kern = gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>;
+  auto kern_rs = gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>;
+  auto kern_dl = gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R>;
   static bool configured = false;   // per instantiation; the attribute is process-wide for the function
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)kern_rs, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
     if (e != hipSuccess) return e;
     configured = true;
   }
+  const bool direct = direct_ok(g);
+  auto kern = direct ? kern_dl : kern_rs;
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(NTHREADS), SMEM_BYTES, s, (const bf16_t*)g.A,
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(NTHREADS), direct ? 0 : SMEM_BYTES, s, (const bf16_t*)g.A,
                      (const bf16_t*)g.B, (TO*)g.C, (const bf16_t*)g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, g.ldr,
                      tiles_m, tiles_n);
   return hipGetLastError();
