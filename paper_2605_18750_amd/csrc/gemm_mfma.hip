@@ -205,32 +205,43 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __res
 
 
 // ------------------------------------------------------------------------------------------
-// Direct-to-LDS variant (the one the stage tasks run): global -> LDS copies are
-// buffer_load ... lds instructions, 16 bytes per lane, which land in LDS at
-// base + lane * 16 without passing through registers.  The XOR swizzles of the tile layouts
-// are therefore applied on the GLOBAL side: lane p of a 1 KB block fetches the chunk that
-// belongs at LDS position p.  Buffer descriptors bound every operand, so rows past the end
-// of an operand read as zero (that is what zero-fills the ragged K tail of the
-// weight-gradient GEMMs, K = tokens).  Fragment reads are software-pipelined one 16-wide
-// k-step ahead of the MFMAs that consume them.
-// Requires K % 64 == 0 when an operand is K-contiguous (a K tail would wrap into the next row).
+// Direct-to-LDS variant (the one the stage tasks run).
+//   - global -> LDS copies are buffer_load ... lds instructions, 16 bytes per lane, which land
+//     in LDS at base + lane * 16 without passing through registers.  The XOR swizzles of the
+//     tile layouts are therefore applied on the GLOBAL side: lane p of a 1 KB block fetches the
+//     chunk that belongs at LDS position p.
+//   - buffer descriptors bound every operand, so rows past the end of an operand read as zero
+//     (that is what zero-fills the ragged K tail of the weight-gradient GEMMs, K = tokens).
+//   - K advances in steps of 32 through FOUR LDS stages of 32 KB, so the loads of step t+3 are
+//     issued before the MFMAs of step t: three steps (about 3000 MFMA cycles) of latency cover.
+//     The stages are four separate __shared__ arrays and the loop is unrolled by four, so the
+//     compiler can prove that fragment reads of one stage do not alias loads in flight to another.
+//   - fragment reads run one 16-wide k-step ahead of the MFMAs that consume them.
+// Requires K % 32 == 0 when an operand is K-contiguous (a K tail would wrap into the next row).
 // ------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+constexpr int DBK = 32;                              // k per stage
+constexpr int DTILE = 256 * DBK * 2;                 // bytes of one operand tile (16 KB)
+constexpr int DSTAGE = 2 * DTILE;                    // A + B (32 KB)
+
+// K-contiguous tile [256 rows][32 k]: 64-byte rows, 4 chunks; chunk c of row r sits at c ^ ((r >> 1) & 3).
+__device__ __forceinline__ int dkc_off(int row, int c) { return row * 64 + ((c ^ ((row >> 1) & 3)) << 4); }
 
 template <bool KC>
 struct DirectLoader {
   __amdgpu_buffer_rsrc_t rsrc;
-  int voff[8];
-  int k_stride;     // bytes per k-tile
+  int voff[4];
+  int k_stride;     // bytes per k-step
   __device__ __forceinline__ void init(const bf16_t* base, int ld, int outer0, int outer_n, int K, int wave, int lane) {
     const size_t bytes = KC ? ((size_t)(outer_n - 1) * ld + K) * 2 : ((size_t)(K - 1) * ld + outer_n) * 2;
     rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
-    k_stride = KC ? BK * 2 : BK * ld * 2;
+    k_stride = KC ? DBK * 2 : DBK * ld * 2;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int blk = i * 4 + wave;
+    for (int i = 0; i < 4; ++i) {
+      const int blk = i * 4 + wave;                  // 1 KB block of the 16 KB tile
       if (KC) {
-        const int r = lane >> 3, row = blk * 8 + r, c = (lane & 7) ^ r;
+        const int row = blk * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 1) & 3);
         voff[i] = (outer0 + row < outer_n) ? ((outer0 + row) * ld + c * 8) * 2 : (int)0x80000000;
       } else {
         const int k = blk * 2 + (lane >> 5), cp = lane & 31;
@@ -243,44 +254,65 @@ struct DirectLoader {
   __device__ __forceinline__ void issue(char* tile, int kt, int wave) const {
     const int soff = kt * k_stride;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 4; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * 4 + wave) * 1024), 16, voff[i], soff, 0, 0);
   }
 };
 
-// One 64-deep k-tile of MFMAs from one LDS stage; fragment reads run one 16-wide k-step ahead.
+template <bool KC>
+__device__ __forceinline__ bf16x8 dread_frag(const char* tile, int row0, int ks, int lane) {
+  if (KC) {
+    const int row = row0 + (lane & 31);
+    const uint4 v = *reinterpret_cast<const uint4*>(tile + dkc_off(row, ks * 2 + (lane >> 5)));
+    return __builtin_bit_cast(bf16x8, v);
+  } else {
+    return read_frag<false>(tile, row0, ks, lane);   // [32 k][256 rows]: same layout as the 64-deep tile
+  }
+}
+
+// Workgroup barrier between pipeline steps.  The caller has already waited (s_waitcnt vmcnt) for its
+// own direct loads of the stage that is read next; a plain s_barrier then makes every wavefront's
+// share of that stage visible.  No fence: a release fence would make the compiler drain ALL loads
+// in flight, including those of the stages two and three steps ahead.  The empty asm statements
+// keep the compiler from moving LDS accesses across the barrier.
+__device__ __forceinline__ void stage_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("" ::: "memory");
+}
+
+// One 32-deep k-step of MFMAs from one LDS stage (two 16-wide MFMA k-steps).
 template <bool A_KC, bool B_KC>
 __device__ __forceinline__ void compute_stage(floatx16 (&acc)[4][4], const char* sa, int wm, int wn, int lane) {
   constexpr int DS_PER_KS = (A_KC ? 4 : 8) + (B_KC ? 4 : 8);
-  const char* sb = sa + TILE_BYTES;
+  const char* sb = sa + DTILE;
   bf16x8 fa[2][4], fb[2][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) fa[0][i] = read_frag<A_KC>(sa, wm + i * 32, 0, lane);
+  for (int i = 0; i < 4; ++i) fa[0][i] = dread_frag<A_KC>(sa, wm + i * 32, 0, lane);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) fb[0][j] = read_frag<B_KC>(sb, wn + j * 32, 0, lane);
+  for (int j = 0; j < 4; ++j) fb[0][j] = dread_frag<B_KC>(sb, wn + j * 32, 0, lane);
 #pragma unroll
-  for (int ks = 0; ks < BK / 16; ++ks) {
-    const int cur = ks & 1, nxt = cur ^ 1;
-    if (ks + 1 < BK / 16) {
+  for (int i = 0; i < 4; ++i) fa[1][i] = dread_frag<A_KC>(sa, wm + i * 32, 1, lane);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) fa[nxt][i] = read_frag<A_KC>(sa, wm + i * 32, ks + 1, lane);
+  for (int j = 0; j < 4; ++j) fb[1][j] = dread_frag<B_KC>(sb, wn + j * 32, 1, lane);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) fb[nxt][j] = read_frag<B_KC>(sb, wn + j * 32, ks + 1, lane);
-    }
+  for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
-    if (ks + 1 < BK / 16) {
-      // interleave the next step's fragment reads with this step's MFMAs
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_KS / 4, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-      }
-    }
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks][j], fa[ks][i], acc[i][j], 0, 0, 0);
   }
+  // first k-step's reads up front, the second k-step's reads interleaved with the first 16 MFMAs
+  __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_KS, 0);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_KS / 4, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
 }
 
 template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
@@ -288,11 +320,10 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_dl_kernel(const bf16_t* __
                                                                 TO* __restrict__ C, const bf16_t* __restrict__ R, int M,
                                                                 int N, int K, int lda, int ldb, int ldc, int ldr,
                                                                 int tiles_m, int tiles_n) {
-  // Two separate LDS arrays (not one buffer with an offset): the compiler can then prove that the
-  // fragment reads of one stage do not alias the in-flight direct loads into the other, and does not
-  // wait for them.
-  __shared__ __attribute__((aligned(1024))) char stage0[STAGE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char stage1[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char stage0[DSTAGE];
+  __shared__ __attribute__((aligned(1024))) char stage1[DSTAGE];
+  __shared__ __attribute__((aligned(1024))) char stage2[DSTAGE];
+  __shared__ __attribute__((aligned(1024))) char stage3[DSTAGE];
   int tm, tn;
   tile_coords(tiles_m, tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
@@ -312,27 +343,50 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_dl_kernel(const bf16_t* __
   DirectLoader<B_KC> lb;
   la.init(A, lda, m0, M, K, wave, lane);
   lb.init(B, ldb, n0, N, K, wave, lane);
-  const int nk = (K + BK - 1) / BK;
-  la.issue(stage0, 0, wave);
-  lb.issue(stage0 + TILE_BYTES, 0, wave);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
+  const int nk = (K + DBK - 1) / DBK;
 
-  for (int kt = 0; kt + 1 < nk; kt += 2) {
-    la.issue(stage1, kt + 1, wave);
-    lb.issue(stage1 + TILE_BYTES, kt + 1, wave);
-    compute_stage<A_KC, B_KC>(acc, stage0, wm, wn, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (kt + 2 < nk) {
-      la.issue(stage0, kt + 2, wave);
-      lb.issue(stage0 + TILE_BYTES, kt + 2, wave);
-    }
-    compute_stage<A_KC, B_KC>(acc, stage1, wm, wn, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+  // s_waitcnt immediates (vmcnt only): each step issues 8 loads per wavefront.
+  constexpr int WAIT_VM0 = 0x0F70, WAIT_VM16 = 0x4F70;
+#define RRFP_ISSUE(stage, t) do { la.issue(stage, (t), wave); lb.issue(stage + DTILE, (t), wave); } while (0)
+#define RRFP_STEP_FULL(cur, nxt3, t)                                                       \
+  do {                                                                                     \
+    RRFP_ISSUE(nxt3, (t) + 3);                                                             \
+    compute_stage<A_KC, B_KC>(acc, cur, wm, wn, lane);                                     \
+    __builtin_amdgcn_s_waitcnt(WAIT_VM16);                                                 \
+    stage_barrier();                                                                       \
+  } while (0)
+#define RRFP_STEP_TAIL(cur, nxt3, t)                                                       \
+  do {                                                                                     \
+    const bool ahead_ = (t) + 3 < nk;                                                      \
+    if (ahead_) RRFP_ISSUE(nxt3, (t) + 3);                                                 \
+    compute_stage<A_KC, B_KC>(acc, cur, wm, wn, lane);                                     \
+    if (ahead_) __builtin_amdgcn_s_waitcnt(WAIT_VM16); else __builtin_amdgcn_s_waitcnt(WAIT_VM0); \
+    stage_barrier();                                                                       \
+  } while (0)
+
+  RRFP_ISSUE(stage0, 0);
+  if (nk > 1) RRFP_ISSUE(stage1, 1);
+  if (nk > 2) RRFP_ISSUE(stage2, 2);
+  if (nk > 2) __builtin_amdgcn_s_waitcnt(WAIT_VM16); else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+  stage_barrier();
+
+  int t = 0;
+  for (; t + 6 < nk; t += 4) {      // every step of this loop has a step t+3 to prefetch
+    RRFP_STEP_FULL(stage0, stage3, t);
+    RRFP_STEP_FULL(stage1, stage0, t + 1);
+    RRFP_STEP_FULL(stage2, stage1, t + 2);
+    RRFP_STEP_FULL(stage3, stage2, t + 3);
   }
-  if (nk & 1) compute_stage<A_KC, B_KC>(acc, stage0, wm, wn, lane);
+  // at most 6 steps remain
+  if (t < nk) RRFP_STEP_TAIL(stage0, stage3, t);
+  if (t + 1 < nk) RRFP_STEP_TAIL(stage1, stage0, t + 1);
+  if (t + 2 < nk) RRFP_STEP_TAIL(stage2, stage1, t + 2);
+  if (t + 3 < nk) RRFP_STEP_TAIL(stage3, stage2, t + 3);
+  if (t + 4 < nk) RRFP_STEP_TAIL(stage0, stage3, t + 4);
+  if (t + 5 < nk) RRFP_STEP_TAIL(stage1, stage0, t + 5);
+#undef RRFP_STEP_FULL
+#undef RRFP_STEP_TAIL
+#undef RRFP_ISSUE
 
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -368,7 +422,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_dl_kernel(const bf16_t* __
 // True when the direct-to-LDS kernel can take the call (else the register-staged one does).
 inline bool direct_ok(const GemmArgs& g) {
   const bool a_kc = !g.transA, b_kc = g.transB;
-  if ((a_kc || b_kc) && (g.K % BK)) return false;
+  if ((a_kc || b_kc) && (g.K % DBK)) return false;
   const size_t lim = (size_t)1 << 31;
   const size_t a_bytes = (size_t)(a_kc ? g.M + BM : g.K + BK) * g.lda * 2;
   const size_t b_bytes = (size_t)(b_kc ? g.N + BN : g.K + BK) * g.ldb * 2;
