@@ -221,6 +221,10 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __res
 // ------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
+// Wavefronts per workgroup of the direct-load kernel, by operand orientation (measured on the
+// language-stage shapes): two per SIMD when at least one operand is K-contiguous, one per SIMD when
+// both are K-strided (the transpose reads double the LDS instruction count).
+constexpr int dl_waves(bool a_kc, bool b_kc) { return (a_kc || b_kc) ? 8 : 4; }
 constexpr int DBK = 32;                              // k per stage
 constexpr int DTILE = 256 * DBK * 2;                 // bytes of one operand tile (16 KB)
 constexpr int DSTAGE = 2 * DTILE;                    // A + B (32 KB)
@@ -228,18 +232,21 @@ constexpr int DSTAGE = 2 * DTILE;                    // A + B (32 KB)
 // K-contiguous tile [256 rows][32 k]: 64-byte rows, 4 chunks; chunk c of row r sits at c ^ ((r >> 1) & 3).
 __device__ __forceinline__ int dkc_off(int row, int c) { return row * 64 + ((c ^ ((row >> 1) & 3)) << 4); }
 
-template <bool KC>
+// NW = wavefronts per workgroup: 4 (2x2, 128x128 each, one per SIMD) or 8 (2x4, 128x64 each, two per
+// SIMD so that one wavefront's waits hide behind the other's MFMAs).
+template <bool KC, int NW>
 struct DirectLoader {
+  static constexpr int NL = 16 / NW;               // 1 KB blocks of the 16 KB tile per wavefront
   __amdgpu_buffer_rsrc_t rsrc;
-  int voff[4];
+  int voff[NL];
   int k_stride;     // bytes per k-step
   __device__ __forceinline__ void init(const bf16_t* base, int ld, int outer0, int outer_n, int K, int wave, int lane) {
     const size_t bytes = KC ? ((size_t)(outer_n - 1) * ld + K) * 2 : ((size_t)(K - 1) * ld + outer_n) * 2;
     rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
     k_stride = KC ? DBK * 2 : DBK * ld * 2;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int blk = i * 4 + wave;                  // 1 KB block of the 16 KB tile
+    for (int i = 0; i < NL; ++i) {
+      const int blk = i * NW + wave;                 // 1 KB block of the 16 KB tile
       if (KC) {
         const int row = blk * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 1) & 3);
         voff[i] = (outer0 + row < outer_n) ? ((outer0 + row) * ld + c * 8) * 2 : (int)0x80000000;
@@ -254,8 +261,8 @@ struct DirectLoader {
   __device__ __forceinline__ void issue(char* tile, int kt, int wave) const {
     const int soff = kt * k_stride;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * 4 + wave) * 1024), 16, voff[i], soff, 0, 0);
+    for (int i = 0; i < NL; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * NW + wave) * 1024), 16, voff[i], soff, 0, 0);
   }
 };
 
@@ -283,43 +290,44 @@ __device__ __forceinline__ void stage_barrier() {
   asm volatile("" ::: "memory");
 }
 
-// One 32-deep k-step of MFMAs from one LDS stage (two 16-wide MFMA k-steps).
-template <bool A_KC, bool B_KC>
-__device__ __forceinline__ void compute_stage(floatx16 (&acc)[4][4], const char* sa, int wm, int wn, int lane) {
-  constexpr int DS_PER_KS = (A_KC ? 4 : 8) + (B_KC ? 4 : 8);
+// Fragments of one 16-wide MFMA k-step: 4 row blocks of A and NB column blocks of B of this wavefront.
+template <int NB>
+struct Frags { bf16x8 a[4], b[NB]; };
+
+template <bool A_KC, bool B_KC, int NB>
+__device__ __forceinline__ void load_frags(Frags<NB>& f, const char* sa, int ks, int wm, int wn, int lane) {
   const char* sb = sa + DTILE;
-  bf16x8 fa[2][4], fb[2][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) fa[0][i] = dread_frag<A_KC>(sa, wm + i * 32, 0, lane);
+  for (int i = 0; i < 4; ++i) f.a[i] = dread_frag<A_KC>(sa, wm + i * 32, ks, lane);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) fb[0][j] = dread_frag<B_KC>(sb, wn + j * 32, 0, lane);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) fa[1][i] = dread_frag<A_KC>(sa, wm + i * 32, 1, lane);
-#pragma unroll
-  for (int j = 0; j < 4; ++j) fb[1][j] = dread_frag<B_KC>(sb, wn + j * 32, 1, lane);
-#pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks][j], fa[ks][i], acc[i][j], 0, 0, 0);
-  }
-  // first k-step's reads up front, the second k-step's reads interleaved with the first 16 MFMAs
-  __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_KS, 0);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_KS / 4, 0);
-  }
-  __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+  for (int j = 0; j < NB; ++j) f.b[j] = dread_frag<B_KC>(sb, wn + j * 32, ks, lane);
 }
 
-template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
-__global__ __launch_bounds__(NTHREADS) void gemm_mfma_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
-                                                                TO* __restrict__ C, const bf16_t* __restrict__ R, int M,
-                                                                int N, int K, int lda, int ldb, int ldc, int ldr,
-                                                                int tiles_m, int tiles_n) {
+template <int NB>
+__device__ __forceinline__ void mfma16(floatx16 (&acc)[4][NB], const Frags<NB>& f) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+}
+
+// Ask the scheduler to interleave N_DS LDS reads with N_MFMA MFMAs in four groups, reads leading.
+template <int N_DS, int N_MFMA>
+__device__ __forceinline__ void interleave_ds_mfma() {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    __builtin_amdgcn_sched_group_barrier(0x100, N_DS / 4, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA / 4, 0);
+  }
+}
+
+template <bool A_KC, bool B_KC, typename TO, bool HAS_R, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                               TO* __restrict__ C, const bf16_t* __restrict__ R, int M,
+                                                               int N, int K, int lda, int ldb, int ldc, int ldr,
+                                                               int tiles_m, int tiles_n) {
+  constexpr int NB = 16 / NW;                       // 32-wide column blocks per wavefront: 4 or 2
+  constexpr int WAVE_N = NB * 32;                   // 128 or 64
   __shared__ __attribute__((aligned(1024))) char stage0[DSTAGE];
   __shared__ __attribute__((aligned(1024))) char stage1[DSTAGE];
   __shared__ __attribute__((aligned(1024))) char stage2[DSTAGE];
@@ -329,61 +337,86 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_dl_kernel(const bf16_t* __
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  const int wm = (wave / (NW / 2)) * 128, wn = (wave % (NW / 2)) * WAVE_N;
 
-  floatx16 acc[4][4];
+  floatx16 acc[4][NB];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NB; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  DirectLoader<A_KC> la;
-  DirectLoader<B_KC> lb;
+  DirectLoader<A_KC, NW> la;
+  DirectLoader<B_KC, NW> lb;
   la.init(A, lda, m0, M, K, wave, lane);
   lb.init(B, ldb, n0, N, K, wave, lane);
   const int nk = (K + DBK - 1) / DBK;
 
-  // s_waitcnt immediates (vmcnt only): each step issues 8 loads per wavefront.
-  constexpr int WAIT_VM0 = 0x0F70, WAIT_VM16 = 0x4F70;
+  // Software pipeline over 32-deep steps.  Entering step t the fragments of its first k-step are in
+  // registers (fx).  First half: read the second k-step's fragments (fy) under the MFMAs of the
+  // first.  Middle: wait for this wavefront's loads of step t+1 and for its own LDS reads, barrier
+  // (now stage t%4 is consumed by everybody and stage (t+1)%4 is complete), refill stage t%4 with
+  // step t+4, and read step t+1's first fragments under the MFMAs of the second k-step.
+  // Each step issues LPS loads per wavefront; "all but 2*LPS outstanding" means step t+1 has landed
+  // while t+2 and t+3 may still be in flight.
+  constexpr int LPS = 2 * (16 / NW);
+  constexpr int VM_ALL = 0x0070;                                   // vmcnt(0), lgkmcnt(0)
+  constexpr int VM_2 = 0x0070 | ((2 * LPS) & 15) | (((2 * LPS) >> 4) << 14);   // vmcnt(2*LPS), lgkmcnt(0)
+  constexpr int VM_3 = 0x0070 | ((3 * LPS) & 15) | (((3 * LPS) >> 4) << 14);   // vmcnt(3*LPS), lgkmcnt(0)
+  constexpr int N_DS = (A_KC ? 4 : 8) + (B_KC ? NB : 2 * NB);
+  constexpr int N_MFMA = 4 * NB;
 #define RRFP_ISSUE(stage, t) do { la.issue(stage, (t), wave); lb.issue(stage + DTILE, (t), wave); } while (0)
-#define RRFP_STEP_FULL(cur, nxt3, t)                                                       \
+#define RRFP_STEP_FULL(cur, nxt, t)                                                        \
   do {                                                                                     \
-    RRFP_ISSUE(nxt3, (t) + 3);                                                             \
-    compute_stage<A_KC, B_KC>(acc, cur, wm, wn, lane);                                     \
-    __builtin_amdgcn_s_waitcnt(WAIT_VM16);                                                 \
+    load_frags<A_KC, B_KC, NB>(fy, cur, 1, wm, wn, lane);                                  \
+    mfma16<NB>(acc, fx);                                                                   \
+    interleave_ds_mfma<N_DS, N_MFMA>();                                                    \
+    __builtin_amdgcn_s_waitcnt(VM_2);                                                      \
     stage_barrier();                                                                       \
+    RRFP_ISSUE(cur, (t) + 4);                                                              \
+    load_frags<A_KC, B_KC, NB>(fx, nxt, 0, wm, wn, lane);                                  \
+    mfma16<NB>(acc, fy);                                                                   \
+    interleave_ds_mfma<N_DS, N_MFMA>();                                                    \
   } while (0)
-#define RRFP_STEP_TAIL(cur, nxt3, t)                                                       \
+#define RRFP_STEP_TAIL(cur, nxt, t)                                                        \
   do {                                                                                     \
-    const bool ahead_ = (t) + 3 < nk;                                                      \
-    if (ahead_) RRFP_ISSUE(nxt3, (t) + 3);                                                 \
-    compute_stage<A_KC, B_KC>(acc, cur, wm, wn, lane);                                     \
-    if (ahead_) __builtin_amdgcn_s_waitcnt(WAIT_VM16); else __builtin_amdgcn_s_waitcnt(WAIT_VM0); \
-    stage_barrier();                                                                       \
+    load_frags<A_KC, B_KC, NB>(fy, cur, 1, wm, wn, lane);                                  \
+    mfma16<NB>(acc, fx);                                                                   \
+    if ((t) + 1 < nk) {                                                                    \
+      if ((t) + 3 < nk) __builtin_amdgcn_s_waitcnt(VM_2);                                  \
+      else __builtin_amdgcn_s_waitcnt(VM_ALL);                                             \
+      stage_barrier();                                                                     \
+      if ((t) + 4 < nk) RRFP_ISSUE(cur, (t) + 4);                                          \
+      load_frags<A_KC, B_KC, NB>(fx, nxt, 0, wm, wn, lane);                                \
+    }                                                                                      \
+    mfma16<NB>(acc, fy);                                                                   \
   } while (0)
 
+  Frags<NB> fx, fy;
   RRFP_ISSUE(stage0, 0);
   if (nk > 1) RRFP_ISSUE(stage1, 1);
   if (nk > 2) RRFP_ISSUE(stage2, 2);
-  if (nk > 2) __builtin_amdgcn_s_waitcnt(WAIT_VM16); else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+  if (nk > 3) RRFP_ISSUE(stage3, 3);
+  if (nk > 3) __builtin_amdgcn_s_waitcnt(VM_3); else __builtin_amdgcn_s_waitcnt(VM_ALL);
   stage_barrier();
+  load_frags<A_KC, B_KC, NB>(fx, stage0, 0, wm, wn, lane);
 
   int t = 0;
-  for (; t + 6 < nk; t += 4) {      // every step of this loop has a step t+3 to prefetch
-    RRFP_STEP_FULL(stage0, stage3, t);
-    RRFP_STEP_FULL(stage1, stage0, t + 1);
-    RRFP_STEP_FULL(stage2, stage1, t + 2);
-    RRFP_STEP_FULL(stage3, stage2, t + 3);
+  for (; t + 7 < nk; t += 4) {      // every step of this loop has a step t+4 to prefetch
+    RRFP_STEP_FULL(stage0, stage1, t);
+    RRFP_STEP_FULL(stage1, stage2, t + 1);
+    RRFP_STEP_FULL(stage2, stage3, t + 2);
+    RRFP_STEP_FULL(stage3, stage0, t + 3);
   }
-  // at most 6 steps remain
-  if (t < nk) RRFP_STEP_TAIL(stage0, stage3, t);
-  if (t + 1 < nk) RRFP_STEP_TAIL(stage1, stage0, t + 1);
-  if (t + 2 < nk) RRFP_STEP_TAIL(stage2, stage1, t + 2);
-  if (t + 3 < nk) RRFP_STEP_TAIL(stage3, stage2, t + 3);
-  if (t + 4 < nk) RRFP_STEP_TAIL(stage0, stage3, t + 4);
-  if (t + 5 < nk) RRFP_STEP_TAIL(stage1, stage0, t + 5);
+  // at most 7 steps remain
+  if (t < nk) RRFP_STEP_TAIL(stage0, stage1, t);
+  if (t + 1 < nk) RRFP_STEP_TAIL(stage1, stage2, t + 1);
+  if (t + 2 < nk) RRFP_STEP_TAIL(stage2, stage3, t + 2);
+  if (t + 3 < nk) RRFP_STEP_TAIL(stage3, stage0, t + 3);
+  if (t + 4 < nk) RRFP_STEP_TAIL(stage0, stage1, t + 4);
+  if (t + 5 < nk) RRFP_STEP_TAIL(stage1, stage2, t + 5);
+  if (t + 6 < nk) RRFP_STEP_TAIL(stage2, stage3, t + 6);
 #undef RRFP_STEP_FULL
 #undef RRFP_STEP_TAIL
 #undef RRFP_ISSUE
@@ -393,7 +426,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_dl_kernel(const bf16_t* __
     const int m = m0 + wm + i * 32 + (lane & 31);
     if (m >= M) continue;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NB; ++j) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int n = n0 + wn + j * 32 + g * 8 + (lane >> 5) * 4;
@@ -419,6 +452,16 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_dl_kernel(const bf16_t* __
   }
 }
 
+// Explicit instantiations of every variant the launcher can pick.
+#define RRFP_INST(AKC, BKC, TO, HR)                                                                          \
+  template __global__ void gemm_mfma_dl_kernel<AKC, BKC, TO, HR, dl_waves(AKC, BKC)>(const bf16_t*, const bf16_t*, TO*, \
+                                                                           const bf16_t*, int, int, int, int, int, int, int, int, int);
+#define RRFP_INST4(AKC, BKC) RRFP_INST(AKC, BKC, float, true) RRFP_INST(AKC, BKC, float, false) \
+                             RRFP_INST(AKC, BKC, bf16_t, true) RRFP_INST(AKC, BKC, bf16_t, false)
+RRFP_INST4(true, false) RRFP_INST4(true, true) RRFP_INST4(false, false) RRFP_INST4(false, true)
+#undef RRFP_INST4
+#undef RRFP_INST
+
 // True when the direct-to-LDS kernel can take the call (else the register-staged one does).
 inline bool direct_ok(const GemmArgs& g) {
   const bool a_kc = !g.transA, b_kc = g.transB;
@@ -431,20 +474,24 @@ inline bool direct_ok(const GemmArgs& g) {
 
 template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
 hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
-  auto kern_rs = gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>;
-  auto kern_dl = gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R>;
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  if (direct_ok(g)) {
+    hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_waves(A_KC, B_KC)>), dim3(tiles_m * tiles_n),
+                       dim3(dl_waves(A_KC, B_KC) * 64), 0,
+                       s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, (const bf16_t*)g.R, g.M, g.N, g.K, g.lda,
+                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n);
+    return hipGetLastError();
+  }
   static bool configured = false;   // per instantiation; the attribute is process-wide for the function
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern_rs, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const bool direct = direct_ok(g);
-  auto kern = direct ? kern_dl : kern_rs;
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(NTHREADS), direct ? 0 : SMEM_BYTES, s, (const bf16_t*)g.A,
-                     (const bf16_t*)g.B, (TO*)g.C, (const bf16_t*)g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, g.ldr,
-                     tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>), dim3(tiles_m * tiles_n), dim3(NTHREADS), SMEM_BYTES, s,
+                     (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, (const bf16_t*)g.R, g.M, g.N, g.K, g.lda, g.ldb,
+                     g.ldc, g.ldr, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
