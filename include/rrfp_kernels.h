@@ -23,11 +23,12 @@ enum { RRFP_GEMM_AUTO = 0, RRFP_GEMM_SIMT = 1, RRFP_GEMM_MFMA = 2 };
 /* C[M,N] = A(m,k) B(k,n) (+ R[M,N]) with fp32 accumulation.  All pointers are device pointers.
  * trans_a == 0: A is [M,K] row-major with leading dimension lda; 1: A is stored [K,M].
  * trans_b == 0: B is [K,N] row-major with leading dimension ldb; 1: B is stored [N,K].
- * in_dtype (STAGE_DTYPE_*) is the type of A, B and R (R may be NULL); out_dtype the type of C
- * (fp32 output with bf16 inputs is the weight-gradient form).  family picks the kernel:
+ * in_dtype (STAGE_DTYPE_*) is the type of A and B; out_dtype the type of C (fp32 output with bf16
+ * inputs is the weight-gradient form and the residual-stream form).  R, the residual, may be NULL and
+ * is ALWAYS fp32 [M,N] with leading dimension ldr: the stage keeps its residual stream in fp32.  family picks the kernel:
  * AUTO = what the stage tasks use for this shape; MFMA fails with STAGE_EINVAL when the shape
  * breaks its rules (bf16 inputs, 16-byte aligned pointers, leading dimensions and N multiples
- * of 8, K multiple of 8 if an operand is K-contiguous, M multiple of 8 if A is stored [K,M]). */
+ * of 8 (ldr of 4), K multiple of 8 if an operand is K-contiguous, M multiple of 8 if A is stored [K,M]). */
 int rrfp_gemm(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda,
               int ldb, int ldc, int ldr, int trans_a, int trans_b, int in_dtype, int out_dtype,
               int family, void* stream);

@@ -146,6 +146,29 @@ int stage_grad_reduce(stage_t* st, void* grad_out_dev /*device*/, void* stream);
  * the stream of W(mb) has passed it and until the slot's next F.  For tests and tools. */
 int stage_grad_slot(stage_t* st, int mb, void** slot_dev /*host*/);
 
+/* Intermediate tensors the tasks keep per microbatch and layer (for tests and tools: lets every
+ * kernel of a task be compared with the oracle's value of the same tensor). */
+enum {
+  STAGE_T_X = 0,      /* fp32 [T, hidden]   layer input (residual stream)           */
+  STAGE_T_H1 = 1,     /* storage [T, hidden] first RMSNorm output                   */
+  STAGE_T_QKV = 2,    /* storage [T, (n_q + 2 n_kv) d]                              */
+  STAGE_T_O = 3,      /* storage [T, n_q d]  attention output                       */
+  STAGE_T_X1 = 4,     /* fp32 [T, hidden]   x + o Wo                                */
+  STAGE_T_H2 = 5,     /* storage [T, hidden] second RMSNorm output                  */
+  STAGE_T_UP = 6,     /* storage [T, 2 ffn] (gate|up) or [T, ffn]                   */
+  STAGE_T_M = 7,      /* storage [T, ffn]   activation output                       */
+  STAGE_T_DY = 8,     /* storage [T, hidden] gradient w.r.t. the layer output       */
+  STAGE_T_DUP = 9,    /* storage, shape of STAGE_T_UP                               */
+  STAGE_T_DX1 = 10,   /* storage [T, hidden] gradient w.r.t. x1                     */
+  STAGE_T_DQKV = 11,  /* storage, shape of STAGE_T_QKV                              */
+  STAGE_T_LSE = 12,   /* fp32 [n_q, T]      log-sum-exp of the attention scores     */
+  STAGE_T_COUNT = 13
+};
+
+/* Device pointer of intermediate tensor `which` (STAGE_T_*) of `layer` for microbatch mb; valid to
+ * read after the task that writes it has completed and until the slot's next F. */
+int stage_intermediate(stage_t* st, int mb, int layer, int which, void** ptr_dev /*host*/);
+
 /* Destroys events and the handle.  The caller must have synchronised the streams used.  */
 int stage_destroy(stage_t* st);
 

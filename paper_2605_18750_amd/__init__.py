@@ -49,6 +49,8 @@ def lib() -> C.CDLL:
         L.stage_W.argtypes = [vp, C.c_int, vp]
         L.stage_grad_reduce.argtypes = [vp, vp, vp]
         L.stage_grad_slot.argtypes = [vp, C.c_int, C.POINTER(vp)]
+        L.stage_intermediate.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
+        L.stage_intermediate.restype = C.c_int
         L.stage_destroy.argtypes = [vp]
         L.stage_last_error.argtypes = [vp]
         L.stage_last_error.restype = C.c_char_p
@@ -135,6 +137,16 @@ def stage_grad_reduce(st, grad_out_dev, stream=None):
 def stage_grad_slot(st, mb: int) -> int:
     p = C.c_void_p()
     _check(lib().stage_grad_slot(st, mb, C.byref(p)), st)
+    return p.value
+
+
+(STAGE_T_X, STAGE_T_H1, STAGE_T_QKV, STAGE_T_O, STAGE_T_X1, STAGE_T_H2, STAGE_T_UP, STAGE_T_M, STAGE_T_DY,
+ STAGE_T_DUP, STAGE_T_DX1, STAGE_T_DQKV, STAGE_T_LSE, STAGE_T_COUNT) = range(14)
+
+
+def stage_intermediate(st, mb: int, layer: int, which: int) -> int:
+    p = C.c_void_p()
+    _check(lib().stage_intermediate(st, mb, layer, which, C.byref(p)), st)
     return p.value
 
 

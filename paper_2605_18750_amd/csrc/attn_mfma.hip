@@ -89,7 +89,8 @@ __device__ __forceinline__ void kv_store(const uint4 (&rk)[FwdCfg<D>::PER_THREAD
 
 template <int D>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
-                                                            float* __restrict__ lse, const AttnTile* __restrict__ tiles,
+                                                            float* __restrict__ o32, float* __restrict__ lse,
+                                                            const AttnTile* __restrict__ tiles,
                                                             int Tn, int nq, int nkv, int causal, float scale_log2e) {
   using C = FwdCfg<D>;
   constexpr int NDS = D / 16;        // contraction steps of Q K^T
@@ -241,10 +242,13 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
       for (int g = 0; g < 4; ++g) {
         const int dd = db * 32 + g * 8 + h * 4;
         if (dd >= D) continue;
+        const float v0 = oacc[db][ib][g * 4 + 0] * inv, v1 = oacc[db][ib][g * 4 + 1] * inv;
+        const float v2 = oacc[db][ib][g * 4 + 2] * inv, v3 = oacc[db][ib][g * 4 + 3] * inv;
         uint2 w;
-        w.x = pack_bf16x2(oacc[db][ib][g * 4 + 0] * inv, oacc[db][ib][g * 4 + 1] * inv);
-        w.y = pack_bf16x2(oacc[db][ib][g * 4 + 2] * inv, oacc[db][ib][g * 4 + 3] * inv);
+        w.x = pack_bf16x2(v0, v1);
+        w.y = pack_bf16x2(v2, v3);
         *reinterpret_cast<uint2*>(orow + dd) = w;
+        if (o32) *reinterpret_cast<float4*>(o32 + (size_t)i * nq * D + qcol + dd) = make_float4(v0, v1, v2, v3);
       }
   }
 }
@@ -319,15 +323,22 @@ __device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int pitch, int 
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
-                                                              float* __restrict__ delta, int Tn, int nq) {
+__global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __restrict__ o, const float* __restrict__ o32,
+                                                              const bf16_t* __restrict__ d_o, float* __restrict__ delta,
+                                                              int Tn, int nq) {
   // 16 lanes per (token, head) pair, 8 elements per lane.
   const int pair = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int c = threadIdx.x & 15;
   float s = 0.f;
   if (pair < Tn * nq && c < D / 8) {
     float x[8], y[8];
-    load_vec<bf16_t>(o + (size_t)pair * D + c * 8, x);
+    if (o32) {
+      const float4 a0 = *reinterpret_cast<const float4*>(o32 + (size_t)pair * D + c * 8);
+      const float4 a1 = *reinterpret_cast<const float4*>(o32 + (size_t)pair * D + c * 8 + 4);
+      x[0] = a0.x; x[1] = a0.y; x[2] = a0.z; x[3] = a0.w; x[4] = a1.x; x[5] = a1.y; x[6] = a1.z; x[7] = a1.w;
+    } else {
+      load_vec<bf16_t>(o + (size_t)pair * D + c * 8, x);
+    }
     load_vec<bf16_t>(d_o + (size_t)pair * D + c * 8, y);
 #pragma unroll
     for (int e = 0; e < 8; ++e) s += x[e] * y[e];
@@ -639,7 +650,7 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
   }
   const float scale = 1.0f / sqrtf((float)D);
   hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((a.T * a.nq + 15) / 16), dim3(256), 0, s, (const bf16_t*)a.o,
-                     (const bf16_t*)a.d_o, a.delta, a.T, a.nq);
+                     a.o32, (const bf16_t*)a.d_o, a.delta, a.T, a.nq);
   hipLaunchKernelGGL(kkv, dim3(a.nkv, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const bf16_t*)a.qkv,
                      (const bf16_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale);
   hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(256), DqCfg<D>::SMEM, s, (const bf16_t*)a.qkv, (const bf16_t*)a.d_o,
@@ -658,7 +669,7 @@ hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
     configured = true;
   }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(256), C::SMEM, s, (const bf16_t*)a.qkv, (bf16_t*)a.o, a.lse,
+  hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(256), C::SMEM, s, (const bf16_t*)a.qkv, (bf16_t*)a.o, a.o32, a.lse,
                      a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale_log2e);
   return hipGetLastError();
 }

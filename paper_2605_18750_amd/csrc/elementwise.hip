@@ -16,30 +16,58 @@ __device__ inline float wave_sum(float v) {
   return v;
 }
 
+// Vec<T>::N consecutive fp32 values (the residual stream is fp32 whatever the storage type).
+template <int V>
+__device__ inline void load_f32(const float* p, float* out) {
+#pragma unroll
+  for (int i = 0; i < V; i += 4) {
+    const float4 v = *reinterpret_cast<const float4*>(p + i);
+    out[i] = v.x; out[i + 1] = v.y; out[i + 2] = v.z; out[i + 3] = v.w;
+  }
+}
+template <int V>
+__device__ inline void store_f32(float* p, const float* in) {
+#pragma unroll
+  for (int i = 0; i < V; i += 4) *reinterpret_cast<float4*>(p + i) = make_float4(in[i], in[i + 1], in[i + 2], in[i + 3]);
+}
+
+// ---------------------------------------------------------------- storage type -> fp32 copy
+template <typename T>
+__global__ __launch_bounds__(256) void widen_kernel(const T* __restrict__ src, float* __restrict__ dst, size_t n) {
+  constexpr int V = Vec<T>::N;
+  const size_t nv = n / V;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
+    float v[V];
+    load_vec<T>(src + i * V, v);
+    store_f32<V>(dst + i * V, v);
+  }
+  for (size_t i = nv * V + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = to_float(src[i]);
+}
+
 // ---------------------------------------------------------------- RMSNorm forward
 // One wavefront per row; 4 rows per workgroup.  Two sweeps over the row (the second is
-// served by cache): sum of squares, then scale.
+// served by cache): sum of squares, then scale.  x is the fp32 residual stream.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ g,
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restrict__ x, const T* __restrict__ g,
                                                           T* __restrict__ h, float* __restrict__ r_out,
                                                           int Tn, int H, float eps) {
   constexpr int V = Vec<T>::N;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= Tn) return;
-  const T* xr = x + (size_t)row * H;
+  const float* xr = x + (size_t)row * H;
   T* hr = h + (size_t)row * H;
   float ss = 0.f;
   const bool vec = (H % V) == 0;
   if (vec) {
     for (int c = lane * V; c < H; c += WAVE * V) {
       float v[V];
-      load_vec<T>(xr + c, v);
+      load_f32<V>(xr + c, v);
 #pragma unroll
       for (int i = 0; i < V; ++i) ss += v[i] * v[i];
     }
   } else {
-    for (int c = lane; c < H; c += WAVE) { float v = to_float(xr[c]); ss += v * v; }
+    for (int c = lane; c < H; c += WAVE) { float v = xr[c]; ss += v * v; }
   }
   ss = wave_sum(ss);
   const float r = 1.0f / sqrtf(ss / (float)H + eps);
@@ -47,24 +75,26 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ 
   if (vec) {
     for (int c = lane * V; c < H; c += WAVE * V) {
       float v[V], gv[V];
-      load_vec<T>(xr + c, v);
+      load_f32<V>(xr + c, v);
       load_vec<T>(g + c, gv);
 #pragma unroll
       for (int i = 0; i < V; ++i) v[i] = v[i] * r * gv[i];
       store_vec<T>(hr + c, v);
     }
   } else {
-    for (int c = lane; c < H; c += WAVE) hr[c] = from_float<T>(to_float(xr[c]) * r * to_float(g[c]));
+    for (int c = lane; c < H; c += WAVE) hr[c] = from_float<T>(xr[c] * r * to_float(g[c]));
   }
 }
 
 // ---------------------------------------------------------------- RMSNorm backward, rows
 // dx = add_in + r * (w - xhat * mean(w * xhat)),  w = dh * g,  xhat = x * r.
+// dh (a GEMM output consumed only here), x and add_in (residual stream) are fp32.  dx goes to out32 (fp32, next link of the residual-gradient
+// chain) and/or out_t (storage type: GEMM operand, or the task's dx output); either may be null.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_bwd_rows_kernel(const T* __restrict__ dh, const T* __restrict__ x,
+__global__ __launch_bounds__(256) void rmsnorm_bwd_rows_kernel(const float* __restrict__ dh, const float* __restrict__ x,
                                                                const float* __restrict__ r, const T* __restrict__ g,
-                                                               const T* __restrict__ add_in, T* __restrict__ dx,
-                                                               int Tn, int H) {
+                                                               const float* __restrict__ add_in, float* __restrict__ out32,
+                                                               T* __restrict__ out_t, int Tn, int H) {
   constexpr int V = Vec<T>::N;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
@@ -76,31 +106,34 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_rows_kernel(const T* __restri
   if (vec) {
     for (int c = lane * V; c < H; c += WAVE * V) {
       float a[V], b[V], gv[V];
-      load_vec<T>(dh + off + c, a);
-      load_vec<T>(x + off + c, b);
+      load_f32<V>(dh + off + c, a);
+      load_f32<V>(x + off + c, b);
       load_vec<T>(g + c, gv);
 #pragma unroll
       for (int i = 0; i < V; ++i) dot += a[i] * gv[i] * (b[i] * rr);
     }
   } else {
-    for (int c = lane; c < H; c += WAVE) dot += to_float(dh[off + c]) * to_float(g[c]) * (to_float(x[off + c]) * rr);
+    for (int c = lane; c < H; c += WAVE) dot += dh[off + c] * to_float(g[c]) * (x[off + c] * rr);
   }
   dot = wave_sum(dot) / (float)H;
   if (vec) {
     for (int c = lane * V; c < H; c += WAVE * V) {
       float a[V], b[V], gv[V], ad[V];
-      load_vec<T>(dh + off + c, a);
-      load_vec<T>(x + off + c, b);
+      load_f32<V>(dh + off + c, a);
+      load_f32<V>(x + off + c, b);
       load_vec<T>(g + c, gv);
-      load_vec<T>(add_in + off + c, ad);
+      load_f32<V>(add_in + off + c, ad);
 #pragma unroll
       for (int i = 0; i < V; ++i) a[i] = ad[i] + rr * (a[i] * gv[i] - (b[i] * rr) * dot);
-      store_vec<T>(dx + off + c, a);
+      if (out32) store_f32<V>(out32 + off + c, a);
+      if (out_t) store_vec<T>(out_t + off + c, a);
     }
   } else {
     for (int c = lane; c < H; c += WAVE) {
-      float w = to_float(dh[off + c]) * to_float(g[c]);
-      dx[off + c] = from_float<T>(to_float(add_in[off + c]) + rr * (w - (to_float(x[off + c]) * rr) * dot));
+      const float w = dh[off + c] * to_float(g[c]);
+      const float v = add_in[off + c] + rr * (w - (x[off + c] * rr) * dot);
+      if (out32) out32[off + c] = v;
+      if (out_t) out_t[off + c] = from_float<T>(v);
     }
   }
 }
@@ -108,7 +141,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_rows_kernel(const T* __restri
 // ---------------------------------------------------------------- RMSNorm backward, gain partials
 // partial[chunk][c] = sum over the chunk's rows (ascending) of dh[t][c] * x[t][c] * r[t].
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_bwd_gain_kernel(const T* __restrict__ dh, const T* __restrict__ x,
+__global__ __launch_bounds__(256) void rmsnorm_bwd_gain_kernel(const float* __restrict__ dh, const float* __restrict__ x,
                                                                const float* __restrict__ r, float* __restrict__ partial,
                                                                int Tn, int H) {
   const int c = blockIdx.x * 256 + threadIdx.x;
@@ -117,7 +150,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_gain_kernel(const T* __restri
   const int t0 = chunk * NORM_BWD_ROWS;
   const int t1 = min(t0 + NORM_BWD_ROWS, Tn);
   float acc = 0.f;
-  for (int t = t0; t < t1; ++t) acc += to_float(dh[(size_t)t * H + c]) * (to_float(x[(size_t)t * H + c]) * r[t]);
+  for (int t = t0; t < t1; ++t) acc += dh[(size_t)t * H + c] * (x[(size_t)t * H + c] * r[t]);
   partial[(size_t)chunk * H + c] = acc;
 }
 
@@ -151,7 +184,7 @@ __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T* __restrict__ g
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ dm, const T* __restrict__ gu,
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const float* __restrict__ dm, const T* __restrict__ gu,
                                                          T* __restrict__ dgu, int Tn, int F) {
   constexpr int V = Vec<T>::N;
   const int fv = F / V;
@@ -162,7 +195,7 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ d
     float a[V], b[V], d[V], da[V], db[V];
     load_vec<T>(gu + t * 2 * F + f, a);
     load_vec<T>(gu + t * 2 * F + F + f, b);
-    load_vec<T>(dm + t * F + f, d);
+    load_f32<V>(dm + t * F + f, d);
 #pragma unroll
     for (int k = 0; k < V; ++k) {
       const float sg = sigmoidf_(a[k]);
@@ -187,13 +220,13 @@ __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T* __restrict__ u, 
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* __restrict__ dm, const T* __restrict__ u,
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(const float* __restrict__ dm, const T* __restrict__ u,
                                                        T* __restrict__ du, size_t nv) {
   constexpr int V = Vec<T>::N;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
     float a[V], d[V];
     load_vec<T>(u + i * V, a);
-    load_vec<T>(dm + i * V, d);
+    load_f32<V>(dm + i * V, d);
 #pragma unroll
     for (int k = 0; k < V; ++k) {
       const float Phi = 0.5f * (1.0f + erff(a[k] * 0.70710678118654752f));
@@ -228,21 +261,26 @@ inline int grid_for(size_t n, int cap = 256 * 32) {
   if ((dtype) == F32) { using T = float; __VA_ARGS__; } \
   else { using T = bf16_t; __VA_ARGS__; }
 
-hipError_t launch_rmsnorm_fwd(const void* x, const void* g, void* h, float* r_out, int Tn, int H, float eps,
-                              int dtype, hipStream_t s) {
-  DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_fwd_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, (const T*)x,
-                                       (const T*)g, (T*)h, r_out, Tn, H, eps));
+hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, hipLaunchKernelGGL(widen_kernel<T>, dim3(grid_for(n / Vec<T>::N + 1)), dim3(256), 0, s, (const T*)src, dst, n));
   return hipGetLastError();
 }
 
-hipError_t launch_rmsnorm_bwd(const void* dh, const void* x, const float* r, const void* g, const void* add_in,
-                              void* dx, float* dg_partial, int Tn, int H, int dtype, hipStream_t s) {
+hipError_t launch_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_out, int Tn, int H, float eps,
+                              int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_fwd_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, x, (const T*)g, (T*)h,
+                                       r_out, Tn, H, eps));
+  return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_bwd(const float* dh, const float* x, const float* r, const void* g, const float* add_in,
+                              float* out32, void* out_t, float* dg_partial, int Tn, int H, int dtype, hipStream_t s) {
   const int chunks = (Tn + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS;
   DISPATCH_T(dtype, {
-    hipLaunchKernelGGL(rmsnorm_bwd_gain_kernel<T>, dim3((H + 255) / 256, chunks), dim3(256), 0, s, (const T*)dh,
-                       (const T*)x, r, dg_partial, Tn, H);
-    hipLaunchKernelGGL(rmsnorm_bwd_rows_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, (const T*)dh, (const T*)x, r,
-                       (const T*)g, (const T*)add_in, (T*)dx, Tn, H);
+    hipLaunchKernelGGL(rmsnorm_bwd_gain_kernel<T>, dim3((H + 255) / 256, chunks), dim3(256), 0, s, dh, x, r,
+                       dg_partial, Tn, H);
+    hipLaunchKernelGGL(rmsnorm_bwd_rows_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, dh, x, r, (const T*)g,
+                       add_in, out32, (T*)out_t, Tn, H);
   });
   return hipGetLastError();
 }
@@ -261,10 +299,10 @@ hipError_t launch_swiglu_fwd(const void* gu, void* m, int Tn, int F, int dtype, 
   return hipGetLastError();
 }
 
-hipError_t launch_swiglu_bwd(const void* dm, const void* gu, void* dgu, int Tn, int F, int dtype, hipStream_t s) {
+hipError_t launch_swiglu_bwd(const float* dm, const void* gu, void* dgu, int Tn, int F, int dtype, hipStream_t s) {
   DISPATCH_T(dtype, {
     if (F % Vec<T>::N) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(swiglu_bwd_kernel<T>, dim3(grid_for((size_t)Tn * F / Vec<T>::N)), dim3(256), 0, s, (const T*)dm,
+    hipLaunchKernelGGL(swiglu_bwd_kernel<T>, dim3(grid_for((size_t)Tn * F / Vec<T>::N)), dim3(256), 0, s, dm,
                        (const T*)gu, (T*)dgu, Tn, F);
   });
   return hipGetLastError();
@@ -279,11 +317,11 @@ hipError_t launch_gelu_fwd(const void* u, void* m, int Tn, int F, int dtype, hip
   return hipGetLastError();
 }
 
-hipError_t launch_gelu_bwd(const void* dm, const void* u, void* du, int Tn, int F, int dtype, hipStream_t s) {
+hipError_t launch_gelu_bwd(const float* dm, const void* u, void* du, int Tn, int F, int dtype, hipStream_t s) {
   DISPATCH_T(dtype, {
     if (F % Vec<T>::N) return hipErrorInvalidValue;
     const size_t nv = (size_t)Tn * F / Vec<T>::N;
-    hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for(nv)), dim3(256), 0, s, (const T*)dm, (const T*)u, (T*)du, nv);
+    hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for(nv)), dim3(256), 0, s, dm, (const T*)u, (T*)du, nv);
   });
   return hipGetLastError();
 }

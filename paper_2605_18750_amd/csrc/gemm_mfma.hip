@@ -116,7 +116,7 @@ __device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, i
 
 template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
 __global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
-                                                             TO* __restrict__ C, const bf16_t* __restrict__ R, int M,
+                                                             TO* __restrict__ C, const float* __restrict__ R, int M,
                                                              int N, int K, int lda, int ldb, int ldc, int ldr,
                                                              int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -186,9 +186,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __res
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e];
         if (HAS_R) {
-          const uint2 rr = *reinterpret_cast<const uint2*>(R + (size_t)m * ldr + n);
-          v[0] += __uint_as_float(rr.x << 16); v[1] += __uint_as_float(rr.x & 0xffff0000u);
-          v[2] += __uint_as_float(rr.y << 16); v[3] += __uint_as_float(rr.y & 0xffff0000u);
+          const float4 rr = *reinterpret_cast<const float4*>(R + (size_t)m * ldr + n);
+          v[0] += rr.x; v[1] += rr.y; v[2] += rr.z; v[3] += rr.w;
         }
         if (sizeof(TO) == 4) {
           *reinterpret_cast<float4*>((float*)C + (size_t)m * ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
@@ -323,7 +322,7 @@ __device__ __forceinline__ void interleave_ds_mfma() {
 
 template <bool A_KC, bool B_KC, typename TO, bool HAS_R, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
-                                                               TO* __restrict__ C, const bf16_t* __restrict__ R, int M,
+                                                               TO* __restrict__ C, const float* __restrict__ R, int M,
                                                                int N, int K, int lda, int ldb, int ldc, int ldr,
                                                                int tiles_m, int tiles_n) {
   constexpr int NB = 16 / NW;                       // 32-wide column blocks per wavefront: 4 or 2
@@ -435,9 +434,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __r
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e];
         if (HAS_R) {
-          const uint2 rr = *reinterpret_cast<const uint2*>(R + (size_t)m * ldr + n);
-          v[0] += __uint_as_float(rr.x << 16); v[1] += __uint_as_float(rr.x & 0xffff0000u);
-          v[2] += __uint_as_float(rr.y << 16); v[3] += __uint_as_float(rr.y & 0xffff0000u);
+          const float4 rr = *reinterpret_cast<const float4*>(R + (size_t)m * ldr + n);
+          v[0] += rr.x; v[1] += rr.y; v[2] += rr.z; v[3] += rr.w;
         }
         if (sizeof(TO) == 4) {
           *reinterpret_cast<float4*>((float*)C + (size_t)m * ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
@@ -455,7 +453,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __r
 // Explicit instantiations of every variant the launcher can pick.
 #define RRFP_INST(AKC, BKC, TO, HR)                                                                          \
   template __global__ void gemm_mfma_dl_kernel<AKC, BKC, TO, HR, dl_waves(AKC, BKC)>(const bf16_t*, const bf16_t*, TO*, \
-                                                                           const bf16_t*, int, int, int, int, int, int, int, int, int);
+                                                                           const float*, int, int, int, int, int, int, int, int, int);
 #define RRFP_INST4(AKC, BKC) RRFP_INST(AKC, BKC, float, true) RRFP_INST(AKC, BKC, float, false) \
                              RRFP_INST(AKC, BKC, bf16_t, true) RRFP_INST(AKC, BKC, bf16_t, false)
 RRFP_INST4(true, false) RRFP_INST4(true, true) RRFP_INST4(false, false) RRFP_INST4(false, true)
@@ -478,7 +476,7 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
   if (direct_ok(g)) {
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_waves(A_KC, B_KC)>), dim3(tiles_m * tiles_n),
                        dim3(dl_waves(A_KC, B_KC) * 64), 0,
-                       s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, (const bf16_t*)g.R, g.M, g.N, g.K, g.lda,
+                       s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda,
                        g.ldb, g.ldc, g.ldr, tiles_m, tiles_n);
     return hipGetLastError();
   }
@@ -490,7 +488,7 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
     configured = true;
   }
   hipLaunchKernelGGL((gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>), dim3(tiles_m * tiles_n), dim3(NTHREADS), SMEM_BYTES, s,
-                     (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, (const bf16_t*)g.R, g.M, g.N, g.K, g.lda, g.ldb,
+                     (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb,
                      g.ldc, g.ldr, tiles_m, tiles_n);
   return hipGetLastError();
 }
@@ -507,13 +505,13 @@ bool gemm_mfma_supports(const GemmArgs& g) {
   if (g.in_dtype != BF16) return false;
   if (g.M < 1 || g.N < 1 || g.K < 1) return false;
   if ((g.lda | g.ldb | g.ldc) & 7) return false;
-  if (g.R && (g.ldr & 7)) return false;
+  if (g.R && ((g.ldr & 3) || ((uintptr_t)g.R & 15))) return false;
   if (g.N & 7) return false;
   const bool a_kc = !g.transA, b_kc = g.transB;
   if ((a_kc || b_kc) && (g.K & 7)) return false;      // K-contiguous chunks must be whole
   if (!a_kc && (g.M & 7)) return false;               // K-strided A: rows of C come in chunks of 8
   auto aligned = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
-  return aligned(g.A) && aligned(g.B) && aligned(g.C) && (!g.R || aligned(g.R));
+  return aligned(g.A) && aligned(g.B) && aligned(g.C);
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {

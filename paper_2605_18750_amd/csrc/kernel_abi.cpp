@@ -14,7 +14,7 @@ extern "C" int rrfp_gemm(const void* A, const void* B, void* C, const void* R, i
   if (out_dtype != F32 && !(out_dtype == BF16 && in_dtype == BF16)) return STAGE_EINVAL;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N || (R && ldr < N)) return STAGE_EINVAL;
   GemmArgs g{};
-  g.A = A; g.B = B; g.C = C; g.R = R; g.M = M; g.N = N; g.K = K;
+  g.A = A; g.B = B; g.C = C; g.R = (const float*)R; g.M = M; g.N = N; g.K = K;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ldr = ldr;
   g.transA = trans_a != 0; g.transB = trans_b != 0; g.in_dtype = in_dtype; g.out_dtype = out_dtype;
   hipError_t e;

@@ -10,12 +10,14 @@ enum DType : int { F32 = 0, BF16 = 1 };
 
 static inline size_t dtype_size(int dt) { return dt == F32 ? 4 : 2; }
 
-// C[M,N] = A(m,k) * B(k,n) (+ R[M,N]), fp32 accumulation.
+// C[M,N] = A(m,k) * B(k,n) (+ R[M,N]), fp32 accumulation.  R, when present, is always fp32 (the
+// residual stream is kept in fp32 between layers whatever the storage type).
 //   transA == false: A stored [M,K] (lda), true: stored [K,M] (lda).
 //   transB == false: B stored [K,N] (ldb), true: stored [N,K] (ldb).
-// in_dtype is the type of A, B and R; out_dtype the type of C (F32 for weight gradients).
+// in_dtype is the type of A and B; out_dtype the type of C (F32 for weight gradients and for the
+// residual stream).
 struct GemmArgs {
-  const void* A; const void* B; void* C; const void* R;
+  const void* A; const void* B; void* C; const float* R;
   int M, N, K;
   int lda, ldb, ldc, ldr;
   bool transA, transB;
@@ -35,6 +37,8 @@ constexpr int ATTN_TILE_KV = 128;  // rows per key tile (dK/dV kernel)
 struct AttnArgs {
   const void* qkv;      // [T, (nq + 2 nkv) d]: Q heads, K heads, V heads
   void* o;              // [T, nq d]
+  float* o32;           // [T, nq d] fp32 copy of o before rounding (bf16 MFMA path; else null): the
+                        // backward forms delta from it so that rounding o does not break sum_j dS_ij = 0
   float* lse;           // [nq, T]   log-sum-exp of the scaled, masked scores (natural log)
   const AttnTile* q_tiles; int n_q_tiles;     // device pointers to the tile lists
   const AttnTile* kv_tiles; int n_kv_tiles;
@@ -52,26 +56,31 @@ hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s);
 bool attn_mfma_supports(const AttnArgs& a);
 
-// h = x * r * g, r = rsqrt(mean(x^2) + eps); r_out [T] fp32.
-hipError_t launch_rmsnorm_fwd(const void* x, const void* g, void* h, float* r_out,
+// dst[i] = (float)src[i]: storage type -> fp32 (entry of the residual stream).
+hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s);
+
+// h = x * r * g, r = rsqrt(mean(x^2) + eps); x fp32, r_out [T] fp32, g and h storage type.
+hipError_t launch_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_out,
                               int T, int H, float eps, int dtype, hipStream_t s);
 
 constexpr int NORM_BWD_ROWS = 64;  // rows per partial of the gain-gradient column sum
-// dx = add_in + r * (w - xhat * mean(w * xhat)), w = dh * g, xhat = x * r.
+// dx = add_in + r * (w - xhat * mean(w * xhat)), w = dh * g, xhat = x * r; dh, x and add_in fp32.
+// dx is written to out32 (fp32) and/or out_t (storage type); either may be null.
 // dg_partial [ceil(T / NORM_BWD_ROWS), H] fp32 receives per-row-chunk sums of dh * xhat;
 // launch_colsum then adds the partials in chunk order into dg [H].
-hipError_t launch_rmsnorm_bwd(const void* dh, const void* x, const float* r, const void* g,
-                              const void* add_in, void* dx, float* dg_partial,
+hipError_t launch_rmsnorm_bwd(const float* dh, const float* x, const float* r, const void* g,
+                              const float* add_in, float* out32, void* out_t, float* dg_partial,
                               int T, int H, int dtype, hipStream_t s);
 hipError_t launch_colsum(const float* partial, int n_partial, int H, float* out, hipStream_t s);
 
 // SwiGLU on gu [T, 2F] (gate columns then up columns): m = silu(gate) * up.
 hipError_t launch_swiglu_fwd(const void* gu, void* m, int T, int F, int dtype, hipStream_t s);
-hipError_t launch_swiglu_bwd(const void* dm, const void* gu, void* dgu, int T, int F, int dtype,
+// dm is fp32 (a GEMM output consumed only by the activation backward).
+hipError_t launch_swiglu_bwd(const float* dm, const void* gu, void* dgu, int T, int F, int dtype,
                              hipStream_t s);
 // GELU (erf form) on u [T, F].
 hipError_t launch_gelu_fwd(const void* u, void* m, int T, int F, int dtype, hipStream_t s);
-hipError_t launch_gelu_bwd(const void* dm, const void* u, void* du, int T, int F, int dtype,
+hipError_t launch_gelu_bwd(const float* dm, const void* u, void* du, int T, int F, int dtype,
                            hipStream_t s);
 
 // out[i] = ((slot_0[i] + slot_1[i]) + ...) + slot_{M-1}[i], slots spaced slot_stride floats apart.

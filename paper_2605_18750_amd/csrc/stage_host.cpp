@@ -29,9 +29,14 @@ void set_tls_error(const char* fmt, ...) {
 constexpr size_t ALIGN = 256;
 size_t align_up(size_t v, size_t a = ALIGN) { return (v + a - 1) / a * a; }
 
-struct LayerStash {       // byte offsets inside one microbatch region
-  size_t x, r1, h1, qkv, lse, o, x1, r2, h2, up, m;   // written by F
-  size_t dy, dup, dx1, dqkv;                          // written by B, read by W
+// Byte offsets inside one microbatch region.  The residual stream (x, x1 and the gradients dy, dx1
+// that flow along it) is kept in fp32 between layers; GEMM operands are in the storage type, so the
+// two residual gradients exist twice: fp32 for the chain, storage type for the GEMMs and for W.
+struct LayerStash {
+  size_t x, r1, h1, qkv, lse, o, x1, r2, h2, up, m;   // written by F (x and x1 fp32)
+  size_t dy, dup, dx1, dqkv;                          // written by B, read by W (storage type)
+  size_t dy32, dx1_32;                                // written by B, fp32 residual-gradient chain
+  size_t o32;                                         // written by F: attention output before rounding (bf16 path)
 };
 
 struct Plan {
@@ -106,15 +111,17 @@ int make_plan(const stage_config* c, Plan* p) {
   const size_t e = p->esz;
   p->layer.resize(c->n_layers);
   for (auto& s : p->layer) {
-    s.x = take(T * H * e);   s.r1 = take(T * 4);        s.h1 = take(T * H * e);
+    s.x = take(T * H * 4);   s.r1 = take(T * 4);        s.h1 = take(T * H * e);
     s.qkv = take(T * p->n_qkv * e);  s.lse = take(nq * T * 4);  s.o = take(T * nq * d * e);
-    s.x1 = take(T * H * e);  s.r2 = take(T * 4);        s.h2 = take(T * H * e);
+    s.x1 = take(T * H * 4);  s.r2 = take(T * 4);        s.h2 = take(T * H * e);
     s.up = take(T * p->n_up * e);    s.m = take(T * F * e);
     s.dy = take(T * H * e);  s.dup = take(T * p->n_up * e);
     s.dx1 = take(T * H * e); s.dqkv = take(T * p->n_qkv * e);
+    s.dy32 = take(T * H * 4); s.dx1_32 = take(T * H * 4);
+    s.o32 = c->dtype == STAGE_DTYPE_BF16 ? take(T * nq * d * 4) : 0;
   }
-  p->t_dm = take(T * F * e);
-  p->t_dh = take(T * H * e);
+  p->t_dm = take(T * F * 4);     // fp32: GEMM outputs that only an elementwise kernel consumes are not rounded
+  p->t_dh = take(T * H * 4);
   p->t_do = take(T * nq * d * e);
   p->t_delta = take(nq * T * 4);
   p->t_dgp = take(((T + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS) * H * 4);
@@ -305,6 +312,19 @@ int stage_grad_slot(stage_t* st, int mb, void** slot_dev) {
   return STAGE_OK;
 }
 
+int stage_intermediate(stage_t* st, int mb, int layer, int which, void** ptr_dev) {
+  int rc = check_handle_mb(st, mb);
+  if (rc) return rc;
+  if (!ptr_dev || layer < 0 || layer >= st->plan.c.n_layers || which < 0 || which >= STAGE_T_COUNT) {
+    set_error(st, "stage_intermediate: bad layer %d / tensor %d / NULL output", layer, which);
+    return STAGE_EINVAL;
+  }
+  const LayerStash& L = st->plan.layer[layer];
+  const size_t off[STAGE_T_COUNT] = {L.x, L.h1, L.qkv, L.o, L.x1, L.h2, L.up, L.m, L.dy, L.dup, L.dx1, L.dqkv, L.lse};
+  *ptr_dev = st->dry ? nullptr : (void*)(mb_base(st, mb) + off[which]);
+  return STAGE_OK;
+}
+
 int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg, void* y_dev, void* stream) {
   int rc = check_handle_mb(st, mb);
   if (rc) return rc;
@@ -343,12 +363,12 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
   m.copy_pending = true;
 
   const int H = c.hidden, F = c.ffn, dt = c.dtype, nqd = c.n_q_heads * c.head_dim;
-  const size_t e = P.esz;
-  HIP_TRY(st, hipMemcpyAsync(base + P.layer[0].x, x_dev, (size_t)T * H * e, hipMemcpyDeviceToDevice, s));
+  HIP_TRY(st, launch_widen(x_dev, (float*)(base + P.layer[0].x), (size_t)T * H, dt, s));
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerStash& L = P.layer[l];
-    void* y_out = (l == c.n_layers - 1) ? y_dev : (void*)(base + P.layer[l + 1].x);
-    HIP_TRY(st, launch_rmsnorm_fwd(base + L.x, param_ptr(st, l, STAGE_P_G1), base + L.h1, (float*)(base + L.r1), T, H, c.norm_eps, dt, s));
+    const bool last = l == c.n_layers - 1;
+    void* y_out = last ? y_dev : (void*)(base + P.layer[l + 1].x);
+    HIP_TRY(st, launch_rmsnorm_fwd((const float*)(base + L.x), param_ptr(st, l, STAGE_P_G1), base + L.h1, (float*)(base + L.r1), T, H, c.norm_eps, dt, s));
     GemmArgs g{};
     g.in_dtype = dt; g.out_dtype = dt; g.transA = false; g.transB = false; g.M = T;
     g.A = base + L.h1; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WQKV); g.ldb = P.n_qkv;
@@ -356,22 +376,27 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     HIP_TRY(st, launch_gemm(g, s));
     AttnArgs a{};
     a.qkv = base + L.qkv; a.o = base + L.o; a.lse = (float*)(base + L.lse);
+    a.o32 = dt == BF16 ? (float*)(base + L.o32) : nullptr;
     a.q_tiles = (const AttnTile*)(base + P.t_qtiles); a.n_q_tiles = m.n_q_tiles;
     a.kv_tiles = (const AttnTile*)(base + P.t_kvtiles); a.n_kv_tiles = m.n_kv_tiles;
     a.T = T; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.d = c.head_dim; a.causal = c.causal; a.dtype = dt;
     HIP_TRY(st, launch_attn_fwd(a, s));
     g.A = base + L.o; g.lda = nqd; g.B = param_ptr(st, l, STAGE_P_WO); g.ldb = H;
-    g.C = base + L.x1; g.ldc = H; g.R = base + L.x; g.ldr = H; g.N = H; g.K = nqd;
+    g.C = base + L.x1; g.ldc = H; g.R = (const float*)(base + L.x); g.ldr = H; g.N = H; g.K = nqd;
+    g.out_dtype = F32;                       // x1 stays in the fp32 residual stream
     HIP_TRY(st, launch_gemm(g, s));
-    HIP_TRY(st, launch_rmsnorm_fwd(base + L.x1, param_ptr(st, l, STAGE_P_G2), base + L.h2, (float*)(base + L.r2), T, H, c.norm_eps, dt, s));
+    g.out_dtype = dt;
+    HIP_TRY(st, launch_rmsnorm_fwd((const float*)(base + L.x1), param_ptr(st, l, STAGE_P_G2), base + L.h2, (float*)(base + L.r2), T, H, c.norm_eps, dt, s));
     g.A = base + L.h2; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WUP); g.ldb = P.n_up;
     g.C = base + L.up; g.ldc = P.n_up; g.R = nullptr; g.N = P.n_up; g.K = H;
     HIP_TRY(st, launch_gemm(g, s));
     if (c.mlp_kind == STAGE_MLP_SWIGLU) HIP_TRY(st, launch_swiglu_fwd(base + L.up, base + L.m, T, F, dt, s));
     else HIP_TRY(st, launch_gelu_fwd(base + L.up, base + L.m, T, F, dt, s));
     g.A = base + L.m; g.lda = F; g.B = param_ptr(st, l, STAGE_P_WD); g.ldb = H;
-    g.C = y_out; g.ldc = H; g.R = base + L.x1; g.ldr = H; g.N = H; g.K = F;
+    g.C = y_out; g.ldc = H; g.R = (const float*)(base + L.x1); g.ldr = H; g.N = H; g.K = F;
+    g.out_dtype = last ? dt : (int)F32;      // the stage output is rounded once; between layers fp32
     HIP_TRY(st, launch_gemm(g, s));
+    g.out_dtype = dt;
   }
   HIP_TRY(st, hipEventRecord(m.ev_F, s));
   m.state = MB_F;
@@ -398,30 +423,33 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
   const size_t e = P.esz;
   const int n_part = (T + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS;
   HIP_TRY(st, hipMemcpyAsync(base + P.layer[c.n_layers - 1].dy, dy_dev, (size_t)T * H * e, hipMemcpyDeviceToDevice, s));
+  HIP_TRY(st, launch_widen(dy_dev, (float*)(base + P.layer[c.n_layers - 1].dy32), (size_t)T * H, dt, s));
   for (int l = c.n_layers - 1; l >= 0; --l) {
     const LayerStash& L = P.layer[l];
     void* dx_out = (l == 0) ? dx_dev : (void*)(base + P.layer[l - 1].dy);
+    float* dx_out32 = (l == 0) ? nullptr : (float*)(base + P.layer[l - 1].dy32);
     GemmArgs g{};
     g.in_dtype = dt; g.out_dtype = dt; g.transA = false; g.transB = true; g.M = T; g.R = nullptr;
     // dm = dy Wd^T
     g.A = base + L.dy; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WD); g.ldb = H;
-    g.C = base + P.t_dm; g.ldc = F; g.N = F; g.K = H;
+    g.C = base + P.t_dm; g.ldc = F; g.N = F; g.K = H; g.out_dtype = F32;
     HIP_TRY(st, launch_gemm(g, s));
-    if (c.mlp_kind == STAGE_MLP_SWIGLU) HIP_TRY(st, launch_swiglu_bwd(base + P.t_dm, base + L.up, base + L.dup, T, F, dt, s));
-    else HIP_TRY(st, launch_gelu_bwd(base + P.t_dm, base + L.up, base + L.dup, T, F, dt, s));
+    if (c.mlp_kind == STAGE_MLP_SWIGLU) HIP_TRY(st, launch_swiglu_bwd((const float*)(base + P.t_dm), base + L.up, base + L.dup, T, F, dt, s));
+    else HIP_TRY(st, launch_gelu_bwd((const float*)(base + P.t_dm), base + L.up, base + L.dup, T, F, dt, s));
     // dh2 = [dgate|dup] Wup^T
     g.A = base + L.dup; g.lda = P.n_up; g.B = param_ptr(st, l, STAGE_P_WUP); g.ldb = P.n_up;
-    g.C = base + P.t_dh; g.ldc = H; g.N = H; g.K = P.n_up;
+    g.C = base + P.t_dh; g.ldc = H; g.N = H; g.K = P.n_up; g.out_dtype = F32;
     HIP_TRY(st, launch_gemm(g, s));
-    HIP_TRY(st, launch_rmsnorm_bwd(base + P.t_dh, base + L.x1, (const float*)(base + L.r2), param_ptr(st, l, STAGE_P_G2),
-                                   base + L.dy, base + L.dx1, (float*)(base + P.t_dgp), T, H, dt, s));
+    HIP_TRY(st, launch_rmsnorm_bwd((const float*)(base + P.t_dh), (const float*)(base + L.x1), (const float*)(base + L.r2), param_ptr(st, l, STAGE_P_G2),
+                                   (const float*)(base + L.dy32), (float*)(base + L.dx1_32), base + L.dx1, (float*)(base + P.t_dgp), T, H, dt, s));
     HIP_TRY(st, launch_colsum((const float*)(base + P.t_dgp), n_part, H, slot + P.p_off[l][STAGE_P_G2], s));
     // do = dx1 Wo^T
     g.A = base + L.dx1; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WO); g.ldb = H;
-    g.C = base + P.t_do; g.ldc = nqd; g.N = nqd; g.K = H;
+    g.C = base + P.t_do; g.ldc = nqd; g.N = nqd; g.K = H; g.out_dtype = dt;
     HIP_TRY(st, launch_gemm(g, s));
     AttnArgs a{};
     a.qkv = base + L.qkv; a.o = base + L.o; a.lse = (float*)(base + L.lse);
+    a.o32 = dt == BF16 ? (float*)(base + L.o32) : nullptr;
     a.q_tiles = (const AttnTile*)(base + P.t_qtiles); a.n_q_tiles = m.n_q_tiles;
     a.kv_tiles = (const AttnTile*)(base + P.t_kvtiles); a.n_kv_tiles = m.n_kv_tiles;
     a.T = T; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.d = c.head_dim; a.causal = c.causal; a.dtype = dt;
@@ -429,10 +457,10 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     HIP_TRY(st, launch_attn_bwd(a, s));
     // dh1 = [dq|dk|dv] Wqkv^T
     g.A = base + L.dqkv; g.lda = P.n_qkv; g.B = param_ptr(st, l, STAGE_P_WQKV); g.ldb = P.n_qkv;
-    g.C = base + P.t_dh; g.ldc = H; g.N = H; g.K = P.n_qkv;
+    g.C = base + P.t_dh; g.ldc = H; g.N = H; g.K = P.n_qkv; g.out_dtype = F32;
     HIP_TRY(st, launch_gemm(g, s));
-    HIP_TRY(st, launch_rmsnorm_bwd(base + P.t_dh, base + L.x, (const float*)(base + L.r1), param_ptr(st, l, STAGE_P_G1),
-                                   base + L.dx1, dx_out, (float*)(base + P.t_dgp), T, H, dt, s));
+    HIP_TRY(st, launch_rmsnorm_bwd((const float*)(base + P.t_dh), (const float*)(base + L.x), (const float*)(base + L.r1), param_ptr(st, l, STAGE_P_G1),
+                                   (const float*)(base + L.dx1_32), dx_out32, dx_out, (float*)(base + P.t_dgp), T, H, dt, s));
     HIP_TRY(st, launch_colsum((const float*)(base + P.t_dgp), n_part, H, slot + P.p_off[l][STAGE_P_G1], s));
   }
   HIP_TRY(st, hipEventRecord(m.ev_B, s));

@@ -30,7 +30,21 @@ class Workload:
         self.shape = shape
         self.cus = [np.asarray(c, dtype=np.int32) for c in cus]
         self.M = len(cus)
-        self.layers = SI.make_stage_params(shape, seed)
+        if shape.hidden >= 1024:     # big stages: generate the tensors on a thread pool (numpy releases the GIL)
+            from concurrent.futures import ThreadPoolExecutor
+            jobs = [(l, nm, shp) for l in range(shape.n_layers) for nm, shp in SI.layer_param_shapes(shape).items()]
+
+            def gen(job):
+                l, nm, shp = job
+                return SI.make_tensor(seed, f"{shape.name}/L{l}/{nm}", shp, shape.w_std, shape.dtype,
+                                      mean=1.0 if nm in ("g1", "g2") else 0.0)
+            with ThreadPoolExecutor(max_workers=8) as ex:
+                out = list(ex.map(gen, jobs))
+            self.layers = [dict() for _ in range(shape.n_layers)]
+            for (l, nm, _), t in zip(jobs, out):
+                self.layers[l][nm] = t
+        else:
+            self.layers = SI.make_stage_params(shape, seed)
         self.x = [SI.make_x(shape, j, int(c[-1]), seed) for j, c in enumerate(self.cus)]
         self.dy = [SI.make_dy(shape, j, int(c[-1]), seed) for j, c in enumerate(self.cus)]
 
@@ -116,24 +130,43 @@ def assert_bit_identical(a: dict, b: dict):
             assert np.array_equal(gl[k], hl[k]), f"reduced grad {k} layer {l} differs between dispatch orders"
 
 
-def compare(got: dict, ref: dict, tol: float, what: str = ""):
-    """Asserts the max-norm relative error bound for y, dx, every per-microbatch gradient
-    tensor and the reduced gradients.  Returns the worst error seen."""
+def fuse_grads(layer: dict) -> dict:
+    """Per-layer gradient dict keyed by logical names -> the library's own gradient tensors
+    (include/rrfp_stage.h, STAGE_P_*): g1, Wqkv = [Wq|Wk|Wv], Wo, g2, Wup = [Wg|Wu] (or W1), Wd."""
+    out = {"g1": layer["g1"], "g2": layer["g2"], "Wo": layer["Wo"], "Wd": layer["Wd"],
+           "Wqkv": np.concatenate([layer["Wq"], layer["Wk"], layer["Wv"]], axis=1)}
+    out["Wup"] = np.concatenate([layer["Wg"], layer["Wu"]], axis=1) if "Wg" in layer else layer["W1"]
+    return out
+
+
+def compare(got: dict, ref: dict, tol: float, what: str = "", report=None):
+    """Asserts the max-norm relative error bound for y, dx, every per-microbatch gradient tensor
+    and the reduced gradients, tensor by tensor as the library defines them (STAGE_P_*: the fused
+    Wqkv and Wup are one tensor each).  Returns the worst error seen.  `report`, if given, receives
+    (name, error) for every tensor, including the logical blocks Wq, Wk, Wv, Wg, Wu on their own."""
     worst = 0.0
     for key in ("y", "dx"):
         for j, (g, r) in enumerate(zip(got[key], ref[key])):
             e = max_norm_rel_err(g, r)
             worst = max(worst, e)
+            if report is not None:
+                report.append((f"{key}[mb {j}]", e))
             assert e <= tol, f"{what} {key}[mb {j}]: rel err {e:.3e} > {tol}"
-    for j, (gm, rm) in enumerate(zip(got["grads"], ref["grads"])):
-        for l, (gl, rl) in enumerate(zip(gm, rm)):
-            for k in rl:
-                e = max_norm_rel_err(gl[k], rl[k])
+
+    def layers(gl_list, rl_list, tag):
+        nonlocal worst
+        for l, (gl, rl) in enumerate(zip(gl_list, rl_list)):
+            if report is not None:
+                for k in rl:
+                    report.append((f"{tag} block {k} layer {l}", max_norm_rel_err(gl[k], rl[k])))
+            gf, rf = fuse_grads(gl), fuse_grads(rl)
+            for k in rf:
+                e = max_norm_rel_err(gf[k], rf[k])
                 worst = max(worst, e)
-                assert e <= tol, f"{what} grad {k} layer {l} mb {j}: rel err {e:.3e} > {tol}"
-    for l, (gl, rl) in enumerate(zip(got["reduced"], ref["reduced"])):
-        for k in rl:
-            e = max_norm_rel_err(gl[k], rl[k])
-            worst = max(worst, e)
-            assert e <= tol, f"{what} reduced grad {k} layer {l}: rel err {e:.3e} > {tol}"
+                assert e <= tol, f"{what} {tag} {k} layer {l}: rel err {e:.3e} > {tol}"
+
+    for j, (gm, rm) in enumerate(zip(got["grads"], ref["grads"])):
+        layers(gm, rm, f"grad mb {j}")
+    if ref["reduced"]:
+        layers(got["reduced"], ref["reduced"], "reduced grad")
     return worst

@@ -1,0 +1,167 @@
+"""Full-size GPU checks, in the launch configuration bench.py times (same stage_config, same
+kernels and grids).  The oracle computes one sampled microbatch of the language stage at full
+size; the other full-size claims are properties that hold at any size: bit-identical results
+under two dispatch orders and grad_out == the index-ordered fp32 sum of the slots."""
+import time
+
+import numpy as np
+import pytest
+
+import stage_inputs as SI
+from tests import helpers as Hp
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _run_one_mb(shape, cu, M_slots, mb, seed=SI.BASE_SEED):
+    """F, B, W of microbatch `mb` on a stage created with M_slots slots; returns GPU and oracle results."""
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+    from oracle import stage_oracle as O
+    t0 = time.time()
+    w = Hp.Workload(shape, [cu])
+    _say(f"  inputs generated in {time.time() - t0:.1f} s")
+    T = int(cu[-1])
+    cfg = Hn.make_config(shape, T, len(cu) - 1, n_microbatches=M_slots)
+    stage = Hn.Stage(cfg, Hn.pack_params(cfg, w.layers))
+    x = Hn.to_device(w.x[0].storage, shape.dtype)
+    dy = Hn.to_device(w.dy[0].storage, shape.dtype)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    s = torch.cuda.Stream()
+    R.stage_F(stage.handle, mb, x, cu, y, s)
+    R.stage_B(stage.handle, mb, dy, dx, s)
+    R.stage_W(stage.handle, mb, s)
+    torch.cuda.synchronize()
+    got = {"y": [Hn.to_f64(y)], "dx": [Hn.to_f64(dx)],
+           "grads": [Hn.unpack_grads(cfg, stage.slot(mb).cpu().numpy())]}
+    stage.close()
+    del stage
+    torch.cuda.empty_cache()
+    t0 = time.time()
+    ocfg = Hp.oracle_config(shape)
+    params = w.oracle_params()
+    yr, caches = O.stage_F(w.x[0].f64, params, cu, ocfg)
+    dxr, gains, wst = O.stage_B(w.dy[0].f64, caches, params, ocfg)
+    gr = O.merge_B_W(gains, O.stage_W(caches, wst, ocfg))
+    _say(f"  oracle F+B+W in {time.time() - t0:.1f} s")
+    ref = {"y": [yr], "dx": [dxr], "grads": [gr]}
+    got["reduced"], ref["reduced"] = [], []
+    return got, ref
+
+
+def test_language_stage_full_size_sampled_microbatch():
+    """4 layers, hidden 4096, 32 heads x 128, FFN 11008, causal seq 4096, 8 slots; microbatch 3."""
+    shape = SI.LANGUAGE
+    _say("[full] language stage, microbatch 3 of 8, T=4096")
+    got, ref = _run_one_mb(shape, np.array([0, SI.LANGUAGE_SEQ], dtype=np.int32), shape.n_microbatches, 3)
+    rep = []
+    try:
+        worst = Hp.compare(got, ref, 2e-2, "language full size", report=rep)
+    finally:
+        for name, e in sorted(rep, key=lambda t: -t[1])[:12]:
+            _say(f"    {name}: {e:.3e}")
+    _say(f"[full] language: worst rel err {worst:.3e}")
+
+
+def test_vision_stage_full_size_sampled_microbatch():
+    """8 bidirectional layers, hidden 1280, 16 heads x 80, GELU 5120, 8 images x 784 tokens."""
+    shape = SI.VISION
+    _say("[full] vision stage, microbatch 5 of 8, T=6272 in 8 segments")
+    got, ref = _run_one_mb(shape, SI.default_cu_seqlens(shape), shape.n_microbatches, 5)
+    worst = Hp.compare(got, ref, 2e-2, "vision full size")
+    _say(f"[full] vision: worst rel err {worst:.3e}")
+
+
+def test_wide_gqa_full_width_one_layer():
+    """Wide GQA stage at full width (hidden 8192, 64 q / 8 kv heads, FFN 28672), one layer, T=1024."""
+    shape = SI.WIDE_GQA.replace(n_layers=1, name="wide_gqa_bf16/one_layer")
+    _say("[full] wide GQA, 1 layer, T=1024")
+    got, ref = _run_one_mb(shape, np.array([0, 1024], dtype=np.int32), 2, 1)
+    worst = Hp.compare(got, ref, 2e-2, "wide gqa full width")
+    _say(f"[full] wide: worst rel err {worst:.3e}")
+
+
+def test_multimodal_ragged_full_width_one_layer():
+    """Language-width layer with a ragged packed microbatch: two causal segments, odd lengths."""
+    shape = SI.MULTIMODAL.replace(n_layers=1, name="multimodal_varlen_bf16/one_layer")
+    _say("[full] multimodal ragged, 1 layer, segments 777 + 1301")
+    got, ref = _run_one_mb(shape, np.array([0, 777, 2078], dtype=np.int32), 2, 0)
+    worst = Hp.compare(got, ref, 2e-2, "multimodal ragged full width")
+    _say(f"[full] multimodal: worst rel err {worst:.3e}")
+
+
+def test_language_stage_full_size_order_and_reduce_properties():
+    """All 8 microbatches at full size (device-generated inputs, as in bench.py): two dispatch orders
+    give bit-identical y, dx, slots and grad_out, and grad_out is exactly ((s0+s1)+s2)+... in fp32."""
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+    shape = SI.LANGUAGE
+    M, T = shape.n_microbatches, SI.LANGUAGE_SEQ
+    cfg = Hn.make_config(shape, T, 1)
+    pb, gb, ab = R.stage_query(cfg)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(7)
+    params = torch.empty(pb // 2, dtype=torch.bfloat16, device="cuda:0").normal_(0.0, 0.02, generator=gen)
+    for l in range(cfg.n_layers):
+        for which in (R.STAGE_P_G1, R.STAGE_P_G2):
+            off, (r, _) = R.stage_param_layout(cfg, l, which)
+            params[off:off + r] += 1.0
+    arena = torch.empty(ab, dtype=torch.uint8, device="cuda:0")
+    grad_out = torch.empty(gb // 4, dtype=torch.float32, device="cuda:0")
+    st = R.stage_create(cfg, params, arena, ab)
+    xs = [torch.empty((T, shape.hidden), dtype=torch.bfloat16, device="cuda:0").normal_(0, 1, generator=gen) for _ in range(M)]
+    dys = [torch.empty((T, shape.hidden), dtype=torch.bfloat16, device="cuda:0").normal_(0, 1, generator=gen) for _ in range(M)]
+    cu = [0, T]
+    # tensor regions of a flat gradient buffer (padding between tensors is never written)
+    regions = []
+    for l in range(cfg.n_layers):
+        for which in range(R.STAGE_P_COUNT):
+            off, (r, c) = R.stage_param_layout(cfg, l, which)
+            regions.append((off, off + r * c))
+    slot_off = [R.stage_grad_slot(st, j) - arena.data_ptr() for j in range(M)]
+
+    def run(order, n_streams):
+        ys = [torch.empty_like(x) for x in xs]
+        dxs = [torch.empty_like(x) for x in xs]
+        streams = [torch.cuda.Stream() for _ in range(n_streams)]
+        for i, (kind, j) in enumerate(order):
+            s = streams[i % n_streams]
+            if kind == "F":
+                R.stage_F(st, j, xs[j], cu, ys[j], s)
+            elif kind == "B":
+                R.stage_B(st, j, dys[j], dxs[j], s)
+            else:
+                R.stage_W(st, j, s)
+        R.stage_grad_reduce(st, grad_out, streams[0])
+        torch.cuda.synchronize()
+        sums = []
+        for (a, b) in regions:       # checksums of the bit patterns keep host traffic small
+            sums.append(int(grad_out[a:b].view(torch.int32).to(torch.int64).sum().item()))
+        ysum = [int(t.view(torch.int16).to(torch.int64).sum().item()) for t in ys + dxs]
+        return ys, dxs, sums, ysum
+
+    _say("[full] canonical order, 1 stream")
+    ys0, dxs0, g0, c0 = run(Hp.canonical_order(M), 1)
+    # grad_out == index-ordered fp32 sum of the slots, region by region, bit for bit
+    for (a, b) in regions:
+        acc = arena[slot_off[0] + 4 * a: slot_off[0] + 4 * b].view(torch.float32).clone()
+        for j in range(1, M):
+            acc += arena[slot_off[j] + 4 * a: slot_off[j] + 4 * b].view(torch.float32)
+        assert torch.equal(acc.view(torch.int32), grad_out[a:b].view(torch.int32)), "grad_out is not the index-ordered sum"
+    keep_y = [t.clone() for t in ys0]
+    keep_dx = [t.clone() for t in dxs0]
+    keep_g = grad_out.clone()
+    order = SI.ready_order(M, 11)
+    _say(f"[full] seeded ready order on 3 streams: {order}")
+    ys1, dxs1, g1, c1 = run(order, 3)
+    for a, b in zip(keep_y + keep_dx, ys1 + dxs1):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16)), "y/dx differ between dispatch orders"
+    for (a, b) in regions:
+        assert torch.equal(keep_g[a:b].view(torch.int32), grad_out[a:b].view(torch.int32)), "grad_out differs between dispatch orders"
+    R.stage_destroy(st)

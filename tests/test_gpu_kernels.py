@@ -22,12 +22,12 @@ def _gemm_case(M, N, K, ta, tb, out_fp32, with_r, family, in_dtype="bf16", seed=
     _say(f"[kernel] {name}")
     A = SI.make_tensor(seed, name + "A", (K, M) if ta else (M, K), 1.0, in_dtype)
     B = SI.make_tensor(seed, name + "B", (N, K) if tb else (K, N), 1.0, in_dtype)
-    Rr = SI.make_tensor(seed, name + "R", (M, N), 4.0, in_dtype) if with_r else None
+    Rr = SI.make_tensor(seed, name + "R", (M, N), 4.0, "fp32") if with_r else None     # the residual is always fp32
     ref = (A.f64.T if ta else A.f64) @ (B.f64.T if tb else B.f64)     # the definition, fp64
     if with_r:
         ref = ref + Rr.f64
     dA, dB = Hn.to_device(A.storage, in_dtype), Hn.to_device(B.storage, in_dtype)
-    dR = Hn.to_device(Rr.storage, in_dtype) if with_r else None
+    dR = Hn.to_device(Rr.storage, "fp32") if with_r else None
     odt = torch.float32 if (out_fp32 or in_dtype == "fp32") else torch.bfloat16
     dC = torch.full((M, N), float("nan"), dtype=odt, device="cuda:0")
     idt = R.STAGE_DTYPE_FP32 if in_dtype == "fp32" else R.STAGE_DTYPE_BF16
