@@ -354,7 +354,8 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __re
 template <int D>
 struct DqCfg {
   static constexpr int DP = (D + 31) / 32 * 32;
-  static constexpr int KP = DP * 2 + 32;             // K tile: row fragments and transposed fragments
+  static constexpr int KP = 304;                     // K tile: row fragments AND transposed fragments.  304 = 48 (mod 256):
+                                                     // 16 rows x 16 B and 4 rows x 32 B both land on distinct banks
   static constexpr int VP = D * 2 + 16;              // V tile: row fragments only
   static constexpr int K_BYTES = BKV * KP;
   static constexpr int STAGE = (K_BYTES + BKV * VP + 255) / 256 * 256;
@@ -498,7 +499,7 @@ constexpr int WK = 32;         // keys per wavefront of the dK/dV kernel
 template <int D>
 struct DkvCfg {
   static constexpr int DP = (D + 31) / 32 * 32;
-  static constexpr int QP = DP * 2 + 32;             // Q and dO tiles: row and transposed fragments
+  static constexpr int QP = 304;                     // Q and dO tiles: row and transposed fragments (see DqCfg::KP)
   static constexpr int T_BYTES = BQ_KV * QP;
   static constexpr int STAGE = (2 * T_BYTES + 2 * BQ_KV * 4 + 255) / 256 * 256;   // Q, dO, lse2[64], delta[64]
   static constexpr int SMEM = 2 * STAGE;

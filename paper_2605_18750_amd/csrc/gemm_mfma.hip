@@ -8,7 +8,7 @@
 // Operand tiles sit in LDS in their memory orientation, so every global load is a coalesced
 // 16-byte access:
 //   K-contiguous operand ([rows][K] in memory): LDS [256 rows][64 k], 16-byte chunks XOR-swizzled
-//     by (row & 7); a fragment (8 consecutive k of one row) is one ds_read_b128.
+//     by ((row >> 1) & 7); a fragment (8 consecutive k of one row) is one ds_read_b128.
 //   K-strided operand ([K][rows] in memory): LDS [64 k][256 rows], 64-byte units XOR-swizzled by
 //     k; a fragment is two ds_read_b64_tr_b16, the LDS transpose read of gfx950 that hands each
 //     lane 4 consecutive k of one row out of a 4(k) x 16(rows) block.
@@ -37,7 +37,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
 
 // Byte offset of the 16-byte chunk (row, c) of a K-contiguous tile [256][64].
-__device__ __forceinline__ int kc_off(int row, int c) { return row * 128 + ((c ^ (row & 7)) << 4); }
+__device__ __forceinline__ int kc_off(int row, int c) { return row * 128 + ((c ^ ((row >> 1) & 7)) << 4); }
 // Byte offset of the 16-byte chunk (k, c) of a K-strided tile [64][256]; c in 0..31.
 __device__ __forceinline__ int ks_off(int k, int c) {
   const int f = (k & 3) | (((k >> 3) & 1) << 2);
@@ -228,8 +228,10 @@ constexpr int DBK = 32;                              // k per stage
 constexpr int DTILE = 256 * DBK * 2;                 // bytes of one operand tile (16 KB)
 constexpr int DSTAGE = 2 * DTILE;                    // A + B (32 KB)
 
-// K-contiguous tile [256 rows][32 k]: 64-byte rows, 4 chunks; chunk c of row r sits at c ^ ((r >> 1) & 3).
-__device__ __forceinline__ int dkc_off(int row, int c) { return row * 64 + ((c ^ ((row >> 1) & 3)) << 4); }
+// K-contiguous tile [256 rows][32 k]: 64-byte rows, 4 chunks; chunk c of row r sits at c ^ ((r >> 2) & 3).
+// LDS serves 256 bytes per clock (64 banks): the 16 lanes of one ds_read_b128 phase read 16 consecutive
+// rows at the same logical chunk, and (row & 3, (row >> 2) & 3) sends them to 16 distinct 16-byte slots.
+__device__ __forceinline__ int dkc_off(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
 
 // NW = wavefronts per workgroup: 4 (2x2, 128x128 each, one per SIMD) or 8 (2x4, 128x64 each, two per
 // SIMD so that one wavefront's waits hide behind the other's MFMAs).
@@ -247,7 +249,7 @@ struct DirectLoader {
     for (int i = 0; i < NL; ++i) {
       const int blk = i * NW + wave;                 // 1 KB block of the 16 KB tile
       if (KC) {
-        const int row = blk * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 1) & 3);
+        const int row = blk * 16 + (lane >> 2), c = (lane & 3) ^ ((row >> 2) & 3);
         voff[i] = (outer0 + row < outer_n) ? ((outer0 + row) * ld + c * 8) * 2 : (int)0x80000000;
       } else {
         const int k = blk * 2 + (lane >> 5), cp = lane & 31;
