@@ -14,6 +14,8 @@
 #include "kernels.h"
 #include "numeric.h"
 
+#include <type_traits>
+
 namespace rrfp {
 namespace {
 
@@ -31,6 +33,24 @@ __device__ __forceinline__ bf16x8 pack8(const float* p) {
 
 constexpr int BKV = 64;        // keys per step
 constexpr int WQ = 64;         // query rows per wavefront
+
+// Fragment of a tile stored [row][k] (pitch bytes): lane gets row row0 + (lane & 31), k = ks*16 + h*8 .. +8.
+__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int pitch, int row0, int ks, int lane) {
+  const uint4 v = *reinterpret_cast<const uint4*>(tile + (row0 + (lane & 31)) * pitch + (ks * 2 + (lane >> 5)) * 16);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Transposed fragment of a tile stored [k][col] (pitch bytes): lane gets column col0 + (lane & 31) and
+// the eight k values kstart + {0..3} and kstart + 8 + {0..3}, kstart = k0 + (lane >> 5) * 4.  This is the
+// k order in which a 32x32 accumulator block, packed to bf16, serves as the other MFMA operand.
+__device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int pitch, int k0, int col0, int lane) {
+  const int krow = k0 + (lane >> 5) * 4 + ((lane & 15) >> 2);
+  const int col = col0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  union { short4v hh[2]; bf16x8 v; } f;
+  f.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + krow * pitch + col * 2));
+  f.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + (krow + 8) * pitch + col * 2));
+  return f.v;
+}
 
 template <int D>
 struct FwdCfg {
@@ -100,7 +120,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
   const int a = blockIdx.x, b = a / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
   const int qcol = a * D, kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: wave-level branches stay uniform
   const int h = lane >> 5, li = lane & 31;
   const int wq0 = tl.r0 + wave * WQ;
   const bool wave_has_rows = wq0 < tl.r1;
@@ -134,97 +155,135 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
   kv_store<D>(rk, rv, smem);
   __syncthreads();
 
-  for (int st = 0; st < nsteps; ++st) {
+  // The running maximum is a REFERENCE point only: the result is exact for any reference as long as
+  // exp2(score - reference) stays in range.  A "fast" step keeps the reference fixed and never touches
+  // the output accumulators except through MFMAs, so they stay in place in the accumulator registers;
+  // it gives up (before changing any state) when some score of the step exceeds the reference by more
+  // than 2^TAU.  A "slow" step moves the reference to the new maximum and rescales.  The first step of
+  // a wavefront is slow; with typical data nearly all the others are fast.
+  constexpr float TAU = 12.0f;
+  // number of leading steps in which this wavefront has unmasked keys (the rest only move data)
+  const int n_active = !wave_has_rows ? 0 : (causal ? min(nsteps, (wq0 + WQ - 1 - tl.s0) / BKV + 1) : nsteps);
+
+  auto io_end = [&](int st) {
+    if (st + 1 < nsteps) kv_store<D>(rk, rv, smem + ((st + 1) & 1) * C::STAGE);
+    __syncthreads();
+  };
+  // One key step.  RESCALE is a compile-time flag; returns false (fast step only) if the step must be
+  // redone as a slow step: nothing but registers local to the step has been changed then.
+  auto step = [&](int st, auto rescale_tag) -> bool {
+    constexpr bool RESCALE = decltype(rescale_tag)::value;
     const int k0 = tl.s0 + st * BKV;
     const char* sk = smem + (st & 1) * C::STAGE;
     const char* sv = sk + C::K_BYTES;
-    const bool more = st + 1 < nsteps;
-    if (more) kv_load<D>(rk, rv, qkv, ld, kcol, vcol, k0 + BKV, kv_end);
-
-    const bool active = wave_has_rows && (!causal || k0 <= wq0 + WQ - 1);
-    if (active) {
-      // S^T[jb][ib]: rows = keys k0 + jb*32 + .., columns = queries
-      floatx16 s[2][2];
+    if (st + 1 < nsteps) kv_load<D>(rk, rv, qkv, ld, kcol, vcol, k0 + BKV, kv_end);
+    // S^T[jb][ib]: rows = keys k0 + jb*32 + .., columns = queries.  All K fragments of a 32-key block
+    // are read before its MFMAs.
+    floatx16 s[2][2];
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-        for (int ib = 0; ib < 2; ++ib)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) s[jb][ib][e] = 0.f;
+    for (int jb = 0; jb < 2; ++jb) {
+      bf16x8 kfr[NDS];
 #pragma unroll
       for (int ds = 0; ds < NDS; ++ds) {
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb) {
-          const uint4 kv4 = *reinterpret_cast<const uint4*>(sk + (jb * 32 + li) * C::KP + (ds * 2 + h) * 16);
-          const bf16x8 kf = __builtin_bit_cast(bf16x8, kv4);
-#pragma unroll
-          for (int ib = 0; ib < 2; ++ib) s[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ib][ds], s[jb][ib], 0, 0, 0);
-        }
+        const uint4 kv4 = *reinterpret_cast<const uint4*>(sk + (jb * 32 + li) * C::KP + (ds * 2 + h) * 16);
+        kfr[ds] = __builtin_bit_cast(bf16x8, kv4);
       }
-      const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
-      bf16x8 pf[2][2][2];   // [ib][jb][u]: probabilities of 16 keys as a B operand
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[jb][ib][e] = 0.f;
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) s[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ds], qf[ib][ds], s[jb][ib], 0, 0, 0);
+      }
+    }
+    const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
+    if (need_mask) {
 #pragma unroll
       for (int ib = 0; ib < 2; ++ib) {
         const int i = wq0 + ib * 32 + li;
-        if (need_mask) {
-#pragma unroll
-          for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-              s[jb][ib][e] = (j >= kv_end || (causal && j > i)) ? -INFINITY : s[jb][ib][e];
-            }
-        }
-        float mx = -INFINITY;   // maximum of the raw scores (the scale is positive)
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[jb][ib][e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[ib], mx * scale_log2e);
-        const float alpha = __builtin_amdgcn_exp2f(m_run[ib] - m_new);
-        m_run[ib] = m_new;
-        float ps = 0.f;
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb) {
-          float p[16];
-#pragma unroll
           for (int e = 0; e < 16; ++e) {
-            p[e] = __builtin_amdgcn_exp2f(fmaf(s[jb][ib][e], scale_log2e, -m_new));
-            ps += p[e];
+            const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+            float v = (j >= kv_end || (causal && j > i)) ? -INFINITY : s[jb][ib][e];
+            asm volatile("" : "+v"(v));   // pins the select inside this (wave-uniform) branch
+            s[jb][ib][e] = v;
           }
-#pragma unroll
-          for (int u = 0; u < 2; ++u) pf[ib][jb][u] = pack8(p + u * 8);
-        }
-        l_run[ib] = l_run[ib] * alpha + ps;
-        if (__any(alpha != 1.0f)) {   // the running maximum moved for some query of this wavefront
-#pragma unroll
-          for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[db][ib][e] *= alpha;
-        }
       }
-      // O^T[db][ib] += V^T P^T.  B-operand slot s of half h is key 16u + (s/4)*8 + h*4 + s%4 of the
-      // 32-key block, so the matching V fragment is two transpose reads starting at keys h*4 and 8 + h*4.
+    }
+    float m_cand[2];
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib) {
+      float mx = -INFINITY;   // maximum of the raw scores (the scale is positive)
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int krow = jb * 32 + u * 16 + h * 4 + ((lane & 15) >> 2);
-#pragma unroll
-          for (int db = 0; db < NDB; ++db) {
-            const int col = db * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-            union { short4v hh[2]; bf16x8 v; } vf;
-            vf.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(sv + krow * C::VP + col * 2));
-            vf.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(sv + (krow + 8) * C::VP + col * 2));
-#pragma unroll
-            for (int ib = 0; ib < 2; ++ib)
-              oacc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[ib][jb][u], oacc[db][ib], 0, 0, 0);
-          }
-        }
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[jb][ib][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      m_cand[ib] = mx * scale_log2e;
     }
-    if (more) kv_store<D>(rk, rv, smem + ((st + 1) & 1) * C::STAGE);
-    __syncthreads();
+    if (!RESCALE) {
+      const bool over = (m_cand[0] > m_run[0] + TAU) || (m_cand[1] > m_run[1] + TAU);
+      if (__any(over)) return false;
+    } else {
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib) {
+        const float m_new = fmaxf(m_run[ib], m_cand[ib]);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[ib] - m_new);
+        m_run[ib] = m_new;
+        l_run[ib] *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[db][ib][e] *= alpha;
+      }
+    }
+    bf16x8 pf[2][2][2];   // [ib][jb][u]: probabilities of 16 keys as a B operand
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib) {
+      float ps = 0.f;
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb) {
+        float p[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          p[e] = __builtin_amdgcn_exp2f(fmaf(s[jb][ib][e], scale_log2e, -m_run[ib]));
+          ps += p[e];
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) pf[ib][jb][u] = pack8(p + u * 8);
+      }
+      l_run[ib] += ps;
+    }
+    // O^T[db][ib] += V^T P^T.  B-operand slot s of half h is key 16u + (s/4)*8 + h*4 + s%4 of the
+    // 32-key block, so the matching V fragment is two transpose reads starting at keys h*4 and 8 + h*4.
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        bf16x8 vfr[NDB];
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) vfr[db] = frag_cols_tr(sv, C::VP, jb * 32 + u * 16, db * 32, lane);
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int ib = 0; ib < 2; ++ib)
+            oacc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[db], pf[ib][jb][u], oacc[db][ib], 0, 0, 0);
+      }
+    io_end(st);
+    return true;
+  };
+
+  int st = 0;
+  while (st < n_active) {
+    step(st, std::true_type{});
+    ++st;
+    while (st < n_active && step(st, std::false_type{})) ++st;
+  }
+  for (; st < nsteps; ++st) {      // steps that are fully masked for this wavefront: data movement only
+    if (st + 1 < nsteps) kv_load<D>(rk, rv, qkv, ld, kcol, vcol, tl.s0 + (st + 1) * BKV, kv_end);
+    io_end(st);
   }
 
   // Finalise: the two halves of the wavefront hold disjoint key subsets of every query column.
@@ -304,24 +363,6 @@ __device__ __forceinline__ void tile_store(const TileArr<D, ROWS>& r, char* lds)
   }
 }
 
-// Fragment of a tile stored [row][k] (pitch bytes): lane gets row row0 + (lane & 31), k = ks*16 + h*8 .. +8.
-__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int pitch, int row0, int ks, int lane) {
-  const uint4 v = *reinterpret_cast<const uint4*>(tile + (row0 + (lane & 31)) * pitch + (ks * 2 + (lane >> 5)) * 16);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-// Transposed fragment of a tile stored [k][col] (pitch bytes): lane gets column col0 + (lane & 31) and
-// the eight k values kstart + {0..3} and kstart + 8 + {0..3}, kstart = k0 + (lane >> 5) * 4.  This is the
-// k order in which a 32x32 accumulator block, packed to bf16, serves as the other MFMA operand.
-__device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int pitch, int k0, int col0, int lane) {
-  const int krow = k0 + (lane >> 5) * 4 + ((lane & 15) >> 2);
-  const int col = col0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  union { short4v hh[2]; bf16x8 v; } f;
-  f.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + krow * pitch + col * 2));
-  f.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + (krow + 8) * pitch + col * 2));
-  return f.v;
-}
-
 template <int D>
 __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __restrict__ o, const float* __restrict__ o32,
                                                               const bf16_t* __restrict__ d_o, float* __restrict__ delta,
@@ -375,7 +416,8 @@ __global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restr
   const int a = blockIdx.x, b = a / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
   const int qcol = a * D, kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: wave-level branches stay uniform
   const int h = lane >> 5, li = lane & 31;
   const int wq0 = tl.r0 + wave * WQ;
   const bool wave_has_rows = wq0 < tl.r1;
@@ -417,62 +459,84 @@ __global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restr
   tile_store<D, BKV, C::VP, D>(rv, smem + C::K_BYTES);
   __syncthreads();
 
-  for (int st = 0; st < nsteps; ++st) {
-    const int k0 = tl.s0 + st * BKV;
-    const char* sk = smem + (st & 1) * C::STAGE;
-    const char* sv = sk + C::K_BYTES;
-    const bool more = st + 1 < nsteps;
-    if (more) {
-      tile_load<D, BKV>(rk, qkv + kcol, ld, k0 + BKV, kv_end);
-      tile_load<D, BKV>(rv, qkv + vcol, ld, k0 + BKV, kv_end);
+  // Leading steps in which this wavefront has unmasked keys; the rest only move data.  The dQ
+  // accumulators are touched in the first loop alone and unconditionally (they stay in place).
+  const int n_active = !wave_has_rows ? 0 : (causal ? min(nsteps, (wq0 + WQ - 1 - tl.s0) / BKV + 1) : nsteps);
+  auto io_begin = [&](int st) {
+    if (st + 1 < nsteps) {
+      tile_load<D, BKV>(rk, qkv + kcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
+      tile_load<D, BKV>(rv, qkv + vcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
     }
-    const bool active = wave_has_rows && (!causal || k0 <= wq0 + WQ - 1);
-    if (active) {
-      const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
-#pragma unroll
-      for (int ib = 0; ib < 2; ++ib) {
-        const int i = wq0 + ib * 32 + li;
-        floatx16 s[2], dp[2];
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) { s[jb][e] = 0.f; dp[jb][e] = 0.f; }
-#pragma unroll
-        for (int ds = 0; ds < NDS; ++ds)
-#pragma unroll
-          for (int jb = 0; jb < 2; ++jb) {
-            s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sk, C::KP, jb * 32, ds, lane), qf[ib][ds], s[jb], 0, 0, 0);
-            dp[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sv, C::VP, jb * 32, ds, lane), dof[ib][ds], dp[jb], 0, 0, 0);
-          }
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb) {
-          float dsv[16];
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            float p = __builtin_amdgcn_exp2f(s[jb][e] * scale_log2e - lse2[ib]);
-            if (need_mask) {
-              const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-              if (j >= kv_end || (causal && j > i)) p = 0.f;
-            }
-            dsv[e] = p * (dp[jb][e] - dl[ib]);
-          }
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const bf16x8 dsf = pack8(dsv + u * 8);
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-              acc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(sk, C::KP, jb * 32 + u * 16, db * 32, lane), dsf,
-                                                                    acc[db][ib], 0, 0, 0);
-          }
-        }
-      }
-    }
-    if (more) {
+  };
+  auto io_end = [&](int st) {
+    if (st + 1 < nsteps) {
       char* nk = smem + ((st + 1) & 1) * C::STAGE;
       tile_store<D, BKV, C::KP, C::DP>(rk, nk);
       tile_store<D, BKV, C::VP, D>(rv, nk + C::K_BYTES);
     }
     __syncthreads();
+  };
+  int st = 0;
+  for (; st < n_active; ++st) {
+    const int k0 = tl.s0 + st * BKV;
+    const char* sk = smem + (st & 1) * C::STAGE;
+    const char* sv = sk + C::K_BYTES;
+    io_begin(st);
+    const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib) {
+      const int i = wq0 + ib * 32 + li;
+      floatx16 s[2], dp[2];
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb) {
+        bf16x8 kfr[NDS], vfr[NDS];      // all fragments of the 32-key block before its MFMAs
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) {
+          kfr[ds] = frag_rows(sk, C::KP, jb * 32, ds, lane);
+          vfr[ds] = frag_rows(sv, C::VP, jb * 32, ds, lane);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[jb][e] = 0.f; dp[jb][e] = 0.f; }
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) {
+          s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ds], qf[ib][ds], s[jb], 0, 0, 0);
+          dp[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[ds], dof[ib][ds], dp[jb], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb) {
+        float dsv[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[jb][e], scale_log2e, -lse2[ib]));
+          dsv[e] = p * (dp[jb][e] - dl[ib]);
+        }
+        if (need_mask) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+            float v = (j >= kv_end || (causal && j > i)) ? 0.f : dsv[e];
+            asm volatile("" : "+v"(v));   // pins the select inside this (wave-uniform) branch
+            dsv[e] = v;
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const bf16x8 dsf = pack8(dsv + u * 8);
+          bf16x8 ktr[NDB];
+#pragma unroll
+          for (int db = 0; db < NDB; ++db) ktr[db] = frag_cols_tr(sk, C::KP, jb * 32 + u * 16, db * 32, lane);
+#pragma unroll
+          for (int db = 0; db < NDB; ++db)
+            acc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr[db], dsf, acc[db][ib], 0, 0, 0);
+        }
+      }
+    }
+    io_end(st);
+  }
+  for (; st < nsteps; ++st) {
+    io_begin(st);
+    io_end(st);
   }
 #pragma unroll
   for (int ib = 0; ib < 2; ++ib) {
@@ -518,7 +582,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
   const int b = blockIdx.x, G = nq / nkv;
   const int ld = (nq + 2 * nkv) * D;
   const int kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: wave-level branches stay uniform
   const int h = lane >> 5, li = lane & 31;
   const int wj0 = tl.r0 + wave * WK;
   const int j = wj0 + li;                       // this lane's key column
@@ -571,52 +636,95 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
   commit(smem);
   __syncthreads();
 
-  for (int st = 0; st < nsteps; ++st) {
-    const int q0 = q_begin + (st % nq_steps) * BQ_KV;
-    const char* sq = smem + (st & 1) * C::STAGE;
-    const char* sd = sq + C::T_BYTES;
-    const float* s_lse = reinterpret_cast<const float*>(sq + 2 * C::T_BYTES);
-    const float* s_dl = s_lse + BQ_KV;
-    const bool more = st + 1 < nsteps;
-    if (more) fetch(st + 1);
-    const bool active = wave_has_keys && (!causal || q0 + BQ_KV - 1 >= wj0);
-    if (active) {
+  // Steps are (query head of the group, 64-row query block) pairs in ascending order.  Under a causal
+  // mask the first n_skip blocks of every head lie wholly before this wavefront's keys: those steps
+  // only move data.  The MFMA accumulators are touched in the second loop alone and unconditionally,
+  // so they stay in place in the accumulator registers for the whole kernel.
+  const int n_skip = !wave_has_keys ? nq_steps : (causal ? min(nq_steps, (wj0 - q_begin) / BQ_KV) : 0);
+  int st = 0;
+  for (int ah = 0; ah < G; ++ah) {
+    for (int t = 0; t < n_skip; ++t, ++st) {
+      if (st + 1 < nsteps) { fetch(st + 1); commit(smem + ((st + 1) & 1) * C::STAGE); }
+      __syncthreads();
+    }
+    for (int t = n_skip; t < nq_steps; ++t, ++st) {
+      const int q0 = q_begin + t * BQ_KV;
+      const char* sq = smem + (st & 1) * C::STAGE;
+      const char* sd = sq + C::T_BYTES;
+      const float* s_lse = reinterpret_cast<const float*>(sq + 2 * C::T_BYTES);
+      const float* s_dl = s_lse + BQ_KV;
+      const bool more = st + 1 < nsteps;
+      if (more) fetch(st + 1);
+      {
       const bool need_mask = (causal && q0 < wj0 + WK - 1) || (q0 + BQ_KV > tl.s1) || (wj0 + WK > tl.r1);
+      // Per 32-row block of queries: S = Q K^T and dP = dO V^T (all fragments of the block are read
+      // before its MFMAs, so the LDS latency is paid once per block, not once per MFMA), then P and dS
+      // in registers, then dV^T += dO^T P and dK^T += Q^T dS from transposed fragments.
 #pragma unroll
       for (int ib = 0; ib < 2; ++ib) {
-        floatx16 s, dp;
+        floatx16 sacc, dpacc;
+        {
+          bf16x8 qa[NDS], da[NDS];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+          for (int ds = 0; ds < NDS; ++ds) {
+            qa[ds] = frag_rows(sq, C::QP, ib * 32, ds, lane);
+            da[ds] = frag_rows(sd, C::QP, ib * 32, ds, lane);
+          }
 #pragma unroll
-        for (int ds = 0; ds < NDS; ++ds) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sq, C::QP, ib * 32, ds, lane), kf[ds], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(sd, C::QP, ib * 32, ds, lane), vf[ds], dp, 0, 0, 0);
+          for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; dpacc[e] = 0.f; }
+#pragma unroll
+          for (int ds = 0; ds < NDS; ++ds) {
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ds], kf[ds], sacc, 0, 0, 0);
+            dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da[ds], vf[ds], dpacc, 0, 0, 0);
+          }
         }
+        // accumulator value e belongs to row ib*32 + (e/4)*8 + h*4 + e%4
         float pv[16], dsv[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int il = ib * 32 + (e >> 2) * 8 + h * 4 + (e & 3);     // row of this accumulator value
-          float p = __builtin_amdgcn_exp2f(s[e] * scale_log2e - s_lse[il]);
-          if (need_mask) {
-            const int i = q0 + il;
-            if (i >= tl.s1 || j >= tl.r1 || (causal && j > i)) p = 0.f;
+        for (int g = 0; g < 4; ++g) {
+          const int il = ib * 32 + g * 8 + h * 4;
+          const float4 l4 = *reinterpret_cast<const float4*>(s_lse + il);
+          const float4 d4 = *reinterpret_cast<const float4*>(s_dl + il);
+          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int e = g * 4 + c;
+            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], scale_log2e, -lv[c]));
+            pv[e] = p;
+            dsv[e] = p * (dpacc[e] - dl4[c]);
           }
-          pv[e] = p;
-          dsv[e] = p * (dp[e] - s_dl[il]);
+        }
+        if (need_mask) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int i = q0 + ib * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+            const bool dead = i >= tl.s1 || j >= tl.r1 || (causal && j > i);
+            float pm = dead ? 0.f : pv[e], dm = dead ? 0.f : dsv[e];
+            asm volatile("" : "+v"(pm), "+v"(dm));   // pins the selects inside this (wave-uniform) branch
+            pv[e] = pm;
+            dsv[e] = dm;
+          }
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
           const bf16x8 pf = pack8(pv + u * 8), dsf = pack8(dsv + u * 8);
+          bf16x8 td[NDB], tq[NDB];
 #pragma unroll
           for (int db = 0; db < NDB; ++db) {
-            dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(sd, C::QP, ib * 32 + u * 16, db * 32, lane), pf, dv[db], 0, 0, 0);
-            dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_tr(sq, C::QP, ib * 32 + u * 16, db * 32, lane), dsf, dk[db], 0, 0, 0);
+            td[db] = frag_cols_tr(sd, C::QP, ib * 32 + u * 16, db * 32, lane);
+            tq[db] = frag_cols_tr(sq, C::QP, ib * 32 + u * 16, db * 32, lane);
+          }
+#pragma unroll
+          for (int db = 0; db < NDB; ++db) {
+            dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td[db], pf, dv[db], 0, 0, 0);
+            dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[db], dsf, dk[db], 0, 0, 0);
           }
         }
       }
+      }
+      if (more) commit(smem + ((st + 1) & 1) * C::STAGE);
+      __syncthreads();
     }
-    if (more) commit(smem + ((st + 1) & 1) * C::STAGE);
-    __syncthreads();
   }
   if (j < tl.r1) {
     bf16_t* krow = dqkv + (size_t)j * ld + kcol;
