@@ -5,6 +5,7 @@
 namespace rrfp {
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
+  if (g.act != ACT_NONE) return gemm_act_supported(g) ? launch_gemm_mfma(g, s) : hipErrorInvalidValue;
   return gemm_mfma_supports(g) ? launch_gemm_mfma(g, s) : launch_gemm_simt(g, s);
 }
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {

@@ -154,13 +154,109 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_gain_kernel(const float* __re
   partial[(size_t)chunk * H + c] = acc;
 }
 
+// ---------------------------------------------------------------- RMSNorm backward, fused
+// Rows and gain partials in one pass over dh and x.  A workgroup owns FUSED_ROWS consecutive rows, two
+// per wavefront; every lane keeps the running sums of dh * xhat of its own columns (NV vectors of
+// Vec<T>::N columns) in registers, the four wavefronts are added in wavefront order through LDS, and
+// the workgroup writes one partial row.  H <= NV * 64 * Vec<T>::N and H % Vec<T>::N == 0.
+constexpr int FUSED_ROWS = 8;
+
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_fused_kernel(const float* __restrict__ dh, const float* __restrict__ x,
+                                                                const float* __restrict__ r, const T* __restrict__ g,
+                                                                const float* __restrict__ add_in, float* __restrict__ out32,
+                                                                T* __restrict__ out_t, float* __restrict__ partial,
+                                                                int Tn, int H) {
+  constexpr int V = Vec<T>::N;
+  extern __shared__ float red[];                 // [4][H]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float gsum[NV][V];
+#pragma unroll
+  for (int v = 0; v < NV; ++v)
+#pragma unroll
+    for (int i = 0; i < V; ++i) gsum[v][i] = 0.f;
+  for (int rr_ = 0; rr_ < FUSED_ROWS / 4; ++rr_) {
+    const int row = blockIdx.x * FUSED_ROWS + wave * (FUSED_ROWS / 4) + rr_;
+    if (row >= Tn) break;
+    const size_t off = (size_t)row * H;
+    const float rr = r[row];
+    float dot = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int c = (v * WAVE + lane) * V;
+      if (c < H) {
+        float a[V], b[V], gv[V];
+        load_f32<V>(dh + off + c, a);
+        load_f32<V>(x + off + c, b);
+        load_vec<T>(g + c, gv);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          const float xh = b[i] * rr;
+          dot += a[i] * gv[i] * xh;
+          gsum[v][i] += a[i] * xh;
+        }
+      }
+    }
+    dot = wave_sum(dot) / (float)H;
+    // second sweep (served by cache): the row is not kept in registers, which keeps occupancy up
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int c = (v * WAVE + lane) * V;
+      if (c < H) {
+        float a[V], b[V], gv[V], ad[V];
+        load_f32<V>(dh + off + c, a);
+        load_f32<V>(x + off + c, b);
+        load_vec<T>(g + c, gv);
+        load_f32<V>(add_in + off + c, ad);
+#pragma unroll
+        for (int i = 0; i < V; ++i) ad[i] += rr * (a[i] * gv[i] - (b[i] * rr) * dot);
+        if (out32) store_f32<V>(out32 + off + c, ad);
+        if (out_t) store_vec<T>(out_t + off + c, ad);
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int c = (v * WAVE + lane) * V;
+    if (c < H) store_f32<V>(red + (size_t)wave * H + c, gsum[v]);
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < H; c += 256)
+    partial[(size_t)blockIdx.x * H + c] = ((red[c] + red[H + c]) + red[2 * H + c]) + red[3 * H + c];
+}
+
+// Column sums of `partial` [n_partial][H] in one fixed order: 16 contiguous slices of the rows are
+// summed front to back by 16 thread groups (4 columns per thread), then added in slice order.
 __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ partial, int n_partial, int H,
                                                      float* __restrict__ out) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= H) return;
-  float acc = 0.f;
-  for (int p = 0; p < n_partial; ++p) acc += partial[(size_t)p * H + c];
-  out[c] = acc;
+  __shared__ float red[16][64];
+  const int cv = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int c = blockIdx.x * 64 + cv * 4;
+  const int per = (n_partial + 15) / 16;
+  const int p0 = grp * per, p1 = min(p0 + per, n_partial);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (c + 3 < H && (H & 3) == 0) {
+    for (int p = p0; p < p1; ++p) {
+      const float4 v = *reinterpret_cast<const float4*>(partial + (size_t)p * H + c);
+      acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+    }
+  } else {
+    for (int p = p0; p < p1; ++p)
+      for (int i = 0; i < 4; ++i)
+        if (c + i < H) acc[i] += partial[(size_t)p * H + c + i];
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) red[grp][cv * 4 + i] = acc[i];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int cc = blockIdx.x * 64 + threadIdx.x;
+    if (cc < H) {
+      float t = red[0][threadIdx.x];
+#pragma unroll
+      for (int q = 1; q < 16; ++q) t += red[q][threadIdx.x];
+      out[cc] = t;
+    }
+  }
 }
 
 // ---------------------------------------------------------------- SwiGLU / GELU
@@ -273,8 +369,41 @@ hipError_t launch_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_o
   return hipGetLastError();
 }
 
+template <typename T, int NV>
+hipError_t launch_bwd_fused(const float* dh, const float* x, const float* r, const void* g, const float* add_in,
+                            float* out32, void* out_t, float* dg_partial, int Tn, int H, hipStream_t s) {
+  auto kern = rmsnorm_bwd_fused_kernel<T, NV>;
+  const size_t smem = (size_t)4 * H * sizeof(float);
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * NV * WAVE * Vec<T>::N * 4);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((Tn + FUSED_ROWS - 1) / FUSED_ROWS), dim3(256), smem, s, dh, x, r, (const T*)g, add_in, out32,
+                     (T*)out_t, dg_partial, Tn, H);
+  return hipGetLastError();
+}
+
+int norm_bwd_partials(int Tn, int H, int dtype) {
+  const int V = dtype == F32 ? 4 : 8;
+  const bool fused = (H % V) == 0 && H <= 16 * WAVE * V && (dtype != F32 || H <= 8 * WAVE * V);
+  return fused ? (Tn + FUSED_ROWS - 1) / FUSED_ROWS : (Tn + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS;
+}
+
 hipError_t launch_rmsnorm_bwd(const float* dh, const float* x, const float* r, const void* g, const float* add_in,
                               float* out32, void* out_t, float* dg_partial, int Tn, int H, int dtype, hipStream_t s) {
+  const int V = dtype == F32 ? 4 : 8;
+  if (norm_bwd_partials(Tn, H, dtype) == (Tn + FUSED_ROWS - 1) / FUSED_ROWS && (H % V) == 0) {
+    const int nv = (H + WAVE * V - 1) / (WAVE * V);
+#define RRFP_FUSED(NVV)                                                                                         \
+  if (nv <= NVV) {                                                                                              \
+    DISPATCH_T(dtype, return (launch_bwd_fused<T, NVV>(dh, x, r, g, add_in, out32, out_t, dg_partial, Tn, H, s))); \
+  }
+    RRFP_FUSED(1) RRFP_FUSED(2) RRFP_FUSED(3) RRFP_FUSED(4) RRFP_FUSED(6) RRFP_FUSED(8)
+    if (dtype != F32) { RRFP_FUSED(16) }
+#undef RRFP_FUSED
+  }
   const int chunks = (Tn + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS;
   DISPATCH_T(dtype, {
     hipLaunchKernelGGL(rmsnorm_bwd_gain_kernel<T>, dim3((H + 255) / 256, chunks), dim3(256), 0, s, dh, x, r,
@@ -286,7 +415,7 @@ hipError_t launch_rmsnorm_bwd(const float* dh, const float* x, const float* r, c
 }
 
 hipError_t launch_colsum(const float* partial, int n_partial, int H, float* out, hipStream_t s) {
-  hipLaunchKernelGGL(colsum_kernel, dim3((H + 255) / 256), dim3(256), 0, s, partial, n_partial, H, out);
+  hipLaunchKernelGGL(colsum_kernel, dim3((H + 63) / 64), dim3(256), 0, s, partial, n_partial, H, out);
   return hipGetLastError();
 }
 

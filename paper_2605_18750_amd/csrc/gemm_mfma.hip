@@ -23,6 +23,11 @@
 #include "kernels.h"
 #include "numeric.h"
 
+#ifndef RRFP_WM_KC
+#define RRFP_WM_KC 2
+#define RRFP_WN_KC 4
+#endif
+
 namespace rrfp {
 namespace {
 
@@ -223,7 +228,8 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 // Wavefronts per workgroup of the direct-load kernel, by operand orientation (measured on the
 // language-stage shapes): two per SIMD when at least one operand is K-contiguous, one per SIMD when
 // both are K-strided (the transpose reads double the LDS instruction count).
-constexpr int dl_waves(bool a_kc, bool b_kc) { return (a_kc || b_kc) ? 8 : 4; }
+constexpr int dl_wm(bool a_kc, bool b_kc) { return (a_kc || b_kc) ? RRFP_WM_KC : 2; }
+constexpr int dl_wn(bool a_kc, bool b_kc) { return (a_kc || b_kc) ? RRFP_WN_KC : 2; }
 constexpr int DBK = 32;                              // k per stage
 constexpr int DTILE = 256 * DBK * 2;                 // bytes of one operand tile (16 KB)
 constexpr int DSTAGE = 2 * DTILE;                    // A + B (32 KB)
@@ -241,7 +247,11 @@ struct DirectLoader {
   __amdgpu_buffer_rsrc_t rsrc;
   int voff[NL];
   int k_stride;     // bytes per k-step
-  __device__ __forceinline__ void init(const bf16_t* base, int ld, int outer0, int outer_n, int K, int wave, int lane) {
+  // pair_f > 0 (K-strided operand only): the 256 tile columns are 4 groups of [32 "gate" columns
+  // f .. f+31 | 32 "up" columns pair_f + f .. pair_f + f+31], f = outer0/2 + 32 * group, so that one
+  // wavefront holds gate and up of the same 32 features.
+  __device__ __forceinline__ void init(const bf16_t* base, int ld, int outer0, int outer_n, int K, int wave, int lane,
+                                       int pair_f = 0) {
     const size_t bytes = KC ? ((size_t)(outer_n - 1) * ld + K) * 2 : ((size_t)(K - 1) * ld + outer_n) * 2;
     rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
     k_stride = KC ? DBK * 2 : DBK * ld * 2;
@@ -255,7 +265,12 @@ struct DirectLoader {
         const int k = blk * 2 + (lane >> 5), cp = lane & 31;
         const int f = (k & 3) | (((k >> 3) & 1) << 2);
         const int c = ((((cp >> 2) ^ f) << 2) | (cp & 3));
-        voff[i] = (k * ld + outer0 + c * 8) * 2;
+        int col = outer0 + c * 8;
+        if (pair_f > 0) {
+          const int nl = c * 8;                                  // column inside the tile
+          col = ((nl >> 5) & 1) * pair_f + (outer0 >> 1) + (nl >> 6) * 32 + (nl & 31);
+        }
+        voff[i] = (k * ld + col) * 2;
       }
     }
   }
@@ -291,23 +306,23 @@ __device__ __forceinline__ void stage_barrier() {
   asm volatile("" ::: "memory");
 }
 
-// Fragments of one 16-wide MFMA k-step: 4 row blocks of A and NB column blocks of B of this wavefront.
-template <int NB>
-struct Frags { bf16x8 a[4], b[NB]; };
+// Fragments of one 16-wide MFMA k-step: MI row blocks of A and NB column blocks of B of this wavefront.
+template <int MI, int NB>
+struct Frags { bf16x8 a[MI], b[NB]; };
 
-template <bool A_KC, bool B_KC, int NB>
-__device__ __forceinline__ void load_frags(Frags<NB>& f, const char* sa, int ks, int wm, int wn, int lane) {
+template <bool A_KC, bool B_KC, int MI, int NB>
+__device__ __forceinline__ void load_frags(Frags<MI, NB>& f, const char* sa, int ks, int wm, int wn, int lane) {
   const char* sb = sa + DTILE;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) f.a[i] = dread_frag<A_KC>(sa, wm + i * 32, ks, lane);
+  for (int i = 0; i < MI; ++i) f.a[i] = dread_frag<A_KC>(sa, wm + i * 32, ks, lane);
 #pragma unroll
   for (int j = 0; j < NB; ++j) f.b[j] = dread_frag<B_KC>(sb, wn + j * 32, ks, lane);
 }
 
-template <int NB>
-__device__ __forceinline__ void mfma16(floatx16 (&acc)[4][NB], const Frags<NB>& f) {
+template <int MI, int NB>
+__device__ __forceinline__ void mfma16(floatx16 (&acc)[MI][NB], const Frags<MI, NB>& f) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
 }
@@ -315,20 +330,44 @@ __device__ __forceinline__ void mfma16(floatx16 (&acc)[4][NB], const Frags<NB>& 
 // Ask the scheduler to interleave N_DS LDS reads with N_MFMA MFMAs in four groups, reads leading.
 template <int N_DS, int N_MFMA>
 __device__ __forceinline__ void interleave_ds_mfma() {
+  constexpr int G = (N_DS % 4 == 0 && N_MFMA % 4 == 0) ? 4 : 2;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    __builtin_amdgcn_sched_group_barrier(0x100, N_DS / 4, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA / 4, 0);
+  for (int q = 0; q < G; ++q) {
+    __builtin_amdgcn_sched_group_barrier(0x100, N_DS / G, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA / G, 0);
   }
 }
 
-template <bool A_KC, bool B_KC, typename TO, bool HAS_R, int NW>
-__global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+// WM x WN wavefronts tile the 256x256 block; each owns (256/WM) x (256/WN).
+__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __expf(-z)); }
+__device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float u) {
+  return 0.5f * (1.0f + erff(u * 0.70710678118654752f)) + u * 0.39894228040143268f * __expf(-0.5f * u * u);
+}
+__device__ __forceinline__ void load_f32x8(const float* p, float* v) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void unpack4(uint2 w, float* v) {
+  v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
+  v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
+}
+__device__ __forceinline__ uint2 pack4(const float* v) {
+  uint2 o;
+  o.x = pack_bf16x2(v[0], v[1]);
+  o.y = pack_bf16x2(v[2], v[3]);
+  return o;
+}
+
+template <bool A_KC, bool B_KC, typename TO, bool HAS_R, int WM, int WN, int ACT>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                TO* __restrict__ C, const float* __restrict__ R, int M,
                                                                int N, int K, int lda, int ldb, int ldc, int ldr,
-                                                               int tiles_m, int tiles_n) {
-  constexpr int NB = 16 / NW;                       // 32-wide column blocks per wavefront: 4 or 2
-  constexpr int WAVE_N = NB * 32;                   // 128 or 64
+                                                               int tiles_m, int tiles_n, bf16_t* __restrict__ E, int lde) {
+  constexpr int NW = WM * WN;
+  constexpr int MI = 8 / WM;                        // 32-high row blocks per wavefront
+  constexpr int NB = 8 / WN;                        // 32-wide column blocks per wavefront
+  constexpr int WAVE_M = MI * 32, WAVE_N = NB * 32;
   __shared__ __attribute__((aligned(1024))) char stage0[DSTAGE];
   __shared__ __attribute__((aligned(1024))) char stage1[DSTAGE];
   __shared__ __attribute__((aligned(1024))) char stage2[DSTAGE];
@@ -338,11 +377,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __r
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = (wave / (NW / 2)) * 128, wn = (wave % (NW / 2)) * WAVE_N;
+  const int wm = (wave / WN) * WAVE_M, wn = (wave % WN) * WAVE_N;
 
-  floatx16 acc[4][NB];
+  floatx16 acc[MI][NB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NB; ++j)
 #pragma unroll
@@ -351,7 +390,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __r
   DirectLoader<A_KC, NW> la;
   DirectLoader<B_KC, NW> lb;
   la.init(A, lda, m0, M, K, wave, lane);
-  lb.init(B, ldb, n0, N, K, wave, lane);
+  lb.init(B, ldb, n0, N, K, wave, lane, ACT == ACT_SWIGLU_FWD ? N / 2 : 0);
   const int nk = (K + DBK - 1) / DBK;
 
   // Software pipeline over 32-deep steps.  Entering step t the fragments of its first k-step are in
@@ -365,43 +404,43 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __r
   constexpr int VM_ALL = 0x0070;                                   // vmcnt(0), lgkmcnt(0)
   constexpr int VM_2 = 0x0070 | ((2 * LPS) & 15) | (((2 * LPS) >> 4) << 14);   // vmcnt(2*LPS), lgkmcnt(0)
   constexpr int VM_3 = 0x0070 | ((3 * LPS) & 15) | (((3 * LPS) >> 4) << 14);   // vmcnt(3*LPS), lgkmcnt(0)
-  constexpr int N_DS = (A_KC ? 4 : 8) + (B_KC ? NB : 2 * NB);
-  constexpr int N_MFMA = 4 * NB;
+  constexpr int N_DS = (A_KC ? MI : 2 * MI) + (B_KC ? NB : 2 * NB);
+  constexpr int N_MFMA = MI * NB;
 #define RRFP_ISSUE(stage, t) do { la.issue(stage, (t), wave); lb.issue(stage + DTILE, (t), wave); } while (0)
 #define RRFP_STEP_FULL(cur, nxt, t)                                                        \
   do {                                                                                     \
-    load_frags<A_KC, B_KC, NB>(fy, cur, 1, wm, wn, lane);                                  \
-    mfma16<NB>(acc, fx);                                                                   \
+    load_frags<A_KC, B_KC, MI, NB>(fy, cur, 1, wm, wn, lane);                                  \
+    mfma16<MI, NB>(acc, fx);                                                                   \
     interleave_ds_mfma<N_DS, N_MFMA>();                                                    \
     __builtin_amdgcn_s_waitcnt(VM_2);                                                      \
     stage_barrier();                                                                       \
     RRFP_ISSUE(cur, (t) + 4);                                                              \
-    load_frags<A_KC, B_KC, NB>(fx, nxt, 0, wm, wn, lane);                                  \
-    mfma16<NB>(acc, fy);                                                                   \
+    load_frags<A_KC, B_KC, MI, NB>(fx, nxt, 0, wm, wn, lane);                                  \
+    mfma16<MI, NB>(acc, fy);                                                                   \
     interleave_ds_mfma<N_DS, N_MFMA>();                                                    \
   } while (0)
 #define RRFP_STEP_TAIL(cur, nxt, t)                                                        \
   do {                                                                                     \
-    load_frags<A_KC, B_KC, NB>(fy, cur, 1, wm, wn, lane);                                  \
-    mfma16<NB>(acc, fx);                                                                   \
+    load_frags<A_KC, B_KC, MI, NB>(fy, cur, 1, wm, wn, lane);                                  \
+    mfma16<MI, NB>(acc, fx);                                                                   \
     if ((t) + 1 < nk) {                                                                    \
       if ((t) + 3 < nk) __builtin_amdgcn_s_waitcnt(VM_2);                                  \
       else __builtin_amdgcn_s_waitcnt(VM_ALL);                                             \
       stage_barrier();                                                                     \
       if ((t) + 4 < nk) RRFP_ISSUE(cur, (t) + 4);                                          \
-      load_frags<A_KC, B_KC, NB>(fx, nxt, 0, wm, wn, lane);                                \
+      load_frags<A_KC, B_KC, MI, NB>(fx, nxt, 0, wm, wn, lane);                                \
     }                                                                                      \
-    mfma16<NB>(acc, fy);                                                                   \
+    mfma16<MI, NB>(acc, fy);                                                                   \
   } while (0)
 
-  Frags<NB> fx, fy;
+  Frags<MI, NB> fx, fy;
   RRFP_ISSUE(stage0, 0);
   if (nk > 1) RRFP_ISSUE(stage1, 1);
   if (nk > 2) RRFP_ISSUE(stage2, 2);
   if (nk > 3) RRFP_ISSUE(stage3, 3);
   if (nk > 3) __builtin_amdgcn_s_waitcnt(VM_3); else __builtin_amdgcn_s_waitcnt(VM_ALL);
   stage_barrier();
-  load_frags<A_KC, B_KC, NB>(fx, stage0, 0, wm, wn, lane);
+  load_frags<A_KC, B_KC, MI, NB>(fx, stage0, 0, wm, wn, lane);
 
   int t = 0;
   for (; t + 7 < nk; t += 4) {      // every step of this loop has a step t+4 to prefetch
@@ -422,30 +461,97 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __r
 #undef RRFP_STEP_TAIL
 #undef RRFP_ISSUE
 
+  // Epilogue through LDS.  In the accumulator layout a lane owns 4 consecutive columns of one row, so a
+  // direct store instruction would touch 32 different rows with 16 bytes each.  Instead every wavefront
+  // writes one 32-row block of its accumulators to its own LDS scratch (the pipeline stages are free
+  // now), and reads it back with 8 consecutive columns per lane and whole rows per group of lanes: all
+  // global loads and stores of the epilogue (C, the residual, the activation operand) are then row-
+  // contiguous 16- or 32-byte accesses per lane.
+  __syncthreads();     // every wavefront has finished its fragment reads of the last step
+  float* scratch;
+  {
+    constexpr int PER = DSTAGE * 4 / NW;            // bytes of scratch per wavefront: 16 KB (8 waves) or 32 KB (4)
+    const int sel = wave * PER / DSTAGE, sub = (wave * PER) % DSTAGE;
+    char* base = sel == 0 ? stage0 : sel == 1 ? stage1 : sel == 2 ? stage2 : stage3;
+    scratch = reinterpret_cast<float*>(base + sub);
+  }
+  constexpr int NBC = NB * 32;                      // columns of the wavefront's tile
+  constexpr int PITCH = NBC + 4;                    // floats; 16-byte skew per row
+  const int li = lane & 31, hh = lane >> 5;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = m0 + wm + i * 32 + (lane & 31);
-    if (m >= M) continue;
+  for (int i = 0; i < MI; ++i) {
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
+    for (int j = 0; j < NB; ++j)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn + j * 32 + g * 8 + (lane >> 5) * 4;
-        if (n >= N) continue;
-        float v[4];
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<float4*>(scratch + li * PITCH + j * 32 + g * 8 + hh * 4) =
+            make_float4(acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
+    if (ACT == ACT_SWIGLU_FWD) {
+      // scratch columns 0..31 = gate, 32..63 = up of features f0 .. f0+31; 4 lanes per row, 16 rows per sweep
+      const int F = N >> 1;
+      const int f0 = (n0 >> 1) + (wn >> 6) * 32;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e];
-        if (HAS_R) {
-          const float4 rr = *reinterpret_cast<const float4*>(R + (size_t)m * ldr + n);
-          v[0] += rr.x; v[1] += rr.y; v[2] += rr.z; v[3] += rr.w;
+      for (int rr = 0; rr < 2; ++rr) {
+        const int row = rr * 16 + (lane >> 2), fc = (lane & 3) * 8;
+        const int m = m0 + wm + i * 32 + row;
+        float gt[8], up[8], mm[8];
+        load_f32x8(scratch + row * PITCH + fc, gt);
+        load_f32x8(scratch + row * PITCH + 32 + fc, up);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mm[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
+        if (m < M) {
+          bf16_t* crow = (bf16_t*)C + (size_t)m * ldc + f0 + fc;
+          store_vec<bf16_t>(crow, gt);
+          store_vec<bf16_t>(crow + F, up);
+          store_vec<bf16_t>(E + (size_t)m * lde + f0 + fc, mm);
         }
-        if (sizeof(TO) == 4) {
-          *reinterpret_cast<float4*>((float*)C + (size_t)m * ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    } else {
+      constexpr int LPR = NBC / 8;                  // lanes per row
+      constexpr int RPS = 64 / LPR;                 // rows per sweep
+#pragma unroll
+      for (int rr = 0; rr < 32 / RPS; ++rr) {
+        const int row = rr * RPS + lane / LPR, c0 = (lane % LPR) * 8;
+        const int m = m0 + wm + i * 32 + row, n = n0 + wn + c0;
+        float v[8];
+        load_f32x8(scratch + row * PITCH + c0, v);
+        if (m >= M || n >= N) continue;            // N is a multiple of 8: the eight columns are in or out together
+        if (HAS_R) {
+          float rv[8];
+          load_f32x8(R + (size_t)m * ldr + n, rv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += rv[e];
+        }
+        if (ACT == ACT_GELU_FWD) {
+          float mm[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) mm[e] = gelu_f(v[e]);
+          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
+          store_vec<bf16_t>(E + (size_t)m * lde + n, mm);
+        } else if (ACT == ACT_GELU_BWD) {
+          float u[8];
+          load_vec<bf16_t>(E + (size_t)m * lde + n, u);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e]);
+          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
+        } else if (ACT == ACT_SWIGLU_BWD) {
+          float gt[8], up[8], dg[8], du[8];
+          load_vec<bf16_t>(E + (size_t)m * lde + n, gt);
+          load_vec<bf16_t>(E + (size_t)m * lde + N + n, up);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float sg = sigmoid_f(gt[e]);
+            dg[e] = v[e] * up[e] * sg * (1.0f + gt[e] * (1.0f - sg));
+            du[e] = v[e] * gt[e] * sg;
+          }
+          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, dg);
+          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + N + n, du);
+        } else if (sizeof(TO) == 4) {
+          float* crow = (float*)C + (size_t)m * ldc + n;
+          *reinterpret_cast<float4*>(crow) = make_float4(v[0], v[1], v[2], v[3]);
+          *reinterpret_cast<float4*>(crow + 4) = make_float4(v[4], v[5], v[6], v[7]);
         } else {
-          uint2 o;
-          o.x = pack_bf16x2(v[0], v[1]);
-          o.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2*>((bf16_t*)C + (size_t)m * ldc + n) = o;
+          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
         }
       }
     }
@@ -453,12 +559,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_dl_kernel(const bf16_t* __r
 }
 
 // Explicit instantiations of every variant the launcher can pick.
-#define RRFP_INST(AKC, BKC, TO, HR)                                                                          \
-  template __global__ void gemm_mfma_dl_kernel<AKC, BKC, TO, HR, dl_waves(AKC, BKC)>(const bf16_t*, const bf16_t*, TO*, \
-                                                                           const float*, int, int, int, int, int, int, int, int, int);
-#define RRFP_INST4(AKC, BKC) RRFP_INST(AKC, BKC, float, true) RRFP_INST(AKC, BKC, float, false) \
-                             RRFP_INST(AKC, BKC, bf16_t, true) RRFP_INST(AKC, BKC, bf16_t, false)
+#define RRFP_INST(AKC, BKC, TO, HR, ACT)                                                                     \
+  template __global__ void gemm_mfma_dl_kernel<AKC, BKC, TO, HR, dl_wm(AKC, BKC), dl_wn(AKC, BKC), ACT>(      \
+      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int);
+#define RRFP_INST4(AKC, BKC) RRFP_INST(AKC, BKC, float, true, ACT_NONE) RRFP_INST(AKC, BKC, float, false, ACT_NONE) \
+                             RRFP_INST(AKC, BKC, bf16_t, true, ACT_NONE) RRFP_INST(AKC, BKC, bf16_t, false, ACT_NONE)
 RRFP_INST4(true, false) RRFP_INST4(true, true) RRFP_INST4(false, false) RRFP_INST4(false, true)
+RRFP_INST(true, false, bf16_t, false, ACT_SWIGLU_FWD) RRFP_INST(true, false, bf16_t, false, ACT_GELU_FWD)
+RRFP_INST(true, true, bf16_t, false, ACT_SWIGLU_BWD) RRFP_INST(true, true, bf16_t, false, ACT_GELU_BWD)
 #undef RRFP_INST4
 #undef RRFP_INST
 
@@ -476,10 +584,10 @@ template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
 hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   if (direct_ok(g)) {
-    hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_waves(A_KC, B_KC)>), dim3(tiles_m * tiles_n),
-                       dim3(dl_waves(A_KC, B_KC) * 64), 0,
+    hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
+                       dim3(tiles_m * tiles_n), dim3(dl_wm(A_KC, B_KC) * dl_wn(A_KC, B_KC) * 64), 0,
                        s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda,
-                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n);
+                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0);
     return hipGetLastError();
   }
   static bool configured = false;   // per instantiation; the attribute is process-wide for the function
@@ -503,6 +611,31 @@ hipError_t launch_orient(const GemmArgs& g, hipStream_t s) {
 
 }  // namespace
 
+// Fused-activation launch: forward forms are (A K-contiguous, B K-strided), backward forms (both K-contiguous).
+template <bool B_KC, int ACT>
+hipError_t launch_act(const GemmArgs& g, hipStream_t s) {
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, bf16_t, false, dl_wm(true, B_KC), dl_wn(true, B_KC), ACT>),
+                     dim3(tiles_m * tiles_n), dim3(dl_wm(true, B_KC) * dl_wn(true, B_KC) * 64), 0, s, (const bf16_t*)g.A,
+                     (const bf16_t*)g.B, (bf16_t*)g.C, (const float*)nullptr, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0,
+                     tiles_m, tiles_n, (bf16_t*)g.E, g.lde);
+  return hipGetLastError();
+}
+
+bool gemm_act_supported(const GemmArgs& g) {
+  if (g.act == ACT_NONE) return true;
+  if (!gemm_mfma_supports(g) || !direct_ok(g) || g.R || g.out_dtype != BF16 || !g.E || (g.lde & 7) ||
+      ((uintptr_t)g.E & 15) || g.transA)
+    return false;
+  static_assert(dl_wm(true, false) == 2 && dl_wn(true, false) == 4 && dl_wn(true, true) == 4, "epilogue pairing assumes 2x4 wavefronts");
+  switch (g.act) {
+    case ACT_SWIGLU_FWD: return !g.transB && (g.N % 256) == 0;          // F a multiple of 128: whole paired tiles
+    case ACT_GELU_FWD: return !g.transB;
+    case ACT_SWIGLU_BWD: case ACT_GELU_BWD: return g.transB;
+    default: return false;
+  }
+}
+
 bool gemm_mfma_supports(const GemmArgs& g) {
   if (g.in_dtype != BF16) return false;
   if (g.M < 1 || g.N < 1 || g.K < 1) return false;
@@ -518,6 +651,15 @@ bool gemm_mfma_supports(const GemmArgs& g) {
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
   if (!gemm_mfma_supports(g)) return hipErrorInvalidValue;
+  if (g.act != ACT_NONE) {
+    if (!gemm_act_supported(g)) return hipErrorInvalidValue;
+    switch (g.act) {
+      case ACT_SWIGLU_FWD: return launch_act<false, ACT_SWIGLU_FWD>(g, s);
+      case ACT_GELU_FWD: return launch_act<false, ACT_GELU_FWD>(g, s);
+      case ACT_SWIGLU_BWD: return launch_act<true, ACT_SWIGLU_BWD>(g, s);
+      default: return launch_act<true, ACT_GELU_BWD>(g, s);
+    }
+  }
   const bool a_kc = !g.transA, b_kc = g.transB;
   if (a_kc && !b_kc) return launch_orient<true, false>(g, s);
   if (a_kc && b_kc) return launch_orient<true, true>(g, s);

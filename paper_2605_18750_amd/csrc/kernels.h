@@ -16,13 +16,26 @@ static inline size_t dtype_size(int dt) { return dt == F32 ? 4 : 2; }
 //   transB == false: B stored [K,N] (ldb), true: stored [N,K] (ldb).
 // in_dtype is the type of A and B; out_dtype the type of C (F32 for weight gradients and for the
 // residual stream).
+// Optional activation fused into the epilogue (bf16 MFMA kernel only; see gemm_act_supported):
+//   ACT_SWIGLU_FWD  N = 2F, B = [K, 2F] (gate columns then up columns).  C [M, 2F] receives gate|up,
+//                   E [M, F] (lde) receives m = silu(gate) * up computed from the fp32 accumulators.
+//   ACT_GELU_FWD    N = F.  C [M, F] receives u, E [M, F] receives gelu(u).
+//   ACT_SWIGLU_BWD  N = F, the product is dm (not stored).  E [M, 2F] (lde) holds gate|up of the forward;
+//                   C [M, 2F] receives dgate|dup.
+//   ACT_GELU_BWD    N = F.  E [M, F] holds u; C [M, F] receives du = dm * gelu'(u).
+enum GemmAct : int { ACT_NONE = 0, ACT_SWIGLU_FWD = 1, ACT_GELU_FWD = 2, ACT_SWIGLU_BWD = 3, ACT_GELU_BWD = 4 };
+
 struct GemmArgs {
   const void* A; const void* B; void* C; const float* R;
   int M, N, K;
   int lda, ldb, ldc, ldr;
   bool transA, transB;
   int in_dtype, out_dtype;
+  int act;         // GemmAct
+  void* E;         // activation operand (see GemmAct); written for *_FWD, read for *_BWD
+  int lde;
 };
+bool gemm_act_supported(const GemmArgs& g);   // true if launch_gemm can run g.act fused for this shape
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);       // picks the kernel family
 hipError_t launch_gemm_simt(const GemmArgs& g, hipStream_t s);  // fp32-FMA tiles, any shape
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);  // bf16 MFMA 256x256x64 tiles
@@ -63,10 +76,13 @@ hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStr
 hipError_t launch_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_out,
                               int T, int H, float eps, int dtype, hipStream_t s);
 
-constexpr int NORM_BWD_ROWS = 64;  // rows per partial of the gain-gradient column sum
+constexpr int NORM_BWD_ROWS = 64;  // rows per partial of the gain-gradient column sum (unfused kernels)
+// Number of partial rows launch_rmsnorm_bwd writes for this shape (a pure function of shape and dtype:
+// the fused kernel writes one per 8 rows, the unfused pair one per 64).
+int norm_bwd_partials(int T, int H, int dtype);
 // dx = add_in + r * (w - xhat * mean(w * xhat)), w = dh * g, xhat = x * r; dh, x and add_in fp32.
 // dx is written to out32 (fp32) and/or out_t (storage type); either may be null.
-// dg_partial [ceil(T / NORM_BWD_ROWS), H] fp32 receives per-row-chunk sums of dh * xhat;
+// dg_partial [norm_bwd_partials(T, H, dtype), H] fp32 receives per-row-chunk sums of dh * xhat;
 // launch_colsum then adds the partials in chunk order into dg [H].
 hipError_t launch_rmsnorm_bwd(const float* dh, const float* x, const float* r, const void* g,
                               const float* add_in, float* out32, void* out_t, float* dg_partial,

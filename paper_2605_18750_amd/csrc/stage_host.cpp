@@ -124,7 +124,7 @@ int make_plan(const stage_config* c, Plan* p) {
   p->t_dh = take(T * H * 4);
   p->t_do = take(T * nq * d * e);
   p->t_delta = take(nq * T * 4);
-  p->t_dgp = take(((T + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS) * H * 4);
+  p->t_dgp = take((size_t)norm_bwd_partials((int)T, (int)H, c->dtype) * H * 4);
   const int tile = std::min(ATTN_TILE_Q, ATTN_TILE_KV);
   p->max_tiles = (int)((T + tile - 1) / tile) + c->max_segments;
   p->t_qtiles = take((size_t)p->max_tiles * sizeof(AttnTile));
@@ -389,9 +389,17 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     HIP_TRY(st, launch_rmsnorm_fwd((const float*)(base + L.x1), param_ptr(st, l, STAGE_P_G2), base + L.h2, (float*)(base + L.r2), T, H, c.norm_eps, dt, s));
     g.A = base + L.h2; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WUP); g.ldb = P.n_up;
     g.C = base + L.up; g.ldc = P.n_up; g.R = nullptr; g.N = P.n_up; g.K = H;
-    HIP_TRY(st, launch_gemm(g, s));
-    if (c.mlp_kind == STAGE_MLP_SWIGLU) HIP_TRY(st, launch_swiglu_fwd(base + L.up, base + L.m, T, F, dt, s));
-    else HIP_TRY(st, launch_gelu_fwd(base + L.up, base + L.m, T, F, dt, s));
+    // the activation runs in the GEMM epilogue on the fp32 accumulators when the shape allows it
+    g.act = c.mlp_kind == STAGE_MLP_SWIGLU ? ACT_SWIGLU_FWD : ACT_GELU_FWD; g.E = base + L.m; g.lde = F;
+    if (gemm_act_supported(g)) {
+      HIP_TRY(st, launch_gemm(g, s));
+      g.act = ACT_NONE; g.E = nullptr;
+    } else {
+      g.act = ACT_NONE; g.E = nullptr;
+      HIP_TRY(st, launch_gemm(g, s));
+      if (c.mlp_kind == STAGE_MLP_SWIGLU) HIP_TRY(st, launch_swiglu_fwd(base + L.up, base + L.m, T, F, dt, s));
+      else HIP_TRY(st, launch_gelu_fwd(base + L.up, base + L.m, T, F, dt, s));
+    }
     g.A = base + L.m; g.lda = F; g.B = param_ptr(st, l, STAGE_P_WD); g.ldb = H;
     g.C = y_out; g.ldc = H; g.R = (const float*)(base + L.x1); g.ldr = H; g.N = H; g.K = F;
     g.out_dtype = last ? dt : (int)F32;      // the stage output is rounded once; between layers fp32
@@ -421,7 +429,7 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
   float* slot = slot_base(st, mb);
   const int T = m.T, H = c.hidden, F = c.ffn, dt = c.dtype, nqd = c.n_q_heads * c.head_dim;
   const size_t e = P.esz;
-  const int n_part = (T + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS;
+  const int n_part = norm_bwd_partials(T, H, dt);
   HIP_TRY(st, hipMemcpyAsync(base + P.layer[c.n_layers - 1].dy, dy_dev, (size_t)T * H * e, hipMemcpyDeviceToDevice, s));
   HIP_TRY(st, launch_widen(dy_dev, (float*)(base + P.layer[c.n_layers - 1].dy32), (size_t)T * H, dt, s));
   for (int l = c.n_layers - 1; l >= 0; --l) {
@@ -432,10 +440,19 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     g.in_dtype = dt; g.out_dtype = dt; g.transA = false; g.transB = true; g.M = T; g.R = nullptr;
     // dm = dy Wd^T
     g.A = base + L.dy; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WD); g.ldb = H;
-    g.C = base + P.t_dm; g.ldc = F; g.N = F; g.K = H; g.out_dtype = F32;
-    HIP_TRY(st, launch_gemm(g, s));
-    if (c.mlp_kind == STAGE_MLP_SWIGLU) HIP_TRY(st, launch_swiglu_bwd((const float*)(base + P.t_dm), base + L.up, base + L.dup, T, F, dt, s));
-    else HIP_TRY(st, launch_gelu_bwd((const float*)(base + P.t_dm), base + L.up, base + L.dup, T, F, dt, s));
+    // dm = dy Wd^T feeds only the activation backward: fused into the epilogue when the shape allows it
+    g.C = base + L.dup; g.ldc = P.n_up; g.N = F; g.K = H; g.out_dtype = dt;
+    g.act = c.mlp_kind == STAGE_MLP_SWIGLU ? ACT_SWIGLU_BWD : ACT_GELU_BWD; g.E = base + L.up; g.lde = P.n_up;
+    if (gemm_act_supported(g)) {
+      HIP_TRY(st, launch_gemm(g, s));
+      g.act = ACT_NONE; g.E = nullptr;
+    } else {
+      g.act = ACT_NONE; g.E = nullptr;
+      g.C = base + P.t_dm; g.ldc = F; g.out_dtype = F32;
+      HIP_TRY(st, launch_gemm(g, s));
+      if (c.mlp_kind == STAGE_MLP_SWIGLU) HIP_TRY(st, launch_swiglu_bwd((const float*)(base + P.t_dm), base + L.up, base + L.dup, T, F, dt, s));
+      else HIP_TRY(st, launch_gelu_bwd((const float*)(base + P.t_dm), base + L.up, base + L.dup, T, F, dt, s));
+    }
     // dh2 = [dgate|dup] Wup^T
     g.A = base + L.dup; g.lda = P.n_up; g.B = param_ptr(st, l, STAGE_P_WUP); g.ldb = P.n_up;
     g.C = base + P.t_dh; g.ldc = H; g.N = H; g.K = P.n_up; g.out_dtype = F32;
