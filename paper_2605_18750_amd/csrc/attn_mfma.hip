@@ -32,7 +32,10 @@ __device__ __forceinline__ bf16x8 pack8(const float* p) {
 }
 
 constexpr int BKV = 64;        // keys per step
-constexpr int WQ = 64;         // query rows per wavefront
+constexpr int FWD_Q_ROWS = ATTN_TILE_Q;   // query rows per workgroup of the forward and dQ kernels
+constexpr int FWD_NIB = 1;                // 32-query blocks per wavefront: 8 wavefronts, two per SIMD, so that one
+                                          // wavefront's softmax arithmetic runs under the other's MFMAs
+constexpr int DQ_NIB = 1;
 
 // Fragment of a tile stored [row][k] (pitch bytes): lane gets row row0 + (lane & 31), k = ks*16 + h*8 .. +8.
 __device__ __forceinline__ bf16x8 frag_rows(const char* tile, int pitch, int row0, int ks, int lane) {
@@ -52,7 +55,7 @@ __device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int pitch, int 
   return f.v;
 }
 
-template <int D>
+template <int D, int NT>
 struct FwdCfg {
   static constexpr int DP = (D + 31) / 32 * 32;      // value columns padded to whole 32-wide MFMA blocks
   static constexpr int KP = D * 2 + 16;              // K row pitch in bytes: 16-byte skew per row
@@ -63,16 +66,19 @@ struct FwdCfg {
   static constexpr int SMEM = 2 * STAGE;
   static constexpr int CH = D / 8;                   // 16-byte chunks per row
   static constexpr int NCHUNK = BKV * CH;            // chunks per K (or V) tile
-  static constexpr int PER_THREAD = (NCHUNK + 255) / 256;
+  static constexpr int PER_THREAD = (NCHUNK + NT - 1) / NT;
 };
 
-template <int D>
-__device__ __forceinline__ void kv_load(uint4 (&rk)[FwdCfg<D>::PER_THREAD], uint4 (&rv)[FwdCfg<D>::PER_THREAD],
+template <int D, int NT>
+using KvRegs = uint4[FwdCfg<D, NT>::PER_THREAD];
+
+template <int D, int NT>
+__device__ __forceinline__ void kv_load(KvRegs<D, NT>& rk, KvRegs<D, NT>& rv,
                                         const bf16_t* __restrict__ qkv, int ld, int kcol, int vcol, int k0, int k_end) {
-  using C = FwdCfg<D>;
+  using C = FwdCfg<D, NT>;
 #pragma unroll
   for (int i = 0; i < C::PER_THREAD; ++i) {
-    const int q = i * 256 + threadIdx.x;
+    const int q = i * NT + threadIdx.x;
     const int row = q / C::CH, c = q - row * C::CH;
     uint4 a = make_uint4(0, 0, 0, 0), b = a;
     if (q < C::NCHUNK && k0 + row < k_end) {
@@ -85,13 +91,13 @@ __device__ __forceinline__ void kv_load(uint4 (&rk)[FwdCfg<D>::PER_THREAD], uint
   }
 }
 
-template <int D>
-__device__ __forceinline__ void kv_store(const uint4 (&rk)[FwdCfg<D>::PER_THREAD], const uint4 (&rv)[FwdCfg<D>::PER_THREAD],
+template <int D, int NT>
+__device__ __forceinline__ void kv_store(const KvRegs<D, NT>& rk, const KvRegs<D, NT>& rv,
                                          char* stage) {
-  using C = FwdCfg<D>;
+  using C = FwdCfg<D, NT>;
 #pragma unroll
   for (int i = 0; i < C::PER_THREAD; ++i) {
-    const int q = i * 256 + threadIdx.x;
+    const int q = i * NT + threadIdx.x;
     const int row = q / C::CH, c = q - row * C::CH;
     if (q < C::NCHUNK) {
       *reinterpret_cast<uint4*>(stage + row * C::KP + c * 16) = rk[i];
@@ -100,19 +106,21 @@ __device__ __forceinline__ void kv_store(const uint4 (&rk)[FwdCfg<D>::PER_THREAD
   }
   if (C::DP != D) {   // zero the padded value columns so that the unused output rows stay finite
     constexpr int PADCH = (C::DP - D) / 8;
-    for (int q = threadIdx.x; q < BKV * PADCH; q += 256) {
+    for (int q = threadIdx.x; q < BKV * PADCH; q += NT) {
       const int row = q / PADCH, c = q - row * PADCH;
       *reinterpret_cast<uint4*>(stage + C::K_BYTES + row * C::VP + (C::CH + c) * 16) = make_uint4(0, 0, 0, 0);
     }
   }
 }
 
-template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+template <int D, int NIB>
+__global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                             float* __restrict__ o32, float* __restrict__ lse,
                                                             const AttnTile* __restrict__ tiles,
                                                             int Tn, int nq, int nkv, int causal, float scale_log2e) {
-  using C = FwdCfg<D>;
+  constexpr int NT = FWD_Q_ROWS / (32 * NIB) * 64;   // threads: one wavefront per 32 * NIB query rows
+  constexpr int WQ = 32 * NIB;
+  using C = FwdCfg<D, NT>;
   constexpr int NDS = D / 16;        // contraction steps of Q K^T
   constexpr int NDB = C::DP / 32;    // 32-row blocks of O^T
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -127,9 +135,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
   const bool wave_has_rows = wq0 < tl.r1;
 
   // Q fragments (B operand): column = query wq0 + ib*32 + li, k = ds*16 + h*8 .. +8.
-  bf16x8 qf[2][NDS];
+  bf16x8 qf[NIB][NDS];
 #pragma unroll
-  for (int ib = 0; ib < 2; ++ib) {
+  for (int ib = 0; ib < NIB; ++ib) {
     const int i = wq0 + ib * 32 + li;
 #pragma unroll
     for (int ds = 0; ds < NDS; ++ds) {
@@ -139,20 +147,22 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
     }
   }
 
-  floatx16 oacc[NDB][2];
+  floatx16 oacc[NDB][NIB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib)
+    for (int ib = 0; ib < NIB; ++ib)
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[db][ib][e] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  float m_run[NIB], l_run[NIB];
+#pragma unroll
+  for (int ib = 0; ib < NIB; ++ib) { m_run[ib] = -INFINITY; l_run[ib] = 0.f; }
 
   const int kv_end = causal ? tl.r1 : tl.s1;
   const int nsteps = (kv_end - tl.s0 + BKV - 1) / BKV;
   uint4 rk[C::PER_THREAD], rv[C::PER_THREAD];
-  kv_load<D>(rk, rv, qkv, ld, kcol, vcol, tl.s0, kv_end);
-  kv_store<D>(rk, rv, smem);
+  kv_load<D, NT>(rk, rv, qkv, ld, kcol, vcol, tl.s0, kv_end);
+  kv_store<D, NT>(rk, rv, smem);
   __syncthreads();
 
   // The running maximum is a REFERENCE point only: the result is exact for any reference as long as
@@ -166,7 +176,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
   const int n_active = !wave_has_rows ? 0 : (causal ? min(nsteps, (wq0 + WQ - 1 - tl.s0) / BKV + 1) : nsteps);
 
   auto io_end = [&](int st) {
-    if (st + 1 < nsteps) kv_store<D>(rk, rv, smem + ((st + 1) & 1) * C::STAGE);
+    if (st + 1 < nsteps) kv_store<D, NT>(rk, rv, smem + ((st + 1) & 1) * C::STAGE);
     __syncthreads();
   };
   // One key step.  RESCALE is a compile-time flag; returns false (fast step only) if the step must be
@@ -176,10 +186,10 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
     const int k0 = tl.s0 + st * BKV;
     const char* sk = smem + (st & 1) * C::STAGE;
     const char* sv = sk + C::K_BYTES;
-    if (st + 1 < nsteps) kv_load<D>(rk, rv, qkv, ld, kcol, vcol, k0 + BKV, kv_end);
+    if (st + 1 < nsteps) kv_load<D, NT>(rk, rv, qkv, ld, kcol, vcol, k0 + BKV, kv_end);
     // S^T[jb][ib]: rows = keys k0 + jb*32 + .., columns = queries.  All K fragments of a 32-key block
     // are read before its MFMAs.
-    floatx16 s[2][2];
+    floatx16 s[2][NIB];
 #pragma unroll
     for (int jb = 0; jb < 2; ++jb) {
       bf16x8 kfr[NDS];
@@ -189,7 +199,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
         kfr[ds] = __builtin_bit_cast(bf16x8, kv4);
       }
 #pragma unroll
-      for (int ib = 0; ib < 2; ++ib) {
+      for (int ib = 0; ib < NIB; ++ib) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[jb][ib][e] = 0.f;
 #pragma unroll
@@ -199,7 +209,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
     const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
     if (need_mask) {
 #pragma unroll
-      for (int ib = 0; ib < 2; ++ib) {
+      for (int ib = 0; ib < NIB; ++ib) {
         const int i = wq0 + ib * 32 + li;
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
@@ -212,9 +222,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
           }
       }
     }
-    float m_cand[2];
+    float m_cand[NIB];
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
+    for (int ib = 0; ib < NIB; ++ib) {
       float mx = -INFINITY;   // maximum of the raw scores (the scale is positive)
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
@@ -224,11 +234,13 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
       m_cand[ib] = mx * scale_log2e;
     }
     if (!RESCALE) {
-      const bool over = (m_cand[0] > m_run[0] + TAU) || (m_cand[1] > m_run[1] + TAU);
+      bool over = false;
+#pragma unroll
+      for (int ib = 0; ib < NIB; ++ib) over = over || (m_cand[ib] > m_run[ib] + TAU);
       if (__any(over)) return false;
     } else {
 #pragma unroll
-      for (int ib = 0; ib < 2; ++ib) {
+      for (int ib = 0; ib < NIB; ++ib) {
         const float m_new = fmaxf(m_run[ib], m_cand[ib]);
         const float alpha = __builtin_amdgcn_exp2f(m_run[ib] - m_new);
         m_run[ib] = m_new;
@@ -239,9 +251,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
           for (int e = 0; e < 16; ++e) oacc[db][ib][e] *= alpha;
       }
     }
-    bf16x8 pf[2][2][2];   // [ib][jb][u]: probabilities of 16 keys as a B operand
+    bf16x8 pf[NIB][2][2];   // [ib][jb][u]: probabilities of 16 keys as a B operand
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
+    for (int ib = 0; ib < NIB; ++ib) {
       float ps = 0.f;
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb) {
@@ -268,7 +280,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
-          for (int ib = 0; ib < 2; ++ib)
+          for (int ib = 0; ib < NIB; ++ib)
             oacc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[db], pf[ib][jb][u], oacc[db][ib], 0, 0, 0);
       }
     io_end(st);
@@ -282,13 +294,13 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
     while (st < n_active && step(st, std::false_type{})) ++st;
   }
   for (; st < nsteps; ++st) {      // steps that are fully masked for this wavefront: data movement only
-    if (st + 1 < nsteps) kv_load<D>(rk, rv, qkv, ld, kcol, vcol, tl.s0 + (st + 1) * BKV, kv_end);
+    if (st + 1 < nsteps) kv_load<D, NT>(rk, rv, qkv, ld, kcol, vcol, tl.s0 + (st + 1) * BKV, kv_end);
     io_end(st);
   }
 
   // Finalise: the two halves of the wavefront hold disjoint key subsets of every query column.
 #pragma unroll
-  for (int ib = 0; ib < 2; ++ib) {
+  for (int ib = 0; ib < NIB; ++ib) {
     const int i = wq0 + ib * 32 + li;
     const float l_tot = l_run[ib] + __shfl_xor(l_run[ib], 32, 64);
     if (i >= tl.r1) continue;
@@ -326,18 +338,18 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t* __rest
 
 // Generic tile movers: ROWS x D bf16 from global rows [row0, row_end) into registers, then into
 // LDS with a row pitch of PITCH bytes; columns D .. DPAD-1 are zero-filled.
-template <int D, int ROWS>
-struct TileRegs { static constexpr int N = (ROWS * (D / 8) + 255) / 256; };
-template <int D, int ROWS>
-using TileArr = uint4[TileRegs<D, ROWS>::N];
+template <int D, int ROWS, int NT = 256>
+struct TileRegs { static constexpr int N = (ROWS * (D / 8) + NT - 1) / NT; };
+template <int D, int ROWS, int NT = 256>
+using TileArr = uint4[TileRegs<D, ROWS, NT>::N];
 
-template <int D, int ROWS>
-__device__ __forceinline__ void tile_load(TileArr<D, ROWS>& r, const bf16_t* __restrict__ base, int ld,
+template <int D, int ROWS, int NT = 256>
+__device__ __forceinline__ void tile_load(TileArr<D, ROWS, NT>& r, const bf16_t* __restrict__ base, int ld,
                                           int row0, int row_end) {
   constexpr int CH = D / 8;
 #pragma unroll
-  for (int i = 0; i < TileRegs<D, ROWS>::N; ++i) {
-    const int q = i * 256 + threadIdx.x;
+  for (int i = 0; i < TileRegs<D, ROWS, NT>::N; ++i) {
+    const int q = i * NT + threadIdx.x;
     const int row = q / CH, c = q - row * CH;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (q < ROWS * CH && row0 + row < row_end) v = *reinterpret_cast<const uint4*>(base + (size_t)(row0 + row) * ld + c * 8);
@@ -345,18 +357,18 @@ __device__ __forceinline__ void tile_load(TileArr<D, ROWS>& r, const bf16_t* __r
   }
 }
 
-template <int D, int ROWS, int PITCH, int DPAD>
-__device__ __forceinline__ void tile_store(const TileArr<D, ROWS>& r, char* lds) {
+template <int D, int ROWS, int PITCH, int DPAD, int NT = 256>
+__device__ __forceinline__ void tile_store(const TileArr<D, ROWS, NT>& r, char* lds) {
   constexpr int CH = D / 8;
 #pragma unroll
-  for (int i = 0; i < TileRegs<D, ROWS>::N; ++i) {
-    const int q = i * 256 + threadIdx.x;
+  for (int i = 0; i < TileRegs<D, ROWS, NT>::N; ++i) {
+    const int q = i * NT + threadIdx.x;
     const int row = q / CH, c = q - row * CH;
     if (q < ROWS * CH) *reinterpret_cast<uint4*>(lds + row * PITCH + c * 16) = r[i];
   }
   if (DPAD != D) {
     constexpr int PADCH = (DPAD - D) / 8;
-    for (int q = threadIdx.x; q < ROWS * PADCH; q += 256) {
+    for (int q = threadIdx.x; q < ROWS * PADCH; q += NT) {
       const int row = q / PADCH, c = q - row * PADCH;
       *reinterpret_cast<uint4*>(lds + row * PITCH + (CH + c) * 16) = make_uint4(0, 0, 0, 0);
     }
@@ -403,11 +415,13 @@ struct DqCfg {
   static constexpr int SMEM = 2 * STAGE;
 };
 
-template <int D>
-__global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+template <int D, int NIB>
+__global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
                                                            int Tn, int nq, int nkv, int causal, float scale) {
+  constexpr int NT = FWD_Q_ROWS / (32 * NIB) * 64;   // threads: one wavefront per 32 * NIB query rows
+  constexpr int WQ = 32 * NIB;
   using C = DqCfg<D>;
   constexpr int NDS = D / 16, NDB = C::DP / 32;
   constexpr float LOG2E = 1.4426950408889634f;
@@ -423,10 +437,10 @@ __global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restr
   const bool wave_has_rows = wq0 < tl.r1;
   const float scale_log2e = scale * LOG2E;
 
-  bf16x8 qf[2][NDS], dof[2][NDS];
-  float lse2[2], dl[2];
+  bf16x8 qf[NIB][NDS], dof[NIB][NDS];
+  float lse2[NIB], dl[NIB];
 #pragma unroll
-  for (int ib = 0; ib < 2; ++ib) {
+  for (int ib = 0; ib < NIB; ++ib) {
     const int i = wq0 + ib * 32 + li;
     const bool ok = i < tl.r1;
     lse2[ib] = ok ? lse[(size_t)a * Tn + i] * LOG2E : 0.f;
@@ -442,21 +456,21 @@ __global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restr
       dof[ib][ds] = __builtin_bit_cast(bf16x8, w);
     }
   }
-  floatx16 acc[NDB][2];
+  floatx16 acc[NDB][NIB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib)
+    for (int ib = 0; ib < NIB; ++ib)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[db][ib][e] = 0.f;
 
   const int kv_end = causal ? tl.r1 : tl.s1;
   const int nsteps = (kv_end - tl.s0 + BKV - 1) / BKV;
-  uint4 rk[TileRegs<D, BKV>::N], rv[TileRegs<D, BKV>::N];
-  tile_load<D, BKV>(rk, qkv + kcol, ld, tl.s0, kv_end);
-  tile_load<D, BKV>(rv, qkv + vcol, ld, tl.s0, kv_end);
-  tile_store<D, BKV, C::KP, C::DP>(rk, smem);
-  tile_store<D, BKV, C::VP, D>(rv, smem + C::K_BYTES);
+  uint4 rk[TileRegs<D, BKV, NT>::N], rv[TileRegs<D, BKV, NT>::N];
+  tile_load<D, BKV, NT>(rk, qkv + kcol, ld, tl.s0, kv_end);
+  tile_load<D, BKV, NT>(rv, qkv + vcol, ld, tl.s0, kv_end);
+  tile_store<D, BKV, C::KP, C::DP, NT>(rk, smem);
+  tile_store<D, BKV, C::VP, D, NT>(rv, smem + C::K_BYTES);
   __syncthreads();
 
   // Leading steps in which this wavefront has unmasked keys; the rest only move data.  The dQ
@@ -464,15 +478,15 @@ __global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restr
   const int n_active = !wave_has_rows ? 0 : (causal ? min(nsteps, (wq0 + WQ - 1 - tl.s0) / BKV + 1) : nsteps);
   auto io_begin = [&](int st) {
     if (st + 1 < nsteps) {
-      tile_load<D, BKV>(rk, qkv + kcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
-      tile_load<D, BKV>(rv, qkv + vcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
+      tile_load<D, BKV, NT>(rk, qkv + kcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
+      tile_load<D, BKV, NT>(rv, qkv + vcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
     }
   };
   auto io_end = [&](int st) {
     if (st + 1 < nsteps) {
       char* nk = smem + ((st + 1) & 1) * C::STAGE;
-      tile_store<D, BKV, C::KP, C::DP>(rk, nk);
-      tile_store<D, BKV, C::VP, D>(rv, nk + C::K_BYTES);
+      tile_store<D, BKV, C::KP, C::DP, NT>(rk, nk);
+      tile_store<D, BKV, C::VP, D, NT>(rv, nk + C::K_BYTES);
     }
     __syncthreads();
   };
@@ -484,7 +498,7 @@ __global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restr
     io_begin(st);
     const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
+    for (int ib = 0; ib < NIB; ++ib) {
       const int i = wq0 + ib * 32 + li;
       floatx16 s[2], dp[2];
 #pragma unroll
@@ -539,7 +553,7 @@ __global__ __launch_bounds__(256) void attn_dq_mfma_kernel(const bf16_t* __restr
     io_end(st);
   }
 #pragma unroll
-  for (int ib = 0; ib < 2; ++ib) {
+  for (int ib = 0; ib < NIB; ++ib) {
     const int i = wq0 + ib * 32 + li;
     if (i >= tl.r1) continue;
     bf16_t* row = dqkv + (size_t)i * ld + qcol;
@@ -748,7 +762,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
 
 template <int D>
 hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
-  auto kq = attn_dq_mfma_kernel<D>;
+  auto kq = attn_dq_mfma_kernel<D, DQ_NIB>;
   auto kkv = attn_dkv_mfma_kernel<D>;
   static bool configured = false;
   if (!configured) {
@@ -762,15 +776,16 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
                      a.o32, (const bf16_t*)a.d_o, a.delta, a.T, a.nq);
   hipLaunchKernelGGL(kkv, dim3(a.nkv, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const bf16_t*)a.qkv,
                      (const bf16_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale);
-  hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(256), DqCfg<D>::SMEM, s, (const bf16_t*)a.qkv, (const bf16_t*)a.d_o,
+  hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(FWD_Q_ROWS / (32 * DQ_NIB) * 64), DqCfg<D>::SMEM, s, (const bf16_t*)a.qkv, (const bf16_t*)a.d_o,
                      a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale);
   return hipGetLastError();
 }
 
 template <int D>
 hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
-  using C = FwdCfg<D>;
-  auto kern = attn_fwd_mfma_kernel<D>;
+  constexpr int NT = FWD_Q_ROWS / (32 * FWD_NIB) * 64;
+  using C = FwdCfg<D, NT>;
+  auto kern = attn_fwd_mfma_kernel<D, FWD_NIB>;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
@@ -778,7 +793,7 @@ hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
     configured = true;
   }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(256), C::SMEM, s, (const bf16_t*)a.qkv, (bf16_t*)a.o, a.o32, a.lse,
+  hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(NT), C::SMEM, s, (const bf16_t*)a.qkv, (bf16_t*)a.o, a.o32, a.lse,
                      a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale_log2e);
   return hipGetLastError();
 }
