@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--workload", default="language")
     ap.add_argument("--streams", type=int, default=1, help="streams the tasks are dealt to (B/F/W order)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -152,7 +152,14 @@ def main():
                 e1 = torch.cuda.Event(enable_timing=True)
                 e1.record(s)
                 events.append((kind, j, e0, e1))
+        if events is not None:
+            e0 = torch.cuda.Event(enable_timing=True)
+            e0.record(streams[0])
         R.stage_grad_reduce(st, grad_out, streams[0])
+        if events is not None:
+            e1 = torch.cuda.Event(enable_timing=True)
+            e1.record(streams[0])
+            events.append(("R", -1, e0, e1))
 
     for _ in range(args.warmup):
         step()
@@ -167,8 +174,8 @@ def main():
     # Per-task times (one stream, events around every task), outside the timed region.
     saved = streams
     streams = streams[:1]
-    per_kind = {"F": [], "B": [], "W": []}
-    for _ in range(2):
+    per_kind = {"F": [], "B": [], "W": [], "R": []}
+    for _ in range(3):
         ev = []
         step(ev)
         torch.cuda.synchronize()
@@ -176,11 +183,18 @@ def main():
             per_kind[kind].append((j, e0.elapsed_time(e1)))
     streams = saved
     tasks = {}
+    red_ms = float(np.median([t for _, t in per_kind.pop("R")]))
     for kind, lst in per_kind.items():
         ms = float(np.median([t for _, t in lst]))
         tf = float(np.median([fl[j][kind] / (t * 1e-3) / 1e12 for j, t in lst]))
-        tasks[kind] = {"ms_per_microbatch": round(ms, 4), "tflops": round(tf, 1),
+        p5, p95 = (float(v) for v in np.percentile([t for _, t in lst], [5, 95]))
+        tasks[kind] = {"ms_per_microbatch": round(ms, 4), "p5_ms": round(p5, 4), "p95_ms": round(p95, 4),
+                       "samples": len(lst), "tflops": round(tf, 1),
                        "frac_of_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    # stage_grad_reduce alone (HBM-bound): (M + 1) gradient buffers move per call.
+    red_gbs = (M + 1) * gb / (red_ms * 1e-3) / 1e9
+    grad_reduce = {"ms": round(red_ms, 4), "GB/s": round(red_gbs, 1), "frac_of_hbm_peak": round(red_gbs / PEAK_HBM_GBS, 4),
+                   "bytes": (M + 1) * gb}
     # Roofline of the dominant kernel: the MFMA GEMM on the largest forward shape of this stage
     # (the MLP up projection), timed alone with HIP events on its stream.
     roof = None
@@ -214,7 +228,7 @@ def main():
                 traffic = json.load(open(tpath)).get(f"{T}x{N_up}x{shape.hidden}")
             except Exception:
                 traffic = None
-        roof = {"bound": "mfma", "kernel": f"gemm_mfma_kernel NN {T}x{N_up}x{shape.hidden} bf16", "achieved": round(ach, 1),
+        roof = {"bound": "mfma", "kernel": f"gemm_mfma_dl_kernel NN {T}x{N_up}x{shape.hidden} bf16", "achieved": round(ach, 1),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
                 "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic}
 
@@ -240,6 +254,7 @@ def main():
                    "step_tflop": round(step_flops / 1e12, 3)},
         "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "tasks": tasks,
+        "grad_reduce": grad_reduce,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

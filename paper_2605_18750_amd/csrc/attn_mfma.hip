@@ -1,8 +1,10 @@
 // bf16 MFMA attention for gfx950: tiled online-softmax forward over packed segments with GQA,
 // causal or bidirectional masks and head_dim 64 / 80 / 128.
 //
-// Forward.  A workgroup (4 wavefronts) owns one query tile (up to 256 rows inside one segment)
-// of one query head; each wavefront owns 64 query rows.  Keys and values stream through LDS in
+// Forward.  A workgroup (8 wavefronts, two per SIMD) owns one query tile (up to 256 rows inside one
+// segment) of one query head; each wavefront owns 32 query rows and stays under 256 registers, so
+// that the softmax arithmetic of one wavefront runs under the MFMAs of the other one on its SIMD.
+// Keys and values stream through LDS in
 // steps of 64 rows with two stages (global loads of step k+1 are in flight while step k runs).
 // Scores are computed TRANSPOSED, S^T[key, query] = K Q^T with v_mfma_f32_32x32x16_bf16, so
 // that a lane holds one query column: the softmax row statistics are lane-local except one
