@@ -76,6 +76,41 @@ def cpu_baseline(shape, T_sample: int):
                       f"{dt:.1f} s wall"}
 
 
+def gemm_roofline(shape, T, Bw, s, gen, n_launch=20):
+    """The bf16 MFMA GEMM [T, hidden] x [hidden, N_up] alone: HIP events on the launch stream."""
+    import torch
+    import paper_2605_18750_amd as R
+    N_up = (2 if shape.mlp_kind == "swiglu" else 1) * shape.ffn
+    A = torch.empty((T, shape.hidden), dtype=torch.bfloat16, device=Bw.device).normal_(0.0, 1.0, generator=gen)
+    Cc = torch.empty((T, N_up), dtype=torch.bfloat16, device=Bw.device)
+
+    def launch():
+        R.rrfp_gemm(A, Bw, Cc, None, T, N_up, shape.hidden, shape.hidden, N_up, N_up, N_up, 0, 0, 1, 1,
+                    R.RRFP_GEMM_MFMA, s)
+    with torch.cuda.stream(s):
+        for _ in range(3):
+            launch()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record(s)
+        for _ in range(n_launch):
+            launch()
+        g1.record(s)
+    torch.cuda.synchronize()
+    g_ms = g0.elapsed_time(g1) / n_launch
+    g_fl = 2.0 * T * N_up * shape.hidden
+    ach = g_fl / (g_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gemm_mfma_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"{T}x{N_up}x{shape.hidden}")
+        except Exception:
+            traffic = None
+    return {"bound": "mfma", "kernel": f"gemm_mfma_dl_kernel NN {T}x{N_up}x{shape.hidden} bf16", "achieved": round(ach, 1),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+            "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +118,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="language")
     ap.add_argument("--streams", type=int, default=1, help="streams the tasks are dealt to (B/F/W order)")
+    ap.add_argument("--only", default="step", choices=["step", "gemm", "copy"],
+                    help="gemm: launch only the roofline GEMM (for counter runs); copy: a 2 GiB device copy, the "
+                         "calibration of the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     args = ap.parse_args()
@@ -99,6 +137,23 @@ def main():
     R.lib()   # fails loudly if the HIP library is not built
     shape = {"language": SI.LANGUAGE, "wide": SI.WIDE_GQA, "vision": SI.VISION, "multimodal": SI.MULTIMODAL,
              "tiny": SI.TINY}[args.workload]
+    if args.only != "step":
+        torch.cuda.set_device(0)
+        gen = torch.Generator(device="cuda:0")
+        gen.manual_seed(SI.BASE_SEED)
+        if args.only == "copy":
+            src = torch.empty(1 << 31, dtype=torch.uint8, device="cuda:0")
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            print(json.dumps({"only": "copy", "bytes_read": 1 << 31, "bytes_written": 1 << 31, "launches": 3}))
+            return
+        T = max(int(SI.default_cu_seqlens(shape, j)[-1]) for j in range(shape.n_microbatches))
+        N_up = (2 if shape.mlp_kind == "swiglu" else 1) * shape.ffn
+        Bw = torch.empty((shape.hidden, N_up), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, shape.w_std, generator=gen)
+        print(json.dumps({"only": "gemm", "roofline": gemm_roofline(shape, T, Bw, torch.cuda.Stream(), gen, n_launch=args.steps)}))
+        return
     M = shape.n_microbatches
     cus = [SI.default_cu_seqlens(shape, j) for j in range(M)]
     T_max = max(int(c[-1]) for c in cus)
@@ -199,38 +254,8 @@ def main():
     # (the MLP up projection), timed alone with HIP events on its stream.
     roof = None
     if shape.dtype == "bf16":
-        T = T_max
-        N_up = (2 if shape.mlp_kind == "swiglu" else 1) * shape.ffn
-        A = torch.empty((T, shape.hidden), dtype=tdt, device=dev).normal_(0.0, 1.0, generator=gen)
         off, (r, c) = R.stage_param_layout(cfg, 0, R.STAGE_P_WUP)
-        Bw = params[off:off + r * c].view(r, c)
-        Cc = torch.empty((T, N_up), dtype=tdt, device=dev)
-        s = streams[0]
-        n_launch = 20
-        with torch.cuda.stream(s):
-            for _ in range(3):
-                R.rrfp_gemm(A, Bw, Cc, None, T, N_up, shape.hidden, shape.hidden, N_up, N_up, N_up, 0, 0, 1, 1,
-                            R.RRFP_GEMM_MFMA, s)
-            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            g0.record(s)
-            for _ in range(n_launch):
-                R.rrfp_gemm(A, Bw, Cc, None, T, N_up, shape.hidden, shape.hidden, N_up, N_up, N_up, 0, 0, 1, 1,
-                            R.RRFP_GEMM_MFMA, s)
-            g1.record(s)
-        torch.cuda.synchronize()
-        g_ms = g0.elapsed_time(g1) / n_launch
-        g_fl = 2.0 * T * N_up * shape.hidden
-        ach = g_fl / (g_ms * 1e-3) / 1e12
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "gemm_mfma_traffic.json")
-        if os.path.exists(tpath):
-            try:
-                traffic = json.load(open(tpath)).get(f"{T}x{N_up}x{shape.hidden}")
-            except Exception:
-                traffic = None
-        roof = {"bound": "mfma", "kernel": f"gemm_mfma_dl_kernel NN {T}x{N_up}x{shape.hidden} bf16", "achieved": round(ach, 1),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic}
+        roof = gemm_roofline(shape, T_max, params[off:off + r * c].view(r, c), streams[0], gen)
 
     torch.cuda.synchronize()
     R.stage_destroy(st)
