@@ -197,8 +197,44 @@ class SimResult:
     deadlock: bool
 
 
+_MASK = (1 << 64) - 1
+
+
+def splitmix64(x: int) -> int:
+    """The splitmix64 output function (Steele, Lea, Flood 2014) on x + golden-ratio increment."""
+    z = (x + 0x9E3779B97F4A7C15) & _MASK
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK
+    return z ^ (z >> 31)
+
+
+def task_uniforms(seed: int, stage: int, d: int, j: int, c: int, M: int, C: int):
+    """Two uniforms in [0, 1) that depend only on (seed, task identity): paired jitter patterns for
+    runs that execute the same tasks in different orders (Sec. 7.6 protocol)."""
+    k = ((stage * 3 + d) * C + c) * M + j
+    h1 = splitmix64(seed ^ splitmix64(2 * k))
+    h2 = splitmix64(seed ^ splitmix64(2 * k + 1))
+    return (h1 >> 11) * 2.0 ** -53, (h2 >> 11) * 2.0 ** -53
+
+
+@dataclass
+class Jitter:
+    """Compute-path jitter of Sec. 7.6: e_t = 0.9 e_{t-1} + 0.1 c_t per stage over its F/B tasks in
+    execution order; with probability p a delay alpha * max(base, e_t) * (0.5 + r_t), r_t ~ U(0,1),
+    is added to the task.  Reading: e starts at the first measured c; W tasks are not delayed and do
+    not enter the average (the paper delays F/B tasks)."""
+    p: float = 0.0
+    base: float = 0.0
+    alpha: float = 0.0
+    seed: int = 0
+
+
+# J0..J3 of the robustness table (Sec. 7.6): p_j, base delay in seconds, alpha
+JITTER_LEVELS = {"J0": (0.0, 0.0, 0.0), "J1": (0.1, 5e-3, 0.5), "J2": (0.2, 10e-3, 1.0), "J3": (0.3, 15e-3, 1.5)}
+
+
 def simulate(N: int, M: int, dur, *, C: int = 1, hint: int = HINT_BF, limit: int = 0, latency: float = 0.0,
-             forward_only: bool = False, backward_only: bool = False) -> SimResult:
+             forward_only: bool = False, backward_only: bool = False, jitter: Jitter | None = None) -> SimResult:
     """N stages, M microbatches, C chunks per stage.  dur(direction, stage, chunk, microbatch) -> seconds.
 
     forward_only / backward_only give the reference executions of Sec. 6: all forward work available
@@ -223,6 +259,7 @@ def simulate(N: int, M: int, dur, *, C: int = 1, hint: int = HINT_BF, limit: int
     max_b = [0] * N
     max_D = [0] * N
     done = [0] * N
+    ema = [None] * N
 
     def deliver(s, d, j, c):
         if d == F:
@@ -298,6 +335,11 @@ def simulate(N: int, M: int, dur, *, C: int = 1, hint: int = HINT_BF, limit: int
                         fwd_held[0].add((j, 0))
                         max_f[0] = max(max_f[0], len(fwd_held[0]))
                     p = dur(d, s, c, j)
+                    if jitter is not None and d != W:
+                        ema[s] = p if ema[s] is None else 0.9 * ema[s] + 0.1 * p
+                        u1, u2 = task_uniforms(jitter.seed, s, d, j, c, M, C)
+                        if u1 < jitter.p:
+                            p = p + jitter.alpha * max(jitter.base, ema[s]) * (0.5 + u2)
                     running[s] = (task, t, t + p)
                     trace[s].append((d, j, c, t, t + p))
                     busy[s] += p

@@ -1,0 +1,402 @@
+// Ready-set arbiter (App. A, Algorithm 1; hint orders of Sec. 7.1 and 7.7; backpressure of App. C.2)
+// and a discrete-event pipeline simulator (setting of Sec. 6 plus message latency and the jitter model
+// of Sec. 7.6).  Host code; no GPU calls.
+//
+// Ready buffers are bitmaps, one per (direction, chunk): NextByPriority is a find-first-set over at
+// most C words groups, so an arbitration costs O(C * M / 64) with no allocation and no locking.
+#include "../../include/rrfp_arbiter.h"
+
+// Simulated times must be reproducible bit for bit by an independent implementation: no fused
+// multiply-adds in this file.
+#pragma clang fp contract(off)
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <queue>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_tls_error;
+
+struct Bits {
+  std::vector<uint64_t> w;
+  int n = 0;
+  void init(int bits) { n = bits; w.assign((bits + 63) / 64, 0); }
+  void clear() { std::fill(w.begin(), w.end(), 0); }
+  bool test(int i) const { return (w[i >> 6] >> (i & 63)) & 1; }
+  void set(int i) { w[i >> 6] |= (uint64_t)1 << (i & 63); }
+  void reset(int i) { w[i >> 6] &= ~((uint64_t)1 << (i & 63)); }
+  int first() const {
+    for (size_t k = 0; k < w.size(); ++k)
+      if (w[k]) return (int)(k * 64 + __builtin_ctzll(w[k]));
+    return -1;
+  }
+};
+
+}  // namespace
+
+struct arbiter {
+  arbiter_config c;
+  // ready[dir][chunk], done[dir][chunk]: bit j = microbatch j
+  std::vector<Bits> ready[3], done[3];
+  int64_t count[3] = {0, 0, 0};     // n_f, n_b, n_w
+  int64_t n_ready[3] = {0, 0, 0};
+  int phase = 0;                    // position inside the current round of BF / FB / BFW
+  bool in_flight = false;
+  arbiter_task flight{};
+  std::vector<arbiter_task> fixed;  // binding sequence (FIXED_1F1B)
+  size_t fixed_pos = 0;
+  std::string error;
+
+  int64_t target() const { return (int64_t)(c.hint == ARB_HINT_BFW ? 3 : 2) * c.n_microbatches * c.n_chunks; }
+  int64_t completed() const { return count[0] + count[1] + count[2]; }
+  bool backpressure() const { return c.buffer_limit > 0 && count[ARB_F] - count[ARB_B] >= c.buffer_limit; }
+};
+
+namespace {
+
+int fail(arbiter* a, int code, const char* fmt, ...) {
+  char buf[256];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (a) a->error = buf; else g_tls_error = buf;
+  return code;
+}
+
+// NextByPriority: forward - smallest chunk, backward and W - largest chunk; ties - smallest microbatch.
+bool pick(arbiter* a, int dir, arbiter_task* out) {
+  if (a->n_ready[dir] == 0) return false;
+  const int C = a->c.n_chunks;
+  for (int k = 0; k < C; ++k) {
+    const int c = dir == ARB_F ? k : C - 1 - k;
+    const int j = a->ready[dir][c].first();
+    if (j >= 0) {
+      a->ready[dir][c].reset(j);
+      --a->n_ready[dir];
+      *out = arbiter_task{dir, j, c};
+      return true;
+    }
+  }
+  return false;
+}
+
+bool take_exact(arbiter* a, int dir, int j, int c, arbiter_task* out) {
+  if (!a->ready[dir][c].test(j)) return false;
+  a->ready[dir][c].reset(j);
+  --a->n_ready[dir];
+  *out = arbiter_task{dir, j, c};
+  return true;
+}
+
+void build_1f1b(arbiter* a) {
+  const int M = a->c.n_microbatches;
+  const int warm = std::min(a->c.n_stages - 1 - a->c.stage, M);
+  a->fixed.clear();
+  for (int j = 0; j < warm; ++j) a->fixed.push_back(arbiter_task{ARB_F, j, 0});
+  int nf = warm, nb = 0;
+  while (nb < M) {
+    if (nf < M) a->fixed.push_back(arbiter_task{ARB_F, nf++, 0});
+    a->fixed.push_back(arbiter_task{ARB_B, nb++, 0});
+  }
+}
+
+bool arbitrate(arbiter* a, arbiter_task* out) {
+  const arbiter_config& c = a->c;
+  const bool bfw = c.hint == ARB_HINT_BFW;
+  if (c.hint == ARB_HINT_FIXED_1F1B) {
+    const arbiter_task& want = a->fixed[a->fixed_pos];
+    if (take_exact(a, want.dir, want.microbatch, want.chunk, out)) { ++a->fixed_pos; return true; }
+    return false;
+  }
+  if (a->backpressure()) {
+    if (c.n_chunks == 1) {
+      if (pick(a, ARB_B, out)) return true;
+      return bfw && pick(a, ARB_W, out);
+    }
+    // interleaved drain order: first unfinished microbatch, its next required task, else wait
+    for (int j = 0; j < c.n_microbatches; ++j) {
+      int dir = -1, ch = -1;
+      for (int k = 0; k < c.n_chunks && dir < 0; ++k)
+        if (!a->done[ARB_F][k].test(j)) { dir = ARB_F; ch = k; }
+      for (int k = c.n_chunks - 1; k >= 0 && dir < 0; --k)
+        if (!a->done[ARB_B][k].test(j)) { dir = ARB_B; ch = k; }
+      if (dir < 0) continue;
+      if (take_exact(a, dir, j, ch, out)) return true;
+      return bfw && pick(a, ARB_W, out);
+    }
+    return bfw && pick(a, ARB_W, out);
+  }
+  if (c.hint == ARB_HINT_B_PRIO) return pick(a, ARB_B, out) || pick(a, ARB_F, out);
+  if (c.hint == ARB_HINT_F_PRIO) return pick(a, ARB_F, out) || pick(a, ARB_B, out);
+  // rounds: BF and BFW check backward then forward, FB forward then backward
+  const int order[2] = {c.hint == ARB_HINT_FB ? ARB_F : ARB_B, c.hint == ARB_HINT_FB ? ARB_B : ARB_F};
+  for (int k = 0; k < 2; ++k) {
+    const int d = order[a->phase];
+    a->phase ^= 1;
+    if (pick(a, d, out)) return true;
+  }
+  a->phase = 0;   // neither direction ready: the next round starts from its first direction
+  return bfw && pick(a, ARB_W, out);
+}
+
+bool valid_cfg(const arbiter_config* c) {
+  if (!c) return false;
+  if (c->n_microbatches < 1 || c->n_chunks < 1 || c->n_stages < 1 || c->stage < 0 || c->stage >= c->n_stages) return false;
+  if (c->hint < ARB_HINT_BF || c->hint > ARB_HINT_FIXED_1F1B || c->buffer_limit < 0) return false;
+  if (c->hint == ARB_HINT_FIXED_1F1B && c->n_chunks != 1) return false;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+arbiter_t* arbiter_create(const arbiter_config* cfg) {
+  if (!valid_cfg(cfg)) { fail(nullptr, ARB_EINVAL, "arbiter_create: invalid configuration"); return nullptr; }
+  arbiter* a = new (std::nothrow) arbiter();
+  if (!a) { fail(nullptr, ARB_EINVAL, "arbiter_create: out of memory"); return nullptr; }
+  a->c = *cfg;
+  for (int d = 0; d < 3; ++d) {
+    a->ready[d].resize(cfg->n_chunks);
+    a->done[d].resize(cfg->n_chunks);
+    for (int k = 0; k < cfg->n_chunks; ++k) { a->ready[d][k].init(cfg->n_microbatches); a->done[d][k].init(cfg->n_microbatches); }
+  }
+  if (cfg->hint == ARB_HINT_FIXED_1F1B) build_1f1b(a);
+  arbiter_reset(a);
+  return a;
+}
+
+void arbiter_destroy(arbiter_t* a) { delete a; }
+
+int arbiter_reset(arbiter_t* a) {
+  if (!a) return fail(nullptr, ARB_EINVAL, "arbiter handle is NULL");
+  for (int d = 0; d < 3; ++d) {
+    for (auto& b : a->ready[d]) b.clear();
+    for (auto& b : a->done[d]) b.clear();
+    a->count[d] = 0;
+    a->n_ready[d] = 0;
+  }
+  a->phase = 0;
+  a->in_flight = false;
+  a->fixed_pos = 0;
+  if (a->c.stage == 0) {   // stage 0 admits the first chunk's forwards itself
+    for (int j = 0; j < a->c.n_microbatches; ++j) a->ready[ARB_F][0].set(j);
+    a->n_ready[ARB_F] = a->c.n_microbatches;
+  }
+  return ARB_OK;
+}
+
+int arbiter_post_ready(arbiter_t* a, int32_t dir, int32_t j, int32_t ch) {
+  if (!a) return fail(nullptr, ARB_EINVAL, "arbiter handle is NULL");
+  if ((dir != ARB_F && dir != ARB_B) || j < 0 || j >= a->c.n_microbatches || ch < 0 || ch >= a->c.n_chunks)
+    return fail(a, ARB_EINVAL, "post_ready: bad task (dir %d, microbatch %d, chunk %d)", dir, j, ch);
+  const bool flying = a->in_flight && a->flight.dir == dir && a->flight.microbatch == j && a->flight.chunk == ch;
+  if (a->ready[dir][ch].test(j) || a->done[dir][ch].test(j) || flying)
+    return fail(a, ARB_ESTATE, "post_ready: %c(%d, chunk %d) already present or done", dir == ARB_F ? 'F' : 'B', j, ch);
+  if (dir == ARB_B && !a->done[ARB_F][ch].test(j))
+    return fail(a, ARB_ESTATE, "post_ready: backward input of (%d, chunk %d) before its local forward completed", j, ch);
+  a->ready[dir][ch].set(j);
+  ++a->n_ready[dir];
+  return ARB_OK;
+}
+
+int arbiter_next(arbiter_t* a, arbiter_task* out) {
+  if (!a || !out) return fail(a, ARB_EINVAL, "arbiter_next: NULL argument");
+  if (a->in_flight) return fail(a, ARB_ESTATE, "arbiter_next: a task is still in flight");
+  if (a->completed() >= a->target()) return ARB_DONE;
+  if (!arbitrate(a, out)) return ARB_WAIT;
+  a->in_flight = true;
+  a->flight = *out;
+  return ARB_TASK;
+}
+
+int arbiter_complete(arbiter_t* a, const arbiter_task* t) {
+  if (!a || !t) return fail(a, ARB_EINVAL, "arbiter_complete: NULL argument");
+  if (!a->in_flight || t->dir != a->flight.dir || t->microbatch != a->flight.microbatch || t->chunk != a->flight.chunk)
+    return fail(a, ARB_ESTATE, "arbiter_complete: not the task in flight");
+  a->in_flight = false;
+  ++a->count[t->dir];
+  a->done[t->dir][t->chunk].set(t->microbatch);
+  if (t->dir == ARB_F && a->c.stage == a->c.n_stages - 1 && t->chunk == a->c.n_chunks - 1) {
+    // last stage, last chunk: the forward output becomes the local backward input (App. C.1)
+    a->ready[ARB_B][t->chunk].set(t->microbatch);
+    ++a->n_ready[ARB_B];
+  }
+  if (t->dir == ARB_B && a->c.hint == ARB_HINT_BFW) {
+    a->ready[ARB_W][t->chunk].set(t->microbatch);
+    ++a->n_ready[ARB_W];
+  }
+  return ARB_OK;
+}
+
+int arbiter_counters(const arbiter_t* a, int64_t out[5]) {
+  if (!a || !out) return ARB_EINVAL;
+  out[0] = a->count[0]; out[1] = a->count[1]; out[2] = a->count[2];
+  out[3] = a->backpressure() ? 1 : 0;
+  out[4] = a->completed();
+  return ARB_OK;
+}
+
+const char* arbiter_last_error(const arbiter_t* a) { return a ? a->error.c_str() : g_tls_error.c_str(); }
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------------
+// Simulator
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+inline uint64_t splitmix64(uint64_t x) {
+  uint64_t z = x + 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+struct Arrival {
+  double time;
+  int32_t stage, dir, microbatch, chunk;
+  bool operator>(const Arrival& o) const { return time > o.time; }
+};
+
+}  // namespace
+
+extern "C" int rrfp_sim_run(const rrfp_sim_config* cfg, const double* dur_f, const double* dur_b, const double* dur_w,
+                            rrfp_sim_result* result, double* per_stage, rrfp_sim_event* trace, int64_t trace_cap) {
+  if (!cfg || !result || !dur_f || !dur_b) return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: NULL argument");
+  const int N = cfg->n_stages, M = cfg->n_microbatches, C = cfg->n_chunks;
+  if (N < 1 || M < 1 || C < 1 || cfg->mode < 0 || cfg->mode > 2 || cfg->latency < 0 || (trace && trace_cap < 0))
+    return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: invalid configuration");
+  if (cfg->hint == ARB_HINT_BFW && !dur_w) return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: BFW needs dur_w");
+  const bool fwd_only = cfg->mode == 1, bwd_only = cfg->mode == 2, only = cfg->mode != 0;
+  std::vector<arbiter*> st(N, nullptr);
+  auto cleanup = [&]() { for (auto* a : st) arbiter_destroy(a); };
+  for (int s = 0; s < N; ++s) {
+    arbiter_config ac{M, C, cfg->hint, cfg->buffer_limit, s, N};
+    if (only) {
+      // reference executions: one direction only; the stage index is set so that no turn-around and
+      // no self-admission happens inside the arbiter, the simulator seeds the first buffer itself
+      ac.hint = ARB_HINT_BF;
+      ac.buffer_limit = 0;
+    }
+    st[s] = arbiter_create(&ac);
+    if (!st[s]) { cleanup(); return ARB_EINVAL; }
+  }
+  struct Run { bool busy = false; arbiter_task t{}; double end = 0; };
+  std::vector<Run> run(N);
+  std::priority_queue<Arrival, std::vector<Arrival>, std::greater<Arrival>> arrivals;
+  std::vector<double> busy(N, 0.0), ema(N, 0.0);
+  std::vector<char> ema_set(N, 0);
+  std::vector<int64_t> fwd_held(N, 0), bwd_held(N, 0), max_f(N, 0), max_b(N, 0), max_D(N, 0), done(N, 0);
+  const int64_t only_target = (int64_t)M * C;
+  int64_t n_events = 0;
+  double makespan = 0.0;
+
+  auto deliver = [&](int s, int dir, int j, int c) {
+    arbiter_post_ready(st[s], dir, j, c);
+    if (dir == ARB_F) { if (++fwd_held[s] > max_f[s]) max_f[s] = fwd_held[s]; }
+    else { if (++bwd_held[s] > max_b[s]) max_b[s] = bwd_held[s]; }
+  };
+  if (bwd_only) {
+    // all backward work available at the last stage: mark the local forwards as done first
+    for (int s = 0; s < N; ++s)
+      for (int c = 0; c < C; ++c)
+        for (int j = 0; j < M; ++j) st[s]->done[ARB_F][c].set(j);
+    for (int j = 0; j < M; ++j) deliver(N - 1, ARB_B, j, C - 1);
+    // stage 0's self-admitted forwards are not part of this reference run
+    st[0]->ready[ARB_F][0].clear();
+    st[0]->n_ready[ARB_F] = 0;
+  }
+  auto finish = [&](int s, const arbiter_task& t, double at) {
+    if (!(fwd_only && s == N - 1 && t.dir == ARB_F && t.chunk == C - 1)) {
+      arbiter_complete(st[s], &t);
+    } else {
+      // forward-only reference: no turn-around at the last stage
+      st[s]->in_flight = false;
+      ++st[s]->count[ARB_F];
+      st[s]->done[ARB_F][t.chunk].set(t.microbatch);
+    }
+    ++done[s];
+    if (t.dir == ARB_F) {
+      if (s + 1 < N) arrivals.push(Arrival{at + cfg->latency, s + 1, ARB_F, t.microbatch, t.chunk});
+      else if (t.chunk + 1 < C) arrivals.push(Arrival{at + cfg->latency, 0, ARB_F, t.microbatch, t.chunk + 1});
+      else if (!fwd_only) { if (++bwd_held[s] > max_b[s]) max_b[s] = bwd_held[s]; }   // local move (done inside the arbiter)
+    } else if (t.dir == ARB_B) {
+      if (!bwd_only) --fwd_held[s];
+      --bwd_held[s];
+      if (s > 0) arrivals.push(Arrival{at + cfg->latency, s - 1, ARB_B, t.microbatch, t.chunk});
+      else if (t.chunk > 0) arrivals.push(Arrival{at + cfg->latency, N - 1, ARB_B, t.microbatch, t.chunk - 1});
+    }
+  };
+  auto all_done = [&]() {
+    for (int s = 0; s < N; ++s) {
+      if (only ? done[s] < only_target : st[s]->completed() < st[s]->target()) return false;
+      if (run[s].busy) return false;
+    }
+    return true;
+  };
+
+  double t = 0.0;
+  int deadlock = 0;
+  for (;;) {
+    for (int s = 0; s < N; ++s)
+      if (run[s].busy && run[s].end <= t) { run[s].busy = false; finish(s, run[s].t, run[s].end); }
+    while (!arrivals.empty() && arrivals.top().time <= t) {
+      const Arrival a = arrivals.top();
+      arrivals.pop();
+      deliver(a.stage, a.dir, a.microbatch, a.chunk);
+    }
+    for (int s = 0; s < N; ++s) {
+      if (run[s].busy) continue;
+      if (only && done[s] >= only_target) continue;
+      const int64_t D = st[s]->count[ARB_F] - st[s]->count[ARB_B];
+      if (D > max_D[s]) max_D[s] = D;
+      arbiter_task task;
+      if (arbiter_next(st[s], &task) != ARB_TASK) continue;
+      if (s == 0 && task.dir == ARB_F && task.chunk == 0) { if (++fwd_held[0] > max_f[0]) max_f[0] = fwd_held[0]; }
+      const size_t idx = ((size_t)s * C + task.chunk) * M + task.microbatch;
+      double p = task.dir == ARB_F ? dur_f[idx] : task.dir == ARB_B ? dur_b[idx] : dur_w[idx];
+      if (cfg->jitter_p > 0.0 && task.dir != ARB_W) {
+        ema[s] = ema_set[s] ? 0.9 * ema[s] + 0.1 * p : p;
+        ema_set[s] = 1;
+        const uint64_t k = (((uint64_t)s * 3 + task.dir) * C + task.chunk) * M + task.microbatch;
+        const double u1 = (double)(splitmix64(cfg->jitter_seed ^ splitmix64(2 * k)) >> 11) * 0x1.0p-53;
+        const double u2 = (double)(splitmix64(cfg->jitter_seed ^ splitmix64(2 * k + 1)) >> 11) * 0x1.0p-53;
+        if (u1 < cfg->jitter_p) p = p + cfg->jitter_alpha * std::max(cfg->jitter_base, ema[s]) * (0.5 + u2);
+      }
+      run[s].busy = true;
+      run[s].t = task;
+      run[s].end = t + p;
+      busy[s] += p;
+      if (run[s].end > makespan) makespan = run[s].end;
+      if (trace && n_events < trace_cap) trace[n_events] = rrfp_sim_event{s, task.dir, task.microbatch, task.chunk, t, t + p};
+      ++n_events;
+    }
+    if (all_done()) break;
+    bool have = false;
+    double nxt = 0.0;
+    for (int s = 0; s < N; ++s)
+      if (run[s].busy && (!have || run[s].end < nxt)) { nxt = run[s].end; have = true; }
+    if (!arrivals.empty() && (!have || arrivals.top().time < nxt)) { nxt = arrivals.top().time; have = true; }
+    if (!have) { deadlock = 1; break; }
+    t = nxt;
+  }
+  result->makespan = makespan;
+  result->n_events = n_events;
+  result->deadlock = deadlock;
+  if (per_stage)
+    for (int s = 0; s < N; ++s) {
+      per_stage[4 * s + 0] = busy[s];
+      per_stage[4 * s + 1] = (double)max_f[s];
+      per_stage[4 * s + 2] = (double)max_b[s];
+      per_stage[4 * s + 3] = (double)max_D[s];
+    }
+  cleanup();
+  return ARB_OK;
+}

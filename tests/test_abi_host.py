@@ -22,10 +22,11 @@ def _cfg(**kw):
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "rrfp_stage.h")).read() + open(os.path.join(ROOT, "include", "rrfp_kernels.h")).read()
+    inc = os.path.join(ROOT, "include")
+    hdr = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b((?:stage|rrfp)_[A-Za-z_]+)\s*\(", hdr))
-    assert {"stage_create", "stage_F", "stage_B", "stage_W", "stage_grad_reduce"} <= names
+    names = set(re.findall(r"\b((?:stage|rrfp|arbiter)_[A-Za-z_0-9]+)\s*\(", hdr))
+    assert {"stage_create", "stage_F", "stage_B", "stage_W", "stage_grad_reduce", "arbiter_next", "rrfp_sim_run"} <= names
     L = ctypes.CDLL(R.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n

@@ -253,3 +253,40 @@ def test_bfw_weight_task_rule_on_hand_worked_states():
     a.complete((A.W, 0, 0))
     assert a.next() is None
     assert a.n_target() == 6
+
+
+def test_jitter_model_statistics_and_pairing():
+    # Sec. 7.6: constant compute time c -> the moving average stays at c; a delay is injected with
+    # probability p and has mean alpha * max(base, c) * 1.0 (E[0.5 + r] = 1) and range [0.5, 1.5) of it
+    N, M, c0 = 1, 4000, 2e-3
+    p, base, alpha = A.JITTER_LEVELS["J2"]
+    assert (p, base, alpha) == (0.2, 10e-3, 1.0)          # the table's J2 row
+    jit = A.Jitter(p=p, base=base, alpha=alpha, seed=11)
+    r = A.simulate(N, M, lambda d, s, c, j: c0, jitter=jit)
+    extra = [(t1 - t0) - c0 for _, _, _, t0, t1 in r.trace[0]]
+    hit = [x for x in extra if x > 1e-12]
+    assert abs(len(hit) / len(extra) - p) < 0.02
+    unit = alpha * max(base, c0)
+    assert min(hit) >= 0.5 * unit * (1 - 1e-9) and max(hit) < 1.5 * unit
+    assert abs(sum(hit) / len(hit) / unit - 1.0) < 0.03
+    # p = 0 leaves the run untouched
+    r0 = A.simulate(2, 5, lambda d, s, c, j: 1.0 + 0.1 * j, jitter=A.Jitter())
+    r1 = A.simulate(2, 5, lambda d, s, c, j: 1.0 + 0.1 * j)
+    assert r0.trace == r1.trace
+    # the pattern is a function of the task, not of the execution order (paired patterns)
+    u = A.task_uniforms(5, 2, A.B, 3, 0, 8, 1)
+    assert u == A.task_uniforms(5, 2, A.B, 3, 0, 8, 1) and 0.0 <= u[0] < 1.0 and 0.0 <= u[1] < 1.0
+    assert u != A.task_uniforms(5, 2, A.F, 3, 0, 8, 1)
+
+
+def test_splitmix64_reference_values():
+    # first outputs of splitmix64 seeded with 0 and with 1234567 (values published with the
+    # reference implementation by Vigna; state advances by the golden-ratio increment)
+    x, outs = 0, []
+    for _ in range(3):
+        outs.append(A.splitmix64(x)); x = (x + 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
+    assert outs == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+    x, outs = 1234567, []
+    for _ in range(2):
+        outs.append(A.splitmix64(x)); x = (x + 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
+    assert outs == [6457827717110365317, 3203168211198807973]
