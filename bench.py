@@ -111,6 +111,58 @@ def gemm_roofline(shape, T, Bw, s, gen, n_launch=20):
             "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic}
 
 
+def pipeline_study(shape, cus, per_mb, n_stages, with_oracle):
+    """Replays measured per-microbatch task times (seconds) through the native simulator: N identical
+    stages, fixed 1F1B against readiness-driven dispatch (BF hint with unsplit backward, BFW hint with
+    the B/W split), under the jitter levels of the robustness table, 10 seeds each."""
+    import numpy as np
+    from paper_2605_18750_amd import arbiter as A
+    M = len(cus)
+    N = n_stages
+    f = np.tile(np.array(per_mb["F"])[None, None, :], (N, 1, 1))
+    b = np.tile(np.array(per_mb["B"])[None, None, :], (N, 1, 1))
+    w = np.tile(np.array(per_mb["W"])[None, None, :], (N, 1, 1))
+    levels = {"J0": (0.0, 0.0, 0.0), "J1": (0.1, 5e-3, 0.5), "J2": (0.2, 10e-3, 1.0), "J3": (0.3, 15e-3, 1.5)}
+    methods = {"1f1b": (A.ARB_HINT_FIXED_1F1B, b + w, None), "rrfp_bf": (A.ARB_HINT_BF, b + w, None),
+               "rrfp_bfw": (A.ARB_HINT_BFW, b, w)}
+    table = {}
+    for lv, (p, base, alpha) in levels.items():
+        row = {}
+        for name, (hint, bb, ww) in methods.items():
+            ms, bub = [], []
+            for seed in range(1 if p == 0.0 else 10):
+                r = A.rrfp_sim_run(N, M, f, bb, ww, hint=hint, buffer_limit=32, jitter=(p, base, alpha, 1000 + seed),
+                                   want_trace=False)
+                assert not r["deadlock"]
+                ms.append(r["makespan"] * 1e3)
+                bub.append(1.0 - float(r["busy"].sum()) / (N * r["makespan"]))
+            row[name] = {"iteration_ms": round(float(np.mean(ms)), 3), "bubble_frac": round(float(np.mean(bub)), 4)}
+        for name in ("rrfp_bf", "rrfp_bfw"):
+            row[name]["speedup_vs_1f1b"] = round(row["1f1b"]["iteration_ms"] / row[name]["iteration_ms"], 4)
+        table[lv] = row
+    # decision throughput of the native arbiter + event loop, and the oracle on a bounded sample
+    rng = np.random.default_rng(7)
+    Nb, Mb = 64, 2048
+    fb, bb = rng.uniform(0.5, 2.0, (Nb, 1, Mb)), rng.uniform(1.0, 4.0, (Nb, 1, Mb))
+    t0 = time.perf_counter()
+    r = A.rrfp_sim_run(Nb, Mb, fb, bb, None, want_trace=False)
+    native_rate = r["n_events"] / (time.perf_counter() - t0)
+    out = {"only": "pipeline", "metric": "simulated iteration time of an N-stage pipeline built from measured task times",
+           "workload": shape.name, "n_stages": N, "n_microbatches": M,
+           "tokens_per_microbatch": [int(c[-1]) for c in cus],
+           "task_ms": {k: [round(v * 1e3, 3) for v in per_mb[k]] for k in ("F", "B", "W")},
+           "buffer_limit": 32, "levels": table,
+           "simulator": {"tasks_per_s": round(native_rate), "n_stages": Nb, "n_microbatches": Mb}}
+    if with_oracle:
+        from oracle import arbiter_oracle as O
+        No, Mo = 8, 256
+        t0 = time.perf_counter()
+        ro = O.simulate(No, Mo, lambda d, s, c, j: float(fb[s, 0, j] if d == O.F else bb[s, 0, j]))
+        out["cpu_baseline"] = {"value": round(2 * No * Mo / (time.perf_counter() - t0)), "unit": "tasks/s", "cores": 1,
+                               "kind": "oracle", "sample": f"python oracle simulator, {No} stages x {Mo} microbatches"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -118,9 +170,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="language")
     ap.add_argument("--streams", type=int, default=1, help="streams the tasks are dealt to (B/F/W order)")
-    ap.add_argument("--only", default="step", choices=["step", "gemm", "copy"],
+    ap.add_argument("--only", default="step", choices=["step", "gemm", "copy", "pipeline"],
                     help="gemm: launch only the roofline GEMM (for counter runs); copy: a 2 GiB device copy, the "
-                         "calibration of the FETCH_SIZE / WRITE_SIZE counters")
+                         "calibration of the FETCH_SIZE / WRITE_SIZE counters; pipeline: measure the per-microbatch "
+                         "task times of the workload and replay them through the native pipeline simulator "
+                         "(fixed 1F1B against readiness-driven dispatch, jitter levels J0-J3)")
+    ap.add_argument("--pipeline-stages", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     args = ap.parse_args()
@@ -135,9 +190,11 @@ def main():
     import stage_inputs as SI
 
     R.lib()   # fails loudly if the HIP library is not built
+    if args.only == "pipeline" and args.workload == "language":
+        args.workload = "multimodal"      # the workload whose microbatches differ in cost
     shape = {"language": SI.LANGUAGE, "wide": SI.WIDE_GQA, "vision": SI.VISION, "multimodal": SI.MULTIMODAL,
              "tiny": SI.TINY}[args.workload]
-    if args.only != "step":
+    if args.only in ("gemm", "copy"):
         torch.cuda.set_device(0)
         gen = torch.Generator(device="cuda:0")
         gen.manual_seed(SI.BASE_SEED)
@@ -239,6 +296,13 @@ def main():
     streams = saved
     tasks = {}
     red_ms = float(np.median([t for _, t in per_kind.pop("R")]))
+    if args.only == "pipeline":
+        per_mb = {k: [float(np.median([t for jj, t in lst if jj == j])) * 1e-3 for j in range(M)] for k, lst in per_kind.items()}
+        torch.cuda.synchronize()
+        R.stage_destroy(st)
+        del arena
+        print(json.dumps(pipeline_study(shape, cus, per_mb, args.pipeline_stages, not args.no_cpu_baseline)))
+        return
     for kind, lst in per_kind.items():
         ms = float(np.median([t for _, t in lst]))
         tf = float(np.median([fl[j][kind] / (t * 1e-3) / 1e12 for j, t in lst]))
