@@ -96,6 +96,25 @@ typedef struct {
 int rrfp_sim_run(const rrfp_sim_config* cfg, const double* dur_f, const double* dur_b, const double* dur_w,
                  rrfp_sim_result* result, double* per_stage, rrfp_sim_event* trace, int64_t trace_cap);
 
+/* ---- jitter injector for real task streams (Sec. 7.6) ----------------------------------------------
+ * The per-stage state of the jitter model above, for a runtime that measures its own tasks: feed the
+ * measured compute time of each F/B task of the stage in execution order; the return value is the
+ * delay in seconds to add behind that task (0 when none is injected).  Same moving average, same
+ * counter-based uniforms as the simulator. */
+typedef struct jitter jitter_t;
+jitter_t* jitter_create(double p, double base_seconds, double alpha, uint64_t seed, int32_t stage,
+                        int32_t n_microbatches, int32_t n_chunks);
+void jitter_destroy(jitter_t* j);
+double jitter_next_delay(jitter_t* j, int32_t dir, int32_t microbatch, int32_t chunk, double compute_seconds);
+
+/* Enqueues on `stream` (a hipStream_t of the current device, NULL = the null stream) a one-wavefront
+ * kernel that returns once `seconds` of the device's constant-rate wall clock have passed: the
+ * device-side sleep the paper adds to a task's stream.  0 <= seconds <= 1; the kernel also stops after a
+ * bounded number of polls, so it ends even if the clock did not advance.  Returns ARB_OK, ARB_EINVAL,
+ * or ARB_ESTATE (a HIP call failed); rrfp_delay_last_error() has the text (thread-local). */
+int rrfp_delay(double seconds, void* stream);
+const char* rrfp_delay_last_error(void);
+
 #ifdef __cplusplus
 }
 #endif

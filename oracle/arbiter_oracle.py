@@ -229,6 +229,22 @@ class Jitter:
     seed: int = 0
 
 
+class JitterInjector:
+    """The per-stage state of the jitter model: feed it the measured compute time of each F/B task in
+    execution order, get the delay to add (0.0 when none is injected)."""
+
+    def __init__(self, jitter: Jitter, stage: int, M: int, C: int = 1):
+        self.j, self.stage, self.M, self.C = jitter, stage, M, C
+        self.e = None
+
+    def delay(self, d: int, microbatch: int, chunk: int, compute_seconds: float) -> float:
+        self.e = compute_seconds if self.e is None else 0.9 * self.e + 0.1 * compute_seconds
+        u1, u2 = task_uniforms(self.j.seed, self.stage, d, microbatch, chunk, self.M, self.C)
+        if u1 < self.j.p:
+            return self.j.alpha * max(self.j.base, self.e) * (0.5 + u2)
+        return 0.0
+
+
 # J0..J3 of the robustness table (Sec. 7.6): p_j, base delay in seconds, alpha
 JITTER_LEVELS = {"J0": (0.0, 0.0, 0.0), "J1": (0.1, 5e-3, 0.5), "J2": (0.2, 10e-3, 1.0), "J3": (0.3, 15e-3, 1.5)}
 
@@ -259,7 +275,7 @@ def simulate(N: int, M: int, dur, *, C: int = 1, hint: int = HINT_BF, limit: int
     max_b = [0] * N
     max_D = [0] * N
     done = [0] * N
-    ema = [None] * N
+    injectors = [JitterInjector(jitter, s, M, C) for s in range(N)] if jitter is not None else None
 
     def deliver(s, d, j, c):
         if d == F:
@@ -336,10 +352,7 @@ def simulate(N: int, M: int, dur, *, C: int = 1, hint: int = HINT_BF, limit: int
                         max_f[0] = max(max_f[0], len(fwd_held[0]))
                     p = dur(d, s, c, j)
                     if jitter is not None and d != W:
-                        ema[s] = p if ema[s] is None else 0.9 * ema[s] + 0.1 * p
-                        u1, u2 = task_uniforms(jitter.seed, s, d, j, c, M, C)
-                        if u1 < jitter.p:
-                            p = p + jitter.alpha * max(jitter.base, ema[s]) * (0.5 + u2)
+                        p = p + injectors[s].delay(d, j, c, p)
                     running[s] = (task, t, t + p)
                     trace[s].append((d, j, c, t, t + p))
                     busy[s] += p

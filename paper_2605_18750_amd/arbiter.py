@@ -65,6 +65,16 @@ def _lib():
         L.arbiter_last_error.restype = C.c_char_p
         L.rrfp_sim_run.argtypes = [C.POINTER(rrfp_sim_config), vp, vp, vp, C.POINTER(rrfp_sim_result), vp,
                                    C.POINTER(rrfp_sim_event), C.c_int64]
+        L.jitter_create.argtypes = [C.c_double, C.c_double, C.c_double, C.c_uint64, C.c_int32, C.c_int32, C.c_int32]
+        L.jitter_create.restype = vp
+        L.jitter_destroy.argtypes = [vp]
+        L.jitter_destroy.restype = None
+        L.jitter_next_delay.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_double]
+        L.jitter_next_delay.restype = C.c_double
+        L.rrfp_delay.argtypes = [C.c_double, vp]
+        L.rrfp_delay.restype = C.c_int
+        L.rrfp_delay_last_error.argtypes = []
+        L.rrfp_delay_last_error.restype = C.c_char_p
         for f in ("arbiter_reset", "arbiter_post_ready", "arbiter_next", "arbiter_complete", "arbiter_counters",
                   "rrfp_sim_run"):
             getattr(L, f).restype = C.c_int
@@ -149,3 +159,27 @@ def rrfp_sim_run(n_stages: int, n_microbatches: int, dur_f, dur_b, dur_w=None, *
         n = min(res.n_events, cap)
         out["trace"] = [(e.stage, e.dir, e.microbatch, e.chunk, e.start, e.end) for e in trace[:n]]
     return out
+
+
+def jitter_create(p: float, base_seconds: float, alpha: float, seed: int, stage: int, n_microbatches: int,
+                  n_chunks: int = 1):
+    j = _lib().jitter_create(p, base_seconds, alpha, seed, stage, n_microbatches, n_chunks)
+    if not j:
+        raise ArbiterError(ARB_EINVAL, arbiter_last_error(None))
+    return j
+
+
+def jitter_destroy(j):
+    _lib().jitter_destroy(j)
+
+
+def jitter_next_delay(j, direction: int, microbatch: int, chunk: int, compute_seconds: float) -> float:
+    return _lib().jitter_next_delay(j, direction, microbatch, chunk, compute_seconds)
+
+
+def rrfp_delay(seconds: float, stream=None):
+    """Enqueues the device-side sleep on `stream` (a torch stream, a raw handle, or None)."""
+    h = 0 if stream is None else getattr(stream, "cuda_stream", stream)
+    rc = _lib().rrfp_delay(seconds, h)
+    if rc < 0:
+        raise ArbiterError(rc, (_lib().rrfp_delay_last_error() or b"").decode())

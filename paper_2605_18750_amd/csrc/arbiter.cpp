@@ -267,6 +267,40 @@ struct Arrival {
 
 }  // namespace
 
+struct jitter {
+  double p, base, alpha;
+  uint64_t seed;
+  int32_t stage, M, C;
+  double e = 0.0;
+  bool e_set = false;
+};
+
+extern "C" jitter_t* jitter_create(double p, double base_seconds, double alpha, uint64_t seed, int32_t stage,
+                                   int32_t n_microbatches, int32_t n_chunks) {
+  if (p < 0 || p > 1 || base_seconds < 0 || alpha < 0 || stage < 0 || n_microbatches < 1 || n_chunks < 1) {
+    fail(nullptr, ARB_EINVAL, "jitter_create: invalid parameters");
+    return nullptr;
+  }
+  jitter* j = new (std::nothrow) jitter();
+  if (!j) return nullptr;
+  j->p = p; j->base = base_seconds; j->alpha = alpha; j->seed = seed;
+  j->stage = stage; j->M = n_microbatches; j->C = n_chunks;
+  return j;
+}
+
+extern "C" void jitter_destroy(jitter_t* j) { delete j; }
+
+extern "C" double jitter_next_delay(jitter_t* j, int32_t dir, int32_t microbatch, int32_t chunk, double c) {
+  if (!j) return 0.0;
+  j->e = j->e_set ? 0.9 * j->e + 0.1 * c : c;
+  j->e_set = true;
+  const uint64_t k = (((uint64_t)j->stage * 3 + dir) * j->C + chunk) * j->M + microbatch;
+  const double u1 = (double)(splitmix64(j->seed ^ splitmix64(2 * k)) >> 11) * 0x1.0p-53;
+  const double u2 = (double)(splitmix64(j->seed ^ splitmix64(2 * k + 1)) >> 11) * 0x1.0p-53;
+  if (u1 < j->p) return j->alpha * std::max(j->base, j->e) * (0.5 + u2);
+  return 0.0;
+}
+
 extern "C" int rrfp_sim_run(const rrfp_sim_config* cfg, const double* dur_f, const double* dur_b, const double* dur_w,
                             rrfp_sim_result* result, double* per_stage, rrfp_sim_event* trace, int64_t trace_cap) {
   if (!cfg || !result || !dur_f || !dur_b) return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: NULL argument");
@@ -291,8 +325,12 @@ extern "C" int rrfp_sim_run(const rrfp_sim_config* cfg, const double* dur_f, con
   struct Run { bool busy = false; arbiter_task t{}; double end = 0; };
   std::vector<Run> run(N);
   std::priority_queue<Arrival, std::vector<Arrival>, std::greater<Arrival>> arrivals;
-  std::vector<double> busy(N, 0.0), ema(N, 0.0);
-  std::vector<char> ema_set(N, 0);
+  std::vector<double> busy(N, 0.0);
+  std::vector<jitter> inject(N);
+  for (int s = 0; s < N; ++s) {
+    inject[s].p = cfg->jitter_p; inject[s].base = cfg->jitter_base; inject[s].alpha = cfg->jitter_alpha;
+    inject[s].seed = cfg->jitter_seed; inject[s].stage = s; inject[s].M = M; inject[s].C = C;
+  }
   std::vector<int64_t> fwd_held(N, 0), bwd_held(N, 0), max_f(N, 0), max_b(N, 0), max_D(N, 0), done(N, 0);
   const int64_t only_target = (int64_t)M * C;
   int64_t n_events = 0;
@@ -362,14 +400,8 @@ extern "C" int rrfp_sim_run(const rrfp_sim_config* cfg, const double* dur_f, con
       if (s == 0 && task.dir == ARB_F && task.chunk == 0) { if (++fwd_held[0] > max_f[0]) max_f[0] = fwd_held[0]; }
       const size_t idx = ((size_t)s * C + task.chunk) * M + task.microbatch;
       double p = task.dir == ARB_F ? dur_f[idx] : task.dir == ARB_B ? dur_b[idx] : dur_w[idx];
-      if (cfg->jitter_p > 0.0 && task.dir != ARB_W) {
-        ema[s] = ema_set[s] ? 0.9 * ema[s] + 0.1 * p : p;
-        ema_set[s] = 1;
-        const uint64_t k = (((uint64_t)s * 3 + task.dir) * C + task.chunk) * M + task.microbatch;
-        const double u1 = (double)(splitmix64(cfg->jitter_seed ^ splitmix64(2 * k)) >> 11) * 0x1.0p-53;
-        const double u2 = (double)(splitmix64(cfg->jitter_seed ^ splitmix64(2 * k + 1)) >> 11) * 0x1.0p-53;
-        if (u1 < cfg->jitter_p) p = p + cfg->jitter_alpha * std::max(cfg->jitter_base, ema[s]) * (0.5 + u2);
-      }
+      if (cfg->jitter_p > 0.0 && task.dir != ARB_W)
+        p = p + jitter_next_delay(&inject[s], task.dir, task.microbatch, task.chunk, p);
       run[s].busy = true;
       run[s].t = task;
       run[s].end = t + p;

@@ -187,3 +187,25 @@ def test_large_pipeline_runs_and_respects_the_bounds():
     assert got["makespan"] >= (f[N - 1, 0].sum() + b[N - 1, 0].sum()) * (1 - 1e-12)
     lim = A.rrfp_sim_run(N, M, f, b, None, buffer_limit=32, want_trace=False)
     assert not lim["deadlock"] and lim["max_D"].max() <= 32 and lim["max_fwd_buffer"].max() <= 32
+
+
+def test_jitter_injector_matches_oracle_bit_for_bit():
+    rng = random.Random(3)
+    for level in ("J1", "J2", "J3"):
+        p, base, alpha = O.JITTER_LEVELS[level]
+        for stage in (0, 5):
+            M, C, seed = 24, 2, 99 + stage
+            nat = A.jitter_create(p, base, alpha, seed, stage, M, C)
+            ref = O.JitterInjector(O.Jitter(p, base, alpha, seed), stage, M, C)
+            hits = 0
+            for _ in range(300):
+                d, j, c = rng.choice((O.F, O.B)), rng.randrange(M), rng.randrange(C)
+                comp = rng.uniform(1e-3, 30e-3)
+                want = ref.delay(d, j, c, comp)
+                got = A.jitter_next_delay(nat, d, j, c, comp)
+                assert got == want
+                hits += got > 0
+            assert hits > 0
+            A.jitter_destroy(nat)
+    with pytest.raises(A.ArbiterError):
+        A.jitter_create(1.5, 0.0, 1.0, 0, 0, 4)
