@@ -575,6 +575,9 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
 
 constexpr int BQ_KV = 64;      // query rows per step of the dK/dV kernel
 constexpr int WK = 32;         // keys per wavefront of the dK/dV kernel
+#ifndef DKV_VALU_PER_MFMA
+#define DKV_VALU_PER_MFMA 8
+#endif
 
 template <int D>
 struct DkvCfg {
@@ -652,18 +655,107 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
   commit(smem);
   __syncthreads();
 
+  // One 64-row query step as a software pipeline over its two 32-row blocks, so that the P / dS
+  // arithmetic of one block (quarter-rate exponentials included) issues between the MFMAs of the
+  // other block instead of after them (one wavefront per SIMD: nothing else would fill the gaps):
+  //   S,dP(0) | S,dP(1) + arithmetic(0) | dV,dK(0) + arithmetic(1) | dV,dK(1)
+  // MASK is a compile-time flag so that each variant is one basic block the scheduler can interleave.
+  auto compute_step = [&](const char* sq, const char* sd, const float* s_lse, const float* s_dl, int q0, auto mask_tag) {
+    constexpr bool MASK = decltype(mask_tag)::value;
+    floatx16 sacc[2], dpacc[2];
+    bf16x8 pf[2][2], dsf[2][2];
+    auto sdp = [&](int ib) {
+      bf16x8 qa[NDS], da[NDS];
+#pragma unroll
+      for (int ds = 0; ds < NDS; ++ds) {
+        qa[ds] = frag_rows(sq, C::QP, ib * 32, ds, lane);
+        da[ds] = frag_rows(sd, C::QP, ib * 32, ds, lane);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { sacc[ib][e] = 0.f; dpacc[ib][e] = 0.f; }
+#pragma unroll
+      for (int ds = 0; ds < NDS; ++ds) {
+        sacc[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ds], kf[ds], sacc[ib], 0, 0, 0);
+        dpacc[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da[ds], vf[ds], dpacc[ib], 0, 0, 0);
+      }
+    };
+    auto arith = [&](int ib) {
+      // accumulator value e belongs to row ib*32 + (e/4)*8 + h*4 + e%4
+      float pv[16], dsv[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int il = ib * 32 + g * 8 + h * 4;
+        const float4 l4 = *reinterpret_cast<const float4*>(s_lse + il);
+        const float4 d4 = *reinterpret_cast<const float4*>(s_dl + il);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int e = g * 4 + c;
+          float p = __builtin_amdgcn_exp2f(fmaf(sacc[ib][e], scale_log2e, -lv[c]));
+          if (MASK) {
+            const int i = q0 + il + c;
+            p = (i >= tl.s1 || j >= tl.r1 || (causal && j > i)) ? 0.f : p;
+          }
+          pv[e] = p;
+          dsv[e] = p * (dpacc[ib][e] - dl4[c]);    // masked entries: P = 0 and dP finite, so dS = 0
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) { pf[ib][u] = pack8(pv + u * 8); dsf[ib][u] = pack8(dsv + u * 8); }
+    };
+    auto dvdk = [&](int ib) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        bf16x8 td[NDB], tq[NDB];
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          td[db] = frag_cols_tr(sd, C::QP, ib * 32 + u * 16, db * 32, lane);
+          tq[db] = frag_cols_tr(sq, C::QP, ib * 32 + u * 16, db * 32, lane);
+        }
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td[db], pf[ib][u], dv[db], 0, 0, 0);
+          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[db], dsf[ib][u], dk[db], 0, 0, 0);
+        }
+      }
+    };
+    constexpr int NM_SDP = 2 * NDS;          // MFMAs of one S,dP block
+    constexpr int NM_DVK = 4 * NDB;          // MFMAs of one dV,dK block
+    sdp(0);
+    __builtin_amdgcn_sched_barrier(0);
+    sdp(1);
+    arith(0);
+    // fragment reads first, then one MFMA per handful of vector instructions
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * NDS, 0);
+#pragma unroll
+    for (int k = 0; k < NM_SDP; ++k) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, DKV_VALU_PER_MFMA, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    dvdk(0);
+    arith(1);
+    __builtin_amdgcn_sched_group_barrier(0x100, 8 * NDB, 0);
+#pragma unroll
+    for (int k = 0; k < NM_DVK; ++k) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, DKV_VALU_PER_MFMA, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    dvdk(1);
+  };
+
   // Steps are (query head of the group, 64-row query block) pairs in ascending order.  Under a causal
   // mask the first n_skip blocks of every head lie wholly before this wavefront's keys: those steps
   // only move data.  The MFMA accumulators are touched in the second loop alone and unconditionally,
   // so they stay in place in the accumulator registers for the whole kernel.
   const int n_skip = !wave_has_keys ? nq_steps : (causal ? min(nq_steps, (wj0 - q_begin) / BQ_KV) : 0);
-  int st = 0;
-  for (int ah = 0; ah < G; ++ah) {
-    for (int t = 0; t < n_skip; ++t, ++st) {
-      if (st + 1 < nsteps) { fetch(st + 1); commit(smem + ((st + 1) & 1) * C::STAGE); }
-      __syncthreads();
-    }
-    for (int t = n_skip; t < nq_steps; ++t, ++st) {
+  const bool ragged_keys = wj0 + WK > tl.r1;
+  const int t_lead_end = ragged_keys ? nq_steps
+                         : (causal ? min(nq_steps, max(n_skip, (wj0 + WK - 1 - q_begin + BQ_KV - 1) / BQ_KV)) : n_skip);
+  const int t_tail_begin = (q_begin + nq_steps * BQ_KV > tl.s1) ? nq_steps - 1 : nq_steps;
+  auto run_steps = [&](int t, int t_end, int& st, auto mask_tag) -> int {
+    for (; t < t_end; ++t, ++st) {
       const int q0 = q_begin + t * BQ_KV;
       const char* sq = smem + (st & 1) * C::STAGE;
       const char* sd = sq + C::T_BYTES;
@@ -671,76 +763,25 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
       const float* s_dl = s_lse + BQ_KV;
       const bool more = st + 1 < nsteps;
       if (more) fetch(st + 1);
-      {
-      const bool need_mask = (causal && q0 < wj0 + WK - 1) || (q0 + BQ_KV > tl.s1) || (wj0 + WK > tl.r1);
-      // Per 32-row block of queries: S = Q K^T and dP = dO V^T (all fragments of the block are read
-      // before its MFMAs, so the LDS latency is paid once per block, not once per MFMA), then P and dS
-      // in registers, then dV^T += dO^T P and dK^T += Q^T dS from transposed fragments.
-#pragma unroll
-      for (int ib = 0; ib < 2; ++ib) {
-        floatx16 sacc, dpacc;
-        {
-          bf16x8 qa[NDS], da[NDS];
-#pragma unroll
-          for (int ds = 0; ds < NDS; ++ds) {
-            qa[ds] = frag_rows(sq, C::QP, ib * 32, ds, lane);
-            da[ds] = frag_rows(sd, C::QP, ib * 32, ds, lane);
-          }
-#pragma unroll
-          for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; dpacc[e] = 0.f; }
-#pragma unroll
-          for (int ds = 0; ds < NDS; ++ds) {
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ds], kf[ds], sacc, 0, 0, 0);
-            dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da[ds], vf[ds], dpacc, 0, 0, 0);
-          }
-        }
-        // accumulator value e belongs to row ib*32 + (e/4)*8 + h*4 + e%4
-        float pv[16], dsv[16];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int il = ib * 32 + g * 8 + h * 4;
-          const float4 l4 = *reinterpret_cast<const float4*>(s_lse + il);
-          const float4 d4 = *reinterpret_cast<const float4*>(s_dl + il);
-          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl4[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const int e = g * 4 + c;
-            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], scale_log2e, -lv[c]));
-            pv[e] = p;
-            dsv[e] = p * (dpacc[e] - dl4[c]);
-          }
-        }
-        if (need_mask) {
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int i = q0 + ib * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-            const bool dead = i >= tl.s1 || j >= tl.r1 || (causal && j > i);
-            float pm = dead ? 0.f : pv[e], dm = dead ? 0.f : dsv[e];
-            asm volatile("" : "+v"(pm), "+v"(dm));   // pins the selects inside this (wave-uniform) branch
-            pv[e] = pm;
-            dsv[e] = dm;
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const bf16x8 pf = pack8(pv + u * 8), dsf = pack8(dsv + u * 8);
-          bf16x8 td[NDB], tq[NDB];
-#pragma unroll
-          for (int db = 0; db < NDB; ++db) {
-            td[db] = frag_cols_tr(sd, C::QP, ib * 32 + u * 16, db * 32, lane);
-            tq[db] = frag_cols_tr(sq, C::QP, ib * 32 + u * 16, db * 32, lane);
-          }
-#pragma unroll
-          for (int db = 0; db < NDB; ++db) {
-            dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td[db], pf, dv[db], 0, 0, 0);
-            dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[db], dsf, dk[db], 0, 0, 0);
-          }
-        }
-      }
-      }
+      compute_step(sq, sd, s_lse, s_dl, q0, mask_tag);
       if (more) commit(smem + ((st + 1) & 1) * C::STAGE);
       __syncthreads();
     }
+    return t;
+  };
+  int st = 0;
+  for (int ah = 0; ah < G; ++ah) {
+    int t = 0;
+    for (; t < n_skip; ++t, ++st) {
+      if (st + 1 < nsteps) { fetch(st + 1); commit(smem + ((st + 1) & 1) * C::STAGE); }
+      __syncthreads();
+    }
+    // Masked steps come first (the diagonal of a causal segment, or every step when this wavefront's
+    // key block is ragged), then the unmasked bulk, then the ragged last query block: three loops, each
+    // with one compile-time variant of the step, so no loop mixes register assignments.
+    t = run_steps(t, t_lead_end, st, std::true_type{});
+    t = run_steps(t, max(t, t_tail_begin), st, std::false_type{});
+    t = run_steps(t, nq_steps, st, std::true_type{});
   }
   if (j < tl.r1) {
     bf16_t* krow = dqkv + (size_t)j * ld + kcol;

@@ -32,6 +32,12 @@ SMALL = {
     # bf16, bidirectional GELU, head_dim 80
     "bf16_bidir_gelu_d80": (SI.StageShape("s_bf16_b", 2, 320, 4, 4, 80, 256, 2, mlp_kind="gelu", causal=False, w_std=0.05),
                             [[0, 100, 200, 300], [0, 259]]),
+    # bf16 degenerate lengths: a single token, single-token segments, one row past a query tile
+    "bf16_single_tokens": (SI.StageShape("s_bf16_d", 1, 128, 4, 2, 64, 192, 3, w_std=0.05),
+                           [[0, 1], [0, 1, 2, 3], [0, 257]]),
+    # fp32 degenerate lengths
+    "fp32_single_tokens": (SI.StageShape("s_fp32_c", 1, 64, 2, 1, 32, 48, 3, dtype="fp32", x_std=1.0, dy_std=1.0, w_std=0.1),
+                           [[0, 1], [0, 1, 2, 3], [0, 65]]),
     # bf16, head_dim 128, GQA 4:1
     "bf16_d128_gqa4": (SI.StageShape("s_bf16_c", 1, 512, 4, 1, 128, 320, 2, w_std=0.03),
                        [[0, 300], [0, 130, 260]]),
