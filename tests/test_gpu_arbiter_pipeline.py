@@ -25,19 +25,21 @@ def _raw(t):
     return t.cpu().view(bits).numpy()
 
 
-@pytest.mark.parametrize("limit", [0, 2])
-def test_pipeline_in_readiness_order_is_bit_identical_to_canonical(limit):
+@pytest.mark.parametrize("N,C,limit", [(3, 1, 0), (3, 1, 2), (2, 2, 0), (2, 2, 1)])
+def test_pipeline_in_readiness_order_is_bit_identical_to_canonical(N, C, limit):
+    """C = 1: a plain pipeline of N stages.  C = 2: an interleaved pipeline, every physical stage owns
+    two model chunks and a microbatch visits the stages twice (App. C.2)."""
     import torch
     import paper_2605_18750_amd as R
     from paper_2605_18750_amd import arbiter as A, harness as Hn, pipeline as P
 
-    N = 3
     cus = [[0, 200], [0, 77, 333], [0, 64], [0, 130, 260], [0, 301], [0, 96, 97]]
     M = len(cus)
-    shapes = [SI.StageShape(f"pipe_stage{s}", 1 + (s == 1), 128, 4, 2, 64, 192, M, w_std=0.05) for s in range(N)]
-    works = [Hp.Workload(sh, cus, seed=SI.BASE_SEED + s) for s, sh in enumerate(shapes)]
+    V = N * C                      # virtual stages in model order: v = c * N + s
+    shapes = [SI.StageShape(f"pipe_stage{v}", 1 + (v == 1), 128, 4, 2, 64, 192, M, w_std=0.05) for v in range(V)]
+    works = [Hp.Workload(sh, cus, seed=SI.BASE_SEED + v) for v, sh in enumerate(shapes)]
     T_max = max(c[-1] for c in cus)
-    _say(f"[pipeline] N={N} M={M} limit={limit}")
+    _say(f"[pipeline] N={N} C={C} M={M} limit={limit}")
 
     def build():
         st = []
@@ -50,12 +52,12 @@ def test_pipeline_in_readiness_order_is_bit_identical_to_canonical(limit):
     dys = [Hn.to_device(t.storage, "bf16") for t in works[0].dy]
     cus_np = [np.asarray(c, dtype=np.int32) for c in cus]
 
-    # canonical: one stream, stage by stage
+    # canonical: one stream, virtual stage by virtual stage
     stages = build()
     s0 = torch.cuda.Stream()
     torch.cuda.synchronize()
     y = [list(xs)]
-    for s in range(N):
+    for s in range(V):
         outs = []
         for j in range(M):
             o = torch.empty_like(xs[j])
@@ -63,7 +65,7 @@ def test_pipeline_in_readiness_order_is_bit_identical_to_canonical(limit):
             outs.append(o)
         y.append(outs)
     g = list(dys)
-    for s in range(N - 1, -1, -1):
+    for s in range(V - 1, -1, -1):
         outs = []
         for j in range(M):
             o = torch.empty_like(xs[j])
@@ -81,25 +83,29 @@ def test_pipeline_in_readiness_order_is_bit_identical_to_canonical(limit):
 
     # readiness order under seeded, strongly varying virtual task times
     rng = random.Random(5 + limit)
-    tab = {(d, s, j): rng.uniform(0.2, 3.0) * (1 + (d == A.ARB_B)) for d in (0, 1, 2) for s in range(N) for j in range(M)}
+    tab = {(d, s, c, j): rng.uniform(0.2, 3.0) * (1 + (d == A.ARB_B))
+           for d in (0, 1, 2) for s in range(N) for c in range(C) for j in range(M)}
     stages = build()
-    pipe = P.Pipeline(stages, cus_np, hint=A.ARB_HINT_BFW, buffer_limit=limit)
+    grid = [[stages[c * N + s] for c in range(C)] for s in range(N)]
+    pipe = P.Pipeline(grid, cus_np, hint=A.ARB_HINT_BFW, buffer_limit=limit)
     torch.cuda.synchronize()
-    ys, dxs, trace = pipe.run_iteration(xs, dys, lambda d, s, j: tab[(d, s, j)], latency=0.1)
+    ys, dxs, trace = pipe.run_iteration(xs, dys, lambda d, s, j, c: tab[(d, s, c, j)], latency=0.1)
     for j in range(M):
         assert np.array_equal(_raw(ys[j]), ref_y[j]), f"y[{j}] differs"
         assert np.array_equal(_raw(dxs[j]), ref_dx[j]), f"dx[{j}] differs"
-    for s, st in enumerate(stages):
-        assert np.array_equal(st.grad_out.cpu().view(torch.int32).numpy(), ref_grads[s]), f"gradients of stage {s} differ"
+    for v, st in enumerate(stages):
+        assert np.array_equal(st.grad_out.cpu().view(torch.int32).numpy(), ref_grads[v]), f"gradients of virtual stage {v} differ"
 
     # the dispatch order is the simulator's prediction for these task times, and it interleaves the
     # task kinds (the last stage alternates F and B) instead of the canonical all-F-then-B/W order
-    dur = {d: np.array([[[tab[(d, s, j)] for j in range(M)]] for s in range(N)]) for d in (0, 1, 2)}
-    sim = A.rrfp_sim_run(N, M, dur[0], dur[1], dur[2], hint=A.ARB_HINT_BFW, buffer_limit=limit, latency=0.1)
-    assert [(s, d, j, t0, t1) for (s, d, j, c, t0, t1) in sim["trace"]] == trace
-    last = [(d, j) for (s, d, j, _, _) in trace if s == N - 1 and d != A.ARB_W]
-    assert last == [(d, j) for j in range(M) for d in (A.ARB_F, A.ARB_B)]
-    _say(f"[pipeline] stage 0 order: {[('FBW'[d], j) for (s, d, j, _, _) in trace if s == 0]}")
+    dur = {d: np.array([[[tab[(d, s, c, j)] for j in range(M)] for c in range(C)] for s in range(N)]) for d in (0, 1, 2)}
+    sim = A.rrfp_sim_run(N, M, dur[0], dur[1], dur[2], n_chunks=C, hint=A.ARB_HINT_BFW, buffer_limit=limit, latency=0.1)
+    assert not sim["deadlock"]
+    assert sim["trace"] == trace
+    if C == 1:
+        last = [(d, j) for (s, d, j, c, _, _) in trace if s == N - 1 and d != A.ARB_W]
+        assert last == [(d, j) for j in range(M) for d in (A.ARB_F, A.ARB_B)]
+    _say(f"[pipeline] stage 0 order: {[('FBW'[d], j, c) for (s, d, j, c, _, _) in trace if s == 0]}")
     pipe.close()
     for st in stages:
         st.close()
