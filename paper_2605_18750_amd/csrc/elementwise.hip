@@ -334,15 +334,25 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------- gradient reduction
-__global__ __launch_bounds__(256) void grad_reduce_kernel(const float4* __restrict__ slots, size_t stride4, int M,
-                                                          float4* __restrict__ out, size_t n4) {
+// Slots are streamed once: all loads of a group of up to 8 slots are issued before the first add (the
+// adds then run in microbatch index order, which is what fixes the result bit for bit), and the loads
+// bypass temporal caching.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void grad_reduce_kernel(const f32x4* __restrict__ slots, size_t stride4, int M,
+                                                          f32x4* __restrict__ out, size_t n4) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
-    float4 acc = slots[i];
-    for (int j = 1; j < M; ++j) {
-      const float4 v = slots[(size_t)j * stride4 + i];
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    f32x4 acc = __builtin_nontemporal_load(slots + i);
+    for (int j0 = 1; j0 < M; j0 += 8) {
+      f32x4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (j0 + u < M) v[u] = __builtin_nontemporal_load(slots + (size_t)(j0 + u) * stride4 + i);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (j0 + u < M) acc += v[u];
     }
-    out[i] = acc;
+    __builtin_nontemporal_store(acc, out + i);
   }
 }
 
@@ -457,8 +467,8 @@ hipError_t launch_gelu_bwd(const float* dm, const void* u, void* du, int Tn, int
 
 hipError_t launch_grad_reduce(const float* slots, size_t slot_stride, int M, float* out, size_t n, hipStream_t s) {
   if (n % 4 || slot_stride % 4) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(grad_reduce_kernel, dim3(grid_for(n / 4)), dim3(256), 0, s, (const float4*)slots, slot_stride / 4,
-                     M, (float4*)out, n / 4);
+  hipLaunchKernelGGL(grad_reduce_kernel, dim3(grid_for(n / 4)), dim3(256), 0, s, (const f32x4*)slots, slot_stride / 4,
+                     M, (f32x4*)out, n / 4);
   return hipGetLastError();
 }
 
