@@ -241,9 +241,11 @@ __device__ __forceinline__ int dkc_off(int row, int c) { return row * 64 + ((c ^
 
 // NW = wavefronts per workgroup: 4 (2x2, 128x128 each, one per SIMD) or 8 (2x4, 128x64 each, two per
 // SIMD so that one wavefront's waits hide behind the other's MFMAs).
-template <bool KC, int NW>
+template <bool KC, int NW, int ROWS = 256>
 struct DirectLoader {
-  static constexpr int NL = 16 / NW;               // 1 KB blocks of the 16 KB tile per wavefront
+  static_assert(KC || ROWS == 256, "a K-strided tile is always 256 wide");
+  static constexpr int NL = (ROWS / 16) / NW;      // 1 KB blocks of the tile per wavefront (16 rows of 64 B each when K-contiguous)
+  static_assert(NL >= 1, "tile too small for this many wavefronts");
   __amdgpu_buffer_rsrc_t rsrc;
   int voff[NL];
   int k_stride;     // bytes per k-step
@@ -359,13 +361,16 @@ __device__ __forceinline__ uint2 pack4(const float* v) {
   return o;
 }
 
-template <bool A_KC, bool B_KC, typename TO, bool HAS_R, int WM, int WN, int ACT>
+// BMT = rows of the C tile: 256, or 128 for the short tiles that finish a GEMM whose tile count is
+// not a multiple of the CU count (A K-contiguous only).  tn0 = first tile column of this launch.
+template <bool A_KC, bool B_KC, typename TO, bool HAS_R, int WM, int WN, int ACT, int BMT = 256>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                TO* __restrict__ C, const float* __restrict__ R, int M,
                                                                int N, int K, int lda, int ldb, int ldc, int ldr,
-                                                               int tiles_m, int tiles_n, bf16_t* __restrict__ E, int lde) {
+                                                               int tiles_m, int tiles_n, bf16_t* __restrict__ E, int lde,
+                                                               int tn0) {
   constexpr int NW = WM * WN;
-  constexpr int MI = 8 / WM;                        // 32-high row blocks per wavefront
+  constexpr int MI = (BMT / 32) / WM;               // 32-high row blocks per wavefront
   constexpr int NB = 8 / WN;                        // 32-wide column blocks per wavefront
   constexpr int WAVE_M = MI * 32, WAVE_N = NB * 32;
   __shared__ __attribute__((aligned(1024))) char stage0[DSTAGE];
@@ -374,7 +379,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   __shared__ __attribute__((aligned(1024))) char stage3[DSTAGE];
   int tm, tn;
   tile_coords(tiles_m, tiles_n, tm, tn);
-  const int m0 = tm * BM, n0 = tn * BN;
+  const int m0 = tm * BMT, n0 = (tn + tn0) * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = (wave / WN) * WAVE_M, wn = (wave % WN) * WAVE_N;
@@ -387,7 +392,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  DirectLoader<A_KC, NW> la;
+  DirectLoader<A_KC, NW, BMT> la;
   DirectLoader<B_KC, NW> lb;
   la.init(A, lda, m0, M, K, wave, lane);
   lb.init(B, ldb, n0, N, K, wave, lane, ACT == ACT_SWIGLU_FWD ? N / 2 : 0);
@@ -400,7 +405,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   // step t+4, and read step t+1's first fragments under the MFMAs of the second k-step.
   // Each step issues LPS loads per wavefront; "all but 2*LPS outstanding" means step t+1 has landed
   // while t+2 and t+3 may still be in flight.
-  constexpr int LPS = 2 * (16 / NW);
+  constexpr int LPS = DirectLoader<A_KC, NW, BMT>::NL + DirectLoader<B_KC, NW>::NL;
   constexpr int VM_ALL = 0x0070;                                   // vmcnt(0), lgkmcnt(0)
   constexpr int VM_2 = 0x0070 | ((2 * LPS) & 15) | (((2 * LPS) >> 4) << 14);   // vmcnt(2*LPS), lgkmcnt(0)
   constexpr int VM_3 = 0x0070 | ((3 * LPS) & 15) | (((3 * LPS) >> 4) << 14);   // vmcnt(3*LPS), lgkmcnt(0)
@@ -561,7 +566,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
 // Explicit instantiations of every variant the launcher can pick.
 #define RRFP_INST(AKC, BKC, TO, HR, ACT)                                                                     \
   template __global__ void gemm_mfma_dl_kernel<AKC, BKC, TO, HR, dl_wm(AKC, BKC), dl_wn(AKC, BKC), ACT>(      \
-      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int);
+      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int);
+#define RRFP_INST_SHORT(ACT)                                                                                 \
+  template __global__ void gemm_mfma_dl_kernel<true, false, bf16_t, false, dl_wm(true, false), dl_wn(true, false), ACT, 128>( \
+      const bf16_t*, const bf16_t*, bf16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int);
+RRFP_INST_SHORT(ACT_NONE) RRFP_INST_SHORT(ACT_SWIGLU_FWD) RRFP_INST_SHORT(ACT_GELU_FWD)
+#undef RRFP_INST_SHORT
 #define RRFP_INST4(AKC, BKC) RRFP_INST(AKC, BKC, float, true, ACT_NONE) RRFP_INST(AKC, BKC, float, false, ACT_NONE) \
                              RRFP_INST(AKC, BKC, bf16_t, true, ACT_NONE) RRFP_INST(AKC, BKC, bf16_t, false, ACT_NONE)
 RRFP_INST4(true, false) RRFP_INST4(true, true) RRFP_INST4(false, false) RRFP_INST4(false, true)
@@ -580,14 +590,51 @@ inline bool direct_ok(const GemmArgs& g) {
   return a_bytes < lim && b_bytes < lim;
 }
 
+// Number of trailing tile columns to compute with 128-row tiles.  One workgroup occupies a CU, so a
+// GEMM of t tiles runs in ceil(t / n_cu) rounds and a last round of r = t mod n_cu tiles leaves CUs
+// idle.  When r is at most half the CUs and is a whole number of tile columns, those columns are
+// launched separately as 2r half-height tiles: one short round instead of a full one.  A pure
+// function of the shape and the device.
+inline int short_tail_columns(int tiles_m, int tiles_n) {
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+      v = 256;
+    n_cu = v;
+  }
+  const int t = tiles_m * tiles_n, r = t % n_cu;
+  if (t <= n_cu || r == 0 || 2 * r > n_cu || r % tiles_m) return 0;
+  return r / tiles_m;
+}
+
+// Launch of the (A K-contiguous, B K-strided, bf16 out, no residual) forms with the short-tile tail.
+template <int ACT>
+hipError_t launch_nn_bf16(const GemmArgs& g, hipStream_t s) {
+  constexpr int WMv = dl_wm(true, false), WNv = dl_wn(true, false);
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  const int ct = short_tail_columns(tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, false, bf16_t, false, WMv, WNv, ACT>), dim3(tiles_m * (tiles_n - ct)),
+                     dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, (const float*)nullptr,
+                     g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0, tiles_m, tiles_n - ct, (bf16_t*)g.E, g.lde, 0);
+  if (ct > 0) {
+    const int tiles_m2 = (g.M + 127) / 128;
+    hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, false, bf16_t, false, WMv, WNv, ACT, 128>), dim3(tiles_m2 * ct),
+                       dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, (const float*)nullptr,
+                       g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0, tiles_m2, ct, (bf16_t*)g.E, g.lde, tiles_n - ct);
+  }
+  return hipGetLastError();
+}
+
 template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
 hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   if (direct_ok(g)) {
+    if (A_KC && !B_KC && !HAS_R && sizeof(TO) == 2) return launch_nn_bf16<ACT_NONE>(g, s);
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
                        dim3(tiles_m * tiles_n), dim3(dl_wm(A_KC, B_KC) * dl_wn(A_KC, B_KC) * 64), 0,
                        s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda,
-                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0);
+                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0);
     return hipGetLastError();
   }
   static bool configured = false;   // per instantiation; the attribute is process-wide for the function
@@ -614,11 +661,12 @@ hipError_t launch_orient(const GemmArgs& g, hipStream_t s) {
 // Fused-activation launch: forward forms are (A K-contiguous, B K-strided), backward forms (both K-contiguous).
 template <bool B_KC, int ACT>
 hipError_t launch_act(const GemmArgs& g, hipStream_t s) {
+  if (!B_KC) return launch_nn_bf16<ACT>(g, s);
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, bf16_t, false, dl_wm(true, B_KC), dl_wn(true, B_KC), ACT>),
                      dim3(tiles_m * tiles_n), dim3(dl_wm(true, B_KC) * dl_wn(true, B_KC) * 64), 0, s, (const bf16_t*)g.A,
                      (const bf16_t*)g.B, (bf16_t*)g.C, (const float*)nullptr, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0,
-                     tiles_m, tiles_n, (bf16_t*)g.E, g.lde);
+                     tiles_m, tiles_n, (bf16_t*)g.E, g.lde, 0);
   return hipGetLastError();
 }
 

@@ -101,3 +101,28 @@ def test_mfma_gemm_full_size_sampled_rows():
     err = max_norm_rel_err(got, ref)
     _say(f"[kernel] full-size NN gemm: rel err {err:.3e}")
     assert err <= 1e-2
+
+
+def test_mfma_gemm_short_tile_tail():
+    """Shapes whose tile count leaves a small last round on 256 CUs (1000 x 17920: 4 x 70 = 280 tiles,
+    24 left over = 6 tile columns) take 128-row tiles for those columns: every element is compared, so
+    both launches, the seam between them and the ragged last row block are covered."""
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+    from tests.helpers import max_norm_rel_err
+    M, N, K = 1000, 17920, 256
+    _say("[kernel] NN gemm with short-tile tail")
+    A = SI.make_tensor(2, "tailA", (M, K), 1.0, "bf16")
+    B = SI.make_tensor(2, "tailB", (K, N), 0.05, "bf16")
+    dA, dB = Hn.to_device(A.storage, "bf16"), Hn.to_device(B.storage, "bf16")
+    dC = torch.full((M + 8, N), 7.0, dtype=torch.bfloat16, device="cuda:0")       # guard rows behind the output
+    R.rrfp_gemm(dA, dB, dC, None, M, N, K, K, N, N, N, 0, 0, 1, 1, R.RRFP_GEMM_MFMA)
+    torch.cuda.synchronize()
+    got = dC[:M].cpu().to(torch.float64).numpy()
+    ref = A.f64 @ B.f64
+    for lo, hi in ((0, 16384), (16384, N)):        # main launch, tail launch
+        err = max_norm_rel_err(got[:, lo:hi], ref[:, lo:hi])
+        _say(f"[kernel] columns {lo}:{hi}: rel err {err:.3e}")
+        assert err <= 1e-2
+    assert torch.all(dC[M:] == 7.0), "rows past M were written"
