@@ -56,9 +56,58 @@ class OracleConfig:
     mlp_kind: str = "swiglu"      # "swiglu" | "gelu"
     causal: bool = True
     norm_eps: float = 1e-5
+    rope: bool = False            # rotary position embedding on q and k (model-fidelity variant)
+    rope_base: float = 10000.0
+    rope_offset: int = 0          # added to every position (test hook for the relative-position property)
 
 
 # ----------------------------------------------------------------------------- pieces
+
+def rope_positions(cu_seqlens, offset=0):
+    """Position of every token inside its own segment, plus offset."""
+    cu = np.asarray(cu_seqlens)
+    pos = np.empty(int(cu[-1]), dtype=np.float64)
+    for s in range(len(cu) - 1):
+        pos[cu[s]:cu[s + 1]] = np.arange(cu[s + 1] - cu[s]) + offset
+    return pos
+
+
+def rope_rotate(x, pos, n_heads, d, base, sign=1.0):
+    """Rotary embedding in the split-half convention (Su et al. 2021, as used by LLaMA / Qwen
+    implementations): for every head and i < d/2 the pair (x_i, x_{i+d/2}) is rotated by the angle
+    pos * base^(-2i/d).  sign = -1 applies the inverse (= transpose) rotation, which is what maps a
+    gradient w.r.t. the rotated vector back to the un-rotated one."""
+    T = x.shape[0]
+    half = d // 2
+    theta = base ** (-2.0 * np.arange(half) / d)
+    ang = pos[:, None] * theta[None, :]
+    cs, sn = np.cos(ang)[:, None, :], sign * np.sin(ang)[:, None, :]
+    xh = x.reshape(T, n_heads, d)
+    a, b = xh[:, :, :half], xh[:, :, half:]
+    out = np.concatenate([a * cs - b * sn, b * cs + a * sn], axis=2)
+    return out.reshape(T, n_heads * d)
+
+
+def _qk_for_attention(c, cfg):
+    """q, k as the attention sees them: rotated when the variant is on (cached once)."""
+    if not cfg.rope:
+        return c["q"], c["k"]
+    if "q_rot" not in c:
+        pos = rope_positions(c["cu"], cfg.rope_offset)
+        c["q_rot"] = rope_rotate(c["q"], pos, cfg.n_q_heads, cfg.head_dim, cfg.rope_base)
+        c["k_rot"] = rope_rotate(c["k"], pos, cfg.n_kv_heads, cfg.head_dim, cfg.rope_base)
+    return c["q_rot"], c["k_rot"]
+
+
+def _attention_bwd_qk(do, c, cfg):
+    """Gradients w.r.t. the projection outputs q, k, v (rotation undone for q and k)."""
+    q, k = _qk_for_attention(c, cfg)
+    dq, dk, dv = attention_bwd(do, q, k, c["v"], c["cu"], cfg)
+    if cfg.rope:
+        pos = rope_positions(c["cu"], cfg.rope_offset)
+        dq = rope_rotate(dq, pos, cfg.n_q_heads, cfg.head_dim, cfg.rope_base, sign=-1.0)
+        dk = rope_rotate(dk, pos, cfg.n_kv_heads, cfg.head_dim, cfg.rope_base, sign=-1.0)
+    return dq, dk, dv
 
 def rmsnorm_fwd(x, g, eps):
     """h = x * r * g with r = (mean_c x^2 + eps)^(-1/2).  Returns h, xhat = x*r, r."""
@@ -151,7 +200,8 @@ def layer_forward(x, p, cu_seqlens, cfg):
     c["q"] = c["h1"] @ p["Wq"]
     c["k"] = c["h1"] @ p["Wk"]
     c["v"] = c["h1"] @ p["Wv"]
-    c["o"] = attention_fwd(c["q"], c["k"], c["v"], cu_seqlens, cfg)
+    q, k = _qk_for_attention(c, cfg)
+    c["o"] = attention_fwd(q, k, c["v"], cu_seqlens, cfg)
     c["x1"] = x + c["o"] @ p["Wo"]
     c["h2"], c["x1hat"], c["r2"] = rmsnorm_fwd(c["x1"], p["g2"], cfg.norm_eps)
     if cfg.mlp_kind == "swiglu":
@@ -188,7 +238,7 @@ def layer_backward_unsplit(dy, c, p, cfg):
     dx1 = dx1 + dn
     do = dx1 @ p["Wo"].T
     g["Wo"] = c["o"].T @ dx1
-    dq, dk, dv = attention_bwd(do, c["q"], c["k"], c["v"], c["cu"], cfg)
+    dq, dk, dv = _attention_bwd_qk(do, c, cfg)
     dh1 = dq @ p["Wq"].T + dk @ p["Wk"].T + dv @ p["Wv"].T
     g["Wq"] = c["h1"].T @ dq
     g["Wk"] = c["h1"].T @ dk
@@ -215,7 +265,7 @@ def layer_B(dy, c, p, cfg):
     dn, gains["g2"] = rmsnorm_bwd(dh2, c["x1hat"], c["r2"], p["g2"])
     w["dx1"] = dy + dn
     do = w["dx1"] @ p["Wo"].T
-    w["dq"], w["dk"], w["dv"] = attention_bwd(do, c["q"], c["k"], c["v"], c["cu"], cfg)
+    w["dq"], w["dk"], w["dv"] = _attention_bwd_qk(do, c, cfg)
     dh1 = w["dq"] @ p["Wq"].T + w["dk"] @ p["Wk"].T + w["dv"] @ p["Wv"].T
     dn, gains["g1"] = rmsnorm_bwd(dh1, c["xhat"], c["r1"], p["g1"])
     return w["dx1"] + dn, gains, w

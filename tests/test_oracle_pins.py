@@ -32,6 +32,8 @@ CASES = [
     dict(mlp_kind="swiglu", causal=False, n_kv_heads=4),
     dict(mlp_kind="gelu", causal=False, n_kv_heads=2),
     dict(mlp_kind="gelu", causal=True, n_kv_heads=1),
+    dict(mlp_kind="swiglu", causal=True, n_kv_heads=2, rope=True),
+    dict(mlp_kind="gelu", causal=False, n_kv_heads=4, rope=True, rope_base=50.0),
 ]
 
 
@@ -351,8 +353,20 @@ def test_against_torch_autograd(case):
     h = tx
     for p in tp:
         a = norm(h, p["g1"])
-        q = (a @ p["Wq"]).view(T, nq, d).transpose(0, 1)
-        k = (a @ p["Wk"]).view(T, nkv, d).transpose(0, 1).repeat_interleave(nq // nkv, 0)
+        q = (a @ p["Wq"]).view(T, nq, d)
+        k = (a @ p["Wk"]).view(T, nkv, d)
+        if cfg.rope:
+            # independent formulation: pairs (x_i, x_{i+d/2}) as complex numbers times e^{i pos theta_i}
+            pos = torch.tensor(np.concatenate([np.arange(cu[s + 1] - cu[s]) for s in range(len(cu) - 1)]), dtype=torch.float64)
+            theta = torch.tensor(cfg.rope_base, dtype=torch.float64) ** (-2.0 * torch.arange(d // 2, dtype=torch.float64) / d)
+            rot = torch.polar(torch.ones(T, d // 2, dtype=torch.float64), pos[:, None] * theta[None, :])[:, None, :]
+
+            def rope(z):
+                zc = torch.complex(z[..., :d // 2], z[..., d // 2:]) * rot
+                return torch.cat([zc.real, zc.imag], dim=-1)
+            q, k = rope(q), rope(k)
+        q = q.transpose(0, 1)
+        k = k.transpose(0, 1).repeat_interleave(nq // nkv, 0)
         v = (a @ p["Wv"]).view(T, nkv, d).transpose(0, 1).repeat_interleave(nq // nkv, 0)
         o = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=mask)
         h = h + o.transpose(0, 1).reshape(T, nq * d) @ p["Wo"]
@@ -368,6 +382,55 @@ def test_against_torch_autograd(case):
     for l in range(cfg.n_layers):
         for k_ in grads[l]:
             np.testing.assert_allclose(grads[l][k_], tp[l][k_].grad.numpy(), rtol=1e-10, atol=1e-11)
+
+
+# ------------------------------------------------------------------ rotary embedding variant
+
+def test_rope_rotation_properties():
+    rng = np.random.default_rng(5)
+    # one pair, angle pi/2 at position 1 with base 1 -> theta = 1; use pos = pi/2 directly
+    out = O.rope_rotate(np.array([[1.0, 0.0]]), np.array([np.pi / 2]), 1, 2, base=7.0)
+    np.testing.assert_allclose(out, [[0.0, 1.0]], atol=1e-15)
+    # frequencies base^(-2i/d): pair i of a d = 8 head at position 1 turns by base^(-i/4)
+    x = np.zeros((1, 8)); x[0, :4] = 1.0
+    out = O.rope_rotate(x, np.array([1.0]), 1, 8, base=16.0)
+    np.testing.assert_allclose(out[0, :4], np.cos(16.0 ** (-np.arange(4) / 4.0)), atol=1e-15)
+    np.testing.assert_allclose(out[0, 4:], np.sin(16.0 ** (-np.arange(4) / 4.0)), atol=1e-15)
+    # a rotation: norms per head are kept, the inverse undoes it, position 0 is the identity
+    x = rng.standard_normal((9, 3 * 8)); pos = np.arange(9.0) * 3
+    y = O.rope_rotate(x, pos, 3, 8, 100.0)
+    np.testing.assert_allclose(np.linalg.norm(y.reshape(9, 3, 8), axis=2), np.linalg.norm(x.reshape(9, 3, 8), axis=2), rtol=1e-13)
+    np.testing.assert_allclose(O.rope_rotate(y, pos, 3, 8, 100.0, sign=-1.0), x, atol=1e-13)
+    np.testing.assert_array_equal(O.rope_rotate(x, np.zeros(9), 3, 8, 100.0), x)
+    np.testing.assert_array_equal(O.rope_positions([0, 3, 4, 9]), [0, 1, 2, 0, 0, 1, 2, 3, 4])
+
+
+def test_rope_scores_depend_on_relative_positions_only():
+    # shifting every position by a constant changes neither the outputs nor any gradient
+    cfg0 = _cfg(rope=True, causal=True)
+    cfg1 = _cfg(rope=True, causal=True, rope_offset=37)
+    rng = np.random.default_rng(6)
+    T, cu = 10, [0, 6, 10]
+    params = _rand_params(cfg0, rng)
+    x = rng.standard_normal((T, cfg0.hidden)); dy = rng.standard_normal((T, cfg0.hidden))
+    outs = []
+    for cfg in (cfg0, cfg1):
+        y, caches = O.stage_F(x, params, cu, cfg)
+        dx, grads = O.stage_backward_unsplit(dy, caches, params, cfg)
+        outs.append((y, dx, grads))
+    np.testing.assert_allclose(outs[0][0], outs[1][0], rtol=1e-10, atol=1e-11)
+    np.testing.assert_allclose(outs[0][1], outs[1][1], rtol=1e-9, atol=1e-10)
+    for l in range(cfg0.n_layers):
+        for k in outs[0][2][l]:
+            np.testing.assert_allclose(outs[0][2][l][k], outs[1][2][l][k], rtol=1e-9, atol=1e-10)
+    # and the variant is not a no-op: with several tokens per segment the output differs from no-rope
+    y_plain, _ = O.stage_F(x, params, cu, _cfg(causal=True))
+    assert np.abs(y_plain - outs[0][0]).max() > 1e-3
+    # single-token segments sit at position 0: rope on == rope off, exactly
+    cu1 = list(range(T + 1))
+    ya, _ = O.stage_F(x, params, cu1, cfg0)
+    yb, _ = O.stage_F(x, params, cu1, _cfg(causal=True))
+    np.testing.assert_array_equal(ya, yb)
 
 
 # ------------------------------------------------------------------ input generator sanity
