@@ -176,6 +176,7 @@ def main():
                          "task times of the workload and replay them through the native pipeline simulator "
                          "(fixed 1F1B against readiness-driven dispatch, jitter levels J0-J3)")
     ap.add_argument("--pipeline-stages", type=int, default=8)
+    ap.add_argument("--rope", action="store_true", help="turn on the rotary-embedding variant of the layer (off in the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     args = ap.parse_args()
@@ -194,6 +195,8 @@ def main():
         args.workload = "multimodal"      # the workload whose microbatches differ in cost
     shape = {"language": SI.LANGUAGE, "wide": SI.WIDE_GQA, "vision": SI.VISION, "multimodal": SI.MULTIMODAL,
              "tiny": SI.TINY}[args.workload]
+    if args.rope:
+        shape = shape.replace(rope=True, name=shape.name + "+rope")
     if args.only in ("gemm", "copy"):
         torch.cuda.set_device(0)
         gen = torch.Generator(device="cuda:0")

@@ -75,6 +75,10 @@ typedef struct {
   int32_t causal;         /* 1: key j <= query i inside a segment; 0: whole segment       */
   int32_t norm_kind;      /* 0 = RMSNorm (the only kind)                                  */
   float norm_eps;         /* added to the mean of squares inside the square root          */
+  int32_t rope;           /* 0 = none; 1 = rotary position embedding on q and k (model-fidelity
+                             variant; split-half pairs (x_i, x_{i+d/2}), angle pos * rope_base^(-2i/d),
+                             pos = index of the token inside its own segment)              */
+  float rope_base;        /* > 1 when rope = 1 (10000 in the usual models); ignored otherwise */
 } stage_config;
 
 typedef struct stage_s stage_t;

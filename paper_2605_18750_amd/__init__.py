@@ -19,7 +19,7 @@ class stage_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "max_tokens",
         "n_microbatches", "max_segments", "dtype", "mlp_kind", "causal", "norm_kind")] + [
-        ("norm_eps", C.c_float)]
+        ("norm_eps", C.c_float), ("rope", C.c_int32), ("rope_base", C.c_float)]
 
 
 class StageError(RuntimeError):

@@ -333,6 +333,32 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const float* __restrict__
   }
 }
 
+// ---------------------------------------------------------------- rotary embedding
+// One workgroup per (query tile, head); a wavefront per row, a lane per pair.  The angle is formed in
+// double precision and reduced to [0, 2 pi) before the single-precision sine and cosine, so that the
+// fp32 path keeps its 1e-4 budget at positions in the thousands.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ x, const AttnTile* __restrict__ tiles, int d, int ld,
+                                                   double log2_base, float sign) {
+  const AttnTile tl = tiles[blockIdx.x];
+  const int head = blockIdx.y, half = d >> 1;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i0 = lane; i0 < half; i0 += 64) {
+    const double theta = exp2(-2.0 * (double)i0 / (double)d * log2_base);
+    for (int row = tl.r0 + wave; row < tl.r1; row += 4) {
+      double ang = (double)(row - tl.s0) * theta;
+      ang -= 6.283185307179586476925 * floor(ang * 0.1591549430918953357689);
+      float sn, cs;
+      __sincosf((float)ang, &sn, &cs);
+      sn *= sign;
+      T* p = x + (size_t)row * ld + head * d + i0;
+      const float a = to_float(p[0]), b = to_float(p[half]);
+      p[0] = from_float<T>(a * cs - b * sn);
+      p[half] = from_float<T>(b * cs + a * sn);
+    }
+  }
+}
+
 // ---------------------------------------------------------------- gradient reduction
 // Slots are streamed once: all loads of a group of up to 8 slots are issued before the first add (the
 // adds then run in microbatch index order, which is what fixes the result bit for bit), and the loads
@@ -369,6 +395,14 @@ inline int grid_for(size_t n, int cap = 256 * 32) {
 
 hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s) {
   DISPATCH_T(dtype, hipLaunchKernelGGL(widen_kernel<T>, dim3(grid_for(n / Vec<T>::N + 1)), dim3(256), 0, s, (const T*)src, dst, n));
+  return hipGetLastError();
+}
+
+hipError_t launch_rope(void* x, const AttnTile* q_tiles, int n_q_tiles, int n_heads, int d, int ld, float base,
+                       float sign, int dtype, hipStream_t s) {
+  if (n_q_tiles < 1 || n_heads < 1 || (d & 1) || !(base > 1.0f)) return hipErrorInvalidValue;
+  DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kernel<T>, dim3(n_q_tiles, n_heads), dim3(256), 0, s, (T*)x, q_tiles, d, ld,
+                                       log2((double)base), sign));
   return hipGetLastError();
 }
 

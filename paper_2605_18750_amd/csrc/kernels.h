@@ -71,6 +71,11 @@ bool attn_mfma_supports(const AttnArgs& a);
 
 // dst[i] = (float)src[i]: storage type -> fp32 (entry of the residual stream).
 hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s);
+// Rotary embedding, in place, on the first n_heads heads (head_dim d, even) of every row of a [T, ld]
+// tensor: pair (x_i, x_{i+d/2}) turns by sign * pos * base^(-2i/d), pos = row - segment start, rows and
+// segment starts taken from the query tile list (the tiles partition the rows).
+hipError_t launch_rope(void* x, const AttnTile* q_tiles, int n_q_tiles, int n_heads, int d, int ld, float base,
+                       float sign, int dtype, hipStream_t s);
 
 // h = x * r * g, r = rsqrt(mean(x^2) + eps); x fp32, r_out [T] fp32, g and h storage type.
 hipError_t launch_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_out,

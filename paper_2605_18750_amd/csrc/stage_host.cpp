@@ -72,6 +72,8 @@ int check_config(const stage_config* c) {
   if (c->causal != 0 && c->causal != 1) { set_tls_error("causal must be 0 or 1"); return STAGE_EINVAL; }
   if (c->norm_kind != 0) { set_tls_error("norm_kind must be 0 (RMSNorm)"); return STAGE_EINVAL; }
   if (!(c->norm_eps >= 0.0f) || !(c->norm_eps < 1.0f)) { set_tls_error("norm_eps must be in [0, 1)"); return STAGE_EINVAL; }
+  if (c->rope != 0 && c->rope != 1) { set_tls_error("rope must be 0 or 1"); return STAGE_EINVAL; }
+  if (c->rope == 1 && !(c->rope_base > 1.0f)) { set_tls_error("rope_base must be > 1"); return STAGE_EINVAL; }
   if (c->head_dim % 16 != 0 || c->head_dim > 128) { set_tls_error("head_dim must be a multiple of 16, at most 128"); return STAGE_EINVAL; }
   if (c->dtype == STAGE_DTYPE_FP32 && c->ffn % 4 != 0) { set_tls_error("fp32: ffn must be a multiple of 4"); return STAGE_EINVAL; }
   if (c->dtype == STAGE_DTYPE_BF16) {
@@ -374,6 +376,9 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     g.A = base + L.h1; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WQKV); g.ldb = P.n_qkv;
     g.C = base + L.qkv; g.ldc = P.n_qkv; g.R = nullptr; g.N = P.n_qkv; g.K = H;
     HIP_TRY(st, launch_gemm(g, s));
+    if (c.rope)   // rotate q and k in place: the stash then holds what the attention (and its backward) reads
+      HIP_TRY(st, launch_rope(base + L.qkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,
+                              c.head_dim, P.n_qkv, c.rope_base, 1.0f, dt, s));
     AttnArgs a{};
     a.qkv = base + L.qkv; a.o = base + L.o; a.lse = (float*)(base + L.lse);
     a.o32 = dt == BF16 ? (float*)(base + L.o32) : nullptr;
@@ -472,6 +477,9 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     a.T = T; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.d = c.head_dim; a.causal = c.causal; a.dtype = dt;
     a.d_o = base + P.t_do; a.dqkv = base + L.dqkv; a.delta = (float*)(base + P.t_delta);
     HIP_TRY(st, launch_attn_bwd(a, s));
+    if (c.rope)   // gradients w.r.t. the rotated q, k -> w.r.t. the projection outputs (inverse rotation)
+      HIP_TRY(st, launch_rope(base + L.dqkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,
+                              c.head_dim, P.n_qkv, c.rope_base, -1.0f, dt, s));
     // dh1 = [dq|dk|dv] Wqkv^T
     g.A = base + L.dqkv; g.lda = P.n_qkv; g.B = param_ptr(st, l, STAGE_P_WQKV); g.ldb = P.n_qkv;
     g.C = base + P.t_dh; g.ldc = H; g.N = H; g.K = P.n_qkv; g.out_dtype = F32;

@@ -18,7 +18,8 @@ def make_config(shape, max_tokens: int, max_segments: int = 1, n_microbatches: i
         max_segments=max_segments,
         dtype=R.STAGE_DTYPE_FP32 if shape.dtype == "fp32" else R.STAGE_DTYPE_BF16,
         mlp_kind=R.STAGE_MLP_SWIGLU if shape.mlp_kind == "swiglu" else R.STAGE_MLP_GELU,
-        causal=1 if shape.causal else 0, norm_kind=0, norm_eps=shape.norm_eps)
+        causal=1 if shape.causal else 0, norm_kind=0, norm_eps=shape.norm_eps,
+        rope=1 if getattr(shape, "rope", False) else 0, rope_base=getattr(shape, "rope_base", 10000.0))
 
 
 def _fused(layer: dict, which: int, swiglu: bool) -> np.ndarray:

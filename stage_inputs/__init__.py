@@ -38,6 +38,8 @@ class StageShape:
     mlp_kind: str = "swiglu"     # "swiglu" | "gelu"
     causal: bool = True
     norm_eps: float = 1e-5
+    rope: bool = False            # rotary position embedding on q and k (model-fidelity variant)
+    rope_base: float = 10000.0
     w_std: float = 0.02
     x_std: float = 1.0
     dy_std: float = 1.0

@@ -13,7 +13,8 @@ TOL = {"fp32": 1e-4, "bf16": 2e-2}
 def oracle_config(shape: SI.StageShape) -> O.OracleConfig:
     return O.OracleConfig(n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
                           n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
-                          mlp_kind=shape.mlp_kind, causal=shape.causal, norm_eps=shape.norm_eps)
+                          mlp_kind=shape.mlp_kind, causal=shape.causal, norm_eps=shape.norm_eps,
+                          rope=shape.rope, rope_base=shape.rope_base)
 
 
 def max_norm_rel_err(got: np.ndarray, ref: np.ndarray) -> float:

@@ -38,6 +38,15 @@ SMALL = {
     # fp32 degenerate lengths
     "fp32_single_tokens": (SI.StageShape("s_fp32_c", 1, 64, 2, 1, 32, 48, 3, dtype="fp32", x_std=1.0, dy_std=1.0, w_std=0.1),
                            [[0, 1], [0, 1, 2, 3], [0, 65]]),
+    # rotary position embedding variant: bf16 d = 128 GQA ragged causal; fp32 d = 32 bidirectional GELU
+    "bf16_rope_d128": (SI.StageShape("s_bf16_rope", 2, 512, 4, 2, 128, 320, 3, w_std=0.03, rope=True),
+                       [[0, 300], [0, 130, 391], [0, 5]]),
+    "bf16_rope_d80": (SI.StageShape("s_bf16_rope80", 1, 320, 4, 4, 80, 256, 2, mlp_kind="gelu", causal=False, w_std=0.05,
+                                    rope=True, rope_base=500.0),
+                      [[0, 100, 200, 300], [0, 259]]),
+    "fp32_rope": (SI.StageShape("s_fp32_rope", 2, 64, 2, 1, 32, 48, 2, dtype="fp32", mlp_kind="gelu", causal=False,
+                                x_std=1.0, dy_std=1.0, w_std=0.1, rope=True),
+                  [[0, 65, 130], [0, 129]]),
     # bf16, head_dim 128, GQA 4:1
     "bf16_d128_gqa4": (SI.StageShape("s_bf16_c", 1, 512, 4, 1, 128, 320, 2, w_std=0.03),
                        [[0, 300], [0, 130, 260]]),
@@ -67,7 +76,7 @@ def test_tiny_fp32_config_matches_oracle():
     _say(f"[parity] tiny: worst rel err {worst:.3e}")
 
 
-@pytest.mark.parametrize("name", ["fp32_ragged_causal_gqa", "bf16_ragged_causal_gqa", "bf16_bidir_gelu_d80"])
+@pytest.mark.parametrize("name", ["fp32_ragged_causal_gqa", "bf16_ragged_causal_gqa", "bf16_bidir_gelu_d80", "bf16_rope_d128"])
 def test_dispatch_order_is_bit_exact(name):
     shape, cus = SMALL[name]
     w = Hp.Workload(shape, cus)
