@@ -567,10 +567,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
 #define RRFP_INST(AKC, BKC, TO, HR, ACT)                                                                     \
   template __global__ void gemm_mfma_dl_kernel<AKC, BKC, TO, HR, dl_wm(AKC, BKC), dl_wn(AKC, BKC), ACT>(      \
       const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int);
-#define RRFP_INST_SHORT(ACT)                                                                                 \
-  template __global__ void gemm_mfma_dl_kernel<true, false, bf16_t, false, dl_wm(true, false), dl_wn(true, false), ACT, 128>( \
-      const bf16_t*, const bf16_t*, bf16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int);
-RRFP_INST_SHORT(ACT_NONE) RRFP_INST_SHORT(ACT_SWIGLU_FWD) RRFP_INST_SHORT(ACT_GELU_FWD)
+#define RRFP_INST_SHORT(BKC, TO, HR, ACT)                                                                    \
+  template __global__ void gemm_mfma_dl_kernel<true, BKC, TO, HR, dl_wm(true, BKC), dl_wn(true, BKC), ACT, 128>( \
+      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int);
+#define RRFP_INST_SHORT4(BKC) RRFP_INST_SHORT(BKC, float, true, ACT_NONE) RRFP_INST_SHORT(BKC, float, false, ACT_NONE) \
+                              RRFP_INST_SHORT(BKC, bf16_t, true, ACT_NONE) RRFP_INST_SHORT(BKC, bf16_t, false, ACT_NONE)
+RRFP_INST_SHORT4(false) RRFP_INST_SHORT4(true)
+RRFP_INST_SHORT(false, bf16_t, false, ACT_SWIGLU_FWD) RRFP_INST_SHORT(false, bf16_t, false, ACT_GELU_FWD)
+RRFP_INST_SHORT(true, bf16_t, false, ACT_SWIGLU_BWD) RRFP_INST_SHORT(true, bf16_t, false, ACT_GELU_BWD)
+#undef RRFP_INST_SHORT4
 #undef RRFP_INST_SHORT
 #define RRFP_INST4(AKC, BKC) RRFP_INST(AKC, BKC, float, true, ACT_NONE) RRFP_INST(AKC, BKC, float, false, ACT_NONE) \
                              RRFP_INST(AKC, BKC, bf16_t, true, ACT_NONE) RRFP_INST(AKC, BKC, bf16_t, false, ACT_NONE)
@@ -590,12 +595,7 @@ inline bool direct_ok(const GemmArgs& g) {
   return a_bytes < lim && b_bytes < lim;
 }
 
-// Number of trailing tile columns to compute with 128-row tiles.  One workgroup occupies a CU, so a
-// GEMM of t tiles runs in ceil(t / n_cu) rounds and a last round of r = t mod n_cu tiles leaves CUs
-// idle.  When r is at most half the CUs and is a whole number of tile columns, those columns are
-// launched separately as 2r half-height tiles: one short round instead of a full one.  A pure
-// function of the shape and the device.
-inline int short_tail_columns(int tiles_m, int tiles_n) {
+inline int cu_count() {
   static int n_cu = 0;
   if (n_cu == 0) {
     int dev = 0, v = 0;
@@ -603,25 +603,43 @@ inline int short_tail_columns(int tiles_m, int tiles_n) {
       v = 256;
     n_cu = v;
   }
-  const int t = tiles_m * tiles_n, r = t % n_cu;
-  if (t <= n_cu || r == 0 || 2 * r > n_cu || r % tiles_m) return 0;
-  return r / tiles_m;
+  return n_cu;
 }
 
-// Launch of the (A K-contiguous, B K-strided, bf16 out, no residual) forms with the short-tile tail.
-template <int ACT>
-hipError_t launch_nn_bf16(const GemmArgs& g, hipStream_t s) {
-  constexpr int WMv = dl_wm(true, false), WNv = dl_wn(true, false);
+// How a GEMM with A K-contiguous is cut into launches.  One workgroup occupies a CU, so t tiles of
+// 256 x 256 run in ceil(t / n_cu) rounds.  (a) A grid that fills at most half the CUs is launched
+// entirely with 128-row tiles (twice the workgroups).  (b) Otherwise, when the last round holds r
+// tiles and carving ceil(r / tiles_m) trailing tile columns off removes that round, those columns
+// are launched separately with 128-row tiles, provided they fit one round.  A pure function of the
+// shape and the device.  Returns the number of tile columns of the 256-row launch.
+inline int full_tile_columns(int tiles_m, int tiles_n) {
+  const int n_cu = cu_count(), t = tiles_m * tiles_n;
+  if (2 * t <= n_cu) return 0;
+  const int r = t % n_cu;
+  if (t <= n_cu || r == 0) return tiles_n;
+  const int ct = (r + tiles_m - 1) / tiles_m;
+  if (ct >= tiles_n) return tiles_n;
+  const int t_main = t - ct * tiles_m;
+  const bool removes_round = (t_main + n_cu - 1) / n_cu < (t + n_cu - 1) / n_cu;
+  const bool tail_fits = 2 * ct * tiles_m <= n_cu;
+  return (removes_round && tail_fits) ? tiles_n - ct : tiles_n;
+}
+
+// Launch of the direct-to-LDS kernel for the forms with A K-contiguous, per the cut above.
+template <bool B_KC, typename TO, bool HAS_R, int ACT>
+hipError_t launch_a_kc(const GemmArgs& g, hipStream_t s) {
+  constexpr int WMv = dl_wm(true, B_KC), WNv = dl_wn(true, B_KC);
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  const int ct = short_tail_columns(tiles_m, tiles_n);
-  hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, false, bf16_t, false, WMv, WNv, ACT>), dim3(tiles_m * (tiles_n - ct)),
-                     dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, (const float*)nullptr,
-                     g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0, tiles_m, tiles_n - ct, (bf16_t*)g.E, g.lde, 0);
-  if (ct > 0) {
+  const int cn = full_tile_columns(tiles_m, tiles_n);
+  if (cn > 0)
+    hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT>), dim3(tiles_m * cn), dim3(WMv * WNv * 64),
+                       0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc,
+                       g.ldr, tiles_m, cn, (bf16_t*)g.E, g.lde, 0);
+  if (cn < tiles_n) {
     const int tiles_m2 = (g.M + 127) / 128;
-    hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, false, bf16_t, false, WMv, WNv, ACT, 128>), dim3(tiles_m2 * ct),
-                       dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, (const float*)nullptr,
-                       g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0, tiles_m2, ct, (bf16_t*)g.E, g.lde, tiles_n - ct);
+    hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT, 128>), dim3(tiles_m2 * (tiles_n - cn)),
+                       dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K,
+                       g.lda, g.ldb, g.ldc, g.ldr, tiles_m2, tiles_n - cn, (bf16_t*)g.E, g.lde, cn);
   }
   return hipGetLastError();
 }
@@ -630,7 +648,7 @@ template <bool A_KC, bool B_KC, typename TO, bool HAS_R>
 hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   if (direct_ok(g)) {
-    if (A_KC && !B_KC && !HAS_R && sizeof(TO) == 2) return launch_nn_bf16<ACT_NONE>(g, s);
+    if constexpr (A_KC) return launch_a_kc<B_KC, TO, HAS_R, ACT_NONE>(g, s);
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
                        dim3(tiles_m * tiles_n), dim3(dl_wm(A_KC, B_KC) * dl_wn(A_KC, B_KC) * 64), 0,
                        s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda,
@@ -661,13 +679,7 @@ hipError_t launch_orient(const GemmArgs& g, hipStream_t s) {
 // Fused-activation launch: forward forms are (A K-contiguous, B K-strided), backward forms (both K-contiguous).
 template <bool B_KC, int ACT>
 hipError_t launch_act(const GemmArgs& g, hipStream_t s) {
-  if (!B_KC) return launch_nn_bf16<ACT>(g, s);
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, bf16_t, false, dl_wm(true, B_KC), dl_wn(true, B_KC), ACT>),
-                     dim3(tiles_m * tiles_n), dim3(dl_wm(true, B_KC) * dl_wn(true, B_KC) * 64), 0, s, (const bf16_t*)g.A,
-                     (const bf16_t*)g.B, (bf16_t*)g.C, (const float*)nullptr, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0,
-                     tiles_m, tiles_n, (bf16_t*)g.E, g.lde, 0);
-  return hipGetLastError();
+  return launch_a_kc<B_KC, bf16_t, false, ACT>(g, s);
 }
 
 bool gemm_act_supported(const GemmArgs& g) {
