@@ -20,6 +20,8 @@
 // (fp32) stores.  Rows beyond M, columns beyond N and k beyond K are zero-filled on load and
 // masked on store.  The k loop order and the tile partition depend only on the shape, so the
 // result does not depend on how many CUs were free.
+#include <algorithm>
+
 #include "kernels.h"
 #include "numeric.h"
 
@@ -368,8 +370,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
                                                                TO* __restrict__ C, const float* __restrict__ R, int M,
                                                                int N, int K, int lda, int ldb, int ldc, int ldr,
                                                                int tiles_m, int tiles_n, bf16_t* __restrict__ E, int lde,
-                                                               int tn0) {
+                                                               int tn0, int k_split) {
   constexpr int NW = WM * WN;
+  // Split-K launches (grid y = split): this workgroup contracts k in [y * k_split, min(K, (y+1) * k_split))
+  // and writes its partial tile into the y-th [M, ldc] plane of C.
+  if (k_split > 0) {
+    const int k0 = blockIdx.y * k_split;
+    A += A_KC ? (size_t)k0 : (size_t)k0 * lda;
+    B += B_KC ? (size_t)k0 : (size_t)k0 * ldb;
+    C += (size_t)blockIdx.y * M * ldc;
+    K = min(k_split, K - k0);
+  }
   constexpr int MI = (BMT / 32) / WM;               // 32-high row blocks per wavefront
   constexpr int NB = 8 / WN;                        // 32-wide column blocks per wavefront
   constexpr int WAVE_M = MI * 32, WAVE_N = NB * 32;
@@ -566,10 +577,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
 // Explicit instantiations of every variant the launcher can pick.
 #define RRFP_INST(AKC, BKC, TO, HR, ACT)                                                                     \
   template __global__ void gemm_mfma_dl_kernel<AKC, BKC, TO, HR, dl_wm(AKC, BKC), dl_wn(AKC, BKC), ACT>(      \
-      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int);
+      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int);
 #define RRFP_INST_SHORT(BKC, TO, HR, ACT)                                                                    \
   template __global__ void gemm_mfma_dl_kernel<true, BKC, TO, HR, dl_wm(true, BKC), dl_wn(true, BKC), ACT, 128>( \
-      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int);
+      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int);
 #define RRFP_INST_SHORT4(BKC) RRFP_INST_SHORT(BKC, float, true, ACT_NONE) RRFP_INST_SHORT(BKC, float, false, ACT_NONE) \
                               RRFP_INST_SHORT(BKC, bf16_t, true, ACT_NONE) RRFP_INST_SHORT(BKC, bf16_t, false, ACT_NONE)
 RRFP_INST_SHORT4(false) RRFP_INST_SHORT4(true)
@@ -625,6 +636,15 @@ inline int full_tile_columns(int tiles_m, int tiles_n) {
   return (removes_round && tail_fits) ? tiles_n - ct : tiles_n;
 }
 
+// Split-K factor for a grid of t tiles and a contraction of K: as many ranges as fit the CUs, each at
+// least 16 steps deep, at most 16 ranges; 1 = no split.  A pure function of the shape and the device.
+inline int splitk_factor(int t, int K) {
+  const int n_cu = cu_count();
+  if (2 * t > n_cu) return 1;
+  const int steps = (K + DBK - 1) / DBK;
+  return std::max(1, std::min(std::min(n_cu / t, steps / 16), 16));
+}
+
 // Launch of the direct-to-LDS kernel for the forms with A K-contiguous, per the cut above.
 template <bool B_KC, typename TO, bool HAS_R, int ACT>
 hipError_t launch_a_kc(const GemmArgs& g, hipStream_t s) {
@@ -634,12 +654,12 @@ hipError_t launch_a_kc(const GemmArgs& g, hipStream_t s) {
   if (cn > 0)
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT>), dim3(tiles_m * cn), dim3(WMv * WNv * 64),
                        0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc,
-                       g.ldr, tiles_m, cn, (bf16_t*)g.E, g.lde, 0);
+                       g.ldr, tiles_m, cn, (bf16_t*)g.E, g.lde, 0, 0);
   if (cn < tiles_n) {
     const int tiles_m2 = (g.M + 127) / 128;
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT, 128>), dim3(tiles_m2 * (tiles_n - cn)),
                        dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K,
-                       g.lda, g.ldb, g.ldc, g.ldr, tiles_m2, tiles_n - cn, (bf16_t*)g.E, g.lde, cn);
+                       g.lda, g.ldb, g.ldc, g.ldr, tiles_m2, tiles_n - cn, (bf16_t*)g.E, g.lde, cn, 0);
   }
   return hipGetLastError();
 }
@@ -649,10 +669,27 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   if (direct_ok(g)) {
     if constexpr (A_KC) return launch_a_kc<B_KC, TO, HAS_R, ACT_NONE>(g, s);
+    // Weight-gradient form (both operands K-strided, fp32 out, K = tokens): when the output has too
+    // few tiles to fill the CUs, the contraction is split into S ranges, every range writes its own
+    // partial plane into the scratch, and the planes are summed in range order (one fixed order).
+    if constexpr (!A_KC && !B_KC && !HAS_R && sizeof(TO) == 4) {
+      const int S = splitk_factor(tiles_m * tiles_n, g.K);
+      if (S > 1 && g.ws && g.ldc == g.N && (size_t)S * g.M * g.N * 4 <= g.ws_bytes && ((size_t)g.M * g.N) % 4 == 0) {
+        const int steps = (g.K + DBK - 1) / DBK, k_split = (steps + S - 1) / S * DBK;
+        const int S_eff = (g.K + k_split - 1) / k_split;
+        hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
+                           dim3(tiles_m * tiles_n, S_eff), dim3(dl_wm(A_KC, B_KC) * dl_wn(A_KC, B_KC) * 64), 0,
+                           s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.ws, g.R, g.M, g.N, g.K, g.lda,
+                           g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, k_split);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return launch_grad_reduce((const float*)g.ws, (size_t)g.M * g.N, S_eff, (float*)g.C, (size_t)g.M * g.N, s);
+      }
+    }
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
                        dim3(tiles_m * tiles_n), dim3(dl_wm(A_KC, B_KC) * dl_wn(A_KC, B_KC) * 64), 0,
                        s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda,
-                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0);
+                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, 0);
     return hipGetLastError();
   }
   static bool configured = false;   // per instantiation; the attribute is process-wide for the function

@@ -34,6 +34,8 @@ struct GemmArgs {
   int act;         // GemmAct
   void* E;         // activation operand (see GemmAct); written for *_FWD, read for *_BWD
   int lde;
+  void* ws;        // optional scratch for split-K partial results (fp32), else null
+  size_t ws_bytes;
 };
 bool gemm_act_supported(const GemmArgs& g);   // true if launch_gemm can run g.act fused for this shape
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);       // picks the kernel family

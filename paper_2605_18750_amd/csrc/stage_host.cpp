@@ -513,6 +513,7 @@ int stage_W(stage_t* st, int mb, void* stream) {
     const LayerStash& L = P.layer[l];
     GemmArgs g{};
     g.in_dtype = dt; g.out_dtype = F32; g.transA = true; g.transB = false; g.K = T; g.R = nullptr;
+    g.ws = base + P.t_dm; g.ws_bytes = (size_t)c.max_tokens * F * 4;   // B's fp32 temporary is idle during W
     g.A = base + L.h1; g.lda = H; g.B = base + L.dqkv; g.ldb = P.n_qkv;
     g.C = slot + P.p_off[l][STAGE_P_WQKV]; g.ldc = P.n_qkv; g.M = H; g.N = P.n_qkv;
     HIP_TRY(st, launch_gemm(g, s));

@@ -47,6 +47,9 @@ SMALL = {
     "fp32_rope": (SI.StageShape("s_fp32_rope", 2, 64, 2, 1, 32, 48, 2, dtype="fp32", mlp_kind="gelu", causal=False,
                                 x_std=1.0, dy_std=1.0, w_std=0.1, rope=True),
                   [[0, 65, 130], [0, 129]]),
+    # bf16, many tokens on a narrow stage: the weight-gradient GEMMs (K = tokens) take the split-K path
+    "bf16_long_tokens_splitk": (SI.StageShape("s_bf16_e", 1, 128, 4, 2, 64, 192, 2, w_std=0.05),
+                                [[0, 1100], [0, 600, 1163]]),
     # bf16, head_dim 128, GQA 4:1
     "bf16_d128_gqa4": (SI.StageShape("s_bf16_c", 1, 512, 4, 1, 128, 320, 2, w_std=0.03),
                        [[0, 300], [0, 130, 260]]),
@@ -76,7 +79,8 @@ def test_tiny_fp32_config_matches_oracle():
     _say(f"[parity] tiny: worst rel err {worst:.3e}")
 
 
-@pytest.mark.parametrize("name", ["fp32_ragged_causal_gqa", "bf16_ragged_causal_gqa", "bf16_bidir_gelu_d80", "bf16_rope_d128"])
+@pytest.mark.parametrize("name", ["fp32_ragged_causal_gqa", "bf16_ragged_causal_gqa", "bf16_bidir_gelu_d80", "bf16_rope_d128",
+                                  "bf16_long_tokens_splitk"])
 def test_dispatch_order_is_bit_exact(name):
     shape, cus = SMALL[name]
     w = Hp.Workload(shape, cus)
