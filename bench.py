@@ -106,7 +106,7 @@ def gemm_roofline(shape, T, Bw, s, gen, n_launch=20):
             traffic = json.load(open(tpath)).get(f"{T}x{N_up}x{shape.hidden}")
         except Exception:
             traffic = None
-    return {"bound": "mfma", "kernel": f"gemm_mfma_dl_kernel NN {T}x{N_up}x{shape.hidden} bf16", "achieved": round(ach, 1),
+    return {"bound": "mfma", "kernel": f"gemm_mfma_dl_kernel NN {T}x{N_up}x{shape.hidden} bf16 (one call: 256-row tiles + 128-row tail launch)", "achieved": round(ach, 1),
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
             "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic}
 

@@ -1,25 +1,33 @@
 // bf16 MFMA GEMM for gfx950: C[M,N] = A(m,k) B(k,n) (+R), fp32 accumulation, bf16 or fp32 out.
 //
-// One workgroup (4 wavefronts, one per SIMD) owns a 256x256 tile of C and walks K in steps of
-// 64 with two LDS stages (2 x 64 KB): while the MFMAs of step k run from one stage, the global
-// loads of step k+1 are in flight into registers and are written to the other stage afterwards.
-// Each wavefront owns a 128x128 quadrant as 4x4 v_mfma_f32_32x32x16_bf16 accumulators.
+// Two kernels share the tile geometry (a workgroup owns a 256-wide tile of C, v_mfma_f32_32x32x16_bf16
+// accumulators) and the LDS layouts:
+//
+//   gemm_mfma_dl_kernel  the main kernel.  K advances in 32-deep steps through four LDS stages that
+//     are filled by direct global->LDS loads issued three steps ahead; 8 wavefronts (2 x 4, 128 x 64
+//     each) when an operand is K-contiguous, 4 (2 x 2, 128 x 128 each) when both are K-strided;
+//     epilogue staged through LDS so that all stores, residual loads and activation-operand loads are
+//     row-contiguous; optional fused residual / SwiGLU / GELU forward and backward epilogues; a
+//     128-row tile variant and a split-K mode for grids that do not fill the CUs.
+//   gemm_mfma_kernel     the fallback for K-contiguous operands whose K is not a multiple of 32: four
+//     wavefronts, 64-deep steps, two LDS stages filled through registers.
 //
 // Operand tiles sit in LDS in their memory orientation, so every global load is a coalesced
 // 16-byte access:
-//   K-contiguous operand ([rows][K] in memory): LDS [256 rows][64 k], 16-byte chunks XOR-swizzled
-//     by ((row >> 1) & 7); a fragment (8 consecutive k of one row) is one ds_read_b128.
-//   K-strided operand ([K][rows] in memory): LDS [64 k][256 rows], 64-byte units XOR-swizzled by
+//   K-contiguous operand ([rows][K] in memory): rows of 16-byte chunks, XOR-swizzled so that the 16
+//     rows one ds_read_b128 phase touches fall into distinct bank groups; a fragment (8 consecutive
+//     k of one row) is one ds_read_b128.
+//   K-strided operand ([K][rows] in memory): LDS [k][256 rows], 64-byte units XOR-swizzled by
 //     k; a fragment is two ds_read_b64_tr_b16, the LDS transpose read of gfx950 that hands each
 //     lane 4 consecutive k of one row out of a 4(k) x 16(rows) block.
 // The forward GEMMs use (A K-contiguous, B K-strided), the input-gradient GEMMs (both
 // K-contiguous), the weight-gradient GEMMs (both K-strided, K = tokens).
 //
 // The MFMA is issued with the B fragment as its first operand, so a lane's four consecutive
-// accumulator values are four consecutive columns of one row of C: 8-byte (bf16) or 16-byte
-// (fp32) stores.  Rows beyond M, columns beyond N and k beyond K are zero-filled on load and
-// masked on store.  The k loop order and the tile partition depend only on the shape, so the
-// result does not depend on how many CUs were free.
+// accumulator values are four consecutive columns of one row of C.  Rows beyond M, columns beyond N
+// and k beyond K are zero-filled on load and masked on store.  The k loop order, the tile partition,
+// the choice of 128-row tiles and the split-K factor depend only on the shape and on the device's CU
+// count, never on what else is running, so a given call always sums in the same order.
 #include <algorithm>
 
 #include "kernels.h"

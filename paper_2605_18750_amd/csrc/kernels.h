@@ -40,7 +40,7 @@ struct GemmArgs {
 bool gemm_act_supported(const GemmArgs& g);   // true if launch_gemm can run g.act fused for this shape
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);       // picks the kernel family
 hipError_t launch_gemm_simt(const GemmArgs& g, hipStream_t s);  // fp32-FMA tiles, any shape
-hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);  // bf16 MFMA 256x256x64 tiles
+hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);  // bf16 MFMA kernels (256-wide tiles)
 bool gemm_mfma_supports(const GemmArgs& g);                     // alignment / divisibility rules
 
 // One attention work item: a tile of rows [r0, r1) inside the segment [s0, s1).
