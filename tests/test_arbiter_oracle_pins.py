@@ -279,14 +279,28 @@ def test_jitter_model_statistics_and_pairing():
     assert u != A.task_uniforms(5, 2, A.F, 3, 0, 8, 1)
 
 
+def _golden(name):
+    import os
+    rows = []
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", name)):
+        line = line.split("#")[0].split()
+        if line:
+            rows.append(line)
+    return rows
+
+
 def test_splitmix64_reference_values():
-    # first outputs of splitmix64 seeded with 0 and with 1234567 (values published with the
-    # reference implementation by Vigna; state advances by the golden-ratio increment)
-    x, outs = 0, []
-    for _ in range(3):
-        outs.append(A.splitmix64(x)); x = (x + 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
-    assert outs == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
-    x, outs = 1234567, []
-    for _ in range(2):
-        outs.append(A.splitmix64(x)); x = (x + 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
-    assert outs == [6457827717110365317, 3203168211198807973]
+    # published outputs of splitmix64 (tests/golden/splitmix64.txt)
+    for row in _golden("splitmix64.txt"):
+        x = int(row[0], 0)
+        for want in row[1:]:
+            assert A.splitmix64(x) == int(want, 0)
+            x = (x + 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
+
+
+def test_jitter_levels_are_the_papers_table():
+    # Sec. 7.6 table, parameters only (tests/golden/jitter_levels.txt); base delay in seconds here
+    rows = _golden("jitter_levels.txt")
+    assert [r[0] for r in rows] == ["J0", "J1", "J2", "J3"]
+    for name, p, b_ms, alpha in rows:
+        assert A.JITTER_LEVELS[name] == (float(p), float(b_ms) * 1e-3, float(alpha))
