@@ -33,6 +33,12 @@ optimizer update; norm-gain gradients are produced in B; no biases, no positiona
 encoding; eps inside the square root; masked keys are excluded from the softmax;
 query head a uses KV head a // (n_q / n_kv); GELU is the exact erf form.
 
+Model-fidelity variants (off in the five workloads; the paper names GPT3-Large and ViT models,
+which use them, without printing layer details): rope = rotary embedding on q and k;
+norm_kind = "layer" replaces both RMSNorms by LayerNorm with gain and bias,
+h = (x - mean) * (var + eps)^-1/2 * g + b; bias = True adds a bias vector to each of the four
+projections.  All vector-shaped gradients (gains and biases) are produced in B.
+
 Every function is pinned by tests/test_oracle_pins.py (finite differences, brute-force
 loops, closed forms, exact causality, split == unsplit, microbatch-sum == packed batch,
 an independent autograd cross-check).  Nothing here is "parity unpinned".
@@ -56,12 +62,50 @@ class OracleConfig:
     mlp_kind: str = "swiglu"      # "swiglu" | "gelu"
     causal: bool = True
     norm_eps: float = 1e-5
+    norm_kind: str = "rms"        # "rms" | "layer" (LayerNorm with gain and bias; model-fidelity variant)
+    bias: bool = False            # bias vectors on the four projections (model-fidelity variant)
     rope: bool = False            # rotary position embedding on q and k (model-fidelity variant)
     rope_base: float = 10000.0
     rope_offset: int = 0          # added to every position (test hook for the relative-position property)
 
 
 # ----------------------------------------------------------------------------- pieces
+
+def layernorm_fwd(x, g, b, eps):
+    """h = xhat * g + b with xhat = (x - mean_c x) * r, r = (var_c x + eps)^(-1/2) (biased variance)."""
+    mu = np.mean(x, axis=1, keepdims=True)
+    xc = x - mu
+    r = 1.0 / np.sqrt(np.mean(xc * xc, axis=1, keepdims=True) + eps)
+    xhat = xc * r
+    return xhat * g + b, xhat, r
+
+
+def layernorm_bwd(dh, xhat, r, g):
+    """Gradient of h = xhat * g + b.  Returns dx, dg, db."""
+    w = dh * g
+    dx = r * (w - np.mean(w, axis=1, keepdims=True) - xhat * np.mean(w * xhat, axis=1, keepdims=True))
+    return dx, np.sum(dh * xhat, axis=0), np.sum(dh, axis=0)
+
+
+def _norm_fwd(x, p, which, cfg):
+    if cfg.norm_kind == "layer":
+        return layernorm_fwd(x, p["g" + which], p["b" + which], cfg.norm_eps)
+    return rmsnorm_fwd(x, p["g" + which], cfg.norm_eps)
+
+
+def _norm_bwd(dh, xhat, r, p, which, cfg, out):
+    """Norm backward; stores the vector-shaped parameter gradients in `out`, returns dx."""
+    if cfg.norm_kind == "layer":
+        dx, out["g" + which], out["b" + which] = layernorm_bwd(dh, xhat, r, p["g" + which])
+    else:
+        dx, out["g" + which] = rmsnorm_bwd(dh, xhat, r, p["g" + which])
+    return dx
+
+
+def _b(p, name, cfg):
+    """Bias vector `name` when the variant is on, else 0."""
+    return p[name] if cfg.bias else 0.0
+
 
 def rope_positions(cu_seqlens, offset=0):
     """Position of every token inside its own segment, plus offset."""
@@ -196,24 +240,24 @@ def layer_forward(x, p, cu_seqlens, cfg):
     """Forward of one pre-norm layer.  p: dict of logical fp64 weights (y = x @ W).
     Returns y and a cache of every intermediate the backward uses."""
     c = {"x": x, "cu": np.asarray(cu_seqlens)}
-    c["h1"], c["xhat"], c["r1"] = rmsnorm_fwd(x, p["g1"], cfg.norm_eps)
-    c["q"] = c["h1"] @ p["Wq"]
-    c["k"] = c["h1"] @ p["Wk"]
-    c["v"] = c["h1"] @ p["Wv"]
+    c["h1"], c["xhat"], c["r1"] = _norm_fwd(x, p, "1", cfg)
+    c["q"] = c["h1"] @ p["Wq"] + _b(p, "bq", cfg)
+    c["k"] = c["h1"] @ p["Wk"] + _b(p, "bk", cfg)
+    c["v"] = c["h1"] @ p["Wv"] + _b(p, "bv", cfg)
     q, k = _qk_for_attention(c, cfg)
     c["o"] = attention_fwd(q, k, c["v"], cu_seqlens, cfg)
-    c["x1"] = x + c["o"] @ p["Wo"]
-    c["h2"], c["x1hat"], c["r2"] = rmsnorm_fwd(c["x1"], p["g2"], cfg.norm_eps)
+    c["x1"] = x + c["o"] @ p["Wo"] + _b(p, "bo", cfg)
+    c["h2"], c["x1hat"], c["r2"] = _norm_fwd(c["x1"], p, "2", cfg)
     if cfg.mlp_kind == "swiglu":
-        c["gt"] = c["h2"] @ p["Wg"]
-        c["up"] = c["h2"] @ p["Wu"]
+        c["gt"] = c["h2"] @ p["Wg"] + _b(p, "bg", cfg)
+        c["up"] = c["h2"] @ p["Wu"] + _b(p, "bu", cfg)
         c["m"] = c["gt"] * _sigmoid(c["gt"]) * c["up"]
     elif cfg.mlp_kind == "gelu":
-        c["u"] = c["h2"] @ p["W1"]
+        c["u"] = c["h2"] @ p["W1"] + _b(p, "bf", cfg)
         c["m"] = c["u"] * _Phi(c["u"])
     else:
         raise ValueError(cfg.mlp_kind)
-    y = c["x1"] + c["m"] @ p["Wd"]
+    y = c["x1"] + c["m"] @ p["Wd"] + _b(p, "bd", cfg)
     return y, c
 
 
@@ -230,11 +274,15 @@ def layer_backward_unsplit(dy, c, p, cfg):
         dh2 = dgt @ p["Wg"].T + dup @ p["Wu"].T
         g["Wg"] = c["h2"].T @ dgt
         g["Wu"] = c["h2"].T @ dup
+        if cfg.bias:
+            g["bg"], g["bu"] = dgt.sum(axis=0), dup.sum(axis=0)
     else:
         du = dm * (_Phi(c["u"]) + c["u"] * _phi(c["u"]))
         dh2 = du @ p["W1"].T
         g["W1"] = c["h2"].T @ du
-    dn, g["g2"] = rmsnorm_bwd(dh2, c["x1hat"], c["r2"], p["g2"])
+        if cfg.bias:
+            g["bf"] = du.sum(axis=0)
+    dn = _norm_bwd(dh2, c["x1hat"], c["r2"], p, "2", cfg, g)
     dx1 = dx1 + dn
     do = dx1 @ p["Wo"].T
     g["Wo"] = c["o"].T @ dx1
@@ -243,7 +291,10 @@ def layer_backward_unsplit(dy, c, p, cfg):
     g["Wq"] = c["h1"].T @ dq
     g["Wk"] = c["h1"].T @ dk
     g["Wv"] = c["h1"].T @ dv
-    dn, g["g1"] = rmsnorm_bwd(dh1, c["xhat"], c["r1"], p["g1"])
+    if cfg.bias:
+        g["bd"], g["bo"] = dy.sum(axis=0), dx1.sum(axis=0)
+        g["bq"], g["bk"], g["bv"] = dq.sum(axis=0), dk.sum(axis=0), dv.sum(axis=0)
+    dn = _norm_bwd(dh1, c["xhat"], c["r1"], p, "1", cfg, g)
     dx = dx1 + dn
     return dx, g
 
@@ -262,12 +313,19 @@ def layer_B(dy, c, p, cfg):
         w["du"] = dm * (_Phi(c["u"]) + c["u"] * _phi(c["u"]))
         dh2 = w["du"] @ p["W1"].T
     gains = {}
-    dn, gains["g2"] = rmsnorm_bwd(dh2, c["x1hat"], c["r2"], p["g2"])
+    dn = _norm_bwd(dh2, c["x1hat"], c["r2"], p, "2", cfg, gains)
     w["dx1"] = dy + dn
     do = w["dx1"] @ p["Wo"].T
     w["dq"], w["dk"], w["dv"] = _attention_bwd_qk(do, c, cfg)
     dh1 = w["dq"] @ p["Wq"].T + w["dk"] @ p["Wk"].T + w["dv"] @ p["Wv"].T
-    dn, gains["g1"] = rmsnorm_bwd(dh1, c["xhat"], c["r1"], p["g1"])
+    dn = _norm_bwd(dh1, c["xhat"], c["r1"], p, "1", cfg, gains)
+    if cfg.bias:     # column sums of the GEMM output-gradients: vector-shaped, produced in B like the gains
+        gains["bd"], gains["bo"] = dy.sum(axis=0), w["dx1"].sum(axis=0)
+        gains["bq"], gains["bk"], gains["bv"] = w["dq"].sum(axis=0), w["dk"].sum(axis=0), w["dv"].sum(axis=0)
+        if cfg.mlp_kind == "swiglu":
+            gains["bg"], gains["bu"] = w["dgt"].sum(axis=0), w["dup"].sum(axis=0)
+        else:
+            gains["bf"] = w["du"].sum(axis=0)
     return w["dx1"] + dn, gains, w
 
 

@@ -23,6 +23,14 @@ def _rand_params(cfg, rng, std=0.3):
             p["Wu"] = std * rng.standard_normal((H, F))
         else:
             p["W1"] = std * rng.standard_normal((H, F))
+        if cfg.norm_kind == "layer":
+            p["b1"] = 0.3 * rng.standard_normal(H)
+            p["b2"] = 0.3 * rng.standard_normal(H)
+        if cfg.bias:
+            for nm, n in (("bq", nq * d), ("bk", nkv * d), ("bv", nkv * d), ("bo", H), ("bd", H)):
+                p[nm] = 0.3 * rng.standard_normal(n)
+            for nm in (("bg", "bu") if cfg.mlp_kind == "swiglu" else ("bf",)):
+                p[nm] = 0.3 * rng.standard_normal(F)
         ps.append(p)
     return ps
 
@@ -34,6 +42,9 @@ CASES = [
     dict(mlp_kind="gelu", causal=True, n_kv_heads=1),
     dict(mlp_kind="swiglu", causal=True, n_kv_heads=2, rope=True),
     dict(mlp_kind="gelu", causal=False, n_kv_heads=4, rope=True, rope_base=50.0),
+    dict(mlp_kind="gelu", causal=False, n_kv_heads=4, norm_kind="layer", bias=True),
+    dict(mlp_kind="swiglu", causal=True, n_kv_heads=2, norm_kind="layer", bias=True, rope=True),
+    dict(mlp_kind="gelu", causal=True, n_kv_heads=2, bias=True),
 ]
 
 
@@ -347,14 +358,19 @@ def test_against_torch_autograd(case):
         mask = mask & torch.tril(torch.ones(T, T, dtype=torch.bool))
     d, nq, nkv = cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads
 
-    def norm(z, g):
-        return z * torch.rsqrt(z.pow(2).mean(-1, keepdim=True) + cfg.norm_eps) * g
+    def norm(z, p, which):
+        if cfg.norm_kind == "layer":
+            return torch.nn.functional.layer_norm(z, (cfg.hidden,), p["g" + which], p["b" + which], cfg.norm_eps)
+        return z * torch.rsqrt(z.pow(2).mean(-1, keepdim=True) + cfg.norm_eps) * p["g" + which]
+
+    def lin(z, p, w, b):
+        return torch.nn.functional.linear(z, p[w].T, p[b] if cfg.bias else None)
 
     h = tx
     for p in tp:
-        a = norm(h, p["g1"])
-        q = (a @ p["Wq"]).view(T, nq, d)
-        k = (a @ p["Wk"]).view(T, nkv, d)
+        a = norm(h, p, "1")
+        q = lin(a, p, "Wq", "bq").view(T, nq, d)
+        k = lin(a, p, "Wk", "bk").view(T, nkv, d)
         if cfg.rope:
             # independent formulation: pairs (x_i, x_{i+d/2}) as complex numbers times e^{i pos theta_i}
             pos = torch.tensor(np.concatenate([np.arange(cu[s + 1] - cu[s]) for s in range(len(cu) - 1)]), dtype=torch.float64)
@@ -367,21 +383,60 @@ def test_against_torch_autograd(case):
             q, k = rope(q), rope(k)
         q = q.transpose(0, 1)
         k = k.transpose(0, 1).repeat_interleave(nq // nkv, 0)
-        v = (a @ p["Wv"]).view(T, nkv, d).transpose(0, 1).repeat_interleave(nq // nkv, 0)
+        v = lin(a, p, "Wv", "bv").view(T, nkv, d).transpose(0, 1).repeat_interleave(nq // nkv, 0)
         o = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=mask)
-        h = h + o.transpose(0, 1).reshape(T, nq * d) @ p["Wo"]
-        b = norm(h, p["g2"])
+        h = h + lin(o.transpose(0, 1).reshape(T, nq * d), p, "Wo", "bo")
+        b = norm(h, p, "2")
         if cfg.mlp_kind == "swiglu":
-            m = torch.nn.functional.silu(b @ p["Wg"]) * (b @ p["Wu"])
+            m = torch.nn.functional.silu(lin(b, p, "Wg", "bg")) * lin(b, p, "Wu", "bu")
         else:
-            m = torch.nn.functional.gelu(b @ p["W1"])
-        h = h + m @ p["Wd"]
+            m = torch.nn.functional.gelu(lin(b, p, "W1", "bf"))
+        h = h + lin(m, p, "Wd", "bd")
     (h * torch.tensor(dy)).sum().backward()
     np.testing.assert_allclose(y, h.detach().numpy(), rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(dx, tx.grad.numpy(), rtol=1e-10, atol=1e-11)
     for l in range(cfg.n_layers):
         for k_ in grads[l]:
             np.testing.assert_allclose(grads[l][k_], tp[l][k_].grad.numpy(), rtol=1e-10, atol=1e-11)
+
+
+# ------------------------------------------------------------------ LayerNorm / bias variants
+
+def test_layernorm_closed_forms():
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((5, 12)) * 3 + 2
+    g, b = rng.standard_normal(12), rng.standard_normal(12)
+    h, xhat, r = O.layernorm_fwd(x, g, b, 0.0)
+    # normalised rows: zero mean, unit (biased) variance; shift and scale of the input do not matter
+    np.testing.assert_allclose(xhat.mean(axis=1), 0, atol=1e-14)
+    np.testing.assert_allclose((xhat ** 2).mean(axis=1), 1, rtol=1e-13)
+    h2, _, _ = O.layernorm_fwd(7.0 * x - 11.0, g, b, 0.0)
+    np.testing.assert_allclose(h2, h, rtol=1e-11, atol=1e-12)
+    # against the library definition
+    np.testing.assert_allclose(h, (x - x.mean(1, keepdims=True)) / x.std(1, keepdims=True) * g + b, rtol=1e-12)
+    # eps inside the square root: a constant row maps to the bias
+    hc, _, _ = O.layernorm_fwd(np.full((1, 12), 3.0), g, b, 1e-5)
+    np.testing.assert_allclose(hc[0], b, atol=1e-12)
+    # the input gradient is orthogonal to constants and to xhat (projections removed)
+    dh = rng.standard_normal((5, 12))
+    dx, dg, db = O.layernorm_bwd(dh, xhat, r, g)
+    np.testing.assert_allclose(dx.sum(axis=1), 0, atol=1e-12)
+    np.testing.assert_allclose((dx * xhat).sum(axis=1), 0, atol=1e-12)
+    np.testing.assert_allclose(db, dh.sum(axis=0), rtol=1e-14)
+
+
+def test_bias_variant_reduces_to_plain_layer_at_zero_bias():
+    rng = np.random.default_rng(9)
+    cfg_b, cfg_0 = _cfg(bias=True, mlp_kind="gelu"), _cfg(mlp_kind="gelu")
+    params = _rand_params(cfg_b, rng)
+    for p in params:
+        for k in list(p):
+            if k.startswith("b"):
+                p[k] = np.zeros_like(p[k])
+    x = rng.standard_normal((9, cfg_0.hidden))
+    ya, _ = O.stage_F(x, params, [0, 9], cfg_b)
+    yb, _ = O.stage_F(x, params, [0, 9], cfg_0)
+    np.testing.assert_array_equal(ya, yb)
 
 
 # ------------------------------------------------------------------ rotary embedding variant
