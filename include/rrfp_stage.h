@@ -62,7 +62,14 @@ enum {
   STAGE_P_G2 = 3,   /* [hidden]                       gain of the second RMSNorm           */
   STAGE_P_WUP = 4,  /* SwiGLU: [hidden, 2 ffn] gate columns then up columns; GELU: [hidden, ffn] */
   STAGE_P_WD = 5,   /* [ffn, hidden]                                                        */
-  STAGE_P_COUNT = 6
+  /* Vectors of the model-fidelity variants; zero-sized (shape [0, 1]) when their variant is off. */
+  STAGE_P_B1 = 6,   /* [hidden]                       bias of the first LayerNorm  (norm_kind 1)  */
+  STAGE_P_BQKV = 7, /* [(n_q + 2 n_kv) d]             bias of the QKV projection   (bias 1)       */
+  STAGE_P_BO = 8,   /* [hidden]                       bias of the output projection (bias 1)      */
+  STAGE_P_B2 = 9,   /* [hidden]                       bias of the second LayerNorm (norm_kind 1)  */
+  STAGE_P_BUP = 10, /* [2 ffn] gate then up, or [ffn] bias of the up projection    (bias 1)       */
+  STAGE_P_BD = 11,  /* [hidden]                       bias of the down projection  (bias 1)       */
+  STAGE_P_COUNT = 12
 };
 
 typedef struct {
@@ -73,12 +80,16 @@ typedef struct {
   int32_t dtype;          /* STAGE_DTYPE_*: storage type; accumulation is always fp32     */
   int32_t mlp_kind;       /* STAGE_MLP_*                                                  */
   int32_t causal;         /* 1: key j <= query i inside a segment; 0: whole segment       */
-  int32_t norm_kind;      /* 0 = RMSNorm (the only kind)                                  */
+  int32_t norm_kind;      /* 0 = RMSNorm; 1 = LayerNorm with gain and bias (model-fidelity variant):
+                             h = (x - mean) * (var + eps)^-1/2 * g + b, biased variance      */
   float norm_eps;         /* added to the mean of squares inside the square root          */
   int32_t rope;           /* 0 = none; 1 = rotary position embedding on q and k (model-fidelity
                              variant; split-half pairs (x_i, x_{i+d/2}), angle pos * rope_base^(-2i/d),
                              pos = index of the token inside its own segment)              */
   float rope_base;        /* > 1 when rope = 1 (10000 in the usual models); ignored otherwise */
+  int32_t bias;           /* 1 = a bias vector on each of the four projections (model-fidelity
+                             variant); their gradients are column sums of the projections'
+                             output-gradients, produced by stage_B like the norm gradients   */
 } stage_config;
 
 typedef struct stage_s stage_t;

@@ -333,6 +333,88 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const float* __restrict__
   }
 }
 
+// ---------------------------------------------------------------- LayerNorm (model-fidelity variant)
+// Plain kernels, one wavefront per row: h = (x - mu) * r * g + b with r = (var + eps)^-1/2 (biased
+// variance, two passes over the row: mean first, then squared deviations).
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const float* __restrict__ x, const T* __restrict__ g,
+                                                            const T* __restrict__ b, T* __restrict__ h,
+                                                            float* __restrict__ r_out, float* __restrict__ mu_out,
+                                                            int Tn, int H, float eps) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= Tn) return;
+  const float* xr = x + (size_t)row * H;
+  float sum = 0.f;
+  for (int c = lane; c < H; c += WAVE) sum += xr[c];
+  const float mu = wave_sum(sum) / (float)H;
+  float ss = 0.f;
+  for (int c = lane; c < H; c += WAVE) { const float dlt = xr[c] - mu; ss += dlt * dlt; }
+  const float r = 1.0f / sqrtf(wave_sum(ss) / (float)H + eps);
+  if (lane == 0) { r_out[row] = r; mu_out[row] = mu; }
+  T* hr = h + (size_t)row * H;
+  for (int c = lane; c < H; c += WAVE) hr[c] = from_float<T>((xr[c] - mu) * r * to_float(g[c]) + to_float(b[c]));
+}
+
+// dx = add_in + r * (w - mean(w) - xhat * mean(w * xhat)),  w = dh * g,  xhat = (x - mu) * r.
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_rows_kernel(const float* __restrict__ dh, const float* __restrict__ x,
+                                                                 const float* __restrict__ r, const float* __restrict__ mu,
+                                                                 const T* __restrict__ g, const float* __restrict__ add_in,
+                                                                 float* __restrict__ out32, T* __restrict__ out_t, int Tn, int H) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= Tn) return;
+  const size_t off = (size_t)row * H;
+  const float rr = r[row], m = mu[row];
+  float s1 = 0.f, s2 = 0.f;
+  for (int c = lane; c < H; c += WAVE) {
+    const float w = dh[off + c] * to_float(g[c]);
+    s1 += w;
+    s2 += w * ((x[off + c] - m) * rr);
+  }
+  s1 = wave_sum(s1) / (float)H;
+  s2 = wave_sum(s2) / (float)H;
+  for (int c = lane; c < H; c += WAVE) {
+    const float w = dh[off + c] * to_float(g[c]);
+    const float v = add_in[off + c] + rr * (w - s1 - ((x[off + c] - m) * rr) * s2);
+    if (out32) out32[off + c] = v;
+    if (out_t) out_t[off + c] = from_float<T>(v);
+  }
+}
+
+// Per-chunk partial sums for the LayerNorm gain and bias gradients: partial_g[chunk][c] = sum over the
+// chunk's rows (ascending) of dh * xhat, partial_b[chunk][c] = sum of dh.  One thread per column.
+__global__ __launch_bounds__(256) void layernorm_bwd_partials_kernel(const float* __restrict__ dh, const float* __restrict__ x,
+                                                                     const float* __restrict__ r, const float* __restrict__ mu,
+                                                                     float* __restrict__ partial_g, float* __restrict__ partial_b,
+                                                                     int Tn, int H) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= H) return;
+  const int r0 = blockIdx.y * NORM_BWD_ROWS, r1 = min(r0 + NORM_BWD_ROWS, Tn);
+  float sg = 0.f, sb = 0.f;
+  for (int row = r0; row < r1; ++row) {
+    const float d = dh[(size_t)row * H + c];
+    sg += d * ((x[(size_t)row * H + c] - mu[row]) * r[row]);
+    sb += d;
+  }
+  partial_g[(size_t)blockIdx.y * H + c] = sg;
+  partial_b[(size_t)blockIdx.y * H + c] = sb;
+}
+
+// Per-chunk column sums of a [Tn, N] tensor of the storage type (row pitch ld): partial[chunk][c] = sum
+// over the chunk's rows in ascending order.  With launch_colsum this gives the bias gradients.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_rows_kernel(const T* __restrict__ src, int ld, float* __restrict__ partial,
+                                                          int Tn, int N) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= N) return;
+  const int r0 = blockIdx.y * NORM_BWD_ROWS, r1 = min(r0 + NORM_BWD_ROWS, Tn);
+  float acc = 0.f;
+  for (int row = r0; row < r1; ++row) acc += to_float(src[(size_t)row * ld + c]);
+  partial[(size_t)blockIdx.y * N + c] = acc;
+}
+
 // ---------------------------------------------------------------- rotary embedding
 // One workgroup per (query tile, head); a wavefront per row, a lane per pair.  The angle is formed in
 // double precision and reduced to [0, 2 pi) before the single-precision sine and cosine, so that the
@@ -455,6 +537,31 @@ hipError_t launch_rmsnorm_bwd(const float* dh, const float* x, const float* r, c
     hipLaunchKernelGGL(rmsnorm_bwd_rows_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, dh, x, r, (const T*)g,
                        add_in, out32, (T*)out_t, Tn, H);
   });
+  return hipGetLastError();
+}
+
+int colsum_chunks(int Tn) { return (Tn + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS; }
+
+hipError_t launch_layernorm_fwd(const float* x, const void* g, const void* b, void* h, float* r_out, float* mu_out,
+                                int Tn, int H, float eps, int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, hipLaunchKernelGGL(layernorm_fwd_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, x, (const T*)g,
+                                       (const T*)b, (T*)h, r_out, mu_out, Tn, H, eps));
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm_bwd(const float* dh, const float* x, const float* r, const float* mu, const void* g,
+                                const float* add_in, float* out32, void* out_t, float* partial_g, float* partial_b,
+                                int Tn, int H, int dtype, hipStream_t s) {
+  hipLaunchKernelGGL(layernorm_bwd_partials_kernel, dim3((H + 255) / 256, colsum_chunks(Tn)), dim3(256), 0, s, dh, x, r, mu,
+                     partial_g, partial_b, Tn, H);
+  DISPATCH_T(dtype, hipLaunchKernelGGL(layernorm_bwd_rows_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, dh, x, r, mu,
+                                       (const T*)g, add_in, out32, (T*)out_t, Tn, H));
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum_rows(const void* src, int ld, float* partial, int Tn, int N, int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, hipLaunchKernelGGL(colsum_rows_kernel<T>, dim3((N + 255) / 256, colsum_chunks(Tn)), dim3(256), 0, s,
+                                       (const T*)src, ld, partial, Tn, N));
   return hipGetLastError();
 }
 

@@ -378,7 +378,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
                                                                TO* __restrict__ C, const float* __restrict__ R, int M,
                                                                int N, int K, int lda, int ldb, int ldc, int ldr,
                                                                int tiles_m, int tiles_n, bf16_t* __restrict__ E, int lde,
-                                                               int tn0, int k_split) {
+                                                               int tn0, int k_split, const bf16_t* __restrict__ bias) {
   constexpr int NW = WM * WN;
   // Split-K launches (grid y = split): this workgroup contracts k in [y * k_split, min(K, (y+1) * k_split))
   // and writes its partial tile into the y-th [M, ldc] plane of C.
@@ -521,6 +521,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
         float gt[8], up[8], mm[8];
         load_f32x8(scratch + row * PITCH + fc, gt);
         load_f32x8(scratch + row * PITCH + 32 + fc, up);
+        if (bias) {
+          float bg[8], bu[8];
+          load_vec<bf16_t>(bias + f0 + fc, bg);
+          load_vec<bf16_t>(bias + F + f0 + fc, bu);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { gt[e] += bg[e]; up[e] += bu[e]; }
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) mm[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
         if (m < M) {
@@ -540,6 +547,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
         float v[8];
         load_f32x8(scratch + row * PITCH + c0, v);
         if (m >= M || n >= N) continue;            // N is a multiple of 8: the eight columns are in or out together
+        if (bias) {
+          float bv[8];
+          load_vec<bf16_t>(bias + n, bv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += bv[e];
+        }
         if (HAS_R) {
           float rv[8];
           load_f32x8(R + (size_t)m * ldr + n, rv);
@@ -585,10 +598,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
 // Explicit instantiations of every variant the launcher can pick.
 #define RRFP_INST(AKC, BKC, TO, HR, ACT)                                                                     \
   template __global__ void gemm_mfma_dl_kernel<AKC, BKC, TO, HR, dl_wm(AKC, BKC), dl_wn(AKC, BKC), ACT>(      \
-      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int);
+      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
 #define RRFP_INST_SHORT(BKC, TO, HR, ACT)                                                                    \
   template __global__ void gemm_mfma_dl_kernel<true, BKC, TO, HR, dl_wm(true, BKC), dl_wn(true, BKC), ACT, 128>( \
-      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int);
+      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
 #define RRFP_INST_SHORT4(BKC) RRFP_INST_SHORT(BKC, float, true, ACT_NONE) RRFP_INST_SHORT(BKC, float, false, ACT_NONE) \
                               RRFP_INST_SHORT(BKC, bf16_t, true, ACT_NONE) RRFP_INST_SHORT(BKC, bf16_t, false, ACT_NONE)
 RRFP_INST_SHORT4(false) RRFP_INST_SHORT4(true)
@@ -662,12 +675,12 @@ hipError_t launch_a_kc(const GemmArgs& g, hipStream_t s) {
   if (cn > 0)
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT>), dim3(tiles_m * cn), dim3(WMv * WNv * 64),
                        0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc,
-                       g.ldr, tiles_m, cn, (bf16_t*)g.E, g.lde, 0, 0);
+                       g.ldr, tiles_m, cn, (bf16_t*)g.E, g.lde, 0, 0, (const bf16_t*)g.bias);
   if (cn < tiles_n) {
     const int tiles_m2 = (g.M + 127) / 128;
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT, 128>), dim3(tiles_m2 * (tiles_n - cn)),
                        dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K,
-                       g.lda, g.ldb, g.ldc, g.ldr, tiles_m2, tiles_n - cn, (bf16_t*)g.E, g.lde, cn, 0);
+                       g.lda, g.ldb, g.ldc, g.ldr, tiles_m2, tiles_n - cn, (bf16_t*)g.E, g.lde, cn, 0, (const bf16_t*)g.bias);
   }
   return hipGetLastError();
 }
@@ -688,7 +701,7 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
         hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
                            dim3(tiles_m * tiles_n, S_eff), dim3(dl_wm(A_KC, B_KC) * dl_wn(A_KC, B_KC) * 64), 0,
                            s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.ws, g.R, g.M, g.N, g.K, g.lda,
-                           g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, k_split);
+                           g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, k_split, (const bf16_t*)nullptr);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         return launch_grad_reduce((const float*)g.ws, (size_t)g.M * g.N, S_eff, (float*)g.C, (size_t)g.M * g.N, s);
@@ -697,7 +710,7 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
                        dim3(tiles_m * tiles_n), dim3(dl_wm(A_KC, B_KC) * dl_wn(A_KC, B_KC) * 64), 0,
                        s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda,
-                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, 0);
+                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, 0, (const bf16_t*)g.bias);
     return hipGetLastError();
   }
   static bool configured = false;   // per instantiation; the attribute is process-wide for the function
@@ -743,6 +756,7 @@ bool gemm_act_supported(const GemmArgs& g) {
 
 bool gemm_mfma_supports(const GemmArgs& g) {
   if (g.in_dtype != BF16) return false;
+  if (g.bias && (!direct_ok(g) || ((uintptr_t)g.bias & 15))) return false;   // bias lives in the direct-load kernel's epilogue
   if (g.M < 1 || g.N < 1 || g.K < 1) return false;
   if ((g.lda | g.ldb | g.ldc) & 7) return false;
   if (g.R && ((g.ldr & 3) || ((uintptr_t)g.R & 15))) return false;

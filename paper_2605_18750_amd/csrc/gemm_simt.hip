@@ -10,7 +10,8 @@ namespace {
 template <typename TI, typename TO, bool TA, bool TB, bool HAS_R>
 __global__ __launch_bounds__(256) void gemm_simt_kernel(const TI* __restrict__ A, const TI* __restrict__ B,
                                                         TO* __restrict__ C, const float* __restrict__ R, int M, int N,
-                                                        int K, int lda, int ldb, int ldc, int ldr) {
+                                                        int K, int lda, int ldb, int ldc, int ldr,
+                                                        const TI* __restrict__ bias) {
   __shared__ float As[16][64 + 4];
   __shared__ float Bs[16][64 + 4];
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -62,6 +63,7 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const TI* __restrict__ A
       const int gn = n0 + tx * 4 + j;
       if (gn >= N) continue;
       float v = acc[i][j];
+      if (bias) v += to_float(bias[gn]);
       if (HAS_R) v += R[(size_t)gm * ldr + gn];
       C[(size_t)gm * ldc + gn] = from_float<TO>(v);
     }
@@ -73,7 +75,7 @@ hipError_t launch_typed(const GemmArgs& g, hipStream_t s) {
   dim3 grid((g.N + 63) / 64, (g.M + 63) / 64), block(256);
 #define GO(TA, TB, HR)                                                                                     \
   hipLaunchKernelGGL((gemm_simt_kernel<TI, TO, TA, TB, HR>), grid, block, 0, s, (const TI*)g.A, (const TI*)g.B, \
-                     (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, g.ldr)
+                     (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, g.ldr, (const TI*)g.bias)
   const bool hr = g.R != nullptr;
   if (!g.transA && !g.transB) { if (hr) GO(false, false, true); else GO(false, false, false); }
   else if (!g.transA && g.transB) { if (hr) GO(false, true, true); else GO(false, true, false); }

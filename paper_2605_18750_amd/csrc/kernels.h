@@ -36,6 +36,7 @@ struct GemmArgs {
   int lde;
   void* ws;        // optional scratch for split-K partial results (fp32), else null
   size_t ws_bytes;
+  const void* bias; // optional [N] vector of the storage type added to every row before residual / activation
 };
 bool gemm_act_supported(const GemmArgs& g);   // true if launch_gemm can run g.act fused for this shape
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);       // picks the kernel family
@@ -95,6 +96,16 @@ hipError_t launch_rmsnorm_bwd(const float* dh, const float* x, const float* r, c
                               const float* add_in, float* out32, void* out_t, float* dg_partial,
                               int T, int H, int dtype, hipStream_t s);
 hipError_t launch_colsum(const float* partial, int n_partial, int H, float* out, hipStream_t s);
+// LayerNorm (model-fidelity variant): forward saves r and mu per row; backward writes dx (+ add_in) and
+// the per-chunk partial sums of the gain and bias gradients ([colsum_chunks(T), H] each, for launch_colsum).
+int colsum_chunks(int T);
+hipError_t launch_layernorm_fwd(const float* x, const void* g, const void* b, void* h, float* r_out, float* mu_out,
+                                int T, int H, float eps, int dtype, hipStream_t s);
+hipError_t launch_layernorm_bwd(const float* dh, const float* x, const float* r, const float* mu, const void* g,
+                                const float* add_in, float* out32, void* out_t, float* partial_g, float* partial_b,
+                                int T, int H, int dtype, hipStream_t s);
+// Per-chunk column sums of a [T, N] tensor of the storage type into partial [colsum_chunks(T), N] (bias gradients).
+hipError_t launch_colsum_rows(const void* src, int ld, float* partial, int T, int N, int dtype, hipStream_t s);
 
 // SwiGLU on gu [T, 2F] (gate columns then up columns): m = silu(gate) * up.
 hipError_t launch_swiglu_fwd(const void* gu, void* m, int T, int F, int dtype, hipStream_t s);

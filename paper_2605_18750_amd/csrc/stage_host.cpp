@@ -37,6 +37,7 @@ struct LayerStash {
   size_t dy, dup, dx1, dqkv;                          // written by B, read by W (storage type)
   size_t dy32, dx1_32;                                // written by B, fp32 residual-gradient chain
   size_t o32;                                         // written by F: attention output before rounding (bf16 path)
+  size_t mu1, mu2;                                    // written by F: row means (LayerNorm variant)
 };
 
 struct Plan {
@@ -47,7 +48,7 @@ struct Plan {
   int64_t p_shape[STAGE_P_COUNT][2];
   size_t param_elems;
   std::vector<LayerStash> layer;
-  size_t t_dm, t_dh, t_do, t_delta, t_dgp, t_qtiles, t_kvtiles;  // per-microbatch temporaries
+  size_t t_dm, t_dh, t_do, t_delta, t_dgp, t_dbp, t_qtiles, t_kvtiles;  // per-microbatch temporaries
   int max_tiles;
   size_t mb_bytes;                  // one microbatch region
   size_t slots_off;                 // start of the M gradient slots
@@ -70,7 +71,8 @@ int check_config(const stage_config* c) {
   if (c->dtype != STAGE_DTYPE_FP32 && c->dtype != STAGE_DTYPE_BF16) { set_tls_error("unknown dtype %d", c->dtype); return STAGE_EINVAL; }
   if (c->mlp_kind != STAGE_MLP_SWIGLU && c->mlp_kind != STAGE_MLP_GELU) { set_tls_error("unknown mlp_kind %d", c->mlp_kind); return STAGE_EINVAL; }
   if (c->causal != 0 && c->causal != 1) { set_tls_error("causal must be 0 or 1"); return STAGE_EINVAL; }
-  if (c->norm_kind != 0) { set_tls_error("norm_kind must be 0 (RMSNorm)"); return STAGE_EINVAL; }
+  if (c->norm_kind != 0 && c->norm_kind != 1) { set_tls_error("norm_kind must be 0 (RMSNorm) or 1 (LayerNorm)"); return STAGE_EINVAL; }
+  if (c->bias != 0 && c->bias != 1) { set_tls_error("bias must be 0 or 1"); return STAGE_EINVAL; }
   if (!(c->norm_eps >= 0.0f) || !(c->norm_eps < 1.0f)) { set_tls_error("norm_eps must be in [0, 1)"); return STAGE_EINVAL; }
   if (c->rope != 0 && c->rope != 1) { set_tls_error("rope must be 0 or 1"); return STAGE_EINVAL; }
   if (c->rope == 1 && !(c->rope_base > 1.0f)) { set_tls_error("rope_base must be > 1"); return STAGE_EINVAL; }
@@ -95,9 +97,12 @@ int make_plan(const stage_config* c, Plan* p) {
   p->n_qkv = (int)((nq + 2 * nkv) * d);
   p->n_up = (int)(c->mlp_kind == STAGE_MLP_SWIGLU ? 2 * F : F);
   p->esz = dtype_size(c->dtype);
+  const int64_t ln = c->norm_kind == 1 ? 1 : 0, bs = c->bias ? 1 : 0;   // zero-sized vectors when a variant is off
   const int64_t shapes[STAGE_P_COUNT][2] = {
       {(int64_t)H, 1}, {(int64_t)H, p->n_qkv}, {(int64_t)(nq * d), (int64_t)H},
-      {(int64_t)H, 1}, {(int64_t)H, p->n_up}, {(int64_t)F, (int64_t)H}};
+      {(int64_t)H, 1}, {(int64_t)H, p->n_up}, {(int64_t)F, (int64_t)H},
+      {ln * (int64_t)H, 1}, {bs * (int64_t)p->n_qkv, 1}, {bs * (int64_t)H, 1},
+      {ln * (int64_t)H, 1}, {bs * (int64_t)p->n_up, 1}, {bs * (int64_t)H, 1}};
   memcpy(p->p_shape, shapes, sizeof(shapes));
   size_t off = 0;
   for (int l = 0; l < c->n_layers; ++l)
@@ -121,12 +126,17 @@ int make_plan(const stage_config* c, Plan* p) {
     s.dx1 = take(T * H * e); s.dqkv = take(T * p->n_qkv * e);
     s.dy32 = take(T * H * 4); s.dx1_32 = take(T * H * 4);
     s.o32 = c->dtype == STAGE_DTYPE_BF16 ? take(T * nq * d * 4) : 0;
+    s.mu1 = c->norm_kind == 1 ? take(T * 4) : 0;
+    s.mu2 = c->norm_kind == 1 ? take(T * 4) : 0;
   }
   p->t_dm = take(T * F * 4);     // fp32: GEMM outputs that only an elementwise kernel consumes are not rounded
   p->t_dh = take(T * H * 4);
   p->t_do = take(T * nq * d * e);
   p->t_delta = take(nq * T * 4);
-  p->t_dgp = take((size_t)norm_bwd_partials((int)T, (int)H, c->dtype) * H * 4);
+  p->t_dgp = take((size_t)std::max(norm_bwd_partials((int)T, (int)H, c->dtype), colsum_chunks((int)T)) * H * 4);
+  // second partial array: LayerNorm bias gradient, and the projection-bias gradients (widest tensor)
+  const size_t wide = std::max((size_t)H, (size_t)std::max(p->n_qkv, p->n_up));
+  p->t_dbp = (c->norm_kind == 1 || c->bias) ? take((size_t)colsum_chunks((int)T) * wide * 4) : 0;
   const int tile = std::min(ATTN_TILE_Q, ATTN_TILE_KV);
   p->max_tiles = (int)((T + tile - 1) / tile) + c->max_segments;
   p->t_qtiles = take((size_t)p->max_tiles * sizeof(AttnTile));
@@ -370,11 +380,16 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     const LayerStash& L = P.layer[l];
     const bool last = l == c.n_layers - 1;
     void* y_out = last ? y_dev : (void*)(base + P.layer[l + 1].x);
-    HIP_TRY(st, launch_rmsnorm_fwd((const float*)(base + L.x), param_ptr(st, l, STAGE_P_G1), base + L.h1, (float*)(base + L.r1), T, H, c.norm_eps, dt, s));
+    if (c.norm_kind == 1)
+      HIP_TRY(st, launch_layernorm_fwd((const float*)(base + L.x), param_ptr(st, l, STAGE_P_G1), param_ptr(st, l, STAGE_P_B1), base + L.h1,
+                                       (float*)(base + L.r1), (float*)(base + L.mu1), T, H, c.norm_eps, dt, s));
+    else
+      HIP_TRY(st, launch_rmsnorm_fwd((const float*)(base + L.x), param_ptr(st, l, STAGE_P_G1), base + L.h1, (float*)(base + L.r1), T, H, c.norm_eps, dt, s));
     GemmArgs g{};
     g.in_dtype = dt; g.out_dtype = dt; g.transA = false; g.transB = false; g.M = T;
     g.A = base + L.h1; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WQKV); g.ldb = P.n_qkv;
     g.C = base + L.qkv; g.ldc = P.n_qkv; g.R = nullptr; g.N = P.n_qkv; g.K = H;
+    g.bias = c.bias ? param_ptr(st, l, STAGE_P_BQKV) : nullptr;
     HIP_TRY(st, launch_gemm(g, s));
     if (c.rope)   // rotate q and k in place: the stash then holds what the attention (and its backward) reads
       HIP_TRY(st, launch_rope(base + L.qkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,
@@ -389,11 +404,17 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     g.A = base + L.o; g.lda = nqd; g.B = param_ptr(st, l, STAGE_P_WO); g.ldb = H;
     g.C = base + L.x1; g.ldc = H; g.R = (const float*)(base + L.x); g.ldr = H; g.N = H; g.K = nqd;
     g.out_dtype = F32;                       // x1 stays in the fp32 residual stream
+    g.bias = c.bias ? param_ptr(st, l, STAGE_P_BO) : nullptr;
     HIP_TRY(st, launch_gemm(g, s));
     g.out_dtype = dt;
-    HIP_TRY(st, launch_rmsnorm_fwd((const float*)(base + L.x1), param_ptr(st, l, STAGE_P_G2), base + L.h2, (float*)(base + L.r2), T, H, c.norm_eps, dt, s));
+    if (c.norm_kind == 1)
+      HIP_TRY(st, launch_layernorm_fwd((const float*)(base + L.x1), param_ptr(st, l, STAGE_P_G2), param_ptr(st, l, STAGE_P_B2), base + L.h2,
+                                       (float*)(base + L.r2), (float*)(base + L.mu2), T, H, c.norm_eps, dt, s));
+    else
+      HIP_TRY(st, launch_rmsnorm_fwd((const float*)(base + L.x1), param_ptr(st, l, STAGE_P_G2), base + L.h2, (float*)(base + L.r2), T, H, c.norm_eps, dt, s));
     g.A = base + L.h2; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WUP); g.ldb = P.n_up;
     g.C = base + L.up; g.ldc = P.n_up; g.R = nullptr; g.N = P.n_up; g.K = H;
+    g.bias = c.bias ? param_ptr(st, l, STAGE_P_BUP) : nullptr;
     // the activation runs in the GEMM epilogue on the fp32 accumulators when the shape allows it
     g.act = c.mlp_kind == STAGE_MLP_SWIGLU ? ACT_SWIGLU_FWD : ACT_GELU_FWD; g.E = base + L.m; g.lde = F;
     if (gemm_act_supported(g)) {
@@ -408,8 +429,9 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     g.A = base + L.m; g.lda = F; g.B = param_ptr(st, l, STAGE_P_WD); g.ldb = H;
     g.C = y_out; g.ldc = H; g.R = (const float*)(base + L.x1); g.ldr = H; g.N = H; g.K = F;
     g.out_dtype = last ? dt : (int)F32;      // the stage output is rounded once; between layers fp32
+    g.bias = c.bias ? param_ptr(st, l, STAGE_P_BD) : nullptr;
     HIP_TRY(st, launch_gemm(g, s));
-    g.out_dtype = dt;
+    g.out_dtype = dt; g.bias = nullptr;
   }
   HIP_TRY(st, hipEventRecord(m.ev_F, s));
   m.state = MB_F;
@@ -437,8 +459,31 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
   const int n_part = norm_bwd_partials(T, H, dt);
   HIP_TRY(st, hipMemcpyAsync(base + P.layer[c.n_layers - 1].dy, dy_dev, (size_t)T * H * e, hipMemcpyDeviceToDevice, s));
   HIP_TRY(st, launch_widen(dy_dev, (float*)(base + P.layer[c.n_layers - 1].dy32), (size_t)T * H, dt, s));
+  const int n_chunk = colsum_chunks(T);
+  // bias gradient = column sum of a projection's output-gradient (storage type), in a fixed order
+  auto bias_grad = [&](const void* src, int n, size_t slot_off) -> int {
+    HIP_TRY(st, launch_colsum_rows(src, n, (float*)(base + P.t_dbp), T, n, dt, s));
+    HIP_TRY(st, launch_colsum((const float*)(base + P.t_dbp), n_chunk, n, slot + slot_off, s));
+    return STAGE_OK;
+  };
+  // backward of one norm: dx (+ add_in) and the vector gradients into the slot
+  auto norm_bwd = [&](int l, bool first, const float* dh, const float* x, const float* r, const float* mu, const float* add_in,
+                      float* out32, void* out_t) -> int {
+    const int pg = first ? STAGE_P_G1 : STAGE_P_G2, pb = first ? STAGE_P_B1 : STAGE_P_B2;
+    if (c.norm_kind == 1) {
+      HIP_TRY(st, launch_layernorm_bwd(dh, x, r, mu, param_ptr(st, l, pg), add_in, out32, out_t, (float*)(base + P.t_dgp),
+                                       (float*)(base + P.t_dbp), T, H, dt, s));
+      HIP_TRY(st, launch_colsum((const float*)(base + P.t_dgp), n_chunk, H, slot + P.p_off[l][pg], s));
+      HIP_TRY(st, launch_colsum((const float*)(base + P.t_dbp), n_chunk, H, slot + P.p_off[l][pb], s));
+    } else {
+      HIP_TRY(st, launch_rmsnorm_bwd(dh, x, r, param_ptr(st, l, pg), add_in, out32, out_t, (float*)(base + P.t_dgp), T, H, dt, s));
+      HIP_TRY(st, launch_colsum((const float*)(base + P.t_dgp), n_part, H, slot + P.p_off[l][pg], s));
+    }
+    return STAGE_OK;
+  };
   for (int l = c.n_layers - 1; l >= 0; --l) {
     const LayerStash& L = P.layer[l];
+    if (c.bias) { rc = bias_grad(base + L.dy, H, P.p_off[l][STAGE_P_BD]); if (rc) return rc; }
     void* dx_out = (l == 0) ? dx_dev : (void*)(base + P.layer[l - 1].dy);
     float* dx_out32 = (l == 0) ? nullptr : (float*)(base + P.layer[l - 1].dy32);
     GemmArgs g{};
@@ -462,9 +507,11 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     g.A = base + L.dup; g.lda = P.n_up; g.B = param_ptr(st, l, STAGE_P_WUP); g.ldb = P.n_up;
     g.C = base + P.t_dh; g.ldc = H; g.N = H; g.K = P.n_up; g.out_dtype = F32;
     HIP_TRY(st, launch_gemm(g, s));
-    HIP_TRY(st, launch_rmsnorm_bwd((const float*)(base + P.t_dh), (const float*)(base + L.x1), (const float*)(base + L.r2), param_ptr(st, l, STAGE_P_G2),
-                                   (const float*)(base + L.dy32), (float*)(base + L.dx1_32), base + L.dx1, (float*)(base + P.t_dgp), T, H, dt, s));
-    HIP_TRY(st, launch_colsum((const float*)(base + P.t_dgp), n_part, H, slot + P.p_off[l][STAGE_P_G2], s));
+    if (c.bias) { rc = bias_grad(base + L.dup, P.n_up, P.p_off[l][STAGE_P_BUP]); if (rc) return rc; }
+    rc = norm_bwd(l, false, (const float*)(base + P.t_dh), (const float*)(base + L.x1), (const float*)(base + L.r2),
+                  (const float*)(base + L.mu2), (const float*)(base + L.dy32), (float*)(base + L.dx1_32), base + L.dx1);
+    if (rc) return rc;
+    if (c.bias) { rc = bias_grad(base + L.dx1, H, P.p_off[l][STAGE_P_BO]); if (rc) return rc; }
     // do = dx1 Wo^T
     g.A = base + L.dx1; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WO); g.ldb = H;
     g.C = base + P.t_do; g.ldc = nqd; g.N = nqd; g.K = H; g.out_dtype = dt;
@@ -480,13 +527,14 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     if (c.rope)   // gradients w.r.t. the rotated q, k -> w.r.t. the projection outputs (inverse rotation)
       HIP_TRY(st, launch_rope(base + L.dqkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,
                               c.head_dim, P.n_qkv, c.rope_base, -1.0f, dt, s));
+    if (c.bias) { rc = bias_grad(base + L.dqkv, P.n_qkv, P.p_off[l][STAGE_P_BQKV]); if (rc) return rc; }
     // dh1 = [dq|dk|dv] Wqkv^T
     g.A = base + L.dqkv; g.lda = P.n_qkv; g.B = param_ptr(st, l, STAGE_P_WQKV); g.ldb = P.n_qkv;
     g.C = base + P.t_dh; g.ldc = H; g.N = H; g.K = P.n_qkv; g.out_dtype = F32;
     HIP_TRY(st, launch_gemm(g, s));
-    HIP_TRY(st, launch_rmsnorm_bwd((const float*)(base + P.t_dh), (const float*)(base + L.x), (const float*)(base + L.r1), param_ptr(st, l, STAGE_P_G1),
-                                   (const float*)(base + L.dx1_32), dx_out32, dx_out, (float*)(base + P.t_dgp), T, H, dt, s));
-    HIP_TRY(st, launch_colsum((const float*)(base + P.t_dgp), n_part, H, slot + P.p_off[l][STAGE_P_G1], s));
+    rc = norm_bwd(l, true, (const float*)(base + P.t_dh), (const float*)(base + L.x), (const float*)(base + L.r1),
+                  (const float*)(base + L.mu1), (const float*)(base + L.dx1_32), dx_out32, dx_out);
+    if (rc) return rc;
   }
   HIP_TRY(st, hipEventRecord(m.ev_B, s));
   m.state = MB_B;

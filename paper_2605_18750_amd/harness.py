@@ -18,8 +18,9 @@ def make_config(shape, max_tokens: int, max_segments: int = 1, n_microbatches: i
         max_segments=max_segments,
         dtype=R.STAGE_DTYPE_FP32 if shape.dtype == "fp32" else R.STAGE_DTYPE_BF16,
         mlp_kind=R.STAGE_MLP_SWIGLU if shape.mlp_kind == "swiglu" else R.STAGE_MLP_GELU,
-        causal=1 if shape.causal else 0, norm_kind=0, norm_eps=shape.norm_eps,
-        rope=1 if getattr(shape, "rope", False) else 0, rope_base=getattr(shape, "rope_base", 10000.0))
+        causal=1 if shape.causal else 0, norm_kind=1 if getattr(shape, "norm_kind", "rms") == "layer" else 0,
+        norm_eps=shape.norm_eps, rope=1 if getattr(shape, "rope", False) else 0,
+        rope_base=getattr(shape, "rope_base", 10000.0), bias=1 if getattr(shape, "bias", False) else 0)
 
 
 def _fused(layer: dict, which: int, swiglu: bool) -> np.ndarray:
@@ -37,6 +38,20 @@ def _fused(layer: dict, which: int, swiglu: bool) -> np.ndarray:
         return np.concatenate([st("Wg"), st("Wu")], axis=1) if swiglu else st("W1")
     if which == R.STAGE_P_WD:
         return st("Wd")
+    empty = np.zeros(0, dtype=st("g1").dtype)
+    if which in (R.STAGE_P_B1, R.STAGE_P_B2):
+        nm = "b1" if which == R.STAGE_P_B1 else "b2"
+        return st(nm) if nm in layer else empty
+    if "bo" not in layer:
+        return empty
+    if which == R.STAGE_P_BQKV:
+        return np.concatenate([st("bq"), st("bk"), st("bv")])
+    if which == R.STAGE_P_BO:
+        return st("bo")
+    if which == R.STAGE_P_BUP:
+        return np.concatenate([st("bg"), st("bu")]) if swiglu else st("bf")
+    if which == R.STAGE_P_BD:
+        return st("bd")
     raise ValueError(which)
 
 
@@ -74,6 +89,16 @@ def unpack_grads(cfg, flat: np.ndarray) -> list:
             g["Wu"] = t[R.STAGE_P_WUP][:, F:]
         else:
             g["W1"] = t[R.STAGE_P_WUP]
+        if cfg.norm_kind == 1:
+            g["b1"], g["b2"] = t[R.STAGE_P_B1].reshape(-1), t[R.STAGE_P_B2].reshape(-1)
+        if cfg.bias:
+            bqkv, bup = t[R.STAGE_P_BQKV].reshape(-1), t[R.STAGE_P_BUP].reshape(-1)
+            g["bq"], g["bk"], g["bv"] = bqkv[:nq * d], bqkv[nq * d:(nq + nkv) * d], bqkv[(nq + nkv) * d:]
+            g["bo"], g["bd"] = t[R.STAGE_P_BO].reshape(-1), t[R.STAGE_P_BD].reshape(-1)
+            if swiglu:
+                g["bg"], g["bu"] = bup[:F], bup[F:]
+            else:
+                g["bf"] = bup
         out.append(g)
     return out
 

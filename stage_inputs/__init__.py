@@ -39,6 +39,8 @@ class StageShape:
     causal: bool = True
     norm_eps: float = 1e-5
     rope: bool = False            # rotary position embedding on q and k (model-fidelity variant)
+    norm_kind: str = "rms"        # "rms" | "layer" (model-fidelity variant)
+    bias: bool = False            # biases on the four projections (model-fidelity variant)
     rope_base: float = 10000.0
     w_std: float = 0.02
     x_std: float = 1.0
@@ -163,6 +165,11 @@ def layer_param_shapes(s: StageShape) -> dict:
         shapes.update({"Wg": (H, F), "Wu": (H, F), "Wd": (F, H)})
     else:
         shapes.update({"W1": (H, F), "Wd": (F, H)})
+    if s.norm_kind == "layer":
+        shapes.update({"b1": (H,), "b2": (H,)})
+    if s.bias:
+        shapes.update({"bq": (nq * d,), "bk": (nkv * d,), "bv": (nkv * d,), "bo": (H,), "bd": (H,)})
+        shapes.update({"bg": (F,), "bu": (F,)} if s.mlp_kind == "swiglu" else {"bf": (F,)})
     return shapes
 
 

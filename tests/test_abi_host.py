@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _cfg(**kw):
     base = dict(n_layers=2, hidden=128, n_q_heads=4, n_kv_heads=2, head_dim=32, ffn=192, max_tokens=64,
                 n_microbatches=3, max_segments=2, dtype=0, mlp_kind=0, causal=1, norm_kind=0, norm_eps=1e-5,
-                rope=0, rope_base=10000.0)
+                rope=0, rope_base=10000.0, bias=0)
     base.update(kw)
     return R.stage_config(**base)
 
@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol():
 def test_config_validation():
     R.stage_query(_cfg())
     bad = [dict(n_kv_heads=3), dict(hidden=0), dict(head_dim=24), dict(head_dim=144), dict(dtype=2),
-           dict(mlp_kind=5), dict(causal=2), dict(norm_kind=1), dict(norm_eps=-1.0), dict(rope=2), dict(rope=1, rope_base=1.0), dict(ffn=190),
+           dict(mlp_kind=5), dict(causal=2), dict(norm_kind=2), dict(bias=2), dict(norm_eps=-1.0), dict(rope=2), dict(rope=1, rope_base=1.0), dict(ffn=190),
            dict(dtype=1, head_dim=32), dict(dtype=1, head_dim=64, hidden=96), dict(n_layers=65)]
     for kw in bad:
         with pytest.raises(R.StageError) as e:
@@ -66,7 +66,16 @@ def test_layout_is_disjoint_aligned_and_sized():
     with pytest.raises(R.StageError):
         R.stage_param_layout(cfg, 2, 0)
     with pytest.raises(R.StageError):
-        R.stage_param_layout(cfg, 0, 6)
+        R.stage_param_layout(cfg, 0, R.STAGE_P_COUNT)
+    # vectors of the variants: zero-sized when off, [n, 1] when on, still disjoint and aligned
+    assert R.stage_param_layout(cfg, 0, R.STAGE_P_BQKV)[1] == (0, 1)
+    on = Hn.make_config(SI.VISION.replace(norm_kind="layer", bias=True), 6272, 8)
+    assert R.stage_param_layout(on, 0, R.STAGE_P_B1)[1] == (1280, 1)
+    assert R.stage_param_layout(on, 3, R.STAGE_P_BQKV)[1] == (3 * 1280, 1)
+    assert R.stage_param_layout(on, 3, R.STAGE_P_BUP)[1] == (5120, 1)
+    spans = sorted((lambda o, rc: (o, o + rc[0] * rc[1]))(*R.stage_param_layout(on, l, w))
+                   for l in range(on.n_layers) for w in range(R.STAGE_P_COUNT))
+    assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
 
 
 def test_language_arena_fits_one_gpu():

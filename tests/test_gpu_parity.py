@@ -47,6 +47,18 @@ SMALL = {
     "fp32_rope": (SI.StageShape("s_fp32_rope", 2, 64, 2, 1, 32, 48, 2, dtype="fp32", mlp_kind="gelu", causal=False,
                                 x_std=1.0, dy_std=1.0, w_std=0.1, rope=True),
                   [[0, 65, 130], [0, 129]]),
+    # LayerNorm + projection biases (GPT / ViT style layers): bf16 GELU bidirectional d = 80 (vision-like),
+    # bf16 SwiGLU causal with rope on top, fp32 GELU
+    "bf16_layernorm_bias_gelu": (SI.StageShape("s_bf16_ln", 2, 320, 4, 4, 80, 256, 2, mlp_kind="gelu", causal=False, w_std=0.05,
+                                               norm_kind="layer", bias=True),
+                                 [[0, 100, 200, 300], [0, 259]]),
+    "bf16_layernorm_bias_swiglu_rope": (SI.StageShape("s_bf16_ln2", 2, 512, 4, 2, 128, 384, 2, w_std=0.03,
+                                                      norm_kind="layer", bias=True, rope=True),
+                                        [[0, 300], [0, 130, 391]]),
+    "bf16_bias_only": (SI.StageShape("s_bf16_b", 1, 128, 4, 2, 64, 192, 2, w_std=0.05, bias=True), [[0, 200], [0, 77, 333]]),
+    "fp32_layernorm_bias": (SI.StageShape("s_fp32_ln", 2, 100, 4, 2, 16, 36, 2, dtype="fp32", mlp_kind="gelu", x_std=1.0, dy_std=1.0,
+                                          w_std=0.1, norm_kind="layer", bias=True),
+                            [[0, 37, 150], [0, 70]]),
     # bf16, many tokens on a narrow stage: the weight-gradient GEMMs (K = tokens) take the split-K path
     "bf16_long_tokens_splitk": (SI.StageShape("s_bf16_e", 1, 128, 4, 2, 64, 192, 2, w_std=0.05),
                                 [[0, 1100], [0, 600, 1163]]),
@@ -80,7 +92,7 @@ def test_tiny_fp32_config_matches_oracle():
 
 
 @pytest.mark.parametrize("name", ["fp32_ragged_causal_gqa", "bf16_ragged_causal_gqa", "bf16_bidir_gelu_d80", "bf16_rope_d128",
-                                  "bf16_long_tokens_splitk"])
+                                  "bf16_long_tokens_splitk", "bf16_layernorm_bias_gelu"])
 def test_dispatch_order_is_bit_exact(name):
     shape, cus = SMALL[name]
     w = Hp.Workload(shape, cus)
