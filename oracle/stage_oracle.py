@@ -35,6 +35,8 @@ query head a uses KV head a // (n_q / n_kv); GELU is the exact erf form.
 
 Model-fidelity variants (off in the five workloads; the paper names GPT3-Large and ViT models,
 which use them, without printing layer details): rope = rotary embedding on q and k;
+qk_norm = RMSNorm over head_dim of every query and key head (gains gq, gk of length head_dim shared
+by all heads, same eps), applied to the projection output before the rotary embedding;
 norm_kind = "layer" replaces both RMSNorms by LayerNorm with gain and bias,
 h = (x - mean) * (var + eps)^-1/2 * g + b; bias = True adds a bias vector to each of the four
 projections.  All vector-shaped gradients (gains and biases) are produced in B.
@@ -64,6 +66,7 @@ class OracleConfig:
     norm_eps: float = 1e-5
     norm_kind: str = "rms"        # "rms" | "layer" (LayerNorm with gain and bias; model-fidelity variant)
     bias: bool = False            # bias vectors on the four projections (model-fidelity variant)
+    qk_norm: bool = False         # RMSNorm over head_dim on every q and k head, before rope (model-fidelity variant)
     rope: bool = False            # rotary position embedding on q and k (model-fidelity variant)
     rope_base: float = 10000.0
     rope_offset: int = 0          # added to every position (test hook for the relative-position property)
@@ -132,25 +135,45 @@ def rope_rotate(x, pos, n_heads, d, base, sign=1.0):
     return out.reshape(T, n_heads * d)
 
 
-def _qk_for_attention(c, cfg):
-    """q, k as the attention sees them: rotated when the variant is on (cached once)."""
-    if not cfg.rope:
+def _head_norm_fwd(x, g, n_heads, d, eps):
+    """RMSNorm of every head's d-vector with the gain g [d]: the rows are the (token, head) pairs."""
+    T = x.shape[0]
+    h, xhat, r = rmsnorm_fwd(x.reshape(T * n_heads, d), g, eps)
+    return h.reshape(T, n_heads * d), xhat, r
+
+
+def _qk_for_attention(c, cfg, p=None):
+    """q, k as the attention sees them: head-normalised and rotated when those variants are on
+    (computed once per layer and cached)."""
+    if not (cfg.rope or cfg.qk_norm):
         return c["q"], c["k"]
-    if "q_rot" not in c:
-        pos = rope_positions(c["cu"], cfg.rope_offset)
-        c["q_rot"] = rope_rotate(c["q"], pos, cfg.n_q_heads, cfg.head_dim, cfg.rope_base)
-        c["k_rot"] = rope_rotate(c["k"], pos, cfg.n_kv_heads, cfg.head_dim, cfg.rope_base)
-    return c["q_rot"], c["k_rot"]
+    if "q_att" not in c:
+        q, k = c["q"], c["k"]
+        if cfg.qk_norm:
+            q, c["q_hat"], c["q_r"] = _head_norm_fwd(q, p["gq"], cfg.n_q_heads, cfg.head_dim, cfg.norm_eps)
+            k, c["k_hat"], c["k_r"] = _head_norm_fwd(k, p["gk"], cfg.n_kv_heads, cfg.head_dim, cfg.norm_eps)
+        if cfg.rope:
+            pos = rope_positions(c["cu"], cfg.rope_offset)
+            q = rope_rotate(q, pos, cfg.n_q_heads, cfg.head_dim, cfg.rope_base)
+            k = rope_rotate(k, pos, cfg.n_kv_heads, cfg.head_dim, cfg.rope_base)
+        c["q_att"], c["k_att"] = q, k
+    return c["q_att"], c["k_att"]
 
 
-def _attention_bwd_qk(do, c, cfg):
-    """Gradients w.r.t. the projection outputs q, k, v (rotation undone for q and k)."""
-    q, k = _qk_for_attention(c, cfg)
+def _attention_bwd_qk(do, c, cfg, p=None, out=None):
+    """Gradients w.r.t. the projection outputs q, k, v (rotation and head norm undone for q and k);
+    the head-norm gain gradients go into `out`."""
+    q, k = _qk_for_attention(c, cfg, p)
     dq, dk, dv = attention_bwd(do, q, k, c["v"], c["cu"], cfg)
     if cfg.rope:
         pos = rope_positions(c["cu"], cfg.rope_offset)
         dq = rope_rotate(dq, pos, cfg.n_q_heads, cfg.head_dim, cfg.rope_base, sign=-1.0)
         dk = rope_rotate(dk, pos, cfg.n_kv_heads, cfg.head_dim, cfg.rope_base, sign=-1.0)
+    if cfg.qk_norm:
+        T, d = dq.shape[0], cfg.head_dim
+        dqh, out["gq"] = rmsnorm_bwd(dq.reshape(T * cfg.n_q_heads, d), c["q_hat"], c["q_r"], p["gq"])
+        dkh, out["gk"] = rmsnorm_bwd(dk.reshape(T * cfg.n_kv_heads, d), c["k_hat"], c["k_r"], p["gk"])
+        dq, dk = dqh.reshape(T, cfg.n_q_heads * d), dkh.reshape(T, cfg.n_kv_heads * d)
     return dq, dk, dv
 
 def rmsnorm_fwd(x, g, eps):
@@ -244,7 +267,7 @@ def layer_forward(x, p, cu_seqlens, cfg):
     c["q"] = c["h1"] @ p["Wq"] + _b(p, "bq", cfg)
     c["k"] = c["h1"] @ p["Wk"] + _b(p, "bk", cfg)
     c["v"] = c["h1"] @ p["Wv"] + _b(p, "bv", cfg)
-    q, k = _qk_for_attention(c, cfg)
+    q, k = _qk_for_attention(c, cfg, p)
     c["o"] = attention_fwd(q, k, c["v"], cu_seqlens, cfg)
     c["x1"] = x + c["o"] @ p["Wo"] + _b(p, "bo", cfg)
     c["h2"], c["x1hat"], c["r2"] = _norm_fwd(c["x1"], p, "2", cfg)
@@ -286,7 +309,7 @@ def layer_backward_unsplit(dy, c, p, cfg):
     dx1 = dx1 + dn
     do = dx1 @ p["Wo"].T
     g["Wo"] = c["o"].T @ dx1
-    dq, dk, dv = _attention_bwd_qk(do, c, cfg)
+    dq, dk, dv = _attention_bwd_qk(do, c, cfg, p, g)
     dh1 = dq @ p["Wq"].T + dk @ p["Wk"].T + dv @ p["Wv"].T
     g["Wq"] = c["h1"].T @ dq
     g["Wk"] = c["h1"].T @ dk
@@ -316,7 +339,7 @@ def layer_B(dy, c, p, cfg):
     dn = _norm_bwd(dh2, c["x1hat"], c["r2"], p, "2", cfg, gains)
     w["dx1"] = dy + dn
     do = w["dx1"] @ p["Wo"].T
-    w["dq"], w["dk"], w["dv"] = _attention_bwd_qk(do, c, cfg)
+    w["dq"], w["dk"], w["dv"] = _attention_bwd_qk(do, c, cfg, p, gains)
     dh1 = w["dq"] @ p["Wq"].T + w["dk"] @ p["Wk"].T + w["dv"] @ p["Wv"].T
     dn = _norm_bwd(dh1, c["xhat"], c["r1"], p, "1", cfg, gains)
     if cfg.bias:     # column sums of the GEMM output-gradients: vector-shaped, produced in B like the gains

@@ -26,6 +26,9 @@ def _rand_params(cfg, rng, std=0.3):
         if cfg.norm_kind == "layer":
             p["b1"] = 0.3 * rng.standard_normal(H)
             p["b2"] = 0.3 * rng.standard_normal(H)
+        if cfg.qk_norm:
+            p["gq"] = 1 + 0.3 * rng.standard_normal(d)
+            p["gk"] = 1 + 0.3 * rng.standard_normal(d)
         if cfg.bias:
             for nm, n in (("bq", nq * d), ("bk", nkv * d), ("bv", nkv * d), ("bo", H), ("bd", H)):
                 p[nm] = 0.3 * rng.standard_normal(n)
@@ -45,6 +48,8 @@ CASES = [
     dict(mlp_kind="gelu", causal=False, n_kv_heads=4, norm_kind="layer", bias=True),
     dict(mlp_kind="swiglu", causal=True, n_kv_heads=2, norm_kind="layer", bias=True, rope=True),
     dict(mlp_kind="gelu", causal=True, n_kv_heads=2, bias=True),
+    dict(mlp_kind="swiglu", causal=True, n_kv_heads=2, qk_norm=True, rope=True),
+    dict(mlp_kind="gelu", causal=False, n_kv_heads=1, qk_norm=True, bias=True),
 ]
 
 
@@ -371,6 +376,9 @@ def test_against_torch_autograd(case):
         a = norm(h, p, "1")
         q = lin(a, p, "Wq", "bq").view(T, nq, d)
         k = lin(a, p, "Wk", "bk").view(T, nkv, d)
+        if cfg.qk_norm:
+            q = q * torch.rsqrt(q.pow(2).mean(-1, keepdim=True) + cfg.norm_eps) * p["gq"]
+            k = k * torch.rsqrt(k.pow(2).mean(-1, keepdim=True) + cfg.norm_eps) * p["gk"]
         if cfg.rope:
             # independent formulation: pairs (x_i, x_{i+d/2}) as complex numbers times e^{i pos theta_i}
             pos = torch.tensor(np.concatenate([np.arange(cu[s + 1] - cu[s]) for s in range(len(cu) - 1)]), dtype=torch.float64)
@@ -437,6 +445,23 @@ def test_bias_variant_reduces_to_plain_layer_at_zero_bias():
     ya, _ = O.stage_F(x, params, [0, 9], cfg_b)
     yb, _ = O.stage_F(x, params, [0, 9], cfg_0)
     np.testing.assert_array_equal(ya, yb)
+
+
+def test_qk_norm_makes_scores_independent_of_the_projection_scale():
+    # with head normalisation (eps = 0) scaling Wq or Wk by a positive constant changes nothing
+    rng = np.random.default_rng(10)
+    cfg = O.OracleConfig(n_layers=1, hidden=16, n_q_heads=4, n_kv_heads=2, head_dim=4, ffn=24, qk_norm=True, norm_eps=0.0)
+    params = _rand_params(cfg, rng)
+    x = rng.standard_normal((9, 16))
+    y0, _ = O.stage_F(x, params, [0, 9], cfg)
+    scaled = [dict(p, Wq=3.0 * p["Wq"], Wk=0.25 * p["Wk"]) for p in params]
+    y1, _ = O.stage_F(x, scaled, [0, 9], cfg)
+    np.testing.assert_allclose(y1, y0, rtol=1e-10, atol=1e-12)
+    # unit gains: every normalised head has RMS 1 (checked through the cache)
+    unit = [dict(p, gq=np.ones(4), gk=np.ones(4)) for p in params]
+    _, caches = O.stage_F(x, unit, [0, 9], cfg)
+    q = caches[0]["q_att"].reshape(9, 4, 4)
+    np.testing.assert_allclose(np.sqrt((q ** 2).mean(-1)), 1.0, rtol=1e-12)
 
 
 # ------------------------------------------------------------------ rotary embedding variant
