@@ -177,6 +177,7 @@ def main():
                          "(fixed 1F1B against readiness-driven dispatch, jitter levels J0-J3)")
     ap.add_argument("--pipeline-stages", type=int, default=8)
     ap.add_argument("--rope", action="store_true", help="turn on the rotary-embedding variant of the layer (off in the headline workload)")
+    ap.add_argument("--qk-norm", action="store_true", help="turn on the QK-norm variant of the layer (off in the headline workload)")
     ap.add_argument("--layernorm-bias", action="store_true",
                     help="turn on the LayerNorm + projection-bias variant of the layer (off in the five workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -199,6 +200,8 @@ def main():
              "tiny": SI.TINY}[args.workload]
     if args.rope:
         shape = shape.replace(rope=True, name=shape.name + "+rope")
+    if args.qk_norm:
+        shape = shape.replace(qk_norm=True, name=shape.name + "+qknorm")
     if args.layernorm_bias:
         shape = shape.replace(norm_kind="layer", bias=True, name=shape.name + "+layernorm+bias")
     if args.only in ("gemm", "copy"):

@@ -69,7 +69,9 @@ enum {
   STAGE_P_B2 = 9,   /* [hidden]                       bias of the second LayerNorm (norm_kind 1)  */
   STAGE_P_BUP = 10, /* [2 ffn] gate then up, or [ffn] bias of the up projection    (bias 1)       */
   STAGE_P_BD = 11,  /* [hidden]                       bias of the down projection  (bias 1)       */
-  STAGE_P_COUNT = 12
+  STAGE_P_GQ = 12,  /* [head_dim]                     gain of the query head norm  (qk_norm 1)    */
+  STAGE_P_GK = 13,  /* [head_dim]                     gain of the key head norm    (qk_norm 1)    */
+  STAGE_P_COUNT = 14
 };
 
 typedef struct {
@@ -90,6 +92,9 @@ typedef struct {
   int32_t bias;           /* 1 = a bias vector on each of the four projections (model-fidelity
                              variant); their gradients are column sums of the projections'
                              output-gradients, produced by stage_B like the norm gradients   */
+  int32_t qk_norm;        /* 1 = RMSNorm over head_dim (same eps) on every query and key head after
+                             the QKV projection and before the rotary embedding, gains STAGE_P_GQ /
+                             STAGE_P_GK shared by all heads (model-fidelity variant)          */
 } stage_config;
 
 typedef struct stage_s stage_t;

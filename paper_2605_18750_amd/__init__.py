@@ -13,14 +13,14 @@ STAGE_OK, STAGE_EINVAL, STAGE_ENOTREADY, STAGE_ENOMEM, STAGE_EHIP = 0, -1, -2, -
 STAGE_DTYPE_FP32, STAGE_DTYPE_BF16 = 0, 1
 STAGE_MLP_SWIGLU, STAGE_MLP_GELU = 0, 1
 (STAGE_P_G1, STAGE_P_WQKV, STAGE_P_WO, STAGE_P_G2, STAGE_P_WUP, STAGE_P_WD, STAGE_P_B1, STAGE_P_BQKV, STAGE_P_BO,
- STAGE_P_B2, STAGE_P_BUP, STAGE_P_BD, STAGE_P_COUNT) = range(13)
+ STAGE_P_B2, STAGE_P_BUP, STAGE_P_BD, STAGE_P_GQ, STAGE_P_GK, STAGE_P_COUNT) = range(15)
 
 
 class stage_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "max_tokens",
         "n_microbatches", "max_segments", "dtype", "mlp_kind", "causal", "norm_kind")] + [
-        ("norm_eps", C.c_float), ("rope", C.c_int32), ("rope_base", C.c_float), ("bias", C.c_int32)]
+        ("norm_eps", C.c_float), ("rope", C.c_int32), ("rope_base", C.c_float), ("bias", C.c_int32), ("qk_norm", C.c_int32)]
 
 
 class StageError(RuntimeError):

@@ -2,6 +2,8 @@
 // forward/backward, the fixed-order column sum for norm-gain gradients and the
 // index-ordered gradient reduction.  All arithmetic is fp32; storage is fp32 or bf16.
 // None of these kernels uses atomics: every sum has one fixed order.
+#include <algorithm>
+
 #include "kernels.h"
 #include "numeric.h"
 
@@ -415,6 +417,81 @@ __global__ __launch_bounds__(256) void colsum_rows_kernel(const T* __restrict__ 
   partial[(size_t)blockIdx.y * N + c] = acc;
 }
 
+// ---------------------------------------------------------------- head norm (QK-norm variant)
+// RMSNorm over head_dim of every (token, head) d-vector of the first n_heads heads of a [T, ld] tensor, in
+// place: x <- xhat * g, with xhat = x * r saved (storage type) and r saved (fp32) for the backward.
+// Heads [0, nq) use gq, heads [nq, n_heads) use gk.  One wavefront per (token, head).
+template <typename T>
+__global__ __launch_bounds__(256) void headnorm_fwd_kernel(T* __restrict__ x, int ld, int nq, int n_heads, int d,
+                                                           const T* __restrict__ gq, const T* __restrict__ gk,
+                                                           T* __restrict__ xhat, float* __restrict__ r_out, int Tn, float eps) {
+  const size_t pair = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (pair >= (size_t)Tn * n_heads) return;
+  const int t = (int)(pair / n_heads), hd = (int)(pair - (size_t)t * n_heads);
+  T* p = x + (size_t)t * ld + hd * d;
+  const T* g = hd < nq ? gq : gk;
+  float ss = 0.f;
+  for (int c = lane; c < d; c += WAVE) { const float v = to_float(p[c]); ss += v * v; }
+  const float r = 1.0f / sqrtf(wave_sum(ss) / (float)d + eps);
+  if (lane == 0) r_out[pair] = r;
+  for (int c = lane; c < d; c += WAVE) {
+    const float xh = to_float(p[c]) * r;
+    xhat[pair * d + c] = from_float<T>(xh);
+    p[c] = from_float<T>(xh * to_float(g[c]));
+  }
+}
+
+// Backward, in place on the gradient tensor: dx = r * (w - xhat * mean(w * xhat)), w = dy * g.  A workgroup
+// handles 64 consecutive (token, head) pairs of ONE kind (grid y = 0: query heads, 1: key heads) and writes
+// one partial row of the gain gradient, sum over its pairs (ascending, wavefronts combined in order) of dy * xhat.
+template <typename T>
+__global__ __launch_bounds__(256) void headnorm_bwd_kernel(T* __restrict__ dy, int ld, int nq, int n_heads, int d,
+                                                           const T* __restrict__ gq, const T* __restrict__ gk,
+                                                           const T* __restrict__ xhat, const float* __restrict__ r_in,
+                                                           float* __restrict__ partial_q, float* __restrict__ partial_k, int Tn) {
+  __shared__ float red[4][128];
+  const int kind = blockIdx.y, nh = kind == 0 ? nq : n_heads - nq, h0 = kind == 0 ? 0 : nq;
+  const T* g = kind == 0 ? gq : gk;
+  float* partial = kind == 0 ? partial_q : partial_k;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const size_t n_pairs = (size_t)Tn * nh;
+  if ((size_t)blockIdx.x * 64 >= n_pairs) return;
+  float gs[2] = {0.f, 0.f};
+  for (int i = 0; i < 16; ++i) {
+    const size_t q = (size_t)blockIdx.x * 64 + wave * 16 + i;       // pair index inside this kind
+    if (q >= n_pairs) break;
+    const int t = (int)(q / nh), hd = h0 + (int)(q - (size_t)t * nh);
+    const size_t pair = (size_t)t * n_heads + hd;
+    T* p = dy + (size_t)t * ld + hd * d;
+    const float rr = r_in[pair];
+    float w[2], xh[2], dv[2], dot = 0.f;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = lane + u * WAVE;
+      w[u] = 0.f; xh[u] = 0.f; dv[u] = 0.f;
+      if (c < d) {
+        dv[u] = to_float(p[c]);
+        xh[u] = to_float(xhat[pair * d + c]);
+        w[u] = dv[u] * to_float(g[c]);
+        dot += w[u] * xh[u];
+        gs[u] += dv[u] * xh[u];
+      }
+    }
+    dot = wave_sum(dot) / (float)d;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = lane + u * WAVE;
+      if (c < d) p[c] = from_float<T>(rr * (w[u] - xh[u] * dot));
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) red[wave][lane + u * WAVE] = gs[u];
+  __syncthreads();
+  if (threadIdx.x < d) partial[(size_t)blockIdx.x * d + threadIdx.x] =
+      ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+}
+
 // ---------------------------------------------------------------- rotary embedding
 // One workgroup per (query tile, head); a wavefront per row, a lane per pair.  The angle is formed in
 // double precision and reduced to [0, 2 pi) before the single-precision sine and cosine, so that the
@@ -537,6 +614,26 @@ hipError_t launch_rmsnorm_bwd(const float* dh, const float* x, const float* r, c
     hipLaunchKernelGGL(rmsnorm_bwd_rows_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, dh, x, r, (const T*)g,
                        add_in, out32, (T*)out_t, Tn, H);
   });
+  return hipGetLastError();
+}
+
+int headnorm_partials(int Tn, int n_heads_of_kind) { return (int)(((size_t)Tn * n_heads_of_kind + 63) / 64); }
+
+hipError_t launch_headnorm_fwd(void* x, int ld, int nq, int n_heads, int d, const void* gq, const void* gk, void* xhat,
+                               float* r_out, int Tn, float eps, int dtype, hipStream_t s) {
+  if (d > 128) return hipErrorInvalidValue;
+  const size_t pairs = (size_t)Tn * n_heads;
+  DISPATCH_T(dtype, hipLaunchKernelGGL(headnorm_fwd_kernel<T>, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s, (T*)x, ld, nq,
+                                       n_heads, d, (const T*)gq, (const T*)gk, (T*)xhat, r_out, Tn, eps));
+  return hipGetLastError();
+}
+
+hipError_t launch_headnorm_bwd(void* dy, int ld, int nq, int n_heads, int d, const void* gq, const void* gk, const void* xhat,
+                               const float* r_in, float* partial_q, float* partial_k, int Tn, int dtype, hipStream_t s) {
+  if (d > 128) return hipErrorInvalidValue;
+  const int nb = std::max(headnorm_partials(Tn, nq), headnorm_partials(Tn, n_heads - nq));
+  DISPATCH_T(dtype, hipLaunchKernelGGL(headnorm_bwd_kernel<T>, dim3(nb, 2), dim3(256), 0, s, (T*)dy, ld, nq, n_heads, d,
+                                       (const T*)gq, (const T*)gk, (const T*)xhat, r_in, partial_q, partial_k, Tn));
   return hipGetLastError();
 }
 

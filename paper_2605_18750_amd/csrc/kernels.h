@@ -104,6 +104,15 @@ hipError_t launch_layernorm_fwd(const float* x, const void* g, const void* b, vo
 hipError_t launch_layernorm_bwd(const float* dh, const float* x, const float* r, const float* mu, const void* g,
                                 const float* add_in, float* out32, void* out_t, float* partial_g, float* partial_b,
                                 int T, int H, int dtype, hipStream_t s);
+// Head norm (QK-norm variant): RMSNorm over head_dim of the first n_heads heads of every row of a [T, ld]
+// tensor, in place; heads [0, nq) use gq, the others gk; xhat [T * n_heads, d] and r [T * n_heads] are saved.
+// The backward rewrites the gradient tensor in place and writes headnorm_partials(T, heads of the kind)
+// partial rows [d] of each gain gradient (for launch_colsum).
+int headnorm_partials(int T, int n_heads_of_kind);
+hipError_t launch_headnorm_fwd(void* x, int ld, int nq, int n_heads, int d, const void* gq, const void* gk, void* xhat,
+                               float* r_out, int T, float eps, int dtype, hipStream_t s);
+hipError_t launch_headnorm_bwd(void* dy, int ld, int nq, int n_heads, int d, const void* gq, const void* gk, const void* xhat,
+                               const float* r_in, float* partial_q, float* partial_k, int T, int dtype, hipStream_t s);
 // Per-chunk column sums of a [T, N] tensor of the storage type into partial [colsum_chunks(T), N] (bias gradients).
 hipError_t launch_colsum_rows(const void* src, int ld, float* partial, int T, int N, int dtype, hipStream_t s);
 

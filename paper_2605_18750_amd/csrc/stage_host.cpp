@@ -38,6 +38,7 @@ struct LayerStash {
   size_t dy32, dx1_32;                                // written by B, fp32 residual-gradient chain
   size_t o32;                                         // written by F: attention output before rounding (bf16 path)
   size_t mu1, mu2;                                    // written by F: row means (LayerNorm variant)
+  size_t qk_hat, qk_r;                                // written by F: normalised q, k heads and their 1/rms (QK-norm variant)
 };
 
 struct Plan {
@@ -73,6 +74,7 @@ int check_config(const stage_config* c) {
   if (c->causal != 0 && c->causal != 1) { set_tls_error("causal must be 0 or 1"); return STAGE_EINVAL; }
   if (c->norm_kind != 0 && c->norm_kind != 1) { set_tls_error("norm_kind must be 0 (RMSNorm) or 1 (LayerNorm)"); return STAGE_EINVAL; }
   if (c->bias != 0 && c->bias != 1) { set_tls_error("bias must be 0 or 1"); return STAGE_EINVAL; }
+  if (c->qk_norm != 0 && c->qk_norm != 1) { set_tls_error("qk_norm must be 0 or 1"); return STAGE_EINVAL; }
   if (!(c->norm_eps >= 0.0f) || !(c->norm_eps < 1.0f)) { set_tls_error("norm_eps must be in [0, 1)"); return STAGE_EINVAL; }
   if (c->rope != 0 && c->rope != 1) { set_tls_error("rope must be 0 or 1"); return STAGE_EINVAL; }
   if (c->rope == 1 && !(c->rope_base > 1.0f)) { set_tls_error("rope_base must be > 1"); return STAGE_EINVAL; }
@@ -102,7 +104,8 @@ int make_plan(const stage_config* c, Plan* p) {
       {(int64_t)H, 1}, {(int64_t)H, p->n_qkv}, {(int64_t)(nq * d), (int64_t)H},
       {(int64_t)H, 1}, {(int64_t)H, p->n_up}, {(int64_t)F, (int64_t)H},
       {ln * (int64_t)H, 1}, {bs * (int64_t)p->n_qkv, 1}, {bs * (int64_t)H, 1},
-      {ln * (int64_t)H, 1}, {bs * (int64_t)p->n_up, 1}, {bs * (int64_t)H, 1}};
+      {ln * (int64_t)H, 1}, {bs * (int64_t)p->n_up, 1}, {bs * (int64_t)H, 1},
+      {(c->qk_norm ? 1 : 0) * (int64_t)d, 1}, {(c->qk_norm ? 1 : 0) * (int64_t)d, 1}};
   memcpy(p->p_shape, shapes, sizeof(shapes));
   size_t off = 0;
   for (int l = 0; l < c->n_layers; ++l)
@@ -128,15 +131,21 @@ int make_plan(const stage_config* c, Plan* p) {
     s.o32 = c->dtype == STAGE_DTYPE_BF16 ? take(T * nq * d * 4) : 0;
     s.mu1 = c->norm_kind == 1 ? take(T * 4) : 0;
     s.mu2 = c->norm_kind == 1 ? take(T * 4) : 0;
+    s.qk_hat = c->qk_norm ? take(T * (nq + nkv) * d * e) : 0;
+    s.qk_r = c->qk_norm ? take(T * (nq + nkv) * 4) : 0;
   }
   p->t_dm = take(T * F * 4);     // fp32: GEMM outputs that only an elementwise kernel consumes are not rounded
   p->t_dh = take(T * H * 4);
   p->t_do = take(T * nq * d * e);
   p->t_delta = take(nq * T * 4);
-  p->t_dgp = take((size_t)std::max(norm_bwd_partials((int)T, (int)H, c->dtype), colsum_chunks((int)T)) * H * 4);
+  size_t dgp = (size_t)std::max(norm_bwd_partials((int)T, (int)H, c->dtype), colsum_chunks((int)T)) * H * 4;
+  if (c->qk_norm) dgp = std::max(dgp, (size_t)headnorm_partials((int)T, (int)nq) * d * 4);
+  p->t_dgp = take(dgp);
   // second partial array: LayerNorm bias gradient, and the projection-bias gradients (widest tensor)
   const size_t wide = std::max((size_t)H, (size_t)std::max(p->n_qkv, p->n_up));
-  p->t_dbp = (c->norm_kind == 1 || c->bias) ? take((size_t)colsum_chunks((int)T) * wide * 4) : 0;
+  size_t dbp = (c->norm_kind == 1 || c->bias) ? (size_t)colsum_chunks((int)T) * wide * 4 : 0;
+  if (c->qk_norm) dbp = std::max(dbp, (size_t)headnorm_partials((int)T, (int)nkv) * d * 4);
+  p->t_dbp = dbp ? take(dbp) : 0;
   const int tile = std::min(ATTN_TILE_Q, ATTN_TILE_KV);
   p->max_tiles = (int)((T + tile - 1) / tile) + c->max_segments;
   p->t_qtiles = take((size_t)p->max_tiles * sizeof(AttnTile));
@@ -391,6 +400,10 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     g.C = base + L.qkv; g.ldc = P.n_qkv; g.R = nullptr; g.N = P.n_qkv; g.K = H;
     g.bias = c.bias ? param_ptr(st, l, STAGE_P_BQKV) : nullptr;
     HIP_TRY(st, launch_gemm(g, s));
+    if (c.qk_norm)   // normalise every q and k head in place (before the rotation)
+      HIP_TRY(st, launch_headnorm_fwd(base + L.qkv, P.n_qkv, c.n_q_heads, c.n_q_heads + c.n_kv_heads, c.head_dim,
+                                      param_ptr(st, l, STAGE_P_GQ), param_ptr(st, l, STAGE_P_GK), base + L.qk_hat,
+                                      (float*)(base + L.qk_r), T, c.norm_eps, dt, s));
     if (c.rope)   // rotate q and k in place: the stash then holds what the attention (and its backward) reads
       HIP_TRY(st, launch_rope(base + L.qkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,
                               c.head_dim, P.n_qkv, c.rope_base, 1.0f, dt, s));
@@ -527,6 +540,13 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     if (c.rope)   // gradients w.r.t. the rotated q, k -> w.r.t. the projection outputs (inverse rotation)
       HIP_TRY(st, launch_rope(base + L.dqkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,
                               c.head_dim, P.n_qkv, c.rope_base, -1.0f, dt, s));
+    if (c.qk_norm) {   // gradients w.r.t. the normalised heads -> w.r.t. the projection outputs, gain gradients to the slot
+      HIP_TRY(st, launch_headnorm_bwd(base + L.dqkv, P.n_qkv, c.n_q_heads, c.n_q_heads + c.n_kv_heads, c.head_dim,
+                                      param_ptr(st, l, STAGE_P_GQ), param_ptr(st, l, STAGE_P_GK), base + L.qk_hat,
+                                      (const float*)(base + L.qk_r), (float*)(base + P.t_dgp), (float*)(base + P.t_dbp), T, dt, s));
+      HIP_TRY(st, launch_colsum((const float*)(base + P.t_dgp), headnorm_partials(T, c.n_q_heads), c.head_dim, slot + P.p_off[l][STAGE_P_GQ], s));
+      HIP_TRY(st, launch_colsum((const float*)(base + P.t_dbp), headnorm_partials(T, c.n_kv_heads), c.head_dim, slot + P.p_off[l][STAGE_P_GK], s));
+    }
     if (c.bias) { rc = bias_grad(base + L.dqkv, P.n_qkv, P.p_off[l][STAGE_P_BQKV]); if (rc) return rc; }
     // dh1 = [dq|dk|dv] Wqkv^T
     g.A = base + L.dqkv; g.lda = P.n_qkv; g.B = param_ptr(st, l, STAGE_P_WQKV); g.ldb = P.n_qkv;

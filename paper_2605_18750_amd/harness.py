@@ -20,7 +20,8 @@ def make_config(shape, max_tokens: int, max_segments: int = 1, n_microbatches: i
         mlp_kind=R.STAGE_MLP_SWIGLU if shape.mlp_kind == "swiglu" else R.STAGE_MLP_GELU,
         causal=1 if shape.causal else 0, norm_kind=1 if getattr(shape, "norm_kind", "rms") == "layer" else 0,
         norm_eps=shape.norm_eps, rope=1 if getattr(shape, "rope", False) else 0,
-        rope_base=getattr(shape, "rope_base", 10000.0), bias=1 if getattr(shape, "bias", False) else 0)
+        rope_base=getattr(shape, "rope_base", 10000.0), bias=1 if getattr(shape, "bias", False) else 0,
+        qk_norm=1 if getattr(shape, "qk_norm", False) else 0)
 
 
 def _fused(layer: dict, which: int, swiglu: bool) -> np.ndarray:
@@ -41,6 +42,9 @@ def _fused(layer: dict, which: int, swiglu: bool) -> np.ndarray:
     empty = np.zeros(0, dtype=st("g1").dtype)
     if which in (R.STAGE_P_B1, R.STAGE_P_B2):
         nm = "b1" if which == R.STAGE_P_B1 else "b2"
+        return st(nm) if nm in layer else empty
+    if which in (R.STAGE_P_GQ, R.STAGE_P_GK):
+        nm = "gq" if which == R.STAGE_P_GQ else "gk"
         return st(nm) if nm in layer else empty
     if "bo" not in layer:
         return empty
@@ -91,6 +95,8 @@ def unpack_grads(cfg, flat: np.ndarray) -> list:
             g["W1"] = t[R.STAGE_P_WUP]
         if cfg.norm_kind == 1:
             g["b1"], g["b2"] = t[R.STAGE_P_B1].reshape(-1), t[R.STAGE_P_B2].reshape(-1)
+        if cfg.qk_norm:
+            g["gq"], g["gk"] = t[R.STAGE_P_GQ].reshape(-1), t[R.STAGE_P_GK].reshape(-1)
         if cfg.bias:
             bqkv, bup = t[R.STAGE_P_BQKV].reshape(-1), t[R.STAGE_P_BUP].reshape(-1)
             g["bq"], g["bk"], g["bv"] = bqkv[:nq * d], bqkv[nq * d:(nq + nkv) * d], bqkv[(nq + nkv) * d:]

@@ -41,6 +41,7 @@ class StageShape:
     rope: bool = False            # rotary position embedding on q and k (model-fidelity variant)
     norm_kind: str = "rms"        # "rms" | "layer" (model-fidelity variant)
     bias: bool = False            # biases on the four projections (model-fidelity variant)
+    qk_norm: bool = False         # RMSNorm over head_dim on q and k heads (model-fidelity variant)
     rope_base: float = 10000.0
     w_std: float = 0.02
     x_std: float = 1.0
@@ -167,6 +168,8 @@ def layer_param_shapes(s: StageShape) -> dict:
         shapes.update({"W1": (H, F), "Wd": (F, H)})
     if s.norm_kind == "layer":
         shapes.update({"b1": (H,), "b2": (H,)})
+    if s.qk_norm:
+        shapes.update({"gq": (d,), "gk": (d,)})
     if s.bias:
         shapes.update({"bq": (nq * d,), "bk": (nkv * d,), "bv": (nkv * d,), "bo": (H,), "bd": (H,)})
         shapes.update({"bg": (F,), "bu": (F,)} if s.mlp_kind == "swiglu" else {"bf": (F,)})
@@ -177,7 +180,7 @@ def make_layer_params(s: StageShape, layer: int, seed: int = BASE_SEED) -> dict:
     """Logical parameters of one layer.  Weights N(0, w_std); norm gains 1 + N(0, w_std)."""
     out = {}
     for nm, shp in layer_param_shapes(s).items():
-        is_gain = nm in ("g1", "g2")
+        is_gain = nm in ("g1", "g2", "gq", "gk")
         out[nm] = make_tensor(seed, f"{s.name}/L{layer}/{nm}", shp, s.w_std, s.dtype,
                               mean=1.0 if is_gain else 0.0)
     return out

@@ -14,7 +14,7 @@ def oracle_config(shape: SI.StageShape) -> O.OracleConfig:
     return O.OracleConfig(n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
                           n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
                           mlp_kind=shape.mlp_kind, causal=shape.causal, norm_eps=shape.norm_eps,
-                          rope=shape.rope, rope_base=shape.rope_base, norm_kind=shape.norm_kind, bias=shape.bias)
+                          rope=shape.rope, rope_base=shape.rope_base, norm_kind=shape.norm_kind, bias=shape.bias, qk_norm=shape.qk_norm)
 
 
 def max_norm_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
@@ -137,7 +137,7 @@ def fuse_grads(layer: dict) -> dict:
     out = {"g1": layer["g1"], "g2": layer["g2"], "Wo": layer["Wo"], "Wd": layer["Wd"],
            "Wqkv": np.concatenate([layer["Wq"], layer["Wk"], layer["Wv"]], axis=1)}
     out["Wup"] = np.concatenate([layer["Wg"], layer["Wu"]], axis=1) if "Wg" in layer else layer["W1"]
-    for k in ("b1", "b2", "bo", "bd"):
+    for k in ("b1", "b2", "bo", "bd", "gq", "gk"):
         if k in layer:
             out[k] = layer[k]
     if "bq" in layer:

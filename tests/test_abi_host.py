@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _cfg(**kw):
     base = dict(n_layers=2, hidden=128, n_q_heads=4, n_kv_heads=2, head_dim=32, ffn=192, max_tokens=64,
                 n_microbatches=3, max_segments=2, dtype=0, mlp_kind=0, causal=1, norm_kind=0, norm_eps=1e-5,
-                rope=0, rope_base=10000.0, bias=0)
+                rope=0, rope_base=10000.0, bias=0, qk_norm=0)
     base.update(kw)
     return R.stage_config(**base)
 
@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol():
 def test_config_validation():
     R.stage_query(_cfg())
     bad = [dict(n_kv_heads=3), dict(hidden=0), dict(head_dim=24), dict(head_dim=144), dict(dtype=2),
-           dict(mlp_kind=5), dict(causal=2), dict(norm_kind=2), dict(bias=2), dict(norm_eps=-1.0), dict(rope=2), dict(rope=1, rope_base=1.0), dict(ffn=190),
+           dict(mlp_kind=5), dict(causal=2), dict(norm_kind=2), dict(bias=2), dict(qk_norm=3), dict(norm_eps=-1.0), dict(rope=2), dict(rope=1, rope_base=1.0), dict(ffn=190),
            dict(dtype=1, head_dim=32), dict(dtype=1, head_dim=64, hidden=96), dict(n_layers=65)]
     for kw in bad:
         with pytest.raises(R.StageError) as e:

@@ -55,6 +55,12 @@ SMALL = {
     "bf16_layernorm_bias_swiglu_rope": (SI.StageShape("s_bf16_ln2", 2, 512, 4, 2, 128, 384, 2, w_std=0.03,
                                                       norm_kind="layer", bias=True, rope=True),
                                         [[0, 300], [0, 130, 391]]),
+    "bf16_qk_norm_rope": (SI.StageShape("s_bf16_qkn", 2, 512, 4, 2, 128, 384, 2, w_std=0.03, qk_norm=True, rope=True),
+                          [[0, 130, 300], [0, 257]]),
+    "bf16_qk_norm_d80_bias": (SI.StageShape("s_bf16_qkn80", 1, 320, 4, 4, 80, 256, 2, mlp_kind="gelu", causal=False, w_std=0.05,
+                                            qk_norm=True, bias=True), [[0, 96, 97], [0, 301]]),
+    "fp32_qk_norm": (SI.StageShape("s_fp32_qkn", 2, 100, 4, 2, 16, 36, 2, dtype="fp32", x_std=1.0, dy_std=1.0, qk_norm=True,
+                                   rope=True), [[0, 50, 130], [0, 33]]),
     "bf16_bias_only": (SI.StageShape("s_bf16_b", 1, 128, 4, 2, 64, 192, 2, w_std=0.05, bias=True), [[0, 200], [0, 77, 333]]),
     "fp32_layernorm_bias": (SI.StageShape("s_fp32_ln", 2, 100, 4, 2, 16, 36, 2, dtype="fp32", mlp_kind="gelu", x_std=1.0, dy_std=1.0,
                                           w_std=0.1, norm_kind="layer", bias=True),
@@ -92,7 +98,7 @@ def test_tiny_fp32_config_matches_oracle():
 
 
 @pytest.mark.parametrize("name", ["fp32_ragged_causal_gqa", "bf16_ragged_causal_gqa", "bf16_bidir_gelu_d80", "bf16_rope_d128",
-                                  "bf16_long_tokens_splitk", "bf16_layernorm_bias_gelu"])
+                                  "bf16_long_tokens_splitk", "bf16_layernorm_bias_gelu", "bf16_qk_norm_rope"])
 def test_dispatch_order_is_bit_exact(name):
     shape, cus = SMALL[name]
     w = Hp.Workload(shape, cus)
