@@ -339,15 +339,24 @@ __device__ __forceinline__ void mfma16(floatx16 (&acc)[MI][NB], const Frags<MI, 
     for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
 }
 
-// Ask the scheduler to interleave N_DS LDS reads with N_MFMA MFMAs in four groups, reads leading.
-template <int N_DS, int N_MFMA>
-__device__ __forceinline__ void interleave_ds_mfma() {
-  constexpr int G = (N_DS % 4 == 0 && N_MFMA % 4 == 0) ? 4 : 2;
-#pragma unroll
-  for (int q = 0; q < G; ++q) {
-    __builtin_amdgcn_sched_group_barrier(0x100, N_DS / G, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA / G, 0);
+// Ask the scheduler to interleave N_DS LDS reads, N_VM global->LDS loads and N_MFMA MFMAs in groups, reads
+// leading.  The loads are spread over the groups on purpose: a wavefront that issues its loads of a step
+// back to back sits at the (in-order) issue of the later ones while the texture path works through the
+// earlier ones, and its MFMAs wait behind them; one load between every few MFMAs never queues.
+template <int N_DS, int N_MFMA, int N_VM, int G, int Q>
+__device__ __forceinline__ void interleave_group() {
+  if constexpr (Q < G) {
+    constexpr int DS = (Q + 1) * N_DS / G - Q * N_DS / G, VM = (Q + 1) * N_VM / G - Q * N_VM / G;
+    constexpr int MF = (Q + 1) * N_MFMA / G - Q * N_MFMA / G;
+    if constexpr (DS > 0) __builtin_amdgcn_sched_group_barrier(0x100, DS, 0);
+    if constexpr (VM > 0) __builtin_amdgcn_sched_group_barrier(0x020, VM, 0);
+    if constexpr (MF > 0) __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);
+    interleave_group<N_DS, N_MFMA, N_VM, G, Q + 1>();
   }
+}
+template <int N_DS, int N_MFMA, int N_VM>
+__device__ __forceinline__ void interleave_ds_vm_mfma() {
+  interleave_group<N_DS, N_MFMA, N_VM, (N_MFMA % 4 == 0) ? 4 : 2, 0>();
 }
 
 // WM x WN wavefronts tile the 256x256 block; each owns (256/WM) x (256/WN).
@@ -419,71 +428,77 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
 
   // Software pipeline over 32-deep steps.  Entering step t the fragments of its first k-step are in
   // registers (fx).  First half: read the second k-step's fragments (fy) under the MFMAs of the
-  // first.  Middle: wait for this wavefront's loads of step t+1 and for its own LDS reads, barrier
-  // (now stage t%4 is consumed by everybody and stage (t+1)%4 is complete), refill stage t%4 with
-  // step t+4, and read step t+1's first fragments under the MFMAs of the second k-step.
-  // Each step issues LPS loads per wavefront; "all but 2*LPS outstanding" means step t+1 has landed
-  // while t+2 and t+3 may still be in flight.
-  constexpr int LPS = DirectLoader<A_KC, NW, BMT>::NL + DirectLoader<B_KC, NW>::NL;
+  // first, and issue the B-operand loads of step t+3 into the stage before this one (free since the
+  // previous barrier).  Middle: wait for this wavefront's loads of step t+1 and for its own LDS reads,
+  // barrier (now stage t%4 is consumed by everybody and stage (t+1)%4 is complete).  Second half: issue
+  // the A-operand loads of step t+4 into stage t%4 and read step t+1's first fragments under the MFMAs
+  // of the second k-step.  Every step issues LPS = LA + LB loads per wavefront, half in each half-step,
+  // spread between the MFMAs; at the wait, the loads issued after those of step t+1 are
+  // A(t+2), B(t+2), A(t+3), B(t+3): "all but 2*LPS outstanding" means step t+1 has landed.
+  constexpr int LA = DirectLoader<A_KC, NW, BMT>::NL, LB = DirectLoader<B_KC, NW>::NL, LPS = LA + LB;
   constexpr int VM_ALL = 0x0070;                                   // vmcnt(0), lgkmcnt(0)
   constexpr int VM_2 = 0x0070 | ((2 * LPS) & 15) | (((2 * LPS) >> 4) << 14);   // vmcnt(2*LPS), lgkmcnt(0)
-  constexpr int VM_3 = 0x0070 | ((3 * LPS) & 15) | (((3 * LPS) >> 4) << 14);   // vmcnt(3*LPS), lgkmcnt(0)
+  constexpr int VM_P = 0x0070 | ((2 * LPS + LA) & 15) | (((2 * LPS + LA) >> 4) << 14);   // vmcnt(2*LPS + LA), lgkmcnt(0)
   constexpr int N_DS = (A_KC ? MI : 2 * MI) + (B_KC ? NB : 2 * NB);
   constexpr int N_MFMA = MI * NB;
-#define RRFP_ISSUE(stage, t) do { la.issue(stage, (t), wave); lb.issue(stage + DTILE, (t), wave); } while (0)
-#define RRFP_STEP_FULL(cur, nxt, t)                                                        \
+#define RRFP_ISSUE_A(stage, t) la.issue(stage, (t), wave)
+#define RRFP_ISSUE_B(stage, t) lb.issue(stage + DTILE, (t), wave)
+#define RRFP_STEP_FULL(prev, cur, nxt, t)                                                  \
   do {                                                                                     \
-    load_frags<A_KC, B_KC, MI, NB>(fy, cur, 1, wm, wn, lane);                                  \
-    mfma16<MI, NB>(acc, fx);                                                                   \
-    interleave_ds_mfma<N_DS, N_MFMA>();                                                    \
+    RRFP_ISSUE_B(prev, (t) + 3);                                                           \
+    load_frags<A_KC, B_KC, MI, NB>(fy, cur, 1, wm, wn, lane);                              \
+    mfma16<MI, NB>(acc, fx);                                                               \
+    interleave_ds_vm_mfma<N_DS, N_MFMA, LB>();                                             \
     __builtin_amdgcn_s_waitcnt(VM_2);                                                      \
     stage_barrier();                                                                       \
-    RRFP_ISSUE(cur, (t) + 4);                                                              \
-    load_frags<A_KC, B_KC, MI, NB>(fx, nxt, 0, wm, wn, lane);                                  \
-    mfma16<MI, NB>(acc, fy);                                                                   \
-    interleave_ds_mfma<N_DS, N_MFMA>();                                                    \
+    RRFP_ISSUE_A(cur, (t) + 4);                                                            \
+    load_frags<A_KC, B_KC, MI, NB>(fx, nxt, 0, wm, wn, lane);                              \
+    mfma16<MI, NB>(acc, fy);                                                               \
+    interleave_ds_vm_mfma<N_DS, N_MFMA, LA>();                                             \
   } while (0)
-#define RRFP_STEP_TAIL(cur, nxt, t)                                                        \
+#define RRFP_STEP_TAIL(prev, cur, nxt, t)                                                  \
   do {                                                                                     \
-    load_frags<A_KC, B_KC, MI, NB>(fy, cur, 1, wm, wn, lane);                                  \
-    mfma16<MI, NB>(acc, fx);                                                                   \
+    if ((t) + 3 < nk) RRFP_ISSUE_B(prev, (t) + 3);                                         \
+    load_frags<A_KC, B_KC, MI, NB>(fy, cur, 1, wm, wn, lane);                              \
+    mfma16<MI, NB>(acc, fx);                                                               \
     if ((t) + 1 < nk) {                                                                    \
       if ((t) + 3 < nk) __builtin_amdgcn_s_waitcnt(VM_2);                                  \
       else __builtin_amdgcn_s_waitcnt(VM_ALL);                                             \
       stage_barrier();                                                                     \
-      if ((t) + 4 < nk) RRFP_ISSUE(cur, (t) + 4);                                          \
-      load_frags<A_KC, B_KC, MI, NB>(fx, nxt, 0, wm, wn, lane);                                \
+      if ((t) + 4 < nk) RRFP_ISSUE_A(cur, (t) + 4);                                        \
+      load_frags<A_KC, B_KC, MI, NB>(fx, nxt, 0, wm, wn, lane);                            \
     }                                                                                      \
-    mfma16<MI, NB>(acc, fy);                                                                   \
+    mfma16<MI, NB>(acc, fy);                                                               \
   } while (0)
 
   Frags<MI, NB> fx, fy;
-  RRFP_ISSUE(stage0, 0);
-  if (nk > 1) RRFP_ISSUE(stage1, 1);
-  if (nk > 2) RRFP_ISSUE(stage2, 2);
-  if (nk > 3) RRFP_ISSUE(stage3, 3);
-  if (nk > 3) __builtin_amdgcn_s_waitcnt(VM_3); else __builtin_amdgcn_s_waitcnt(VM_ALL);
+  RRFP_ISSUE_A(stage0, 0); RRFP_ISSUE_B(stage0, 0);
+  if (nk > 1) { RRFP_ISSUE_A(stage1, 1); RRFP_ISSUE_B(stage1, 1); }
+  if (nk > 2) { RRFP_ISSUE_A(stage2, 2); RRFP_ISSUE_B(stage2, 2); }
+  if (nk > 3) RRFP_ISSUE_A(stage3, 3);
+  if (nk > 3) __builtin_amdgcn_s_waitcnt(VM_P); else __builtin_amdgcn_s_waitcnt(VM_ALL);
   stage_barrier();
   load_frags<A_KC, B_KC, MI, NB>(fx, stage0, 0, wm, wn, lane);
 
   int t = 0;
   for (; t + 7 < nk; t += 4) {      // every step of this loop has a step t+4 to prefetch
-    RRFP_STEP_FULL(stage0, stage1, t);
-    RRFP_STEP_FULL(stage1, stage2, t + 1);
-    RRFP_STEP_FULL(stage2, stage3, t + 2);
-    RRFP_STEP_FULL(stage3, stage0, t + 3);
+    RRFP_STEP_FULL(stage3, stage0, stage1, t);
+    RRFP_STEP_FULL(stage0, stage1, stage2, t + 1);
+    RRFP_STEP_FULL(stage1, stage2, stage3, t + 2);
+    RRFP_STEP_FULL(stage2, stage3, stage0, t + 3);
   }
   // at most 7 steps remain
-  if (t < nk) RRFP_STEP_TAIL(stage0, stage1, t);
-  if (t + 1 < nk) RRFP_STEP_TAIL(stage1, stage2, t + 1);
-  if (t + 2 < nk) RRFP_STEP_TAIL(stage2, stage3, t + 2);
-  if (t + 3 < nk) RRFP_STEP_TAIL(stage3, stage0, t + 3);
-  if (t + 4 < nk) RRFP_STEP_TAIL(stage0, stage1, t + 4);
-  if (t + 5 < nk) RRFP_STEP_TAIL(stage1, stage2, t + 5);
-  if (t + 6 < nk) RRFP_STEP_TAIL(stage2, stage3, t + 6);
+  if (t < nk) RRFP_STEP_TAIL(stage3, stage0, stage1, t);
+  if (t + 1 < nk) RRFP_STEP_TAIL(stage0, stage1, stage2, t + 1);
+  if (t + 2 < nk) RRFP_STEP_TAIL(stage1, stage2, stage3, t + 2);
+  if (t + 3 < nk) RRFP_STEP_TAIL(stage2, stage3, stage0, t + 3);
+  if (t + 4 < nk) RRFP_STEP_TAIL(stage3, stage0, stage1, t + 4);
+  if (t + 5 < nk) RRFP_STEP_TAIL(stage0, stage1, stage2, t + 5);
+  if (t + 6 < nk) RRFP_STEP_TAIL(stage1, stage2, stage3, t + 6);
 #undef RRFP_STEP_FULL
 #undef RRFP_STEP_TAIL
-#undef RRFP_ISSUE
+#undef RRFP_ISSUE_A
+#undef RRFP_ISSUE_B
 
   // Epilogue through LDS.  In the accumulator layout a lane owns 4 consecutive columns of one row, so a
   // direct store instruction would touch 32 different rows with 16 bytes each.  Instead every wavefront
