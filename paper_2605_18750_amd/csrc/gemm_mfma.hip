@@ -286,13 +286,42 @@ struct DirectLoader {
       }
     }
   }
-  __device__ __forceinline__ void issue(char* tile, int kt, int wave) const {
-    const int soff = kt * k_stride;
-#pragma unroll
-    for (int i = 0; i < NL; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * NW + wave) * 1024), 16, voff[i], soff, 0, 0);
+  // Load instruction i (of NL) of this wavefront for the k-step whose byte offset is soff.
+  __device__ __forceinline__ void issue_one(char* tile, int i, int soff, int wave) const {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * NW + wave) * 1024), 16, voff[i], soff, 0, 0);
   }
 };
+
+// One quarter (Q = 0..3) of the loads of a pair of consecutive k-steps (e, e+1), e even: step e goes to
+// bufE, step e+1 to bufO.  A wavefront's LA + LB load instructions per step are dealt to the quarters in
+// order (A first); the two instructions that fetch the same rows for the two steps are issued back to
+// back.  For a K-contiguous operand they are the two 64-byte halves of the same 128-byte lines: issued
+// together they reach L2 as one request per line, issued a step apart (as two separate fetches) as two.
+// Steps at or beyond nk get a byte offset past every buffer, which the descriptor turns into a load of
+// zeros without a memory access: the number of loads in flight never depends on the position in K.
+constexpr int OOB_SOFF = 0x7ffffff0;
+template <int Q, int LA, int LB>
+struct QuarterCount { static constexpr int PAIRS = (Q + 1) * (LA + LB) / 4 - Q * (LA + LB) / 4, LOADS = 2 * PAIRS; };
+template <int Q, bool GUARD, typename LoaderA, typename LoaderB>
+__device__ __forceinline__ void issue_quarter(const LoaderA& la, const LoaderB& lb, char* bufE, char* bufO, int e, int nk, int wave) {
+  constexpr int LA = LoaderA::NL, LB = LoaderB::NL;
+  constexpr int P0 = Q * (LA + LB) / 4, P1 = (Q + 1) * (LA + LB) / 4;
+  if constexpr (P1 > P0) {
+    const bool okE = !GUARD || e < nk, okO = !GUARD || e + 1 < nk;
+    const int aE = okE ? e * la.k_stride : OOB_SOFF, aO = okO ? (e + 1) * la.k_stride : OOB_SOFF;
+    const int bE = okE ? e * lb.k_stride : OOB_SOFF, bO = okO ? (e + 1) * lb.k_stride : OOB_SOFF;
+#pragma unroll
+    for (int p = P0; p < P1; ++p) {
+      if (p < LA) {
+        la.issue_one(bufE, p, aE, wave);
+        la.issue_one(bufO, p, aO, wave);
+      } else {
+        lb.issue_one(bufE + DTILE, p - LA, bE, wave);
+        lb.issue_one(bufO + DTILE, p - LA, bO, wave);
+      }
+    }
+  }
+}
 
 template <bool KC>
 __device__ __forceinline__ bf16x8 dread_frag(const char* tile, int row0, int ks, int lane) {
@@ -405,6 +434,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   __shared__ __attribute__((aligned(1024))) char stage1[DSTAGE];
   __shared__ __attribute__((aligned(1024))) char stage2[DSTAGE];
   __shared__ __attribute__((aligned(1024))) char stage3[DSTAGE];
+  __shared__ __attribute__((aligned(1024))) char stage4[DSTAGE];
   int tm, tn;
   tile_coords(tiles_m, tiles_n, tm, tn);
   const int m0 = tm * BMT, n0 = (tn + tn0) * BN;
@@ -426,79 +456,82 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   lb.init(B, ldb, n0, N, K, wave, lane, ACT == ACT_SWIGLU_FWD ? N / 2 : 0);
   const int nk = (K + DBK - 1) / DBK;
 
-  // Software pipeline over 32-deep steps.  Entering step t the fragments of its first k-step are in
-  // registers (fx).  First half: read the second k-step's fragments (fy) under the MFMAs of the
-  // first, and issue the B-operand loads of step t+3 into the stage before this one (free since the
-  // previous barrier).  Middle: wait for this wavefront's loads of step t+1 and for its own LDS reads,
-  // barrier (now stage t%4 is consumed by everybody and stage (t+1)%4 is complete).  Second half: issue
-  // the A-operand loads of step t+4 into stage t%4 and read step t+1's first fragments under the MFMAs
-  // of the second k-step.  Every step issues LPS = LA + LB loads per wavefront, half in each half-step,
-  // spread between the MFMAs; at the wait, the loads issued after those of step t+1 are
-  // A(t+2), B(t+2), A(t+3), B(t+3): "all but 2*LPS outstanding" means step t+1 has landed.
-  constexpr int LA = DirectLoader<A_KC, NW, BMT>::NL, LB = DirectLoader<B_KC, NW>::NL, LPS = LA + LB;
-  constexpr int VM_ALL = 0x0070;                                   // vmcnt(0), lgkmcnt(0)
-  constexpr int VM_2 = 0x0070 | ((2 * LPS) & 15) | (((2 * LPS) >> 4) << 14);   // vmcnt(2*LPS), lgkmcnt(0)
-  constexpr int VM_P = 0x0070 | ((2 * LPS + LA) & 15) | (((2 * LPS + LA) >> 4) << 14);   // vmcnt(2*LPS + LA), lgkmcnt(0)
+  // Software pipeline over 32-deep steps through a ring of five LDS buffers (step t lives in buffer
+  // t % 5).  Loads are issued for PAIRS of steps (e, e+1), e even, in four quarters spread over four
+  // consecutive half-steps, starting right after the barrier in the middle of step e-4 (which frees the
+  // buffer of step e-4 for step e+1; the buffer of step e-5 is free since the barrier before):
+  //   quarter 0 in the second half of step e-4, 1 and 2 in the two halves of step e-3, 3 in the first
+  //   half of step e-2.
+  // Entering step t the fragments of its first k-step are in registers (fx).  First half: read the
+  // second k-step's fragments (fy) under the MFMAs of the first.  Middle: wait for the own LDS reads and,
+  // on odd steps, for this wavefront's loads of the pair (t+1, t+2): everything but quarters 0 and 1 of
+  // the following pair, which were issued later; then barrier: buffer t % 5 is consumed by everybody and
+  // the pair (t+1, t+2) is complete.  On even steps the next step's buffer is complete since the previous
+  // barrier.  Second half: read step t+1's first fragments under the MFMAs of the second k-step.
+  using LoaderA = DirectLoader<A_KC, NW, BMT>;
+  using LoaderB = DirectLoader<B_KC, NW>;
+  constexpr int LA = LoaderA::NL, LB = LoaderB::NL;
+  constexpr int NQ0 = QuarterCount<0, LA, LB>::LOADS, NQ1 = QuarterCount<1, LA, LB>::LOADS;
+  constexpr int NQ2 = QuarterCount<2, LA, LB>::LOADS, NQ3 = QuarterCount<3, LA, LB>::LOADS;
+  constexpr int LGKM_ONLY = 0xC07F;                                // vmcnt(63), lgkmcnt(0)
+  constexpr int VM_01 = 0x0070 | ((NQ0 + NQ1) & 15) | (((NQ0 + NQ1) >> 4) << 14);              // vmcnt(NQ0+NQ1), lgkmcnt(0)
+  constexpr int VM_012 = 0x0070 | ((NQ0 + NQ1 + NQ2) & 15) | (((NQ0 + NQ1 + NQ2) >> 4) << 14);  // vmcnt(NQ0+NQ1+NQ2), lgkmcnt(0)
   constexpr int N_DS = (A_KC ? MI : 2 * MI) + (B_KC ? NB : 2 * NB);
   constexpr int N_MFMA = MI * NB;
-#define RRFP_ISSUE_A(stage, t) la.issue(stage, (t), wave)
-#define RRFP_ISSUE_B(stage, t) lb.issue(stage + DTILE, (t), wave)
-#define RRFP_STEP_FULL(prev, cur, nxt, t)                                                  \
-  do {                                                                                     \
-    RRFP_ISSUE_B(prev, (t) + 3);                                                           \
-    load_frags<A_KC, B_KC, MI, NB>(fy, cur, 1, wm, wn, lane);                              \
-    mfma16<MI, NB>(acc, fx);                                                               \
-    interleave_ds_vm_mfma<N_DS, N_MFMA, LB>();                                             \
-    __builtin_amdgcn_s_waitcnt(VM_2);                                                      \
-    stage_barrier();                                                                       \
-    RRFP_ISSUE_A(cur, (t) + 4);                                                            \
-    load_frags<A_KC, B_KC, MI, NB>(fx, nxt, 0, wm, wn, lane);                              \
-    mfma16<MI, NB>(acc, fy);                                                               \
-    interleave_ds_vm_mfma<N_DS, N_MFMA, LA>();                                             \
-  } while (0)
-#define RRFP_STEP_TAIL(prev, cur, nxt, t)                                                  \
-  do {                                                                                     \
-    if ((t) + 3 < nk) RRFP_ISSUE_B(prev, (t) + 3);                                         \
-    load_frags<A_KC, B_KC, MI, NB>(fy, cur, 1, wm, wn, lane);                              \
-    mfma16<MI, NB>(acc, fx);                                                               \
-    if ((t) + 1 < nk) {                                                                    \
-      if ((t) + 3 < nk) __builtin_amdgcn_s_waitcnt(VM_2);                                  \
-      else __builtin_amdgcn_s_waitcnt(VM_ALL);                                             \
-      stage_barrier();                                                                     \
-      if ((t) + 4 < nk) RRFP_ISSUE_A(cur, (t) + 4);                                        \
-      load_frags<A_KC, B_KC, MI, NB>(fx, nxt, 0, wm, wn, lane);                            \
-    }                                                                                      \
-    mfma16<MI, NB>(acc, fy);                                                               \
-  } while (0)
+  // One step.  PAR = parity of tt; b0..b4 = the buffers of steps tt..tt+4; GUARD = the step may be the
+  // last one or beyond (the tail loop), else every step up to tt+5 exists.
+#define RRFP_STEP(PAR, GUARD, b0, b1, b2, b3, b4, tt)                                                    \
+  if (!GUARD || (tt) < nk) {                                                                             \
+    if constexpr (PAR == 0) issue_quarter<3, GUARD>(la, lb, b2, b3, (tt) + 2, nk, wave);                 \
+    else issue_quarter<1, GUARD>(la, lb, b3, b4, (tt) + 3, nk, wave);                                    \
+    load_frags<A_KC, B_KC, MI, NB>(fy, b0, 1, wm, wn, lane);                                             \
+    mfma16<MI, NB>(acc, fx);                                                                             \
+    interleave_ds_vm_mfma<N_DS, N_MFMA, (PAR == 0 ? NQ3 : NQ1)>();                                       \
+    if (!GUARD || (tt) + 1 < nk) {                                                                       \
+      __builtin_amdgcn_s_waitcnt(PAR == 0 ? LGKM_ONLY : VM_01);                                          \
+      stage_barrier();                                                                                   \
+      if constexpr (PAR == 0) issue_quarter<0, GUARD>(la, lb, b4, b0, (tt) + 4, nk, wave);               \
+      else issue_quarter<2, GUARD>(la, lb, b3, b4, (tt) + 3, nk, wave);                                  \
+      load_frags<A_KC, B_KC, MI, NB>(fx, b1, 0, wm, wn, lane);                                           \
+    }                                                                                                    \
+    mfma16<MI, NB>(acc, fy);                                                                             \
+    if (!GUARD) interleave_ds_vm_mfma<N_DS, N_MFMA, (PAR == 0 ? NQ0 : NQ2)>();                           \
+  }
+#define RRFP_TEN_STEPS(GUARD, t)                                        \
+  RRFP_STEP(0, GUARD, stage0, stage1, stage2, stage3, stage4, (t));     \
+  RRFP_STEP(1, GUARD, stage1, stage2, stage3, stage4, stage0, (t) + 1); \
+  RRFP_STEP(0, GUARD, stage2, stage3, stage4, stage0, stage1, (t) + 2); \
+  RRFP_STEP(1, GUARD, stage3, stage4, stage0, stage1, stage2, (t) + 3); \
+  RRFP_STEP(0, GUARD, stage4, stage0, stage1, stage2, stage3, (t) + 4); \
+  RRFP_STEP(1, GUARD, stage0, stage1, stage2, stage3, stage4, (t) + 5); \
+  RRFP_STEP(0, GUARD, stage1, stage2, stage3, stage4, stage0, (t) + 6); \
+  RRFP_STEP(1, GUARD, stage2, stage3, stage4, stage0, stage1, (t) + 7); \
+  RRFP_STEP(0, GUARD, stage3, stage4, stage0, stage1, stage2, (t) + 8); \
+  RRFP_STEP(1, GUARD, stage4, stage0, stage1, stage2, stage3, (t) + 9)
 
   Frags<MI, NB> fx, fy;
-  RRFP_ISSUE_A(stage0, 0); RRFP_ISSUE_B(stage0, 0);
-  if (nk > 1) { RRFP_ISSUE_A(stage1, 1); RRFP_ISSUE_B(stage1, 1); }
-  if (nk > 2) { RRFP_ISSUE_A(stage2, 2); RRFP_ISSUE_B(stage2, 2); }
-  if (nk > 3) RRFP_ISSUE_A(stage3, 3);
-  if (nk > 3) __builtin_amdgcn_s_waitcnt(VM_P); else __builtin_amdgcn_s_waitcnt(VM_ALL);
+  // Prologue: the pair (0, 1) in full and quarters 0..2 of the pair (2, 3); step 0's first half issues quarter 3.
+  issue_quarter<0, true>(la, lb, stage0, stage1, 0, nk, wave);
+  issue_quarter<1, true>(la, lb, stage0, stage1, 0, nk, wave);
+  issue_quarter<2, true>(la, lb, stage0, stage1, 0, nk, wave);
+  issue_quarter<3, true>(la, lb, stage0, stage1, 0, nk, wave);
+  issue_quarter<0, true>(la, lb, stage2, stage3, 2, nk, wave);
+  issue_quarter<1, true>(la, lb, stage2, stage3, 2, nk, wave);
+  issue_quarter<2, true>(la, lb, stage2, stage3, 2, nk, wave);
+  __builtin_amdgcn_s_waitcnt(VM_012);
   stage_barrier();
   load_frags<A_KC, B_KC, MI, NB>(fx, stage0, 0, wm, wn, lane);
 
   int t = 0;
-  for (; t + 7 < nk; t += 4) {      // every step of this loop has a step t+4 to prefetch
-    RRFP_STEP_FULL(stage3, stage0, stage1, t);
-    RRFP_STEP_FULL(stage0, stage1, stage2, t + 1);
-    RRFP_STEP_FULL(stage1, stage2, stage3, t + 2);
-    RRFP_STEP_FULL(stage2, stage3, stage0, t + 3);
+  for (; t + 13 < nk; t += 10) {    // every load these ten steps issue is for a step below nk
+    RRFP_TEN_STEPS(false, t);
   }
-  // at most 7 steps remain
-  if (t < nk) RRFP_STEP_TAIL(stage3, stage0, stage1, t);
-  if (t + 1 < nk) RRFP_STEP_TAIL(stage0, stage1, stage2, t + 1);
-  if (t + 2 < nk) RRFP_STEP_TAIL(stage1, stage2, stage3, t + 2);
-  if (t + 3 < nk) RRFP_STEP_TAIL(stage2, stage3, stage0, t + 3);
-  if (t + 4 < nk) RRFP_STEP_TAIL(stage3, stage0, stage1, t + 4);
-  if (t + 5 < nk) RRFP_STEP_TAIL(stage0, stage1, stage2, t + 5);
-  if (t + 6 < nk) RRFP_STEP_TAIL(stage1, stage2, stage3, t + 6);
-#undef RRFP_STEP_FULL
-#undef RRFP_STEP_TAIL
-#undef RRFP_ISSUE_A
-#undef RRFP_ISSUE_B
+  for (; t < nk; t += 10) {
+    RRFP_TEN_STEPS(true, t);
+  }
+#undef RRFP_TEN_STEPS
+#undef RRFP_STEP
+  __builtin_amdgcn_s_waitcnt(0x0070);   // the zero loads of the steps past the end have landed too
 
   // Epilogue through LDS.  In the accumulator layout a lane owns 4 consecutive columns of one row, so a
   // direct store instruction would touch 32 different rows with 16 bytes each.  Instead every wavefront
@@ -636,7 +669,7 @@ RRFP_INST(true, true, bf16_t, false, ACT_SWIGLU_BWD) RRFP_INST(true, true, bf16_
 inline bool direct_ok(const GemmArgs& g) {
   const bool a_kc = !g.transA, b_kc = g.transB;
   if ((a_kc || b_kc) && (g.K % DBK)) return false;
-  const size_t lim = (size_t)1 << 31;
+  const size_t lim = (size_t)OOB_SOFF;     // every operand byte offset stays below the offset used for "no such step"
   const size_t a_bytes = (size_t)(a_kc ? g.M + BM : g.K + BK) * g.lda * 2;
   const size_t b_bytes = (size_t)(b_kc ? g.N + BN : g.K + BK) * g.ldb * 2;
   return a_bytes < lim && b_bytes < lim;
