@@ -49,6 +49,7 @@ constexpr int SMEM_BYTES = 2 * STAGE_BYTES;       // two stages
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
 
 // Byte offset of the 16-byte chunk (row, c) of a K-contiguous tile [256][64].
@@ -235,11 +236,12 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __res
 // ------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
-// Wavefronts per workgroup of the direct-load kernel, by operand orientation (measured on the
-// language-stage shapes): two per SIMD when at least one operand is K-contiguous, one per SIMD when
-// both are K-strided (the transpose reads double the LDS instruction count).
-constexpr int dl_wm(bool a_kc, bool b_kc) { return (a_kc || b_kc) ? RRFP_WM_KC : 2; }
-constexpr int dl_wn(bool a_kc, bool b_kc) { return (a_kc || b_kc) ? RRFP_WN_KC : 2; }
+// Wavefronts per workgroup of the direct-load kernel: 2 x 4 (128 x 64 of C each, two per SIMD so that one
+// wavefront's waits hide behind the other's MFMAs) for every operand orientation.  With 2 x 2 (128 x 128
+// each, 256 accumulator registers in 64 four-register tuples) the register allocator shuffles
+// accumulators between MFMAs; measured slower on every shape.
+constexpr int dl_wm(bool, bool) { return RRFP_WM_KC; }
+constexpr int dl_wn(bool, bool) { return RRFP_WN_KC; }
 constexpr int DBK = 32;                              // k per stage
 constexpr int DTILE = 256 * DBK * 2;                 // bytes of one operand tile (16 KB)
 constexpr int DSTAGE = 2 * DTILE;                    // A + B (32 KB)
@@ -249,8 +251,13 @@ constexpr int DSTAGE = 2 * DTILE;                    // A + B (32 KB)
 // rows at the same logical chunk, and (row & 3, (row >> 2) & 3) sends them to 16 distinct 16-byte slots.
 __device__ __forceinline__ int dkc_off(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
 
-// NW = wavefronts per workgroup: 4 (2x2, 128x128 each, one per SIMD) or 8 (2x4, 128x64 each, two per
-// SIMD so that one wavefront's waits hide behind the other's MFMAs).
+// K-strided tile [32 k][256 rows]: 512-byte rows of 32 chunks; chunk c of row k sits at c ^ dks_swz(k).
+// A fragment read (below) touches, per 32 lanes, 8 k-rows (k & 3 and bit 3 of k vary) at the same pair of
+// chunks; the swizzle sends them to 8 distinct 32-byte bank groups.
+__device__ __forceinline__ int dks_swz(int k) { return ((k & 3) | (((k >> 3) & 1) << 2)) << 1; }
+__device__ __forceinline__ int dks_off(int k, int c) { return k * 512 + ((c ^ dks_swz(k)) << 4); }
+
+// NW = wavefronts per workgroup.
 template <bool KC, int NW, int ROWS = 256>
 struct DirectLoader {
   static_assert(KC || ROWS == 256, "a K-strided tile is always 256 wide");
@@ -275,8 +282,7 @@ struct DirectLoader {
         voff[i] = (outer0 + row < outer_n) ? ((outer0 + row) * ld + c * 8) * 2 : (int)0x80000000;
       } else {
         const int k = blk * 2 + (lane >> 5), cp = lane & 31;
-        const int f = (k & 3) | (((k >> 3) & 1) << 2);
-        const int c = ((((cp >> 2) ^ f) << 2) | (cp & 3));
+        const int c = cp ^ dks_swz(k);
         int col = outer0 + c * 8;
         if (pair_f > 0) {
           const int nl = c * 8;                                  // column inside the tile
@@ -323,14 +329,39 @@ __device__ __forceinline__ void issue_quarter(const LoaderA& la, const LoaderB& 
   }
 }
 
+// Fragments of v_mfma_f32_16x16x32_bf16 for a 16-row block and the 32 k of one stage: lane l gets row
+// (l & 15) of the block, k = (l >> 4) * 8 + 0..7.
+//   K-contiguous: one ds_read_b128 at dkc_off(row, l >> 4); blocks are 1024 bytes apart.
+//   K-strided: two ds_read_b64_tr_b16 (k-rows kb and kb + 4, same swizzle); in each, the 16 lanes of a
+//     group address a 4 (k) x 16 (rows) block (lane -> k-row (l & 15) >> 2, rows 4 * (l & 3) .. + 3) and
+//     receive 4 consecutive k of row l & 15.  Block i of the wavefront sits at chunk (cw | 2i | cl),
+//     cw = 16-aligned chunk of the wavefront's first row, cl = (l & 3) >> 1, and the swizzle XORs bits
+//     1..3 of the chunk, so the byte offset of block i is lane_part ^ (i << 5): one XOR per block.
+typedef __attribute__((address_space(3))) const char* lds_char_ptr;
+
+// Per-lane part of the fragment address of this wavefront's blocks starting at row w0.
 template <bool KC>
-__device__ __forceinline__ bf16x8 dread_frag(const char* tile, int row0, int ks, int lane) {
-  if (KC) {
-    const int row = row0 + (lane & 31);
-    const uint4 v = *reinterpret_cast<const uint4*>(tile + dkc_off(row, ks * 2 + (lane >> 5)));
-    return __builtin_bit_cast(bf16x8, v);
-  } else {
-    return read_frag<false>(tile, row0, ks, lane);   // [32 k][256 rows]: same layout as the 64-deep tile
+__device__ __forceinline__ int frag_lane_offset(int w0, int lane) {
+  if (KC) return dkc_off(w0 + (lane & 15), lane >> 4);
+  const int kb = (lane >> 4) * 8 + ((lane & 15) >> 2);
+  return kb * 512 + (lane & 1) * 8 + ((((w0 >> 3) | ((lane & 3) >> 1)) ^ dks_swz(kb)) << 4);
+}
+
+template <bool KC, int N>
+__device__ __forceinline__ void load_blocks(bf16x8 (&f)[N], const char* tile, int lane_off) {
+  if (!KC) asm volatile("" : "+v"(lane_off));   // keeps the per-block addresses from being hoisted out of the k loop (register pressure)
+  const lds_char_ptr t = (lds_char_ptr)tile;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (KC) {
+      f[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) uint4*>(t + lane_off + i * 1024));
+    } else {
+      const int o = lane_off ^ (i << 5);
+      union { short4v h[2]; bf16x8 v; } u;
+      u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(t + o));
+      u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(t + o + 2048));
+      f[i] = u.v;
+    }
   }
 }
 
@@ -347,25 +378,19 @@ __device__ __forceinline__ void stage_barrier() {
   asm volatile("" ::: "memory");
 }
 
-// Fragments of one 16-wide MFMA k-step: MI row blocks of A and NB column blocks of B of this wavefront.
-template <int MI, int NB>
-struct Frags { bf16x8 a[MI], b[NB]; };
+// Fragments of one 32-deep step for v_mfma_f32_16x16x32_bf16: the wavefront's 16-row blocks of A in two
+// halves (lo, hi: MA blocks each) and its NF 16-column blocks of B, the latter double-buffered by step parity.
+template <int MA, int NF>
+struct Frags { bf16x8 alo[MA], ahi[MA], b[2][NF]; };
 
-template <bool A_KC, bool B_KC, int MI, int NB>
-__device__ __forceinline__ void load_frags(Frags<MI, NB>& f, const char* sa, int ks, int wm, int wn, int lane) {
-  const char* sb = sa + DTILE;
+// acc[i0 + i][j] += A block i x B block j.  The B fragment is the first operand: a lane's four accumulator
+// values are four consecutive columns of one row of C.
+template <int MA, int NF, int MI16>
+__device__ __forceinline__ void mfma_blocks(floatx4 (&acc)[MI16][NF], const bf16x8 (&a)[MA], const bf16x8 (&b)[NF], int i0) {
 #pragma unroll
-  for (int i = 0; i < MI; ++i) f.a[i] = dread_frag<A_KC>(sa, wm + i * 32, ks, lane);
+  for (int i = 0; i < MA; ++i)
 #pragma unroll
-  for (int j = 0; j < NB; ++j) f.b[j] = dread_frag<B_KC>(sb, wn + j * 32, ks, lane);
-}
-
-template <int MI, int NB>
-__device__ __forceinline__ void mfma16(floatx16 (&acc)[MI][NB], const Frags<MI, NB>& f) {
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+    for (int j = 0; j < NF; ++j) acc[i0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i0 + i][j], 0, 0, 0);
 }
 
 // Ask the scheduler to interleave N_DS LDS reads, N_VM global->LDS loads and N_MFMA MFMAs in groups, reads
@@ -375,7 +400,10 @@ __device__ __forceinline__ void mfma16(floatx16 (&acc)[MI][NB], const Frags<MI, 
 template <int N_DS, int N_MFMA, int N_VM, int G, int Q>
 __device__ __forceinline__ void interleave_group() {
   if constexpr (Q < G) {
-    constexpr int DS = (Q + 1) * N_DS / G - Q * N_DS / G, VM = (Q + 1) * N_VM / G - Q * N_VM / G;
+    // LDS reads go into the first G-1 groups (the last MFMAs of the half-step cover the latency of the last reads)
+    constexpr int DSG = G - 1;
+    constexpr int DS = Q < DSG ? ((Q + 1) * N_DS + DSG - 1) / DSG - (Q * N_DS + DSG - 1) / DSG : 0;
+    constexpr int VM = (Q + 1) * N_VM / G - Q * N_VM / G;
     constexpr int MF = (Q + 1) * N_MFMA / G - Q * N_MFMA / G;
     if constexpr (DS > 0) __builtin_amdgcn_sched_group_barrier(0x100, DS, 0);
     if constexpr (VM > 0) __builtin_amdgcn_sched_group_barrier(0x020, VM, 0);
@@ -442,13 +470,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = (wave / WN) * WAVE_M, wn = (wave % WN) * WAVE_N;
 
-  floatx16 acc[MI][NB];
+  constexpr int MI16 = 2 * MI, NF = 2 * NB, MA = MI;   // 16-row / 16-column blocks per wavefront; A blocks per half
+  floatx4 acc[MI16][NF];
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
+  for (int i = 0; i < MI16; ++i)
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
+    for (int j = 0; j < NF; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
   DirectLoader<A_KC, NW, BMT> la;
   DirectLoader<B_KC, NW> lb;
@@ -462,12 +491,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   // buffer of step e-4 for step e+1; the buffer of step e-5 is free since the barrier before):
   //   quarter 0 in the second half of step e-4, 1 and 2 in the two halves of step e-3, 3 in the first
   //   half of step e-2.
-  // Entering step t the fragments of its first k-step are in registers (fx).  First half: read the
-  // second k-step's fragments (fy) under the MFMAs of the first.  Middle: wait for the own LDS reads and,
+  // Entering step t the fragments of the first half of the wavefront's A blocks and of all its B blocks
+  // are in registers.  First half: read the second half of the A blocks under the MFMAs of the first
+  // (after this, nobody reads buffer t % 5 any more).  Middle: wait for the own LDS reads and,
   // on odd steps, for this wavefront's loads of the pair (t+1, t+2): everything but quarters 0 and 1 of
   // the following pair, which were issued later; then barrier: buffer t % 5 is consumed by everybody and
   // the pair (t+1, t+2) is complete.  On even steps the next step's buffer is complete since the previous
-  // barrier.  Second half: read step t+1's first fragments under the MFMAs of the second k-step.
+  // barrier.  Second half: read step t+1's first A half and its B blocks (into the other B register
+  // set) under the MFMAs of the second A half.
   using LoaderA = DirectLoader<A_KC, NW, BMT>;
   using LoaderB = DirectLoader<B_KC, NW>;
   constexpr int LA = LoaderA::NL, LB = LoaderB::NL;
@@ -476,26 +507,30 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   constexpr int LGKM_ONLY = 0xC07F;                                // vmcnt(63), lgkmcnt(0)
   constexpr int VM_01 = 0x0070 | ((NQ0 + NQ1) & 15) | (((NQ0 + NQ1) >> 4) << 14);              // vmcnt(NQ0+NQ1), lgkmcnt(0)
   constexpr int VM_012 = 0x0070 | ((NQ0 + NQ1 + NQ2) & 15) | (((NQ0 + NQ1 + NQ2) >> 4) << 14);  // vmcnt(NQ0+NQ1+NQ2), lgkmcnt(0)
-  constexpr int N_DS = (A_KC ? MI : 2 * MI) + (B_KC ? NB : 2 * NB);
-  constexpr int N_MFMA = MI * NB;
+  constexpr int DS_A = A_KC ? MA : 2 * MA, DS_B = B_KC ? NF : 2 * NF;   // LDS read instructions of half the A blocks / all B blocks
+  constexpr int N_MFMA = MA * NF;                                        // MFMAs of a half-step
   // One step.  PAR = parity of tt; b0..b4 = the buffers of steps tt..tt+4; GUARD = the step may be the
   // last one or beyond (the tail loop), else every step up to tt+5 exists.
 #define RRFP_STEP(PAR, GUARD, b0, b1, b2, b3, b4, tt)                                                    \
   if (!GUARD || (tt) < nk) {                                                                             \
     if constexpr (PAR == 0) issue_quarter<3, GUARD>(la, lb, b2, b3, (tt) + 2, nk, wave);                 \
     else issue_quarter<1, GUARD>(la, lb, b3, b4, (tt) + 3, nk, wave);                                    \
-    load_frags<A_KC, B_KC, MI, NB>(fy, b0, 1, wm, wn, lane);                                             \
-    mfma16<MI, NB>(acc, fx);                                                                             \
-    interleave_ds_vm_mfma<N_DS, N_MFMA, (PAR == 0 ? NQ3 : NQ1)>();                                       \
+    load_blocks<A_KC, MA>(fr.ahi, b0, off_ahi);                                               \
+    mfma_blocks<MA, NF, MI16>(acc, fr.alo, fr.b[PAR], 0);                                                \
+    interleave_ds_vm_mfma<DS_A, N_MFMA, (PAR == 0 ? NQ3 : NQ1)>();                                       \
     if (!GUARD || (tt) + 1 < nk) {                                                                       \
       __builtin_amdgcn_s_waitcnt(PAR == 0 ? LGKM_ONLY : VM_01);                                          \
       stage_barrier();                                                                                   \
       if constexpr (PAR == 0) issue_quarter<0, GUARD>(la, lb, b4, b0, (tt) + 4, nk, wave);               \
       else issue_quarter<2, GUARD>(la, lb, b3, b4, (tt) + 3, nk, wave);                                  \
-      load_frags<A_KC, B_KC, MI, NB>(fx, b1, 0, wm, wn, lane);                                           \
+      load_blocks<A_KC, MA>(fr.alo, b1, off_alo);                                                       \
+      load_blocks<B_KC, NF>(fr.b[1 - PAR], b1 + DTILE, off_b);                                        \
     }                                                                                                    \
-    mfma16<MI, NB>(acc, fy);                                                                             \
-    if (!GUARD) interleave_ds_vm_mfma<N_DS, N_MFMA, (PAR == 0 ? NQ0 : NQ2)>();                           \
+    mfma_blocks<MA, NF, MI16>(acc, fr.ahi, fr.b[PAR], MA);                                               \
+    if (!GUARD) {                                                                                        \
+      interleave_ds_vm_mfma<DS_A + DS_B, N_MFMA, (PAR == 0 ? NQ0 : NQ2)>();                              \
+      __builtin_amdgcn_sched_barrier(0);   /* half-steps are scheduled one by one */                     \
+    }                                                                                                    \
   }
 #define RRFP_TEN_STEPS(GUARD, t)                                        \
   RRFP_STEP(0, GUARD, stage0, stage1, stage2, stage3, stage4, (t));     \
@@ -509,7 +544,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   RRFP_STEP(0, GUARD, stage3, stage4, stage0, stage1, stage2, (t) + 8); \
   RRFP_STEP(1, GUARD, stage4, stage0, stage1, stage2, stage3, (t) + 9)
 
-  Frags<MI, NB> fx, fy;
+  Frags<MA, NF> fr;
+  const int off_alo = frag_lane_offset<A_KC>(wm, lane), off_ahi = frag_lane_offset<A_KC>(wm + MA * 16, lane);
+  const int off_b = frag_lane_offset<B_KC>(wn, lane);
   // Prologue: the pair (0, 1) in full and quarters 0..2 of the pair (2, 3); step 0's first half issues quarter 3.
   issue_quarter<0, true>(la, lb, stage0, stage1, 0, nk, wave);
   issue_quarter<1, true>(la, lb, stage0, stage1, 0, nk, wave);
@@ -520,7 +557,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   issue_quarter<2, true>(la, lb, stage2, stage3, 2, nk, wave);
   __builtin_amdgcn_s_waitcnt(VM_012);
   stage_barrier();
-  load_frags<A_KC, B_KC, MI, NB>(fx, stage0, 0, wm, wn, lane);
+  load_blocks<A_KC, MA>(fr.alo, stage0, off_alo);
+  load_blocks<B_KC, NF>(fr.b[0], stage0 + DTILE, off_b);
 
   int t = 0;
   for (; t + 13 < nk; t += 10) {    // every load these ten steps issue is for a step below nk
@@ -549,15 +587,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   }
   constexpr int NBC = NB * 32;                      // columns of the wavefront's tile
   constexpr int PITCH = NBC + 4;                    // floats; 16-byte skew per row
-  const int li = lane & 31, hh = lane >> 5;
+  const int li = lane & 15, hq = lane >> 4;
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<float4*>(scratch + li * PITCH + j * 32 + g * 8 + hh * 4) =
-            make_float4(acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
+      for (int j = 0; j < NF; ++j)
+        *reinterpret_cast<float4*>(scratch + (h * 16 + li) * PITCH + j * 16 + hq * 4) =
+            make_float4(acc[2 * i + h][j][0], acc[2 * i + h][j][1], acc[2 * i + h][j][2], acc[2 * i + h][j][3]);
     if (ACT == ACT_SWIGLU_FWD) {
       // scratch columns 0..31 = gate, 32..63 = up of features f0 .. f0+31; 4 lanes per row, 16 rows per sweep
       const int F = N >> 1;
