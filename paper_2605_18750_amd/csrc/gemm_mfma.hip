@@ -588,6 +588,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   constexpr int NBC = NB * 32;                      // columns of the wavefront's tile
   constexpr int PITCH = NBC + 4;                    // floats; 16-byte skew per row
   const int li = lane & 15, hq = lane >> 4;
+  // The epilogue's global operand loads (residual, activation operand) are issued for a whole 32-row
+  // chunk before the chunk is staged, from addresses clamped into the matrix, so that their latency is
+  // paid once per chunk and not once per sweep; only the stores are predicated.
+  constexpr int LPR = NBC / 8;                      // lanes per row of the read-back
+  constexpr int RPS = 64 / LPR;                     // rows per sweep
+  constexpr int SW = 32 / RPS;                      // sweeps per chunk
+  const int c0 = (lane % LPR) * 8, r0 = lane / LPR;
+  const int n_col = n0 + wn + c0;                   // first of this lane's 8 columns (same for every sweep)
+  const int n_ld = min(n_col, N - 8);
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (ACT != ACT_SWIGLU_FWD && bias) load_vec<bf16_t>(bias + n_ld, bv);
+  struct Pre { float rv[8]; uint4 e0, e1; };
+  auto prefetch = [&](Pre (&pre)[SW], int i) {
+#pragma unroll
+    for (int rr = 0; rr < SW; ++rr) {
+      const int m_ld = min(m0 + wm + i * 32 + rr * RPS + r0, M - 1);
+      if (HAS_R) load_f32x8(R + (size_t)m_ld * ldr + n_ld, pre[rr].rv);
+      if (ACT == ACT_GELU_BWD || ACT == ACT_SWIGLU_BWD) pre[rr].e0 = *reinterpret_cast<const uint4*>(E + (size_t)m_ld * lde + n_ld);
+      if (ACT == ACT_SWIGLU_BWD) pre[rr].e1 = *reinterpret_cast<const uint4*>(E + (size_t)m_ld * lde + N + n_ld);
+    }
+  };
+  Pre pre[2][SW];
+  if (ACT != ACT_SWIGLU_FWD) prefetch(pre[0], 0);
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -600,17 +623,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
       // scratch columns 0..31 = gate, 32..63 = up of features f0 .. f0+31; 4 lanes per row, 16 rows per sweep
       const int F = N >> 1;
       const int f0 = (n0 >> 1) + (wn >> 6) * 32;
+      const int fc = (lane & 3) * 8;
+      float bg[8], bu[8];
+      if (bias) {
+        load_vec<bf16_t>(bias + f0 + fc, bg);
+        load_vec<bf16_t>(bias + F + f0 + fc, bu);
+      }
 #pragma unroll
       for (int rr = 0; rr < 2; ++rr) {
-        const int row = rr * 16 + (lane >> 2), fc = (lane & 3) * 8;
+        const int row = rr * 16 + (lane >> 2);
         const int m = m0 + wm + i * 32 + row;
         float gt[8], up[8], mm[8];
         load_f32x8(scratch + row * PITCH + fc, gt);
         load_f32x8(scratch + row * PITCH + 32 + fc, up);
         if (bias) {
-          float bg[8], bu[8];
-          load_vec<bf16_t>(bias + f0 + fc, bg);
-          load_vec<bf16_t>(bias + F + f0 + fc, bu);
 #pragma unroll
           for (int e = 0; e < 8; ++e) { gt[e] += bg[e]; up[e] += bu[e]; }
         }
@@ -624,57 +650,62 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
         }
       }
     } else {
-      constexpr int LPR = NBC / 8;                  // lanes per row
-      constexpr int RPS = 64 / LPR;                 // rows per sweep
+      if (i + 1 < MI) prefetch(pre[(i + 1) & 1], i + 1);
+      const Pre (&cur)[SW] = pre[i & 1];
 #pragma unroll
-      for (int rr = 0; rr < 32 / RPS; ++rr) {
-        const int row = rr * RPS + lane / LPR, c0 = (lane % LPR) * 8;
-        const int m = m0 + wm + i * 32 + row, n = n0 + wn + c0;
+      for (int rr = 0; rr < SW; ++rr) {
+        const int row = rr * RPS + r0;
+        const int m = m0 + wm + i * 32 + row, n = n_col;
         float v[8];
         load_f32x8(scratch + row * PITCH + c0, v);
-        if (m >= M || n >= N) continue;            // N is a multiple of 8: the eight columns are in or out together
+        const bool ok = m < M && n < N;             // N is a multiple of 8: the eight columns are in or out together
         if (bias) {
-          float bv[8];
-          load_vec<bf16_t>(bias + n, bv);
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] += bv[e];
         }
         if (HAS_R) {
-          float rv[8];
-          load_f32x8(R + (size_t)m * ldr + n, rv);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] += rv[e];
+          for (int e = 0; e < 8; ++e) v[e] += cur[rr].rv[e];
         }
         if (ACT == ACT_GELU_FWD) {
           float mm[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) mm[e] = gelu_f(v[e]);
-          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
-          store_vec<bf16_t>(E + (size_t)m * lde + n, mm);
+          if (ok) {
+            store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
+            store_vec<bf16_t>(E + (size_t)m * lde + n, mm);
+          }
         } else if (ACT == ACT_GELU_BWD) {
           float u[8];
-          load_vec<bf16_t>(E + (size_t)m * lde + n, u);
+          unpack4(make_uint2(cur[rr].e0.x, cur[rr].e0.y), u);
+          unpack4(make_uint2(cur[rr].e0.z, cur[rr].e0.w), u + 4);
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e]);
-          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
+          if (ok) store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
         } else if (ACT == ACT_SWIGLU_BWD) {
           float gt[8], up[8], dg[8], du[8];
-          load_vec<bf16_t>(E + (size_t)m * lde + n, gt);
-          load_vec<bf16_t>(E + (size_t)m * lde + N + n, up);
+          unpack4(make_uint2(cur[rr].e0.x, cur[rr].e0.y), gt);
+          unpack4(make_uint2(cur[rr].e0.z, cur[rr].e0.w), gt + 4);
+          unpack4(make_uint2(cur[rr].e1.x, cur[rr].e1.y), up);
+          unpack4(make_uint2(cur[rr].e1.z, cur[rr].e1.w), up + 4);
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const float sg = sigmoid_f(gt[e]);
             dg[e] = v[e] * up[e] * sg * (1.0f + gt[e] * (1.0f - sg));
             du[e] = v[e] * gt[e] * sg;
           }
-          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, dg);
-          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + N + n, du);
+          if (ok) {
+            store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, dg);
+            store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + N + n, du);
+          }
         } else if (sizeof(TO) == 4) {
-          float* crow = (float*)C + (size_t)m * ldc + n;
-          *reinterpret_cast<float4*>(crow) = make_float4(v[0], v[1], v[2], v[3]);
-          *reinterpret_cast<float4*>(crow + 4) = make_float4(v[4], v[5], v[6], v[7]);
+          if (ok) {
+            float* crow = (float*)C + (size_t)m * ldc + n;
+            *reinterpret_cast<float4*>(crow) = make_float4(v[0], v[1], v[2], v[3]);
+            *reinterpret_cast<float4*>(crow + 4) = make_float4(v[4], v[5], v[6], v[7]);
+          }
         } else {
-          store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
+          if (ok) store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
         }
       }
     }
