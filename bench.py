@@ -76,17 +76,36 @@ def cpu_baseline(shape, T_sample: int):
                       f"{dt:.1f} s wall"}
 
 
-def gemm_roofline(shape, T, Bw, s, gen, n_launch=20):
-    """The bf16 MFMA GEMM [T, hidden] x [hidden, N_up] alone: HIP events on the launch stream."""
+def gemm_roofline(shape, T, Bw, s, gen, n_launch=20, form="nn"):
+    """The bf16 MFMA GEMM of the up projection alone, HIP events on the launch stream.  form "nn": the
+    forward [T, hidden] x [hidden, N_up] (the roofline kernel of the step bench); "nt": its input
+    gradient [T, N_up] x [hidden, N_up]^T -> fp32 [T, hidden]; "tn": its weight gradient
+    [T, hidden]^T x [T, N_up] -> fp32 [hidden, N_up] (for counter runs of the other operand orientations)."""
     import torch
     import paper_2605_18750_amd as R
     N_up = (2 if shape.mlp_kind == "swiglu" else 1) * shape.ffn
-    A = torch.empty((T, shape.hidden), dtype=torch.bfloat16, device=Bw.device).normal_(0.0, 1.0, generator=gen)
-    Cc = torch.empty((T, N_up), dtype=torch.bfloat16, device=Bw.device)
+    H = shape.hidden
+    A = torch.empty((T, H), dtype=torch.bfloat16, device=Bw.device).normal_(0.0, 1.0, generator=gen)
+    if form == "nn":
+        Cc = torch.empty((T, N_up), dtype=torch.bfloat16, device=Bw.device)
+        dims = (T, N_up, H)
 
-    def launch():
-        R.rrfp_gemm(A, Bw, Cc, None, T, N_up, shape.hidden, shape.hidden, N_up, N_up, N_up, 0, 0, 1, 1,
-                    R.RRFP_GEMM_MFMA, s)
+        def launch():
+            R.rrfp_gemm(A, Bw, Cc, None, T, N_up, H, H, N_up, N_up, N_up, 0, 0, 1, 1, R.RRFP_GEMM_MFMA, s)
+    else:
+        G = torch.empty((T, N_up), dtype=torch.bfloat16, device=Bw.device).normal_(0.0, 1.0, generator=gen)
+        if form == "nt":
+            Cc = torch.empty((T, H), dtype=torch.float32, device=Bw.device)
+            dims = (T, H, N_up)
+
+            def launch():
+                R.rrfp_gemm(G, Bw, Cc, None, T, H, N_up, N_up, N_up, H, H, 0, 1, 1, 0, R.RRFP_GEMM_MFMA, s)
+        else:
+            Cc = torch.empty((H, N_up), dtype=torch.float32, device=Bw.device)
+            dims = (H, N_up, T)
+
+            def launch():
+                R.rrfp_gemm(A, G, Cc, None, H, N_up, T, H, N_up, N_up, N_up, 1, 0, 1, 0, R.RRFP_GEMM_MFMA, s)
     with torch.cuda.stream(s):
         for _ in range(3):
             launch()
@@ -97,16 +116,17 @@ def gemm_roofline(shape, T, Bw, s, gen, n_launch=20):
         g1.record(s)
     torch.cuda.synchronize()
     g_ms = g0.elapsed_time(g1) / n_launch
-    g_fl = 2.0 * T * N_up * shape.hidden
+    g_fl = 2.0 * dims[0] * dims[1] * dims[2]
     ach = g_fl / (g_ms * 1e-3) / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemm_mfma_traffic.json")
-    if os.path.exists(tpath):
+    if form == "nn" and os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get(f"{T}x{N_up}x{shape.hidden}")
         except Exception:
             traffic = None
-    return {"bound": "mfma", "kernel": f"gemm_mfma_dl_kernel NN {T}x{N_up}x{shape.hidden} bf16 (one call: 256-row tiles + 128-row tail launch)", "achieved": round(ach, 1),
+    label = "(one call: 256-row tiles + 128-row tail launch)" if form == "nn" else "(fp32 out)"
+    return {"bound": "mfma", "kernel": f"gemm_mfma_dl_kernel {form.upper()} {dims[0]}x{dims[1]}x{dims[2]} bf16 {label}", "achieved": round(ach, 1),
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
             "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic}
 
@@ -170,6 +190,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="language")
     ap.add_argument("--streams", type=int, default=1, help="streams the tasks are dealt to (B/F/W order)")
+    ap.add_argument("--gemm-form", default="nn", choices=["nn", "nt", "tn"],
+                    help="with --only gemm: operand orientation (forward, input-gradient or weight-gradient form of the up projection)")
     ap.add_argument("--only", default="step", choices=["step", "gemm", "copy", "pipeline"],
                     help="gemm: launch only the roofline GEMM (for counter runs); copy: a 2 GiB device copy, the "
                          "calibration of the FETCH_SIZE / WRITE_SIZE counters; pipeline: measure the per-microbatch "
@@ -219,7 +241,8 @@ def main():
         T = max(int(SI.default_cu_seqlens(shape, j)[-1]) for j in range(shape.n_microbatches))
         N_up = (2 if shape.mlp_kind == "swiglu" else 1) * shape.ffn
         Bw = torch.empty((shape.hidden, N_up), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, shape.w_std, generator=gen)
-        print(json.dumps({"only": "gemm", "roofline": gemm_roofline(shape, T, Bw, torch.cuda.Stream(), gen, n_launch=args.steps)}))
+        print(json.dumps({"only": "gemm", "roofline": gemm_roofline(shape, T, Bw, torch.cuda.Stream(), gen, n_launch=args.steps,
+                                                                    form=args.gemm_form)}))
         return
     M = shape.n_microbatches
     cus = [SI.default_cu_seqlens(shape, j) for j in range(M)]

@@ -1,25 +1,25 @@
 // bf16 MFMA GEMM for gfx950: C[M,N] = A(m,k) B(k,n) (+R), fp32 accumulation, bf16 or fp32 out.
 //
-// Two kernels share the tile geometry (a workgroup owns a 256-wide tile of C, v_mfma_f32_32x32x16_bf16
-// accumulators) and the LDS layouts:
+// Two kernels share the tile geometry (a workgroup owns a 256-wide tile of C):
 //
-//   gemm_mfma_dl_kernel  the main kernel.  K advances in 32-deep steps through four LDS stages that
-//     are filled by direct global->LDS loads issued three steps ahead; 8 wavefronts (2 x 4, 128 x 64
-//     each) when an operand is K-contiguous, 4 (2 x 2, 128 x 128 each) when both are K-strided;
+//   gemm_mfma_dl_kernel  the main kernel.  8 wavefronts (2 x 4, 128 x 64 of C each), accumulators of
+//     v_mfma_f32_16x16x32_bf16.  K advances in 32-deep steps through a ring of five LDS buffers that
+//     are filled by direct global->LDS loads, issued for pairs of steps (so that both 64-byte halves of
+//     a 128-byte line of a K-contiguous operand reach L2 as one request) and spread between the MFMAs;
 //     epilogue staged through LDS so that all stores, residual loads and activation-operand loads are
-//     row-contiguous; optional fused residual / SwiGLU / GELU forward and backward epilogues; a
+//     row-contiguous; optional fused residual / bias / SwiGLU / GELU forward and backward epilogues; a
 //     128-row tile variant and a split-K mode for grids that do not fill the CUs.
 //   gemm_mfma_kernel     the fallback for K-contiguous operands whose K is not a multiple of 32: four
-//     wavefronts, 64-deep steps, two LDS stages filled through registers.
+//     wavefronts, v_mfma_f32_32x32x16_bf16, 64-deep steps, two LDS stages filled through registers.
 //
 // Operand tiles sit in LDS in their memory orientation, so every global load is a coalesced
 // 16-byte access:
-//   K-contiguous operand ([rows][K] in memory): rows of 16-byte chunks, XOR-swizzled so that the 16
-//     rows one ds_read_b128 phase touches fall into distinct bank groups; a fragment (8 consecutive
-//     k of one row) is one ds_read_b128.
-//   K-strided operand ([K][rows] in memory): LDS [k][256 rows], 64-byte units XOR-swizzled by
-//     k; a fragment is two ds_read_b64_tr_b16, the LDS transpose read of gfx950 that hands each
-//     lane 4 consecutive k of one row out of a 4(k) x 16(rows) block.
+//   K-contiguous operand ([rows][K] in memory): rows of 16-byte chunks, XOR-swizzled so that the lanes
+//     one ds_read_b128 pass serves fall into distinct bank groups; a fragment (8 consecutive k of one
+//     row) is one ds_read_b128.
+//   K-strided operand ([K][rows] in memory): LDS [k][256 rows], chunks XOR-swizzled by k; a fragment is
+//     two ds_read_b64_tr_b16, the LDS transpose read of gfx950 that hands each lane 4 consecutive k of
+//     one row out of a 4(k) x 16(rows) block.
 // The forward GEMMs use (A K-contiguous, B K-strided), the input-gradient GEMMs (both
 // K-contiguous), the weight-gradient GEMMs (both K-strided, K = tokens).
 //
@@ -227,11 +227,10 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __res
 //     chunk that belongs at LDS position p.
 //   - buffer descriptors bound every operand, so rows past the end of an operand read as zero
 //     (that is what zero-fills the ragged K tail of the weight-gradient GEMMs, K = tokens).
-//   - K advances in steps of 32 through FOUR LDS stages of 32 KB, so the loads of step t+3 are
-//     issued before the MFMAs of step t: three steps (about 3000 MFMA cycles) of latency cover.
-//     The stages are four separate __shared__ arrays and the loop is unrolled by four, so the
-//     compiler can prove that fragment reads of one stage do not alias loads in flight to another.
-//   - fragment reads run one 16-wide k-step ahead of the MFMAs that consume them.
+//   - K advances in steps of 32 through FIVE LDS buffers of 32 KB (all of the CU's LDS); the loads of
+//     steps e and e+1 are issued together, three to four steps ahead of their use.  The buffers are
+//     five separate __shared__ arrays and the loop is unrolled by ten, so the compiler can prove that
+//     fragment reads of one buffer do not alias loads in flight to another.
 // Requires K % 32 == 0 when an operand is K-contiguous (a K tail would wrap into the next row).
 // ------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
