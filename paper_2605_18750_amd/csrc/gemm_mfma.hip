@@ -235,12 +235,16 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(const bf16_t* __res
 // ------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
-// Wavefronts per workgroup of the direct-load kernel: 2 x 4 (128 x 64 of C each, two per SIMD so that one
-// wavefront's waits hide behind the other's MFMAs) for every operand orientation.  With 2 x 2 (128 x 128
-// each, 256 accumulator registers in 64 four-register tuples) the register allocator shuffles
-// accumulators between MFMAs; measured slower on every shape.
-constexpr int dl_wm(bool, bool) { return RRFP_WM_KC; }
-constexpr int dl_wn(bool, bool) { return RRFP_WN_KC; }
+// Wavefronts per workgroup of the direct-load kernel.  With a K-contiguous operand: 2 x 4 (128 x 64 of C
+// each, two per SIMD so that one wavefront's waits hide behind the other's MFMAs), v_mfma_f32_16x16x32_bf16.
+// With both operands K-strided (the weight-gradient form) the kernel is bounded by the issue rate of the
+// LDS transpose reads, two per fragment: 2 x 2 wavefronts (128 x 128 each) need a third fewer of them.
+// 256 accumulator registers per wavefront only allocate cleanly as 16 tuples of 16 (with 64 tuples of 4
+// the register allocator shuffles accumulators between MFMAs), so that form keeps v_mfma_f32_32x32x16_bf16;
+// it is not power bound, so the cheaper 16x16x32 form would buy nothing there.
+constexpr int dl_wm(bool, bool) { return 2; }
+constexpr int dl_wn(bool a_kc, bool b_kc) { return (a_kc || b_kc) ? 4 : 2; }
+constexpr bool dl_m32(bool a_kc, bool b_kc) { return !a_kc && !b_kc; }
 constexpr int DBK = 32;                              // k per stage
 constexpr int DTILE = 256 * DBK * 2;                 // bytes of one operand tile (16 KB)
 constexpr int DSTAGE = 2 * DTILE;                    // A + B (32 KB)
@@ -267,7 +271,9 @@ __device__ __forceinline__ int dks_swz(int k) { return ((k & 3) | (((k >> 3) & 1
 __device__ __forceinline__ int dks_off(int k, int c) { return k * 512 + ((c ^ dks_swz(k)) << 4); }
 
 // NW = wavefronts per workgroup.
-template <bool KC, int NW, int ROWS = 256>
+// SWZ32 (K-strided tiles only): the swizzle of the 32x32x16 fragment reads (64-byte units moved by k,
+// as in ks_off) instead of the one of the 16x16x32 reads.
+template <bool KC, int NW, int ROWS = 256, bool SWZ32 = false>
 struct DirectLoader {
   static_assert(KC || ROWS == 256, "a K-strided tile is always 256 wide");
   static constexpr int NL = (ROWS / 16) / NW;      // 1 KB blocks of the tile per wavefront (16 rows of 64 B each when K-contiguous)
@@ -291,7 +297,8 @@ struct DirectLoader {
         voff[i] = (outer0 + row < outer_n) ? ((outer0 + row) * ld + c * 8) * 2 : (int)0x80000000;
       } else {
         const int k = blk * 2 + (lane >> 5), cp = lane & 31;
-        const int c = cp ^ dks_swz(k);
+        const int f = (k & 3) | (((k >> 3) & 1) << 2);
+        const int c = SWZ32 ? ((((cp >> 2) ^ f) << 2) | (cp & 3)) : (cp ^ dks_swz(k));
         int col = outer0 + c * 8;
         if (pair_f > 0) {
           const int nl = c * 8;                                  // column inside the tile
@@ -402,6 +409,26 @@ __device__ __forceinline__ void mfma_blocks(floatx4 (&acc)[MI16][NF], const bf16
     for (int j = 0; j < NF; ++j) acc[i0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i0 + i][j], 0, 0, 0);
 }
 
+// 32x32x16 path (both operands K-strided): fragments of one 16-wide k-step, MI row blocks of A and NB column
+// blocks of B (32 x 16 each, two transpose reads per fragment).
+template <int MI, int NB>
+struct Frags32 { bf16x8 a[MI], b[NB]; };
+template <int MI, int NB>
+__device__ __forceinline__ void load_frags32(Frags32<MI, NB>& f, const char* sa, int ks, int wm, int wn, int lane) {
+  const char* sb = sa + DTILE;
+#pragma unroll
+  for (int i = 0; i < MI; ++i) f.a[i] = read_frag<false>(sa, wm + i * 32, ks, lane);
+#pragma unroll
+  for (int j = 0; j < NB; ++j) f.b[j] = read_frag<false>(sb, wn + j * 32, ks, lane);
+}
+template <int MI, int NB>
+__device__ __forceinline__ void mfma32(floatx16 (&acc)[MI][NB], const Frags32<MI, NB>& f) {
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+}
+
 // Ask the scheduler to interleave N_DS LDS reads, N_VM global->LDS loads and N_MFMA MFMAs in groups, reads
 // leading.  The loads are spread over the groups on purpose: a wavefront that issues its loads of a step
 // back to back sits at the (in-order) issue of the later ones while the texture path works through the
@@ -479,17 +506,28 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = (wave / WN) * WAVE_M, wn = (wave % WN) * WAVE_N;
 
+  constexpr bool M32 = dl_m32(A_KC, B_KC);          // 32x32x16 accumulators (acc32) instead of 16x16x32 ones (acc)
   constexpr int MI16 = 2 * MI, NF = 2 * NB, MA = MI;   // 16-row / 16-column blocks per wavefront; A blocks per half
-  floatx4 acc[MI16][NF];
+  floatx4 acc[M32 ? 1 : MI16][M32 ? 1 : NF];
+  floatx16 acc32[M32 ? MI : 1][M32 ? NB : 1];
+  if constexpr (M32) {
 #pragma unroll
-  for (int i = 0; i < MI16; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < NF; ++j)
+      for (int j = 0; j < NB; ++j)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+        for (int e = 0; e < 16; ++e) acc32[i][j][e] = 0.f;
+  } else {
+#pragma unroll
+    for (int i = 0; i < MI16; ++i)
+#pragma unroll
+      for (int j = 0; j < NF; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+  }
 
-  DirectLoader<A_KC, NW, BMT> la;
-  DirectLoader<B_KC, NW> lb;
+  DirectLoader<A_KC, NW, BMT, M32> la;
+  DirectLoader<B_KC, NW, 256, M32> lb;
   la.init(A, lda, m0, M, K, wave, lane);
   lb.init(B, ldb, n0, N, K, wave, lane, ACT == ACT_SWIGLU_FWD ? N / 2 : 0);
   const int nk = (K + DBK - 1) / DBK;
@@ -508,8 +546,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   // the pair (t+1, t+2) is complete.  On even steps the next step's buffer is complete since the previous
   // barrier.  Second half: read step t+1's first A half and its B blocks (into the other B register
   // set) under the MFMAs of the second A half.
-  using LoaderA = DirectLoader<A_KC, NW, BMT>;
-  using LoaderB = DirectLoader<B_KC, NW>;
+  using LoaderA = DirectLoader<A_KC, NW, BMT, M32>;
+  using LoaderB = DirectLoader<B_KC, NW, 256, M32>;
   constexpr int LA = LoaderA::NL, LB = LoaderB::NL;
   constexpr int NQ0 = QuarterCount<0, LA, LB>::LOADS, NQ1 = QuarterCount<1, LA, LB>::LOADS;
   constexpr int NQ2 = QuarterCount<2, LA, LB>::LOADS, NQ3 = QuarterCount<3, LA, LB>::LOADS;
@@ -524,20 +562,32 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   if (!GUARD || (tt) < nk) {                                                                             \
     if constexpr (PAR == 0) issue_quarter<3, GUARD>(la, lb, b2, b3, (tt) + 2, nk, wave);                 \
     else issue_quarter<1, GUARD>(la, lb, b3, b4, (tt) + 3, nk, wave);                                    \
-    load_blocks<A_KC, MA>(fr.ahi, b0, off_ahi);                                               \
-    mfma_blocks<MA, NF, MI16>(acc, fr.alo, fr.b[PAR], 0);                                                \
-    interleave_ds_vm_mfma<DS_A, N_MFMA, (PAR == 0 ? NQ3 : NQ1)>();                                       \
+    if constexpr (M32) {                                                                                 \
+      load_frags32<MI, NB>(fy, b0, 1, wm, wn, lane);                                                     \
+      mfma32<MI, NB>(acc32, fx);                                                                         \
+      interleave_ds_vm_mfma<2 * (MI + NB), MI * NB, (PAR == 0 ? NQ3 : NQ1)>();                           \
+    } else {                                                                                             \
+      load_blocks<A_KC, MA>(fr.ahi, b0, off_ahi);                                                        \
+      mfma_blocks<MA, NF, MI16>(acc, fr.alo, fr.b[PAR], 0);                                              \
+      interleave_ds_vm_mfma<DS_A, N_MFMA, (PAR == 0 ? NQ3 : NQ1)>();                                     \
+    }                                                                                                    \
     if (!GUARD || (tt) + 1 < nk) {                                                                       \
       __builtin_amdgcn_s_waitcnt(PAR == 0 ? LGKM_ONLY : VM_01);                                          \
       stage_barrier();                                                                                   \
       if constexpr (PAR == 0) issue_quarter<0, GUARD>(la, lb, b4, b0, (tt) + 4, nk, wave);               \
       else issue_quarter<2, GUARD>(la, lb, b3, b4, (tt) + 3, nk, wave);                                  \
-      load_blocks<A_KC, MA>(fr.alo, b1, off_alo);                                                       \
-      load_blocks<B_KC, NF>(fr.b[1 - PAR], b1 + DTILE, off_b);                                        \
+      if constexpr (M32) {                                                                               \
+        load_frags32<MI, NB>(fx, b1, 0, wm, wn, lane);                                                   \
+      } else {                                                                                           \
+        load_blocks<A_KC, MA>(fr.alo, b1, off_alo);                                                      \
+        load_blocks<B_KC, NF>(fr.b[1 - PAR], b1 + DTILE, off_b);                                         \
+      }                                                                                                  \
     }                                                                                                    \
-    mfma_blocks<MA, NF, MI16>(acc, fr.ahi, fr.b[PAR], MA);                                               \
+    if constexpr (M32) mfma32<MI, NB>(acc32, fy);                                                        \
+    else mfma_blocks<MA, NF, MI16>(acc, fr.ahi, fr.b[PAR], MA);                                          \
     if (!GUARD) {                                                                                        \
-      interleave_ds_vm_mfma<DS_A + DS_B, N_MFMA, (PAR == 0 ? NQ0 : NQ2)>();                              \
+      if constexpr (M32) interleave_ds_vm_mfma<2 * (MI + NB), MI * NB, (PAR == 0 ? NQ0 : NQ2)>();        \
+      else interleave_ds_vm_mfma<DS_A + DS_B, N_MFMA, (PAR == 0 ? NQ0 : NQ2)>();                         \
       __builtin_amdgcn_sched_barrier(0);   /* half-steps are scheduled one by one */                     \
     }                                                                                                    \
   }
@@ -554,6 +604,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   RRFP_STEP(1, GUARD, stage4, stage0, stage1, stage2, stage3, (t) + 9)
 
   Frags<MA, NF> fr;
+  Frags32<MI, NB> fx, fy;
   const int off_alo = frag_lane_offset<A_KC>(wm, lane), off_ahi = frag_lane_offset<A_KC>(wm + MA * 16, lane);
   const int off_b = frag_lane_offset<B_KC>(wn, lane);
   // Prologue: the pair (0, 1) in full and quarters 0..2 of the pair (2, 3); step 0's first half issues quarter 3.
@@ -566,8 +617,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   issue_quarter<2, true>(la, lb, stage2, stage3, 2, nk, wave);
   __builtin_amdgcn_s_waitcnt(VM_012);
   stage_barrier();
-  load_blocks<A_KC, MA>(fr.alo, stage0, off_alo);
-  load_blocks<B_KC, NF>(fr.b[0], stage0 + DTILE, off_b);
+  if constexpr (M32) {
+    load_frags32<MI, NB>(fx, stage0, 0, wm, wn, lane);
+  } else {
+    load_blocks<A_KC, MA>(fr.alo, stage0, off_alo);
+    load_blocks<B_KC, NF>(fr.b[0], stage0 + DTILE, off_b);
+  }
 
   int t = 0;
   for (; t + 13 < nk; t += 10) {    // every load these ten steps issue is for a step below nk
@@ -622,12 +677,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   if (ACT != ACT_SWIGLU_FWD) prefetch(pre[0], 0);
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
+    if constexpr (M32) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+      for (int j = 0; j < NB; ++j)
 #pragma unroll
-      for (int j = 0; j < NF; ++j)
-        *reinterpret_cast<float4*>(scratch + (h * 16 + li) * PITCH + j * 16 + hq * 4) =
-            make_float4(acc[2 * i + h][j][0], acc[2 * i + h][j][1], acc[2 * i + h][j][2], acc[2 * i + h][j][3]);
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(scratch + (lane & 31) * PITCH + j * 32 + g * 8 + (lane >> 5) * 4) =
+              make_float4(acc32[i][j][g * 4 + 0], acc32[i][j][g * 4 + 1], acc32[i][j][g * 4 + 2], acc32[i][j][g * 4 + 3]);
+    } else {
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < NF; ++j)
+          *reinterpret_cast<float4*>(scratch + (h * 16 + li) * PITCH + j * 16 + hq * 4) =
+              make_float4(acc[2 * i + h][j][0], acc[2 * i + h][j][1], acc[2 * i + h][j][2], acc[2 * i + h][j][3]);
+    }
     if (ACT == ACT_SWIGLU_FWD) {
       // scratch columns 0..31 = gate, 32..63 = up of features f0 .. f0+31; 4 lanes per row, 16 rows per sweep
       const int F = N >> 1;
