@@ -54,6 +54,17 @@ def test_mfma_gemm_small_ragged(ta, tb):
     _gemm_case(40, 72, 64, ta, tb, out_fp32=False, with_r=True, family=2)
 
 
+@pytest.mark.parametrize("K", [32, 96, 160, 416, 448, 480, 736, 768, 1056])
+def test_mfma_gemm_k_steps_across_pipeline_boundaries(K):
+    """K / 32 = 1, 3, 5, 13, 14, 15, 23, 24, 33 steps: shorter than the load pipeline, exactly at the point
+    where the unguarded ten-step loop is first entered (14) and re-entered (24), odd and even counts
+    (loads are issued for pairs of steps), for every operand orientation the direct-load kernel takes."""
+    for ta, tb in ((0, 0), (0, 1), (1, 0)):
+        _gemm_case(136, 264, K, ta, tb, out_fp32=(ta == 1), with_r=False, family=2, seed=K)
+    # weight-gradient form with a ragged last step
+    _gemm_case(264, 136, K + 8, 1, 0, out_fp32=True, with_r=False, family=2, seed=K + 1)
+
+
 def test_mfma_gemm_ragged_token_counts():
     # forward / input-gradient forms with T not a multiple of anything; weight-gradient form with K = T odd
     _gemm_case(777, 512, 256, 0, 0, False, True, 2)
