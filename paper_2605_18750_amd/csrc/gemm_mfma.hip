@@ -309,8 +309,11 @@ struct DirectLoader {
     }
   }
   // Load instruction i (of NL) of this wavefront for the k-step whose byte offset is soff.
-  __device__ __forceinline__ void issue_one(char* tile, int i, int soff, int wave) const {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * NW + wave) * 1024), 16, voff[i], soff, 0, 0);
+  // exists == false: every lane gets the per-lane offset that is past any buffer (the same marker rows
+  // past the end of the operand carry), so the descriptor's range check turns the load into zeros.
+  __device__ __forceinline__ void issue_one(char* tile, int i, int soff, int wave, bool exists) const {
+    const int vo = exists ? voff[i] : (int)0x80000000;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * NW + wave) * 1024), 16, vo, soff, 0, 0);
   }
 };
 
@@ -319,9 +322,9 @@ struct DirectLoader {
 // order (A first); the two instructions that fetch the same rows for the two steps are issued back to
 // back.  For a K-contiguous operand they are the two 64-byte halves of the same 128-byte lines: issued
 // together they reach L2 as one request per line, issued a step apart (as two separate fetches) as two.
-// Steps at or beyond nk get a byte offset past every buffer, which the descriptor turns into a load of
-// zeros without a memory access: the number of loads in flight never depends on the position in K.
-constexpr int OOB_SOFF = 0x7ffffff0;
+// Steps at or beyond nk are issued with a per-lane offset past every buffer (2^31; operands are smaller),
+// which the descriptor turns into a load of zeros without a memory access: the number of loads in flight
+// never depends on the position in K.
 template <int Q, int LA, int LB>
 struct QuarterCount { static constexpr int PAIRS = (Q + 1) * (LA + LB) / 4 - Q * (LA + LB) / 4, LOADS = 2 * PAIRS; };
 template <int Q, bool GUARD, typename LoaderA, typename LoaderB>
@@ -330,16 +333,16 @@ __device__ __forceinline__ void issue_quarter(const LoaderA& la, const LoaderB& 
   constexpr int P0 = Q * (LA + LB) / 4, P1 = (Q + 1) * (LA + LB) / 4;
   if constexpr (P1 > P0) {
     const bool okE = !GUARD || e < nk, okO = !GUARD || e + 1 < nk;
-    const int aE = okE ? e * la.k_stride : OOB_SOFF, aO = okO ? (e + 1) * la.k_stride : OOB_SOFF;
-    const int bE = okE ? e * lb.k_stride : OOB_SOFF, bO = okO ? (e + 1) * lb.k_stride : OOB_SOFF;
+    const int aE = okE ? e * la.k_stride : 0, aO = okO ? (e + 1) * la.k_stride : 0;
+    const int bE = okE ? e * lb.k_stride : 0, bO = okO ? (e + 1) * lb.k_stride : 0;
 #pragma unroll
     for (int p = P0; p < P1; ++p) {
       if (p < LA) {
-        la.issue_one(bufE, p, aE, wave);
-        la.issue_one(bufO, p, aO, wave);
+        la.issue_one(bufE, p, aE, wave, okE);
+        la.issue_one(bufO, p, aO, wave, okO);
       } else {
-        lb.issue_one(bufE + DTILE, p - LA, bE, wave);
-        lb.issue_one(bufO + DTILE, p - LA, bO, wave);
+        lb.issue_one(bufE + DTILE, p - LA, bE, wave, okE);
+        lb.issue_one(bufO + DTILE, p - LA, bO, wave, okO);
       }
     }
   }
@@ -811,7 +814,7 @@ RRFP_INST(true, true, bf16_t, false, ACT_SWIGLU_BWD) RRFP_INST(true, true, bf16_
 inline bool direct_ok(const GemmArgs& g) {
   const bool a_kc = !g.transA, b_kc = g.transB;
   if ((a_kc || b_kc) && (g.K % DBK)) return false;
-  const size_t lim = (size_t)OOB_SOFF;     // every operand byte offset stays below the offset used for "no such step"
+  const size_t lim = (size_t)1 << 31;      // every operand byte offset stays below the per-lane offset that means "out of range"
   const size_t a_bytes = (size_t)(a_kc ? g.M + BM : g.K + BK) * g.lda * 2;
   const size_t b_bytes = (size_t)(b_kc ? g.N + BN : g.K + BK) * g.ldb * 2;
   return a_bytes < lim && b_bytes < lim;
