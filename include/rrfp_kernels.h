@@ -33,6 +33,17 @@ int rrfp_gemm(const void* A, const void* B, void* C, const void* R, int M, int N
               int ldb, int ldc, int ldr, int trans_a, int trans_b, int in_dtype, int out_dtype,
               int family, void* stream);
 
+/* How the bf16 MFMA GEMM cuts a shape into launches on a device with n_cu compute units: host logic only
+ * (no GPU call, no pointers; operands are taken as 16-byte aligned).  The cut is a pure function of the
+ * shape and n_cu, which is what keeps the summation order of a call fixed (the bit-exactness requirement
+ * behind readiness-driven reordering, paper Section 7.1).  out[0] = kernel (0 the MFMA family refuses the
+ * shape, 1 direct-to-LDS, 2 register-staged), out[1] = wavefronts per workgroup, out[2] = workgroups of
+ * the 256-row-tile launch, out[3] = workgroups of the 128-row-tile launch that finishes a grid whose last
+ * round would be nearly empty, out[4] = split-K ranges (weight-gradient form with scratch; 1 = none).
+ * Returns STAGE_OK or STAGE_EINVAL. */
+int rrfp_gemm_plan(int M, int N, int K, int lda, int ldb, int ldc, int trans_a, int trans_b, int out_dtype,
+                   int have_scratch, int n_cu, int32_t out[5]);
+
 #ifdef __cplusplus
 }
 #endif

@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
         L.stage_last_error.restype = C.c_char_p
         L.rrfp_gemm.argtypes = [vp, vp, vp, vp] + [C.c_int] * 12 + [vp]
         L.rrfp_gemm.restype = C.c_int
+        L.rrfp_gemm_plan.argtypes = [C.c_int] * 11 + [C.POINTER(C.c_int32)]
+        L.rrfp_gemm_plan.restype = C.c_int
         for f in ("stage_query", "stage_param_layout", "stage_create", "stage_create_dry", "stage_F",
                   "stage_B", "stage_W", "stage_grad_reduce", "stage_grad_slot", "stage_destroy"):
             getattr(L, f).restype = C.c_int
@@ -160,6 +162,19 @@ def rrfp_gemm(A, B, Cout, R, M, N, K, lda, ldb, ldc, ldr, trans_a, trans_b, in_d
                          int(trans_a), int(trans_b), in_dtype, out_dtype, family, _stream(stream))
     if rc != STAGE_OK:
         raise StageError(rc, "rrfp_gemm rejected its arguments" if rc == STAGE_EINVAL else "HIP launch failed")
+
+
+def rrfp_gemm_plan(M, N, K, trans_a, trans_b, out_dtype, n_cu=256, have_scratch=False, lda=None, ldb=None, ldc=None):
+    """Launch plan of the bf16 MFMA GEMM for a shape (host logic only, no GPU): dict with kernel
+    (0 refused, 1 direct-to-LDS, 2 register-staged), wavefronts, main_workgroups, short_workgroups, split_k."""
+    lda = (M if trans_a else K) if lda is None else lda
+    ldb = (K if trans_b else N) if ldb is None else ldb
+    ldc = N if ldc is None else ldc
+    out = (C.c_int32 * 5)()
+    rc = lib().rrfp_gemm_plan(M, N, K, lda, ldb, ldc, int(trans_a), int(trans_b), out_dtype, int(have_scratch), n_cu, out)
+    if rc != STAGE_OK:
+        raise StageError(rc, "rrfp_gemm_plan rejected its arguments")
+    return dict(zip(("kernel", "wavefronts", "main_workgroups", "short_workgroups", "split_k"), (int(v) for v in out)))
 
 
 def stage_destroy(st):

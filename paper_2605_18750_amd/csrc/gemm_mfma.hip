@@ -837,8 +837,8 @@ inline int cu_count() {
 // tiles and carving ceil(r / tiles_m) trailing tile columns off removes that round, those columns
 // are launched separately with 128-row tiles, provided they fit one round.  A pure function of the
 // shape and the device.  Returns the number of tile columns of the 256-row launch.
-inline int full_tile_columns(int tiles_m, int tiles_n) {
-  const int n_cu = cu_count(), t = tiles_m * tiles_n;
+inline int full_tile_columns(int tiles_m, int tiles_n, int n_cu) {
+  const int t = tiles_m * tiles_n;
   if (2 * t <= n_cu) return 0;
   const int r = t % n_cu;
   if (t <= n_cu || r == 0) return tiles_n;
@@ -852,8 +852,7 @@ inline int full_tile_columns(int tiles_m, int tiles_n) {
 
 // Split-K factor for a grid of t tiles and a contraction of K: as many ranges as fit the CUs, each at
 // least 16 steps deep, at most 16 ranges; 1 = no split.  A pure function of the shape and the device.
-inline int splitk_factor(int t, int K) {
-  const int n_cu = cu_count();
+inline int splitk_factor(int t, int K, int n_cu) {
   if (2 * t > n_cu) return 1;
   const int steps = (K + DBK - 1) / DBK;
   return std::max(1, std::min(std::min(n_cu / t, steps / 16), 16));
@@ -864,7 +863,7 @@ template <bool B_KC, typename TO, bool HAS_R, int ACT>
 hipError_t launch_a_kc(const GemmArgs& g, hipStream_t s) {
   constexpr int WMv = dl_wm(true, B_KC), WNv = dl_wn(true, B_KC);
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  const int cn = full_tile_columns(tiles_m, tiles_n);
+  const int cn = full_tile_columns(tiles_m, tiles_n, cu_count());
   if (cn > 0)
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT>), dim3(tiles_m * cn), dim3(WMv * WNv * 64),
                        0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc,
@@ -887,7 +886,7 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
     // few tiles to fill the CUs, the contraction is split into S ranges, every range writes its own
     // partial plane into the scratch, and the planes are summed in range order (one fixed order).
     if constexpr (!A_KC && !B_KC && !HAS_R && sizeof(TO) == 4) {
-      const int S = splitk_factor(tiles_m * tiles_n, g.K);
+      const int S = splitk_factor(tiles_m * tiles_n, g.K, cu_count());
       if (S > 1 && g.ws && g.ldc == g.N && (size_t)S * g.M * g.N * 4 <= g.ws_bytes && ((size_t)g.M * g.N) % 4 == 0) {
         const int steps = (g.K + DBK - 1) / DBK, k_split = (steps + S - 1) / S * DBK;
         const int S_eff = (g.K + k_split - 1) / k_split;
@@ -945,6 +944,38 @@ bool gemm_act_supported(const GemmArgs& g) {
     case ACT_SWIGLU_BWD: case ACT_GELU_BWD: return g.transB;
     default: return false;
   }
+}
+
+// How launch_gemm_mfma would cut g (without an activation) on a device with n_cu compute units: the same
+// decisions as the launchers above, without touching the device.
+GemmPlan gemm_mfma_plan(const GemmArgs& g, int n_cu, bool have_scratch) {
+  GemmPlan p{};
+  if (!gemm_mfma_supports(g)) return p;
+  const bool a_kc = !g.transA, b_kc = g.transB;
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  p.wavefronts = direct_ok(g) ? dl_wm(a_kc, b_kc) * dl_wn(a_kc, b_kc) : NTHREADS / 64;
+  p.split_k = 1;
+  if (!direct_ok(g)) {
+    p.kernel = 2;
+    p.main_workgroups = tiles_m * tiles_n;
+    return p;
+  }
+  p.kernel = 1;
+  if (a_kc) {
+    const int cn = full_tile_columns(tiles_m, tiles_n, n_cu);
+    p.main_workgroups = tiles_m * cn;
+    p.short_workgroups = ((g.M + 127) / 128) * (tiles_n - cn);
+    return p;
+  }
+  p.main_workgroups = tiles_m * tiles_n;
+  if (!b_kc && !g.R && g.out_dtype == F32 && have_scratch && g.ldc == g.N && ((size_t)g.M * g.N) % 4 == 0) {
+    const int S = splitk_factor(tiles_m * tiles_n, g.K, n_cu);
+    if (S > 1) {
+      const int steps = (g.K + DBK - 1) / DBK, k_split = (steps + S - 1) / S * DBK;
+      p.split_k = (g.K + k_split - 1) / k_split;
+    }
+  }
+  return p;
 }
 
 bool gemm_mfma_supports(const GemmArgs& g) {

@@ -26,3 +26,15 @@ extern "C" int rrfp_gemm(const void* A, const void* B, void* C, const void* R, i
   } else return STAGE_EINVAL;
   return e == hipSuccess ? STAGE_OK : STAGE_EHIP;
 }
+
+extern "C" int rrfp_gemm_plan(int M, int N, int K, int lda, int ldb, int ldc, int trans_a, int trans_b, int out_dtype,
+                              int have_scratch, int n_cu, int32_t out[5]) {
+  if (!out || M < 1 || N < 1 || K < 1 || n_cu < 1) return STAGE_EINVAL;
+  if (out_dtype != F32 && out_dtype != BF16) return STAGE_EINVAL;
+  GemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ldr = ldc;
+  g.transA = trans_a != 0; g.transB = trans_b != 0; g.in_dtype = BF16; g.out_dtype = out_dtype;
+  const GemmPlan p = gemm_mfma_plan(g, n_cu, have_scratch != 0);
+  out[0] = p.kernel; out[1] = p.wavefronts; out[2] = p.main_workgroups; out[3] = p.short_workgroups; out[4] = p.split_k;
+  return STAGE_OK;
+}

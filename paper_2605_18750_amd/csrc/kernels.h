@@ -43,6 +43,10 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);       // picks the ker
 hipError_t launch_gemm_simt(const GemmArgs& g, hipStream_t s);  // fp32-FMA tiles, any shape
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);  // bf16 MFMA kernels (256-wide tiles)
 bool gemm_mfma_supports(const GemmArgs& g);                     // alignment / divisibility rules
+// Launch plan of launch_gemm_mfma for a shape (pure host logic): kernel 0 = refused, 1 = direct-to-LDS,
+// 2 = register-staged; workgroups of the 256-row launch and of the 128-row launch; split-K ranges.
+struct GemmPlan { int kernel, wavefronts, main_workgroups, short_workgroups, split_k; };
+GemmPlan gemm_mfma_plan(const GemmArgs& g, int n_cu, bool have_scratch);
 
 // One attention work item: a tile of rows [r0, r1) inside the segment [s0, s1).
 struct AttnTile { int32_t r0, r1, s0, s1; };

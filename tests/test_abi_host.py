@@ -139,3 +139,33 @@ def test_real_create_rejects_bad_buffers_before_any_hip_call():
     _expect(R.STAGE_EINVAL, R.stage_create, cfg, None, None, ab)
     _expect(R.STAGE_EINVAL, R.stage_create, cfg, 256 + 8, 4096, ab)     # misaligned
     _expect(R.STAGE_ENOMEM, R.stage_create, cfg, 256, 4096, ab - 1)     # arena too small
+
+
+def test_gemm_launch_plan_is_a_pure_function_of_shape_and_cu_count():
+    """The cut of a GEMM into launches (tile rows, tail launch, split-K ranges) decides the order in which
+    every output element is summed; it may depend on the shape and the device's CU count only.  Language-stage
+    shapes on 256 CUs: the forward up projection is 1280 workgroups of 256-row tiles (exactly 5 rounds) plus 192
+    of 128-row tiles for the 6 trailing tile columns; the one-round input-gradient shape is untouched; the
+    weight-gradient form runs 2 x 2 wavefronts and is only split along K when its grid leaves CUs idle."""
+    import paper_2605_18750_amd as R
+    BF, F32 = R.STAGE_DTYPE_BF16, R.STAGE_DTYPE_FP32
+    T, H, F2, Q = 4096, 4096, 22016, 12288
+    up = R.rrfp_gemm_plan(T, F2, H, 0, 0, BF)
+    assert up == dict(kernel=1, wavefronts=8, main_workgroups=1280, short_workgroups=192, split_k=1)
+    assert R.rrfp_gemm_plan(T, F2, H, 0, 0, BF) == up                      # same answer every time
+    assert R.rrfp_gemm_plan(T, H, F2, 0, 1, F32) == dict(kernel=1, wavefronts=8, main_workgroups=256, short_workgroups=0, split_k=1)
+    assert R.rrfp_gemm_plan(T, Q, H, 0, 0, BF)["main_workgroups"] == 768   # 3 full rounds: no tail launch
+    assert R.rrfp_gemm_plan(T, Q, H, 0, 0, BF)["short_workgroups"] == 0
+    wg = R.rrfp_gemm_plan(H, F2, T, 1, 0, F32, have_scratch=True)
+    assert wg == dict(kernel=1, wavefronts=4, main_workgroups=1376, short_workgroups=0, split_k=1)
+    # vision stage: dW of the output projection, 1280 x 1280 with K = 6272 tokens: 25 tiles -> split along K
+    small = R.rrfp_gemm_plan(1280, 1280, 6272, 1, 0, F32, have_scratch=True)
+    assert small["main_workgroups"] == 25 and 1 < small["split_k"] <= 16
+    assert R.rrfp_gemm_plan(1280, 1280, 6272, 1, 0, F32, have_scratch=False)["split_k"] == 1
+    # a grid that fills at most half the CUs goes entirely to 128-row tiles
+    assert R.rrfp_gemm_plan(1000, 2048, 1280, 0, 0, BF) == dict(kernel=1, wavefronts=8, main_workgroups=0, short_workgroups=64, split_k=1)
+    # the CU count is an input: with 32 CUs the same 32 tiles are one full round of 256-row tiles
+    assert R.rrfp_gemm_plan(1000, 2048, 1280, 0, 0, BF, n_cu=32) == dict(kernel=1, wavefronts=8, main_workgroups=32, short_workgroups=0, split_k=1)
+    # K not a multiple of 32 with a K-contiguous operand: register-staged kernel; N not a multiple of 8: refused
+    assert R.rrfp_gemm_plan(264, 520, 200, 0, 0, BF)["kernel"] == 2
+    assert R.rrfp_gemm_plan(264, 516, 256, 0, 0, BF)["kernel"] == 0
