@@ -268,7 +268,6 @@ __device__ __forceinline__ int dkc_off(int row, int c) { return row * 64 + ((c ^
 // A fragment read (below) touches, per 32 lanes, 8 k-rows (k & 3 and bit 3 of k vary) at the same pair of
 // chunks; the swizzle sends them to 8 distinct 32-byte bank groups.
 __device__ __forceinline__ int dks_swz(int k) { return ((k & 3) | (((k >> 3) & 1) << 2)) << 1; }
-__device__ __forceinline__ int dks_off(int k, int c) { return k * 512 + ((c ^ dks_swz(k)) << 4); }
 
 // NW = wavefronts per workgroup.
 // SWZ32 (K-strided tiles only): the swizzle of the 32x32x16 fragment reads (64-byte units moved by k,
@@ -468,12 +467,6 @@ __device__ __forceinline__ void load_f32x8(const float* p, float* v) {
 __device__ __forceinline__ void unpack4(uint2 w, float* v) {
   v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
   v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
-}
-__device__ __forceinline__ uint2 pack4(const float* v) {
-  uint2 o;
-  o.x = pack_bf16x2(v[0], v[1]);
-  o.y = pack_bf16x2(v[2], v[3]);
-  return o;
 }
 
 // BMT = rows of the C tile: 256, or 128 for the short tiles that finish a GEMM whose tile count is
