@@ -488,7 +488,7 @@ __global__ __launch_bounds__(256) void headnorm_bwd_kernel(T* __restrict__ dy, i
 #pragma unroll
   for (int u = 0; u < 2; ++u) red[wave][lane + u * WAVE] = gs[u];
   __syncthreads();
-  if (threadIdx.x < d) partial[(size_t)blockIdx.x * d + threadIdx.x] =
+  if ((int)threadIdx.x < d) partial[(size_t)blockIdx.x * d + threadIdx.x] =
       ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
 }
 
