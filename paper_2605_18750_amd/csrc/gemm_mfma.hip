@@ -813,15 +813,17 @@ inline bool direct_ok(const GemmArgs& g) {
   return a_bytes < lim && b_bytes < lim;
 }
 
+// Compute units of the current device (cached per device id; 256 if the query fails).
 inline int cu_count() {
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
-      v = 256;
-    n_cu = v;
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 256;
+    cached[dev] = v;
   }
-  return n_cu;
+  return cached[dev];
 }
 
 // How a GEMM with A K-contiguous is cut into launches.  One workgroup occupies a CU, so t tiles of
