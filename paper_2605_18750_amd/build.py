@@ -17,6 +17,11 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
 
 
+# Per-file additions to FLAGS.  The dQ attention kernel is scheduled with the iterative-ilp strategy
+# (measured: 8-10 % faster for that kernel only).
+EXTRA_FLAGS = {"attn_mfma_dq.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"]}
+
+
 def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith((".hip", ".cpp")))
 
@@ -27,7 +32,7 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
 
     def compile_one(src):
         obj = os.path.join(OBJ, src.rsplit(".", 1)[0] + ".o")
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")

@@ -13,49 +13,13 @@
 // LDS in its memory orientation and its fragments come from the LDS transpose read.
 // Exponentials are base 2 (scores pre-multiplied by log2 e / sqrt(d)); the saved log-sum-exp
 // is in natural-log units.
-#include "kernels.h"
-#include "numeric.h"
-
-#include <type_traits>
+#include "attn_mfma_common.h"
 
 namespace rrfp {
+
+hipError_t launch_attn_dq_mfma(const AttnArgs& a, hipStream_t s);   // attn_mfma_dq.hip
+
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
-
-__device__ __forceinline__ bf16x8 pack8(const float* p) {
-  uint4 w;
-  w.x = pack_bf16x2(p[0], p[1]); w.y = pack_bf16x2(p[2], p[3]);
-  w.z = pack_bf16x2(p[4], p[5]); w.w = pack_bf16x2(p[6], p[7]);
-  return __builtin_bit_cast(bf16x8, w);
-}
-
-constexpr int BKV = 64;        // keys per step
-constexpr int FWD_Q_ROWS = ATTN_TILE_Q;   // query rows per workgroup of the forward and dQ kernels
-constexpr int FWD_NIB = 1;                // 32-query blocks per wavefront: 8 wavefronts, two per SIMD, so that one
-                                          // wavefront's softmax arithmetic runs under the other's MFMAs
-constexpr int DQ_NIB = 1;
-
-// Fragment of a tile stored [row][k] (pitch bytes): lane gets row row0 + (lane & 31), k = ks*16 + h*8 .. +8.
-__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int pitch, int row0, int ks, int lane) {
-  const uint4 v = *reinterpret_cast<const uint4*>(tile + (row0 + (lane & 31)) * pitch + (ks * 2 + (lane >> 5)) * 16);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-// Transposed fragment of a tile stored [k][col] (pitch bytes): lane gets column col0 + (lane & 31) and
-// the eight k values kstart + {0..3} and kstart + 8 + {0..3}, kstart = k0 + (lane >> 5) * 4.  This is the
-// k order in which a 32x32 accumulator block, packed to bf16, serves as the other MFMA operand.
-__device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int pitch, int k0, int col0, int lane) {
-  const int krow = k0 + (lane >> 5) * 4 + ((lane & 15) >> 2);
-  const int col = col0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  union { short4v hh[2]; bf16x8 v; } f;
-  f.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + krow * pitch + col * 2));
-  f.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + (krow + 8) * pitch + col * 2));
-  return f.v;
-}
 
 template <int D, int NT>
 struct FwdCfg {
@@ -338,45 +302,6 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
 //           key column and P, dS are B operands of dV^T += dO^T P and dK^T += Q^T dS.
 // ------------------------------------------------------------------------------------------
 
-// Generic tile movers: ROWS x D bf16 from global rows [row0, row_end) into registers, then into
-// LDS with a row pitch of PITCH bytes; columns D .. DPAD-1 are zero-filled.
-template <int D, int ROWS, int NT = 256>
-struct TileRegs { static constexpr int N = (ROWS * (D / 8) + NT - 1) / NT; };
-template <int D, int ROWS, int NT = 256>
-using TileArr = uint4[TileRegs<D, ROWS, NT>::N];
-
-template <int D, int ROWS, int NT = 256>
-__device__ __forceinline__ void tile_load(TileArr<D, ROWS, NT>& r, const bf16_t* __restrict__ base, int ld,
-                                          int row0, int row_end) {
-  constexpr int CH = D / 8;
-#pragma unroll
-  for (int i = 0; i < TileRegs<D, ROWS, NT>::N; ++i) {
-    const int q = i * NT + threadIdx.x;
-    const int row = q / CH, c = q - row * CH;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (q < ROWS * CH && row0 + row < row_end) v = *reinterpret_cast<const uint4*>(base + (size_t)(row0 + row) * ld + c * 8);
-    r[i] = v;
-  }
-}
-
-template <int D, int ROWS, int PITCH, int DPAD, int NT = 256>
-__device__ __forceinline__ void tile_store(const TileArr<D, ROWS, NT>& r, char* lds) {
-  constexpr int CH = D / 8;
-#pragma unroll
-  for (int i = 0; i < TileRegs<D, ROWS, NT>::N; ++i) {
-    const int q = i * NT + threadIdx.x;
-    const int row = q / CH, c = q - row * CH;
-    if (q < ROWS * CH) *reinterpret_cast<uint4*>(lds + row * PITCH + c * 16) = r[i];
-  }
-  if (DPAD != D) {
-    constexpr int PADCH = (DPAD - D) / 8;
-    for (int q = threadIdx.x; q < ROWS * PADCH; q += NT) {
-      const int row = q / PADCH, c = q - row * PADCH;
-      *reinterpret_cast<uint4*>(lds + row * PITCH + (CH + c) * 16) = make_uint4(0, 0, 0, 0);
-    }
-  }
-}
-
 template <int D>
 __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __restrict__ o, const float* __restrict__ o32,
                                                               const bf16_t* __restrict__ d_o, float* __restrict__ delta,
@@ -406,173 +331,6 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __re
   }
 }
 
-template <int D>
-struct DqCfg {
-  static constexpr int DP = (D + 31) / 32 * 32;
-  static constexpr int KP = 304;                     // K tile: row fragments AND transposed fragments.  304 = 48 (mod 256):
-                                                     // 16 rows x 16 B and 4 rows x 32 B both land on distinct banks
-  static constexpr int VP = D * 2 + 16;              // V tile: row fragments only
-  static constexpr int K_BYTES = BKV * KP;
-  static constexpr int STAGE = (K_BYTES + BKV * VP + 255) / 256 * 256;
-  static constexpr int SMEM = 2 * STAGE;
-};
-
-template <int D, int NIB>
-__global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
-                                                           const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
-                                                           int Tn, int nq, int nkv, int causal, float scale) {
-  constexpr int NT = FWD_Q_ROWS / (32 * NIB) * 64;   // threads: one wavefront per 32 * NIB query rows
-  constexpr int WQ = 32 * NIB;
-  using C = DqCfg<D>;
-  constexpr int NDS = D / 16, NDB = C::DP / 32;
-  constexpr float LOG2E = 1.4426950408889634f;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const AttnTile tl = tiles[blockIdx.y];
-  const int a = blockIdx.x, b = a / (nq / nkv);
-  const int ld = (nq + 2 * nkv) * D;
-  const int qcol = a * D, kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: wave-level branches stay uniform
-  const int h = lane >> 5, li = lane & 31;
-  const int wq0 = tl.r0 + wave * WQ;
-  const bool wave_has_rows = wq0 < tl.r1;
-  const float scale_log2e = scale * LOG2E;
-
-  bf16x8 qf[NIB][NDS], dof[NIB][NDS];
-  float lse2[NIB], dl[NIB];
-#pragma unroll
-  for (int ib = 0; ib < NIB; ++ib) {
-    const int i = wq0 + ib * 32 + li;
-    const bool ok = i < tl.r1;
-    lse2[ib] = ok ? lse[(size_t)a * Tn + i] * LOG2E : 0.f;
-    dl[ib] = ok ? delta[(size_t)a * Tn + i] : 0.f;
-#pragma unroll
-    for (int ds = 0; ds < NDS; ++ds) {
-      uint4 v = make_uint4(0, 0, 0, 0), w = v;
-      if (ok) {
-        v = *reinterpret_cast<const uint4*>(qkv + (size_t)i * ld + qcol + ds * 16 + h * 8);
-        w = *reinterpret_cast<const uint4*>(d_o + (size_t)i * nq * D + qcol + ds * 16 + h * 8);
-      }
-      qf[ib][ds] = __builtin_bit_cast(bf16x8, v);
-      dof[ib][ds] = __builtin_bit_cast(bf16x8, w);
-    }
-  }
-  floatx16 acc[NDB][NIB];
-#pragma unroll
-  for (int db = 0; db < NDB; ++db)
-#pragma unroll
-    for (int ib = 0; ib < NIB; ++ib)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[db][ib][e] = 0.f;
-
-  const int kv_end = causal ? tl.r1 : tl.s1;
-  const int nsteps = (kv_end - tl.s0 + BKV - 1) / BKV;
-  uint4 rk[TileRegs<D, BKV, NT>::N], rv[TileRegs<D, BKV, NT>::N];
-  tile_load<D, BKV, NT>(rk, qkv + kcol, ld, tl.s0, kv_end);
-  tile_load<D, BKV, NT>(rv, qkv + vcol, ld, tl.s0, kv_end);
-  tile_store<D, BKV, C::KP, C::DP, NT>(rk, smem);
-  tile_store<D, BKV, C::VP, D, NT>(rv, smem + C::K_BYTES);
-  __syncthreads();
-
-  // Leading steps in which this wavefront has unmasked keys; the rest only move data.  The dQ
-  // accumulators are touched in the first loop alone and unconditionally (they stay in place).
-  const int n_active = !wave_has_rows ? 0 : (causal ? min(nsteps, (wq0 + WQ - 1 - tl.s0) / BKV + 1) : nsteps);
-  auto io_begin = [&](int st) {
-    if (st + 1 < nsteps) {
-      tile_load<D, BKV, NT>(rk, qkv + kcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
-      tile_load<D, BKV, NT>(rv, qkv + vcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
-    }
-  };
-  auto io_end = [&](int st) {
-    if (st + 1 < nsteps) {
-      char* nk = smem + ((st + 1) & 1) * C::STAGE;
-      tile_store<D, BKV, C::KP, C::DP, NT>(rk, nk);
-      tile_store<D, BKV, C::VP, D, NT>(rv, nk + C::K_BYTES);
-    }
-    __syncthreads();
-  };
-  int st = 0;
-  for (; st < n_active; ++st) {
-    const int k0 = tl.s0 + st * BKV;
-    const char* sk = smem + (st & 1) * C::STAGE;
-    const char* sv = sk + C::K_BYTES;
-    io_begin(st);
-    const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
-#pragma unroll
-    for (int ib = 0; ib < NIB; ++ib) {
-      const int i = wq0 + ib * 32 + li;
-      floatx16 s[2], dp[2];
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb) {
-        bf16x8 kfr[NDS], vfr[NDS];      // all fragments of the 32-key block before its MFMAs
-#pragma unroll
-        for (int ds = 0; ds < NDS; ++ds) {
-          kfr[ds] = frag_rows(sk, C::KP, jb * 32, ds, lane);
-          vfr[ds] = frag_rows(sv, C::VP, jb * 32, ds, lane);
-        }
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { s[jb][e] = 0.f; dp[jb][e] = 0.f; }
-#pragma unroll
-        for (int ds = 0; ds < NDS; ++ds) {
-          s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ds], qf[ib][ds], s[jb], 0, 0, 0);
-          dp[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[ds], dof[ib][ds], dp[jb], 0, 0, 0);
-        }
-      }
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb) {
-        float dsv[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[jb][e], scale_log2e, -lse2[ib]));
-          dsv[e] = p * (dp[jb][e] - dl[ib]);
-        }
-        if (need_mask) {
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-            float v = (j >= kv_end || (causal && j > i)) ? 0.f : dsv[e];
-            asm volatile("" : "+v"(v));   // pins the select inside this (wave-uniform) branch
-            dsv[e] = v;
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const bf16x8 dsf = pack8(dsv + u * 8);
-          bf16x8 ktr[NDB];
-#pragma unroll
-          for (int db = 0; db < NDB; ++db) ktr[db] = frag_cols_tr(sk, C::KP, jb * 32 + u * 16, db * 32, lane);
-#pragma unroll
-          for (int db = 0; db < NDB; ++db)
-            acc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr[db], dsf, acc[db][ib], 0, 0, 0);
-        }
-      }
-    }
-    io_end(st);
-  }
-  for (; st < nsteps; ++st) {
-    io_begin(st);
-    io_end(st);
-  }
-#pragma unroll
-  for (int ib = 0; ib < NIB; ++ib) {
-    const int i = wq0 + ib * 32 + li;
-    if (i >= tl.r1) continue;
-    bf16_t* row = dqkv + (size_t)i * ld + qcol;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int dd = db * 32 + g * 8 + h * 4;
-        if (dd >= D) continue;
-        uint2 w;
-        w.x = pack_bf16x2(acc[db][ib][g * 4 + 0] * scale, acc[db][ib][g * 4 + 1] * scale);
-        w.y = pack_bf16x2(acc[db][ib][g * 4 + 2] * scale, acc[db][ib][g * 4 + 3] * scale);
-        *reinterpret_cast<uint2*>(row + dd) = w;
-      }
-  }
-}
-
 constexpr int BQ_KV = 64;      // query rows per step of the dK/dV kernel
 constexpr int WK = 32;         // keys per wavefront of the dK/dV kernel
 #ifndef DKV_VALU_PER_MFMA
@@ -582,7 +340,7 @@ constexpr int WK = 32;         // keys per wavefront of the dK/dV kernel
 template <int D>
 struct DkvCfg {
   static constexpr int DP = (D + 31) / 32 * 32;
-  static constexpr int QP = 304;                     // Q and dO tiles: row and transposed fragments (see DqCfg::KP)
+  static constexpr int QP = 304;                     // Q and dO tiles: row and transposed fragments (as the K tile of the dQ kernel in attn_mfma_dq.hip)
   static constexpr int T_BYTES = BQ_KV * QP;
   static constexpr int STAGE = (2 * T_BYTES + 2 * BQ_KV * 4 + 255) / 256 * 256;   // Q, dO, lse2[64], delta[64]
   static constexpr int SMEM = 2 * STAGE;
@@ -805,12 +563,10 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
 
 template <int D>
 hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
-  auto kq = attn_dq_mfma_kernel<D, DQ_NIB>;
   auto kkv = attn_dkv_mfma_kernel<D>;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kq, hipFuncAttributeMaxDynamicSharedMemorySize, DqCfg<D>::SMEM);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)kkv, hipFuncAttributeMaxDynamicSharedMemorySize, DkvCfg<D>::SMEM);
+    hipError_t e = hipFuncSetAttribute((const void*)kkv, hipFuncAttributeMaxDynamicSharedMemorySize, DkvCfg<D>::SMEM);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -819,9 +575,9 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
                      a.o32, (const bf16_t*)a.d_o, a.delta, a.T, a.nq);
   hipLaunchKernelGGL(kkv, dim3(a.nkv, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const bf16_t*)a.qkv,
                      (const bf16_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale);
-  hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(FWD_Q_ROWS / (32 * DQ_NIB) * 64), DqCfg<D>::SMEM, s, (const bf16_t*)a.qkv, (const bf16_t*)a.d_o,
-                     a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale);
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_attn_dq_mfma(a, s);
 }
 
 template <int D>

@@ -1,0 +1,89 @@
+// Pieces shared by the bf16 MFMA attention kernels (attn_mfma.hip, attn_mfma_dq.hip): vector types,
+// fragment reads from LDS tiles, and the global -> register -> LDS tile movers.
+#pragma once
+
+#include "kernels.h"
+#include "numeric.h"
+
+#include <type_traits>
+
+namespace rrfp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+
+__device__ __forceinline__ bf16x8 pack8(const float* p) {
+  uint4 w;
+  w.x = pack_bf16x2(p[0], p[1]); w.y = pack_bf16x2(p[2], p[3]);
+  w.z = pack_bf16x2(p[4], p[5]); w.w = pack_bf16x2(p[6], p[7]);
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+constexpr int BKV = 64;        // keys per step
+constexpr int FWD_Q_ROWS = ATTN_TILE_Q;   // query rows per workgroup of the forward and dQ kernels
+constexpr int FWD_NIB = 1;                // 32-query blocks per wavefront: 8 wavefronts, two per SIMD, so that one
+                                          // wavefront's softmax arithmetic runs under the other's MFMAs
+constexpr int DQ_NIB = 1;
+
+// Fragment of a tile stored [row][k] (pitch bytes): lane gets row row0 + (lane & 31), k = ks*16 + h*8 .. +8.
+__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int pitch, int row0, int ks, int lane) {
+  const uint4 v = *reinterpret_cast<const uint4*>(tile + (row0 + (lane & 31)) * pitch + (ks * 2 + (lane >> 5)) * 16);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Transposed fragment of a tile stored [k][col] (pitch bytes): lane gets column col0 + (lane & 31) and
+// the eight k values kstart + {0..3} and kstart + 8 + {0..3}, kstart = k0 + (lane >> 5) * 4.  This is the
+// k order in which a 32x32 accumulator block, packed to bf16, serves as the other MFMA operand.
+__device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int pitch, int k0, int col0, int lane) {
+  const int krow = k0 + (lane >> 5) * 4 + ((lane & 15) >> 2);
+  const int col = col0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  union { short4v hh[2]; bf16x8 v; } f;
+  f.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + krow * pitch + col * 2));
+  f.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + (krow + 8) * pitch + col * 2));
+  return f.v;
+}
+
+// Generic tile movers: ROWS x D bf16 from global rows [row0, row_end) into registers, then into
+// LDS with a row pitch of PITCH bytes; columns D .. DPAD-1 are zero-filled.
+template <int D, int ROWS, int NT = 256>
+struct TileRegs { static constexpr int N = (ROWS * (D / 8) + NT - 1) / NT; };
+template <int D, int ROWS, int NT = 256>
+using TileArr = uint4[TileRegs<D, ROWS, NT>::N];
+
+template <int D, int ROWS, int NT = 256>
+__device__ __forceinline__ void tile_load(TileArr<D, ROWS, NT>& r, const bf16_t* __restrict__ base, int ld,
+                                          int row0, int row_end) {
+  constexpr int CH = D / 8;
+#pragma unroll
+  for (int i = 0; i < TileRegs<D, ROWS, NT>::N; ++i) {
+    const int q = i * NT + threadIdx.x;
+    const int row = q / CH, c = q - row * CH;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (q < ROWS * CH && row0 + row < row_end) v = *reinterpret_cast<const uint4*>(base + (size_t)(row0 + row) * ld + c * 8);
+    r[i] = v;
+  }
+}
+
+template <int D, int ROWS, int PITCH, int DPAD, int NT = 256>
+__device__ __forceinline__ void tile_store(const TileArr<D, ROWS, NT>& r, char* lds) {
+  constexpr int CH = D / 8;
+#pragma unroll
+  for (int i = 0; i < TileRegs<D, ROWS, NT>::N; ++i) {
+    const int q = i * NT + threadIdx.x;
+    const int row = q / CH, c = q - row * CH;
+    if (q < ROWS * CH) *reinterpret_cast<uint4*>(lds + row * PITCH + c * 16) = r[i];
+  }
+  if (DPAD != D) {
+    constexpr int PADCH = (DPAD - D) / 8;
+    for (int q = threadIdx.x; q < ROWS * PADCH; q += NT) {
+      const int row = q / PADCH, c = q - row * PADCH;
+      *reinterpret_cast<uint4*>(lds + row * PITCH + (CH + c) * 16) = make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
+}  // namespace
+}  // namespace rrfp
