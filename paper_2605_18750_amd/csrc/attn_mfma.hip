@@ -334,8 +334,18 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __re
 constexpr int BQ_KV = 64;      // query rows per step of the dK/dV kernel
 constexpr int WK = 32;         // keys per wavefront of the dK/dV kernel
 #ifndef DKV_VALU_PER_MFMA
-#define DKV_VALU_PER_MFMA 8
+#define DKV_VALU_PER_MFMA 8    // vector instructions of the P / dS arithmetic issued after each MFMA of a group
 #endif
+
+// N_MFMA times (one MFMA, N_VALU vector instructions) in the instruction scheduler's order.
+template <int N_MFMA, int N_VALU>
+__device__ __forceinline__ void interleave_mfma_valu() {
+  if constexpr (N_MFMA > 0) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (N_VALU > 0) __builtin_amdgcn_sched_group_barrier(0x002, N_VALU, 0);
+    interleave_mfma_valu<N_MFMA - 1, N_VALU>();
+  }
+}
 
 template <int D>
 struct DkvCfg {
@@ -377,6 +387,9 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
     }
     kf[ds] = __builtin_bit_cast(bf16x8, v);
     vf[ds] = __builtin_bit_cast(bf16x8, w);
+    // MFMA operands only from here on: keep them in the accumulation half of the register file, which has
+    // room, so that the fragment sets and the tile in flight fit in the other half without spilling
+    asm volatile("" : "+a"(kf[ds]), "+a"(vf[ds]));
   }
   floatx16 dk[NDB], dv[NDB];
 #pragma unroll
@@ -388,60 +401,80 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
   const int nq_steps = (tl.s1 - q_begin + BQ_KV - 1) / BQ_KV;
   const int nsteps = G * nq_steps;
   uint4 rq[TileRegs<D, BQ_KV>::N], rd[TileRegs<D, BQ_KV>::N];
-  float r_lse = 0.f, r_dl = 0.f;
+  float r_stat = 0.f;
 
+  // Rows past the end of the segment repeat its last row (finite values): P and dS are exactly zero there.
   auto fetch = [&](int step) {
     const int a = b * G + step / nq_steps;
     const int q0 = q_begin + (step % nq_steps) * BQ_KV;
-    tile_load<D, BQ_KV>(rq, qkv + a * D, ld, q0, tl.s1);
-    tile_load<D, BQ_KV>(rd, d_o + a * D, nq * D, q0, tl.s1);
-    if (threadIdx.x < BQ_KV) {
-      const int i = q0 + threadIdx.x;
-      r_lse = i < tl.s1 ? lse[(size_t)a * Tn + i] * LOG2E : 0.f;
-      r_dl = i < tl.s1 ? delta[(size_t)a * Tn + i] : 0.f;
-    }
+    tile_load_clamped<D, BQ_KV>(rq, qkv + a * D, ld, q0, tl.s1);
+    tile_load_clamped<D, BQ_KV>(rd, d_o + a * D, nq * D, q0, tl.s1);
+    // row statistics: threads 0..63 bring lse, 64..127 delta, the upper half of the workgroup the same again
+    const int i = min(q0 + (int)(threadIdx.x & (BQ_KV - 1)), tl.s1 - 1);
+    const bool is_dl = (threadIdx.x & BQ_KV) != 0;
+    r_stat = (is_dl ? delta : lse)[(size_t)a * Tn + i];       // used (scaled) only in commit: no wait for it here
   };
   auto commit = [&](char* stage) {
     tile_store<D, BQ_KV, C::QP, C::DP>(rq, stage);
     tile_store<D, BQ_KV, C::QP, C::DP>(rd, stage + C::T_BYTES);
-    if (threadIdx.x < BQ_KV) {
-      reinterpret_cast<float*>(stage + 2 * C::T_BYTES)[threadIdx.x] = r_lse;
-      reinterpret_cast<float*>(stage + 2 * C::T_BYTES)[BQ_KV + threadIdx.x] = r_dl;
-    }
+    reinterpret_cast<float*>(stage + 2 * C::T_BYTES)[threadIdx.x & (2 * BQ_KV - 1)] =
+        r_stat * ((threadIdx.x & BQ_KV) ? 1.f : LOG2E);      // both halves of the workgroup write the same values
   };
   fetch(0);
   commit(smem);
   __syncthreads();
 
-  // One 64-row query step as a software pipeline over its two 32-row blocks, so that the P / dS
-  // arithmetic of one block (quarter-rate exponentials included) issues between the MFMAs of the
-  // other block instead of after them (one wavefront per SIMD: nothing else would fill the gaps):
-  //   S,dP(0) | S,dP(1) + arithmetic(0) | dV,dK(0) + arithmetic(1) | dV,dK(1)
-  // MASK is a compile-time flag so that each variant is one basic block the scheduler can interleave.
-  auto compute_step = [&](const char* sq, const char* sd, const float* s_lse, const float* s_dl, int q0, auto mask_tag) {
+  // One 64-row query step is eight groups of MFMAs over its two 32-row blocks:
+  //   S,dP(0) halves | S,dP(1) halves + arithmetic(0) | dV,dK(0) halves + arithmetic(1) | dV,dK(1) halves
+  // (S,dP halved over the head dimension, dV,dK over the 16-row halves of the block).  There is one
+  // wavefront per SIMD, so nothing but this wavefront's own instruction stream can fill the MFMA pipe:
+  // every group issues the LDS fragment reads of the NEXT group before its own MFMAs (two fragment sets
+  // alive, used in turn), and the P / dS arithmetic of a 16-row half (quarter-rate exponentials
+  // included) issues between the MFMAs of a group that does not depend on it.  The next tile goes to
+  // LDS before the sixth group; the step's one barrier sits between the last two groups, under MFMAs in
+  // flight; the last group reads the first fragments of the step after, from the other LDS stage.
+  // MASK is a compile-time flag so that each variant of the step is one basic block.
+  constexpr int NH0 = (NDS + 1) / 2, NH1 = NDS - NH0;      // head-dimension slices of 16 in the two halves
+  constexpr int FS = NH0 > NDB ? NH0 : NDB;
+  struct FragSet { bf16x8 a[FS], b[FS]; };                // (Q, dO) row fragments or (dO^T, Q^T) transposed ones
+  FragSet fx;                                              // carried from step to step: rows of block 0, first half
+  auto load_rows = [&](const char* sq, const char* sd, int ib, int half, FragSet& f) {
+#pragma unroll
+    for (int i = 0; i < (half ? NH1 : NH0); ++i) {
+      f.a[i] = frag_rows(sq, C::QP, ib * 32, half * NH0 + i, lane);
+      f.b[i] = frag_rows(sd, C::QP, ib * 32, half * NH0 + i, lane);
+    }
+  };
+  auto compute_step = [&](const char* sq, const char* sd, const float* s_lse, const float* s_dl, int q0, int next_step,
+                          char* next_stage, auto mask_tag) {
     constexpr bool MASK = decltype(mask_tag)::value;
     floatx16 sacc[2], dpacc[2];
     bf16x8 pf[2][2], dsf[2][2];
-    auto sdp = [&](int ib) {
-      bf16x8 qa[NDS], da[NDS];
+    FragSet fy;
+    auto load_tr = [&](int ib, int u, FragSet& f) {
 #pragma unroll
-      for (int ds = 0; ds < NDS; ++ds) {
-        qa[ds] = frag_rows(sq, C::QP, ib * 32, ds, lane);
-        da[ds] = frag_rows(sd, C::QP, ib * 32, ds, lane);
-      }
-#pragma unroll
-      for (int e = 0; e < 16; ++e) { sacc[ib][e] = 0.f; dpacc[ib][e] = 0.f; }
-#pragma unroll
-      for (int ds = 0; ds < NDS; ++ds) {
-        sacc[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ds], kf[ds], sacc[ib], 0, 0, 0);
-        dpacc[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da[ds], vf[ds], dpacc[ib], 0, 0, 0);
+      for (int db = 0; db < NDB; ++db) {
+        f.a[db] = frag_cols_tr(sd, C::QP, ib * 32 + u * 16, db * 32, lane);
+        f.b[db] = frag_cols_tr(sq, C::QP, ib * 32 + u * 16, db * 32, lane);
       }
     };
-    auto arith = [&](int ib) {
-      // accumulator value e belongs to row ib*32 + (e/4)*8 + h*4 + e%4
-      float pv[16], dsv[16];
+    auto sdp = [&](int ib, int half, const FragSet& f) {
+      if (half == 0) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
+        for (int e = 0; e < 16; ++e) { sacc[ib][e] = 0.f; dpacc[ib][e] = 0.f; }
+      }
+#pragma unroll
+      for (int i = 0; i < (half ? NH1 : NH0); ++i) {
+        sacc[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], kf[half * NH0 + i], sacc[ib], 0, 0, 0);
+        dpacc[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[i], vf[half * NH0 + i], dpacc[ib], 0, 0, 0);
+      }
+    };
+    auto arith = [&](int ib, int u) {
+      // accumulator value e belongs to row ib*32 + (e/4)*8 + h*4 + e%4; half u holds e = 8u .. 8u+7
+      float pv[8], dsv[8];
+#pragma unroll
+      for (int gg = 0; gg < 2; ++gg) {
+        const int g = u * 2 + gg;
         const int il = ib * 32 + g * 8 + h * 4;
         const float4 l4 = *reinterpret_cast<const float4*>(s_lse + il);
         const float4 d4 = *reinterpret_cast<const float4*>(s_dl + il);
@@ -454,53 +487,65 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
             const int i = q0 + il + c;
             p = (i >= tl.s1 || j >= tl.r1 || (causal && j > i)) ? 0.f : p;
           }
-          pv[e] = p;
-          dsv[e] = p * (dpacc[ib][e] - dl4[c]);    // masked entries: P = 0 and dP finite, so dS = 0
+          pv[gg * 4 + c] = p;
+          dsv[gg * 4 + c] = p * (dpacc[ib][e] - dl4[c]);    // masked entries: P = 0 and dP finite, so dS = 0
         }
       }
-#pragma unroll
-      for (int u = 0; u < 2; ++u) { pf[ib][u] = pack8(pv + u * 8); dsf[ib][u] = pack8(dsv + u * 8); }
+      pf[ib][u] = pack8(pv);
+      dsf[ib][u] = pack8(dsv);
     };
-    auto dvdk = [&](int ib) {
+    auto dvdk = [&](int ib, int u, const FragSet& f) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        bf16x8 td[NDB], tq[NDB];
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          td[db] = frag_cols_tr(sd, C::QP, ib * 32 + u * 16, db * 32, lane);
-          tq[db] = frag_cols_tr(sq, C::QP, ib * 32 + u * 16, db * 32, lane);
-        }
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td[db], pf[ib][u], dv[db], 0, 0, 0);
-          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[db], dsf[ib][u], dk[db], 0, 0, 0);
-        }
+      for (int db = 0; db < NDB; ++db) {
+        dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[db], pf[ib][u], dv[db], 0, 0, 0);
+        dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[db], dsf[ib][u], dk[db], 0, 0, 0);
       }
     };
-    constexpr int NM_SDP = 2 * NDS;          // MFMAs of one S,dP block
-    constexpr int NM_DVK = 4 * NDB;          // MFMAs of one dV,dK block
-    sdp(0);
+    // Order inside a group: the LDS reads first, then one MFMA per handful of vector instructions.
+    auto group_order = [&](auto n_reads, auto n_mfma, auto n_valu) {
+      __builtin_amdgcn_sched_group_barrier(0x100, decltype(n_reads)::value, 0);
+      interleave_mfma_valu<decltype(n_mfma)::value, decltype(n_valu)::value>();
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    constexpr int V = DKV_VALU_PER_MFMA;
+#define RRFP_IC(x) std::integral_constant<int, (x)>{}
+    // S,dP of block 0; the next tile's global loads (after the last step: the same tile again, never used)
+    fetch(min(next_step, nsteps - 1));
+    load_rows(sq, sd, 0, 1, fy);
+    sdp(0, 0, fx);
+    group_order(RRFP_IC(2 * NH1), RRFP_IC(2 * NH0), RRFP_IC(0));
+    load_rows(sq, sd, 1, 0, fx);
+    sdp(0, 1, fy);
+    group_order(RRFP_IC(2 * NH0), RRFP_IC(2 * NH1), RRFP_IC(0));
+    // S,dP of block 1 with the arithmetic of block 0
+    load_rows(sq, sd, 1, 1, fy);
+    sdp(1, 0, fx);
+    arith(0, 0);
+    group_order(RRFP_IC(2 * NH1 + 4), RRFP_IC(2 * NH0), RRFP_IC(V));
+    load_tr(0, 0, fx);
+    sdp(1, 1, fy);
+    arith(0, 1);
+    group_order(RRFP_IC(4 * NDB + 4), RRFP_IC(2 * NH1), RRFP_IC(V));
+    // dV,dK of block 0 with the arithmetic of block 1
+    load_tr(0, 1, fy);
+    dvdk(0, 0, fx);
+    arith(1, 0);
+    group_order(RRFP_IC(4 * NDB + 4), RRFP_IC(2 * NDB), RRFP_IC(V));
+    commit(next_stage);
     __builtin_amdgcn_sched_barrier(0);
-    sdp(1);
-    arith(0);
-    // fragment reads first, then one MFMA per handful of vector instructions
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 * NDS, 0);
-#pragma unroll
-    for (int k = 0; k < NM_SDP; ++k) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, DKV_VALU_PER_MFMA, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    dvdk(0);
-    arith(1);
-    __builtin_amdgcn_sched_group_barrier(0x100, 8 * NDB, 0);
-#pragma unroll
-    for (int k = 0; k < NM_DVK; ++k) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, DKV_VALU_PER_MFMA, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    dvdk(1);
+    load_tr(1, 0, fx);
+    dvdk(0, 1, fy);
+    arith(1, 1);
+    group_order(RRFP_IC(4 * NDB + 4), RRFP_IC(2 * NDB), RRFP_IC(V));
+    // dV,dK of block 1
+    load_tr(1, 1, fy);
+    dvdk(1, 0, fx);
+    group_order(RRFP_IC(4 * NDB), RRFP_IC(2 * NDB), RRFP_IC(0));
+    __syncthreads();
+    load_rows(next_stage, next_stage + C::T_BYTES, 0, 0, fx);   // stale data after the last step: read, never used
+    dvdk(1, 1, fy);
+    group_order(RRFP_IC(2 * NH0), RRFP_IC(2 * NDB), RRFP_IC(0));
+#undef RRFP_IC
   };
 
   // Steps are (query head of the group, 64-row query block) pairs in ascending order.  Under a causal
@@ -513,17 +558,14 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
                          : (causal ? min(nq_steps, max(n_skip, (wj0 + WK - 1 - q_begin + BQ_KV - 1) / BQ_KV)) : n_skip);
   const int t_tail_begin = (q_begin + nq_steps * BQ_KV > tl.s1) ? nq_steps - 1 : nq_steps;
   auto run_steps = [&](int t, int t_end, int& st, auto mask_tag) -> int {
+    if (t < t_end) load_rows(smem + (st & 1) * C::STAGE, smem + (st & 1) * C::STAGE + C::T_BYTES, 0, 0, fx);
     for (; t < t_end; ++t, ++st) {
       const int q0 = q_begin + t * BQ_KV;
       const char* sq = smem + (st & 1) * C::STAGE;
       const char* sd = sq + C::T_BYTES;
       const float* s_lse = reinterpret_cast<const float*>(sq + 2 * C::T_BYTES);
       const float* s_dl = s_lse + BQ_KV;
-      const bool more = st + 1 < nsteps;
-      if (more) fetch(st + 1);
-      compute_step(sq, sd, s_lse, s_dl, q0, mask_tag);
-      if (more) commit(smem + ((st + 1) & 1) * C::STAGE);
-      __syncthreads();
+      compute_step(sq, sd, s_lse, s_dl, q0, st + 1, smem + ((st + 1) & 1) * C::STAGE, mask_tag);
     }
     return t;
   };

@@ -67,6 +67,22 @@ __device__ __forceinline__ void tile_load(TileArr<D, ROWS, NT>& r, const bf16_t*
   }
 }
 
+// The same without branches: rows at or past row_end (row_end > row0) re-read row row_end - 1, and a lane
+// whose chunk lies past the tile re-reads the tile's last chunk (tile_store drops it).  For tiles whose
+// rows past the end only ever meet zero weights.
+template <int D, int ROWS, int NT = 256>
+__device__ __forceinline__ void tile_load_clamped(TileArr<D, ROWS, NT>& r, const bf16_t* __restrict__ base, int ld,
+                                                  int row0, int row_end) {
+  constexpr int CH = D / 8;
+#pragma unroll
+  for (int i = 0; i < TileRegs<D, ROWS, NT>::N; ++i) {
+    const int q = min(i * NT + (int)threadIdx.x, ROWS * CH - 1);
+    const int row = q / CH, c = q - row * CH;
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // a plain vector load: the register array stays in registers
+    r[i] = __builtin_bit_cast(uint4, *reinterpret_cast<const u32x4*>(base + (size_t)min(row0 + row, row_end - 1) * ld + c * 8));
+  }
+}
+
 template <int D, int ROWS, int PITCH, int DPAD, int NT = 256>
 __device__ __forceinline__ void tile_store(const TileArr<D, ROWS, NT>& r, char* lds) {
   constexpr int CH = D / 8;
@@ -74,7 +90,7 @@ __device__ __forceinline__ void tile_store(const TileArr<D, ROWS, NT>& r, char* 
   for (int i = 0; i < TileRegs<D, ROWS, NT>::N; ++i) {
     const int q = i * NT + threadIdx.x;
     const int row = q / CH, c = q - row * CH;
-    if (q < ROWS * CH) *reinterpret_cast<uint4*>(lds + row * PITCH + c * 16) = r[i];
+    if ((ROWS * CH) % NT == 0 || q < ROWS * CH) *reinterpret_cast<uint4*>(lds + row * PITCH + c * 16) = r[i];
   }
   if (DPAD != D) {
     constexpr int PADCH = (DPAD - D) / 8;
