@@ -415,8 +415,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
     r_stat = (is_dl ? delta : lse)[(size_t)a * Tn + i];       // used (scaled) only in commit: no wait for it here
   };
   auto commit = [&](char* stage) {
-    tile_store<D, BQ_KV, C::QP, C::DP>(rq, stage);
-    tile_store<D, BQ_KV, C::QP, C::DP>(rd, stage + C::T_BYTES);
+    tile_store<D, BQ_KV, C::QP, C::DP, 256, true>(rq, stage);
+    tile_store<D, BQ_KV, C::QP, C::DP, 256, true>(rd, stage + C::T_BYTES);
     reinterpret_cast<float*>(stage + 2 * C::T_BYTES)[threadIdx.x & (2 * BQ_KV - 1)] =
         r_stat * ((threadIdx.x & BQ_KV) ? 1.f : LOG2E);      // both halves of the workgroup write the same values
   };

@@ -83,14 +83,16 @@ __device__ __forceinline__ void tile_load_clamped(TileArr<D, ROWS, NT>& r, const
   }
 }
 
-template <int D, int ROWS, int PITCH, int DPAD, int NT = 256>
+// STATIC_FULL: leave out the per-chunk guard where the chunk count is a multiple of the thread count (the guard
+// is always true there, but as a run-time test it splits the caller's basic block).
+template <int D, int ROWS, int PITCH, int DPAD, int NT = 256, bool STATIC_FULL = false>
 __device__ __forceinline__ void tile_store(const TileArr<D, ROWS, NT>& r, char* lds) {
   constexpr int CH = D / 8;
 #pragma unroll
   for (int i = 0; i < TileRegs<D, ROWS, NT>::N; ++i) {
     const int q = i * NT + threadIdx.x;
     const int row = q / CH, c = q - row * CH;
-    if ((ROWS * CH) % NT == 0 || q < ROWS * CH) *reinterpret_cast<uint4*>(lds + row * PITCH + c * 16) = r[i];
+    if ((STATIC_FULL && (ROWS * CH) % NT == 0) || q < ROWS * CH) *reinterpret_cast<uint4*>(lds + row * PITCH + c * 16) = r[i];
   }
   if (DPAD != D) {
     constexpr int PADCH = (DPAD - D) / 8;
