@@ -44,16 +44,14 @@ __device__ __forceinline__ void kv_load(KvRegs<D, NT>& rk, KvRegs<D, NT>& rv,
   using C = FwdCfg<D, NT>;
 #pragma unroll
   for (int i = 0; i < C::PER_THREAD; ++i) {
-    const int q = i * NT + threadIdx.x;
+    // No branches: a thread past the last chunk repeats that chunk (kv_store drops it) and rows at or past
+    // k_end repeat row k_end - 1 (finite values; those keys are masked, so their probabilities are zero).
+    const int q = min(i * NT + (int)threadIdx.x, C::NCHUNK - 1);
     const int row = q / C::CH, c = q - row * C::CH;
-    uint4 a = make_uint4(0, 0, 0, 0), b = a;
-    if (q < C::NCHUNK && k0 + row < k_end) {
-      const bf16_t* p = qkv + (size_t)(k0 + row) * ld + c * 8;
-      a = *reinterpret_cast<const uint4*>(p + kcol);
-      b = *reinterpret_cast<const uint4*>(p + vcol);
-    }
-    rk[i] = a;
-    rv[i] = b;
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const bf16_t* p = qkv + (size_t)min(k0 + row, k_end - 1) * ld + c * 8;
+    rk[i] = __builtin_bit_cast(uint4, *reinterpret_cast<const u32x4*>(p + kcol));
+    rv[i] = __builtin_bit_cast(uint4, *reinterpret_cast<const u32x4*>(p + vcol));
   }
 }
 
@@ -65,7 +63,7 @@ __device__ __forceinline__ void kv_store(const KvRegs<D, NT>& rk, const KvRegs<D
   for (int i = 0; i < C::PER_THREAD; ++i) {
     const int q = i * NT + threadIdx.x;
     const int row = q / C::CH, c = q - row * C::CH;
-    if (q < C::NCHUNK) {
+    if (C::NCHUNK % NT == 0 || q < C::NCHUNK) {
       *reinterpret_cast<uint4*>(stage + row * C::KP + c * 16) = rk[i];
       *reinterpret_cast<uint4*>(stage + C::K_BYTES + row * C::VP + c * 16) = rv[i];
     }
