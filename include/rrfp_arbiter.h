@@ -96,6 +96,35 @@ typedef struct {
 int rrfp_sim_run(const rrfp_sim_config* cfg, const double* dur_f, const double* dur_b, const double* dur_w,
                  rrfp_sim_result* result, double* per_stage, rrfp_sim_event* trace, int64_t trace_cap);
 
+/* ---- the same event loop, one dispatch at a time (for a runtime that enqueues real stage tasks) -------
+ * rrfp_sim_run is a loop over these calls with durations from its tables.  A runtime on one GPU drives them
+ * itself: rrfp_pipe_next advances the virtual clock to the next dispatch (completions, message arrivals after
+ * the latency, and one arbitration per idle stage, in stage order: Sec. 4.1, Sec. 5, App. A) and names the task
+ * and the producer of its input tensor; the caller enqueues stage_F / stage_B / stage_W for it, measures or
+ * chooses its duration and reports it with rrfp_pipe_set_duration before the next rrfp_pipe_next.  With
+ * jitter_p > 0 in the configuration the delay of Sec. 7.6 for this task (F and B only) is drawn by the
+ * library, added to the task's duration and returned, so that the caller can put rrfp_delay(delay) behind the
+ * task on its stream.  mode must be 0 for real runs; modes 1 and 2 are the reference executions of Sec. 6. */
+typedef struct rrfp_pipe rrfp_pipe_t;
+typedef struct {
+  int32_t stage, dir, microbatch, chunk;
+  int32_t src_stage, src_chunk;   /* (stage, chunk) whose task of the same direction and microbatch produced this
+                                     task's input; -1, -1 = the caller's tensor (the pipeline input for F at the
+                                     first virtual stage, the output gradient for B at the last).  For W: -1, -1. */
+  double start;                   /* virtual time of the dispatch */
+} rrfp_pipe_dispatch;
+/* NULL + arbiter_last_error(NULL) on an invalid configuration.  Host memory, freed by rrfp_pipe_destroy. */
+rrfp_pipe_t* rrfp_pipe_create(const rrfp_sim_config* cfg);
+void rrfp_pipe_destroy(rrfp_pipe_t* p);
+/* ARB_TASK: *out is the next dispatched task; ARB_DONE: every task of the iteration has completed;
+ * ARB_ESTATE: the previous task still waits for its duration, or the pipeline stalled (unfinished work and
+ * nothing in flight); ARB_EINVAL: NULL argument. */
+int rrfp_pipe_next(rrfp_pipe_t* p, rrfp_pipe_dispatch* out);
+/* Duration in seconds (>= 0) of the task rrfp_pipe_next returned last.  *delay_seconds (may be NULL) receives
+ * the injected jitter delay (0 if none), *end (may be NULL) the task's virtual completion time
+ * start + (seconds + delay). */
+int rrfp_pipe_set_duration(rrfp_pipe_t* p, double seconds, double* delay_seconds, double* end);
+
 /* ---- jitter injector for real task streams (Sec. 7.6) ----------------------------------------------
  * The per-stage state of the jitter model above, for a runtime that measures its own tasks: feed the
  * measured compute time of each F/B task of the stage in execution order; the return value is the

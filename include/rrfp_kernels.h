@@ -44,6 +44,33 @@ int rrfp_gemm(const void* A, const void* B, void* C, const void* R, int M, int N
 int rrfp_gemm_plan(int M, int N, int K, int lda, int ldb, int ldc, int trans_a, int trans_b, int out_dtype,
                    int have_scratch, int n_cu, int32_t out[5]);
 
+/* ---- HBM-bound kernels of the tasks, one by one (steps a1, a10 and a13 of the F and B tasks and of the
+ * gradient reduction; paper Section 3.1 for the tasks, Section 7.1 for the requirement that the result must
+ * not depend on the order tasks ran in, which is why every sum here has one fixed order). ---------------- */
+
+/* RMSNorm forward: h[t,:] = x[t,:] * r[t] * g, r[t] = (mean_c x[t,c]^2 + eps)^-1/2.  x: device fp32 [T,H]
+ * (the residual stream); g: device [H] storage dtype; h: device [T,H] storage dtype, written; r_out: device
+ * fp32 [T], written.  dtype = STAGE_DTYPE_*.  STAGE_EINVAL for NULL pointers or non-positive sizes. */
+int rrfp_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_out, int T, int H, float eps, int dtype,
+                     void* stream);
+
+/* Bytes of workspace rrfp_rmsnorm_bwd needs for this shape (partial gain-gradient rows); pure host. */
+size_t rrfp_rmsnorm_bwd_workspace(int T, int H, int dtype);
+
+/* RMSNorm backward: dx = add_in + r (w - xhat mean_c(w xhat)), w = dh g, xhat = x r; dg[c] = sum_t dh[t,c] xhat[t,c]
+ * with the rows added in one fixed order (per-chunk partial rows in `workspace`, then a fixed-order column sum).
+ * dh, x, add_in: device fp32 [T,H]; r: device fp32 [T]; g: device [H] storage dtype; out32 (fp32) and out_t
+ * (storage dtype): device [T,H], written, either may be NULL; dg: device fp32 [H], written; workspace: device,
+ * caller-owned, at least rrfp_rmsnorm_bwd_workspace bytes, 16-byte aligned, contents undefined afterwards.
+ * STAGE_EINVAL for NULL inputs, a too small workspace or non-positive sizes. */
+int rrfp_rmsnorm_bwd(const float* dh, const float* x, const float* r, const void* g, const float* add_in,
+                     float* out32, void* out_t, float* dg, void* workspace, size_t workspace_bytes, int T, int H,
+                     int dtype, void* stream);
+
+/* out[i] = ((s_0[i] + s_1[i]) + s_2[i]) + ... + s_{M-1}[i] for i < n, slot j at slots + j * slot_stride floats.
+ * All device fp32; n and slot_stride multiples of 4, pointers 16-byte aligned. */
+int rrfp_grad_reduce(const float* slots, size_t slot_stride, int M, float* out, size_t n, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

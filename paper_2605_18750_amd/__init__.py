@@ -59,6 +59,14 @@ def lib() -> C.CDLL:
         L.rrfp_gemm.restype = C.c_int
         L.rrfp_gemm_plan.argtypes = [C.c_int] * 11 + [C.POINTER(C.c_int32)]
         L.rrfp_gemm_plan.restype = C.c_int
+        L.rrfp_rmsnorm_fwd.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_float, C.c_int, vp]
+        L.rrfp_rmsnorm_fwd.restype = C.c_int
+        L.rrfp_rmsnorm_bwd_workspace.argtypes = [C.c_int, C.c_int, C.c_int]
+        L.rrfp_rmsnorm_bwd_workspace.restype = sz
+        L.rrfp_rmsnorm_bwd.argtypes = [vp] * 9 + [sz, C.c_int, C.c_int, C.c_int, vp]
+        L.rrfp_rmsnorm_bwd.restype = C.c_int
+        L.rrfp_grad_reduce.argtypes = [vp, sz, C.c_int, vp, sz, vp]
+        L.rrfp_grad_reduce.restype = C.c_int
         for f in ("stage_query", "stage_param_layout", "stage_create", "stage_create_dry", "stage_F",
                   "stage_B", "stage_W", "stage_grad_reduce", "stage_grad_slot", "stage_destroy"):
             getattr(L, f).restype = C.c_int
@@ -175,6 +183,29 @@ def rrfp_gemm_plan(M, N, K, trans_a, trans_b, out_dtype, n_cu=256, have_scratch=
     if rc != STAGE_OK:
         raise StageError(rc, "rrfp_gemm_plan rejected its arguments")
     return dict(zip(("kernel", "wavefronts", "main_workgroups", "short_workgroups", "split_k"), (int(v) for v in out)))
+
+
+def _kcheck(rc: int, name: str):
+    if rc != STAGE_OK:
+        raise StageError(rc, f"{name} rejected its arguments" if rc == STAGE_EINVAL else f"{name}: HIP launch failed")
+
+
+def rrfp_rmsnorm_fwd(x, g, h, r_out, T: int, H: int, eps: float, dtype: int, stream=None):
+    _kcheck(lib().rrfp_rmsnorm_fwd(_ptr(x), _ptr(g), _ptr(h), _ptr(r_out), T, H, eps, dtype, _stream(stream)), "rrfp_rmsnorm_fwd")
+
+
+def rrfp_rmsnorm_bwd_workspace(T: int, H: int, dtype: int) -> int:
+    return lib().rrfp_rmsnorm_bwd_workspace(T, H, dtype)
+
+
+def rrfp_rmsnorm_bwd(dh, x, r, g, add_in, out32, out_t, dg, workspace, workspace_bytes: int, T: int, H: int, dtype: int,
+                     stream=None):
+    _kcheck(lib().rrfp_rmsnorm_bwd(_ptr(dh), _ptr(x), _ptr(r), _ptr(g), _ptr(add_in), _ptr(out32), _ptr(out_t), _ptr(dg),
+                                   _ptr(workspace), workspace_bytes, T, H, dtype, _stream(stream)), "rrfp_rmsnorm_bwd")
+
+
+def rrfp_grad_reduce(slots, slot_stride: int, M: int, out, n: int, stream=None):
+    _kcheck(lib().rrfp_grad_reduce(_ptr(slots), slot_stride, M, _ptr(out), n, _stream(stream)), "rrfp_grad_reduce")
 
 
 def stage_destroy(st):

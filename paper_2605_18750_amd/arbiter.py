@@ -34,6 +34,11 @@ class rrfp_sim_event(C.Structure):
                 ("start", C.c_double), ("end", C.c_double)]
 
 
+class rrfp_pipe_dispatch(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("stage", "dir", "microbatch", "chunk", "src_stage", "src_chunk")] + [
+        ("start", C.c_double)]
+
+
 class rrfp_sim_result(C.Structure):
     _fields_ = [("makespan", C.c_double), ("n_events", C.c_int64), ("deadlock", C.c_int32)]
 
@@ -65,6 +70,14 @@ def _lib():
         L.arbiter_last_error.restype = C.c_char_p
         L.rrfp_sim_run.argtypes = [C.POINTER(rrfp_sim_config), vp, vp, vp, C.POINTER(rrfp_sim_result), vp,
                                    C.POINTER(rrfp_sim_event), C.c_int64]
+        L.rrfp_pipe_create.argtypes = [C.POINTER(rrfp_sim_config)]
+        L.rrfp_pipe_create.restype = vp
+        L.rrfp_pipe_destroy.argtypes = [vp]
+        L.rrfp_pipe_destroy.restype = None
+        L.rrfp_pipe_next.argtypes = [vp, C.POINTER(rrfp_pipe_dispatch)]
+        L.rrfp_pipe_next.restype = C.c_int
+        L.rrfp_pipe_set_duration.argtypes = [vp, C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.rrfp_pipe_set_duration.restype = C.c_int
         L.jitter_create.argtypes = [C.c_double, C.c_double, C.c_double, C.c_uint64, C.c_int32, C.c_int32, C.c_int32]
         L.jitter_create.restype = vp
         L.jitter_destroy.argtypes = [vp]
@@ -159,6 +172,38 @@ def rrfp_sim_run(n_stages: int, n_microbatches: int, dur_f, dur_b, dur_w=None, *
         n = min(res.n_events, cap)
         out["trace"] = [(e.stage, e.dir, e.microbatch, e.chunk, e.start, e.end) for e in trace[:n]]
     return out
+
+
+def rrfp_pipe_create(n_stages: int, n_microbatches: int, n_chunks: int = 1, hint: int = ARB_HINT_BFW,
+                     buffer_limit: int = 0, latency: float = 0.0, jitter=(0.0, 0.0, 0.0, 0)):
+    """The pipeline event loop as an object; jitter = (p, base seconds, alpha, seed)."""
+    cfg = rrfp_sim_config(n_stages, n_microbatches, n_chunks, hint, buffer_limit, 0, latency,
+                          jitter[0], jitter[1], jitter[2], jitter[3])
+    p = _lib().rrfp_pipe_create(C.byref(cfg))
+    if not p:
+        raise ArbiterError(ARB_EINVAL, arbiter_last_error(None))
+    return p
+
+
+def rrfp_pipe_destroy(p):
+    _lib().rrfp_pipe_destroy(p)
+
+
+def rrfp_pipe_next(p):
+    """(ARB_TASK, dispatch) with dispatch = (stage, dir, microbatch, chunk, src_stage, src_chunk, start),
+    or (ARB_DONE, None)."""
+    d = rrfp_pipe_dispatch()
+    rc = _check(_lib().rrfp_pipe_next(p, C.byref(d)))
+    if rc == ARB_TASK:
+        return rc, (d.stage, d.dir, d.microbatch, d.chunk, d.src_stage, d.src_chunk, d.start)
+    return rc, None
+
+
+def rrfp_pipe_set_duration(p, seconds: float):
+    """-> (injected delay in seconds, virtual completion time) of the task rrfp_pipe_next returned last."""
+    delay, end = C.c_double(), C.c_double()
+    _check(_lib().rrfp_pipe_set_duration(p, seconds, C.byref(delay), C.byref(end)))
+    return delay.value, end.value
 
 
 def jitter_create(p: float, base_seconds: float, alpha: float, seed: int, stage: int, n_microbatches: int,

@@ -301,134 +301,246 @@ extern "C" double jitter_next_delay(jitter_t* j, int32_t dir, int32_t microbatch
   return 0.0;
 }
 
-extern "C" int rrfp_sim_run(const rrfp_sim_config* cfg, const double* dur_f, const double* dur_b, const double* dur_w,
-                            rrfp_sim_result* result, double* per_stage, rrfp_sim_event* trace, int64_t trace_cap) {
-  if (!cfg || !result || !dur_f || !dur_b) return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: NULL argument");
-  const int N = cfg->n_stages, M = cfg->n_microbatches, C = cfg->n_chunks;
-  if (N < 1 || M < 1 || C < 1 || cfg->mode < 0 || cfg->mode > 2 || cfg->latency < 0 || (trace && trace_cap < 0))
-    return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: invalid configuration");
-  if (cfg->hint == ARB_HINT_BFW && !dur_w) return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: BFW needs dur_w");
-  const bool fwd_only = cfg->mode == 1, bwd_only = cfg->mode == 2, only = cfg->mode != 0;
-  std::vector<arbiter*> st(N, nullptr);
-  auto cleanup = [&]() { for (auto* a : st) arbiter_destroy(a); };
-  for (int s = 0; s < N; ++s) {
-    arbiter_config ac{M, C, cfg->hint, cfg->buffer_limit, s, N};
-    if (only) {
-      // reference executions: one direction only; the stage index is set so that no turn-around and
-      // no self-admission happens inside the arbiter, the simulator seeds the first buffer itself
-      ac.hint = ARB_HINT_BF;
-      ac.buffer_limit = 0;
-    }
-    st[s] = arbiter_create(&ac);
-    if (!st[s]) { cleanup(); return ARB_EINVAL; }
-  }
+// The event loop of a whole pipeline as a resumable object: rrfp_pipe_next() advances the virtual clock to
+// the next dispatch and returns it; the caller supplies that task's duration before asking again.  The
+// simulator below and a runtime that enqueues real stage tasks both drive this one loop, so the routing
+// rule (who sends which message to whom, Sec. 4.1; the local turn-around at the last stage, App. C.1) exists
+// once.
+struct rrfp_pipe {
+  rrfp_sim_config cfg{};
+  int N = 0, M = 0, C = 0;
+  bool fwd_only = false, bwd_only = false, only = false;
+  std::vector<arbiter*> st;
   struct Run { bool busy = false; arbiter_task t{}; double end = 0; };
-  std::vector<Run> run(N);
+  std::vector<Run> run;
   std::priority_queue<Arrival, std::vector<Arrival>, std::greater<Arrival>> arrivals;
-  std::vector<double> busy(N, 0.0);
-  std::vector<jitter> inject(N);
-  for (int s = 0; s < N; ++s) {
-    inject[s].p = cfg->jitter_p; inject[s].base = cfg->jitter_base; inject[s].alpha = cfg->jitter_alpha;
-    inject[s].seed = cfg->jitter_seed; inject[s].stage = s; inject[s].M = M; inject[s].C = C;
-  }
-  std::vector<int64_t> fwd_held(N, 0), bwd_held(N, 0), max_f(N, 0), max_b(N, 0), max_D(N, 0), done(N, 0);
-  const int64_t only_target = (int64_t)M * C;
-  int64_t n_events = 0;
-  double makespan = 0.0;
+  std::vector<double> busy;
+  std::vector<jitter> inject;
+  std::vector<int64_t> fwd_held, bwd_held, max_f, max_b, max_D, done;
+  int64_t only_target = 0, n_events = 0;
+  double makespan = 0.0, t = 0.0;
+  int scan = -1;            // -1: completions and arrivals at time t not processed yet; else next stage to arbitrate
+  int pending = -1;         // stage whose dispatched task still waits for its duration
+  bool finished = false, deadlock = false;
 
-  auto deliver = [&](int s, int dir, int j, int c) {
+  ~rrfp_pipe() { for (auto* a : st) arbiter_destroy(a); }
+
+  void deliver(int s, int dir, int j, int c) {
     arbiter_post_ready(st[s], dir, j, c);
     if (dir == ARB_F) { if (++fwd_held[s] > max_f[s]) max_f[s] = fwd_held[s]; }
     else { if (++bwd_held[s] > max_b[s]) max_b[s] = bwd_held[s]; }
-  };
-  if (bwd_only) {
-    // all backward work available at the last stage: mark the local forwards as done first
-    for (int s = 0; s < N; ++s)
-      for (int c = 0; c < C; ++c)
-        for (int j = 0; j < M; ++j) st[s]->done[ARB_F][c].set(j);
-    for (int j = 0; j < M; ++j) deliver(N - 1, ARB_B, j, C - 1);
-    // stage 0's self-admitted forwards are not part of this reference run
-    st[0]->ready[ARB_F][0].clear();
-    st[0]->n_ready[ARB_F] = 0;
   }
-  auto finish = [&](int s, const arbiter_task& t, double at) {
-    if (!(fwd_only && s == N - 1 && t.dir == ARB_F && t.chunk == C - 1)) {
-      arbiter_complete(st[s], &t);
+
+  bool init(const rrfp_sim_config* c) {
+    cfg = *c;
+    N = c->n_stages; M = c->n_microbatches; C = c->n_chunks;
+    fwd_only = c->mode == 1; bwd_only = c->mode == 2; only = c->mode != 0;
+    st.assign(N, nullptr);
+    for (int s = 0; s < N; ++s) {
+      arbiter_config ac{M, C, c->hint, c->buffer_limit, s, N};
+      if (only) {
+        // reference executions: one direction only; no backpressure, the loop seeds the first buffer itself
+        ac.hint = ARB_HINT_BF;
+        ac.buffer_limit = 0;
+      }
+      st[s] = arbiter_create(&ac);
+      if (!st[s]) return false;
+    }
+    run.assign(N, Run{});
+    busy.assign(N, 0.0);
+    inject.assign(N, jitter{});
+    for (int s = 0; s < N; ++s) {
+      inject[s].p = c->jitter_p; inject[s].base = c->jitter_base; inject[s].alpha = c->jitter_alpha;
+      inject[s].seed = c->jitter_seed; inject[s].stage = s; inject[s].M = M; inject[s].C = C;
+    }
+    fwd_held.assign(N, 0); bwd_held.assign(N, 0); max_f.assign(N, 0); max_b.assign(N, 0); max_D.assign(N, 0); done.assign(N, 0);
+    only_target = (int64_t)M * C;
+    if (bwd_only) {
+      // all backward work available at the last stage: mark the local forwards as done first
+      for (int s = 0; s < N; ++s)
+        for (int cc = 0; cc < C; ++cc)
+          for (int j = 0; j < M; ++j) st[s]->done[ARB_F][cc].set(j);
+      for (int j = 0; j < M; ++j) deliver(N - 1, ARB_B, j, C - 1);
+      // stage 0's self-admitted forwards are not part of this reference run
+      st[0]->ready[ARB_F][0].clear();
+      st[0]->n_ready[ARB_F] = 0;
+    }
+    return true;
+  }
+
+  // A task of stage s has ended at time `at`: completion bookkeeping and the message it sends.
+  void finish(int s, const arbiter_task& tk, double at) {
+    if (!(fwd_only && s == N - 1 && tk.dir == ARB_F && tk.chunk == C - 1)) {
+      arbiter_complete(st[s], &tk);
     } else {
       // forward-only reference: no turn-around at the last stage
       st[s]->in_flight = false;
       ++st[s]->count[ARB_F];
-      st[s]->done[ARB_F][t.chunk].set(t.microbatch);
+      st[s]->done[ARB_F][tk.chunk].set(tk.microbatch);
     }
     ++done[s];
-    if (t.dir == ARB_F) {
-      if (s + 1 < N) arrivals.push(Arrival{at + cfg->latency, s + 1, ARB_F, t.microbatch, t.chunk});
-      else if (t.chunk + 1 < C) arrivals.push(Arrival{at + cfg->latency, 0, ARB_F, t.microbatch, t.chunk + 1});
+    if (tk.dir == ARB_F) {
+      if (s + 1 < N) arrivals.push(Arrival{at + cfg.latency, s + 1, ARB_F, tk.microbatch, tk.chunk});
+      else if (tk.chunk + 1 < C) arrivals.push(Arrival{at + cfg.latency, 0, ARB_F, tk.microbatch, tk.chunk + 1});
       else if (!fwd_only) { if (++bwd_held[s] > max_b[s]) max_b[s] = bwd_held[s]; }   // local move (done inside the arbiter)
-    } else if (t.dir == ARB_B) {
+    } else if (tk.dir == ARB_B) {
       if (!bwd_only) --fwd_held[s];
       --bwd_held[s];
-      if (s > 0) arrivals.push(Arrival{at + cfg->latency, s - 1, ARB_B, t.microbatch, t.chunk});
-      else if (t.chunk > 0) arrivals.push(Arrival{at + cfg->latency, N - 1, ARB_B, t.microbatch, t.chunk - 1});
+      if (s > 0) arrivals.push(Arrival{at + cfg.latency, s - 1, ARB_B, tk.microbatch, tk.chunk});
+      else if (tk.chunk > 0) arrivals.push(Arrival{at + cfg.latency, N - 1, ARB_B, tk.microbatch, tk.chunk - 1});
     }
-  };
-  auto all_done = [&]() {
+  }
+
+  bool all_done() const {
     for (int s = 0; s < N; ++s) {
       if (only ? done[s] < only_target : st[s]->completed() < st[s]->target()) return false;
       if (run[s].busy) return false;
     }
     return true;
-  };
-
-  double t = 0.0;
-  int deadlock = 0;
-  for (;;) {
-    for (int s = 0; s < N; ++s)
-      if (run[s].busy && run[s].end <= t) { run[s].busy = false; finish(s, run[s].t, run[s].end); }
-    while (!arrivals.empty() && arrivals.top().time <= t) {
-      const Arrival a = arrivals.top();
-      arrivals.pop();
-      deliver(a.stage, a.dir, a.microbatch, a.chunk);
-    }
-    for (int s = 0; s < N; ++s) {
-      if (run[s].busy) continue;
-      if (only && done[s] >= only_target) continue;
-      const int64_t D = st[s]->count[ARB_F] - st[s]->count[ARB_B];
-      if (D > max_D[s]) max_D[s] = D;
-      arbiter_task task;
-      if (arbiter_next(st[s], &task) != ARB_TASK) continue;
-      if (s == 0 && task.dir == ARB_F && task.chunk == 0) { if (++fwd_held[0] > max_f[0]) max_f[0] = fwd_held[0]; }
-      const size_t idx = ((size_t)s * C + task.chunk) * M + task.microbatch;
-      double p = task.dir == ARB_F ? dur_f[idx] : task.dir == ARB_B ? dur_b[idx] : dur_w[idx];
-      if (cfg->jitter_p > 0.0 && task.dir != ARB_W)
-        p = p + jitter_next_delay(&inject[s], task.dir, task.microbatch, task.chunk, p);
-      run[s].busy = true;
-      run[s].t = task;
-      run[s].end = t + p;
-      busy[s] += p;
-      if (run[s].end > makespan) makespan = run[s].end;
-      if (trace && n_events < trace_cap) trace[n_events] = rrfp_sim_event{s, task.dir, task.microbatch, task.chunk, t, t + p};
-      ++n_events;
-    }
-    if (all_done()) break;
-    bool have = false;
-    double nxt = 0.0;
-    for (int s = 0; s < N; ++s)
-      if (run[s].busy && (!have || run[s].end < nxt)) { nxt = run[s].end; have = true; }
-    if (!arrivals.empty() && (!have || arrivals.top().time < nxt)) { nxt = arrivals.top().time; have = true; }
-    if (!have) { deadlock = 1; break; }
-    t = nxt;
   }
-  result->makespan = makespan;
-  result->n_events = n_events;
-  result->deadlock = deadlock;
-  if (per_stage)
-    for (int s = 0; s < N; ++s) {
-      per_stage[4 * s + 0] = busy[s];
-      per_stage[4 * s + 1] = (double)max_f[s];
-      per_stage[4 * s + 2] = (double)max_b[s];
-      per_stage[4 * s + 3] = (double)max_D[s];
+
+  // Who produced the input of task (dir, chunk) at stage s: the neighbour in that direction, the other end of
+  // the pipeline when the microbatch changes chunk, or nobody (-1: the caller's tensor; for the backward of
+  // the last stage's last chunk, the caller's output gradient).
+  void source(int s, int dir, int c, int32_t* src_stage, int32_t* src_chunk) const {
+    *src_stage = -1; *src_chunk = -1;
+    if (dir == ARB_F) {
+      if (s > 0) { *src_stage = s - 1; *src_chunk = c; }
+      else if (c > 0) { *src_stage = N - 1; *src_chunk = c - 1; }
+    } else if (dir == ARB_B) {
+      if (s + 1 < N) { *src_stage = s + 1; *src_chunk = c; }
+      else if (c + 1 < C) { *src_stage = 0; *src_chunk = c + 1; }
     }
-  cleanup();
+  }
+
+  // Advances to the next dispatch.  ARB_TASK: *out filled, the stage is busy from out->start and the caller owes
+  // set_duration(); ARB_DONE: everything has completed; ARB_ESTATE: stalled (unfinished work, nothing in flight).
+  int next(rrfp_pipe_dispatch* out) {
+    if (pending >= 0) return ARB_ESTATE;
+    if (finished) return deadlock ? ARB_ESTATE : ARB_DONE;
+    for (;;) {
+      if (scan < 0) {
+        for (int s = 0; s < N; ++s)
+          if (run[s].busy && run[s].end <= t) { run[s].busy = false; finish(s, run[s].t, run[s].end); }
+        while (!arrivals.empty() && arrivals.top().time <= t) {
+          const Arrival a = arrivals.top();
+          arrivals.pop();
+          deliver(a.stage, a.dir, a.microbatch, a.chunk);
+        }
+        scan = 0;
+      }
+      for (; scan < N; ++scan) {
+        const int s = scan;
+        if (run[s].busy) continue;
+        if (only && done[s] >= only_target) continue;
+        const int64_t D = st[s]->count[ARB_F] - st[s]->count[ARB_B];
+        if (D > max_D[s]) max_D[s] = D;
+        arbiter_task task;
+        if (arbiter_next(st[s], &task) != ARB_TASK) continue;
+        if (s == 0 && task.dir == ARB_F && task.chunk == 0) { if (++fwd_held[0] > max_f[0]) max_f[0] = fwd_held[0]; }
+        run[s].busy = true;
+        run[s].t = task;
+        run[s].end = t;
+        out->stage = s; out->dir = task.dir; out->microbatch = task.microbatch; out->chunk = task.chunk;
+        out->start = t;
+        source(s, task.dir, task.chunk, &out->src_stage, &out->src_chunk);
+        pending = s;
+        ++scan;
+        ++n_events;
+        return ARB_TASK;
+      }
+      scan = -1;
+      if (all_done()) { finished = true; return ARB_DONE; }
+      bool have = false;
+      double nxt = 0.0;
+      for (int s = 0; s < N; ++s)
+        if (run[s].busy && (!have || run[s].end < nxt)) { nxt = run[s].end; have = true; }
+      if (!arrivals.empty() && (!have || arrivals.top().time < nxt)) { nxt = arrivals.top().time; have = true; }
+      if (!have) { finished = true; deadlock = true; return ARB_ESTATE; }
+      t = nxt;
+    }
+  }
+
+  // Duration of the task next() returned last; adds the jitter delay of the configuration (F and B tasks
+  // only) and returns it through *delay.
+  int set_duration(double seconds, double* delay, double* end) {
+    if (pending < 0 || !(seconds >= 0.0)) return ARB_ESTATE;
+    const int s = pending;
+    pending = -1;
+    double p = seconds, d = 0.0;
+    if (cfg.jitter_p > 0.0 && run[s].t.dir != ARB_W) {
+      d = jitter_next_delay(&inject[s], run[s].t.dir, run[s].t.microbatch, run[s].t.chunk, p);
+      p = p + d;
+    }
+    run[s].end = t + p;
+    busy[s] += p;
+    if (run[s].end > makespan) makespan = run[s].end;
+    if (delay) *delay = d;
+    if (end) *end = run[s].end;
+    return ARB_OK;
+  }
+};
+
+namespace {
+bool valid_sim_cfg(const rrfp_sim_config* cfg) {
+  return cfg && cfg->n_stages >= 1 && cfg->n_microbatches >= 1 && cfg->n_chunks >= 1 && cfg->mode >= 0 && cfg->mode <= 2 &&
+         cfg->latency >= 0 && cfg->jitter_p >= 0 && cfg->jitter_p <= 1 && cfg->jitter_base >= 0 && cfg->jitter_alpha >= 0;
+}
+}  // namespace
+
+extern "C" rrfp_pipe_t* rrfp_pipe_create(const rrfp_sim_config* cfg) {
+  if (!valid_sim_cfg(cfg)) { fail(nullptr, ARB_EINVAL, "rrfp_pipe_create: invalid configuration"); return nullptr; }
+  rrfp_pipe* p = new (std::nothrow) rrfp_pipe();
+  if (!p) { fail(nullptr, ARB_EINVAL, "rrfp_pipe_create: out of memory"); return nullptr; }
+  if (!p->init(cfg)) { delete p; return nullptr; }   // arbiter_create left the message
+  return p;
+}
+
+extern "C" void rrfp_pipe_destroy(rrfp_pipe_t* p) { delete p; }
+
+extern "C" int rrfp_pipe_next(rrfp_pipe_t* p, rrfp_pipe_dispatch* out) {
+  if (!p || !out) return fail(nullptr, ARB_EINVAL, "rrfp_pipe_next: NULL argument");
+  const int rc = p->next(out);
+  if (rc == ARB_ESTATE)
+    fail(nullptr, ARB_ESTATE, p->deadlock ? "rrfp_pipe_next: pipeline stalled (unfinished work, nothing in flight)"
+                                          : "rrfp_pipe_next: the previous task still waits for rrfp_pipe_set_duration");
+  return rc;
+}
+
+extern "C" int rrfp_pipe_set_duration(rrfp_pipe_t* p, double seconds, double* delay_seconds, double* end) {
+  if (!p) return fail(nullptr, ARB_EINVAL, "rrfp_pipe_set_duration: NULL handle");
+  const int rc = p->set_duration(seconds, delay_seconds, end);
+  if (rc != ARB_OK) fail(nullptr, rc, "rrfp_pipe_set_duration: no task waits for a duration, or the duration is negative");
+  return rc;
+}
+
+extern "C" int rrfp_sim_run(const rrfp_sim_config* cfg, const double* dur_f, const double* dur_b, const double* dur_w,
+                            rrfp_sim_result* result, double* per_stage, rrfp_sim_event* trace, int64_t trace_cap) {
+  if (!cfg || !result || !dur_f || !dur_b) return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: NULL argument");
+  if (!valid_sim_cfg(cfg) || (trace && trace_cap < 0)) return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: invalid configuration");
+  if (cfg->hint == ARB_HINT_BFW && !dur_w) return fail(nullptr, ARB_EINVAL, "rrfp_sim_run: BFW needs dur_w");
+  rrfp_pipe pipe;
+  if (!pipe.init(cfg)) return ARB_EINVAL;
+  const int M = cfg->n_microbatches, C = cfg->n_chunks;
+  rrfp_pipe_dispatch d;
+  int rc;
+  while ((rc = pipe.next(&d)) == ARB_TASK) {
+    const size_t idx = ((size_t)d.stage * C + d.chunk) * M + d.microbatch;
+    const double p = d.dir == ARB_F ? dur_f[idx] : d.dir == ARB_B ? dur_b[idx] : dur_w[idx];
+    double end = 0.0;
+    pipe.set_duration(p, nullptr, &end);
+    const int64_t k = pipe.n_events - 1;
+    if (trace && k < trace_cap) trace[k] = rrfp_sim_event{d.stage, d.dir, d.microbatch, d.chunk, d.start, end};
+  }
+  result->makespan = pipe.makespan;
+  result->n_events = pipe.n_events;
+  result->deadlock = pipe.deadlock ? 1 : 0;
+  if (per_stage)
+    for (int s = 0; s < cfg->n_stages; ++s) {
+      per_stage[4 * s + 0] = pipe.busy[s];
+      per_stage[4 * s + 1] = (double)pipe.max_f[s];
+      per_stage[4 * s + 2] = (double)pipe.max_b[s];
+      per_stage[4 * s + 3] = (double)pipe.max_D[s];
+    }
   return ARB_OK;
 }

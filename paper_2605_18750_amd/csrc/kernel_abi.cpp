@@ -38,3 +38,33 @@ extern "C" int rrfp_gemm_plan(int M, int N, int K, int lda, int ldb, int ldc, in
   out[0] = p.kernel; out[1] = p.wavefronts; out[2] = p.main_workgroups; out[3] = p.short_workgroups; out[4] = p.split_k;
   return STAGE_OK;
 }
+
+extern "C" int rrfp_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_out, int T, int H, float eps, int dtype,
+                                void* stream) {
+  if (!x || !g || !h || !r_out || T < 1 || H < 1 || !(eps >= 0.0f)) return STAGE_EINVAL;
+  if (dtype != F32 && dtype != BF16) return STAGE_EINVAL;
+  return launch_rmsnorm_fwd(x, g, h, r_out, T, H, eps, dtype, (hipStream_t)stream) == hipSuccess ? STAGE_OK : STAGE_EHIP;
+}
+
+extern "C" size_t rrfp_rmsnorm_bwd_workspace(int T, int H, int dtype) {
+  if (T < 1 || H < 1 || (dtype != F32 && dtype != BF16)) return 0;
+  return (size_t)norm_bwd_partials(T, H, dtype) * (size_t)H * sizeof(float);
+}
+
+extern "C" int rrfp_rmsnorm_bwd(const float* dh, const float* x, const float* r, const void* g, const float* add_in,
+                                float* out32, void* out_t, float* dg, void* workspace, size_t workspace_bytes, int T, int H,
+                                int dtype, void* stream) {
+  if (!dh || !x || !r || !g || !add_in || !dg || !workspace || T < 1 || H < 1) return STAGE_EINVAL;
+  if (dtype != F32 && dtype != BF16) return STAGE_EINVAL;
+  if (workspace_bytes < rrfp_rmsnorm_bwd_workspace(T, H, dtype) || ((uintptr_t)workspace & 15)) return STAGE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_rmsnorm_bwd(dh, x, r, g, add_in, out32, out_t, (float*)workspace, T, H, dtype, s) != hipSuccess) return STAGE_EHIP;
+  if (launch_colsum((const float*)workspace, norm_bwd_partials(T, H, dtype), H, dg, s) != hipSuccess) return STAGE_EHIP;
+  return STAGE_OK;
+}
+
+extern "C" int rrfp_grad_reduce(const float* slots, size_t slot_stride, int M, float* out, size_t n, void* stream) {
+  if (!slots || !out || M < 1 || n < 1 || (n & 3) || (slot_stride & 3) || (M > 1 && slot_stride < n)) return STAGE_EINVAL;
+  if (((uintptr_t)slots & 15) || ((uintptr_t)out & 15)) return STAGE_EINVAL;
+  return launch_grad_reduce(slots, slot_stride, M, out, n, (hipStream_t)stream) == hipSuccess ? STAGE_OK : STAGE_EHIP;
+}

@@ -1,19 +1,21 @@
 """A miniature of the runtime of Sec. 4.1 / Sec. 5 on ONE GPU: N stage handles chained into a pipeline,
-one native ready-set arbiter per stage, one HIP stream per stage, and messages (tensor, microbatch id,
-direction) between neighbours.  Every stage dispatches whatever its arbiter selects among READY tasks;
-the tasks themselves are the stage_F / stage_B / stage_W calls of the library.
+one HIP stream per stage, and messages (tensor, microbatch id, direction) between neighbours.  Which task
+every stage dispatches, when, and whose output it consumes is decided by the native event loop of the
+library (rrfp_pipe_* of include/rrfp_arbiter.h: one ready-set arbiter per stage, message routing, virtual
+clock); the tasks themselves are the stage_F / stage_B / stage_W calls of the library.  This module only
+keeps the tensors and HIP events that go with the dispatches.
 
-All stages share one device here, so wall-clock readiness would just mirror the enqueue order.  To
-exercise out-of-order dispatch deterministically the loop runs on a VIRTUAL clock: the caller gives a
-duration per task, a message becomes visible to the receiving arbiter at completion + latency of that
-clock, and an idle stage arbitrates whenever something changed (the event loop of the simulator).  The
-GPU work is enqueued at dispatch on the stage's own stream; data dependencies between stages are
-enforced with HIP events recorded by the producer and waited on by the consumer stream, so the device
-executes a valid order whatever the virtual clock says.  No arithmetic of the method lives here.
+All stages share one device here, so wall-clock readiness would just mirror the enqueue order.  The loop
+therefore runs on a VIRTUAL clock: a message becomes visible to the receiving arbiter at the sender's
+completion + latency on that clock, and a task's duration is either given by the caller or MEASURED (HIP
+events around the task on its stream).  The GPU work is enqueued at dispatch on the stage's own stream;
+data dependencies between stages are enforced with HIP events recorded by the producer and waited on by
+the consumer stream, so the device executes a valid order whatever the virtual clock says.  With a jitter
+level (Sec. 7.6) the library draws the delay of each F / B task from its measured time and the delay is
+put behind the task on its stream as a device-side sleep (rrfp_delay).  No arithmetic of the method lives
+here.
 """
 from __future__ import annotations
-
-import heapq
 
 import paper_2605_18750_amd as R
 from . import arbiter as A
@@ -33,114 +35,74 @@ class Pipeline:
         self.M = len(cus)
         self.cus = cus
         self.hint = hint
-        self.with_w = hint == A.ARB_HINT_BFW
-        self.arbiters = [A.arbiter_create(self.M, self.C, hint, buffer_limit, s, self.N) for s in range(self.N)]
+        self.buffer_limit = buffer_limit
+        if hint != A.ARB_HINT_BFW:
+            raise ValueError("the stage library needs W tasks before the reduce: use the BFW hint")
         self.streams = [torch.cuda.Stream() for _ in range(self.N)]
 
     def close(self):
-        for a in self.arbiters:
-            A.arbiter_destroy(a)
-        self.arbiters = []
+        pass
 
-    def run_iteration(self, xs, dys, duration, latency: float = 0.0):
+    def run_iteration(self, xs, dys, duration=None, latency: float = 0.0, jitter=(0.0, 0.0, 0.0, 0)):
         """xs[j]: input of microbatch j to (stage 0, chunk 0); dys[j]: gradient w.r.t. the output of
-        (stage N-1, chunk C-1).  duration(dir, stage, microbatch, chunk) -> virtual seconds.  Returns
-        (final outputs, input gradients, trace) with trace = [(stage, dir, microbatch, chunk, start, end)]
-        in dispatch order; the reduced gradients are in each Stage's grad_out."""
+        (stage N-1, chunk C-1).  duration(dir, stage, microbatch, chunk) -> virtual seconds, or None to
+        measure every task with HIP events on its stream (the host then waits for each task).
+        jitter = (p, base seconds, alpha, seed) of Sec. 7.6.  Returns (final outputs, input gradients,
+        trace) with trace = [(stage, dir, microbatch, chunk, start, end)] in dispatch order; the reduced
+        gradients are in each Stage's grad_out; self.delays lists (stage, dir, microbatch, chunk, compute
+        seconds, injected delay seconds) for every task in dispatch order (W tasks are never delayed)."""
         torch = self.torch
         N, M, C = self.N, self.M, self.C
-        y = {}
-        dx = {}
-        ev_f = {}
-        ev_b = {}
-        for a in self.arbiters:
-            A.arbiter_reset(a)
-        if not self.with_w:
-            raise ValueError("the stage library needs W tasks before the reduce: use the BFW hint")
-        running = [None] * N
-        arrivals = []          # heap of (time, seq, stage, dir, microbatch, chunk)
-        seq = 0
+        y, dx, ev = {}, {}, {}
         trace = []
-        t = 0.0
-
-        def f_source(s, c):    # producer of the forward input of (stage s, chunk c), None = the caller
-            if s > 0:
-                return (s - 1, c)
-            return (N - 1, c - 1) if c > 0 else None
-
-        def b_source(s, c):    # producer of the backward input of (stage s, chunk c), None = the caller
-            if s < N - 1:
-                return (s + 1, c)
-            return (0, c + 1) if c < C - 1 else None
-
-        def enqueue(s, d, j, c):
-            st, stream = self.stages[s][c], self.streams[s]
-            if d == A.ARB_F:
-                src = f_source(s, c)
-                if src is None:
-                    inp = xs[j]
+        self.delays = []
+        pipe = A.rrfp_pipe_create(N, M, C, self.hint, self.buffer_limit, latency, jitter)
+        try:
+            while True:
+                rc, disp = A.rrfp_pipe_next(pipe)
+                if rc == A.ARB_DONE:
+                    break
+                s, d, j, c, src_s, src_c, start = disp
+                st, stream = self.stages[s][c], self.streams[s]
+                t0 = t1 = None
+                if duration is None:
+                    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                if d == A.ARB_W:
+                    if t0 is not None:
+                        t0.record(stream)
+                    R.stage_W(st.handle, j, stream)
                 else:
-                    inp = y[(src[0], src[1], j)]
-                    stream.wait_event(ev_f[(src[0], src[1], j)])
-                y[(s, c, j)] = torch.empty_like(inp)
-                R.stage_F(st.handle, j, inp, self.cus[j], y[(s, c, j)], stream)
-                ev_f[(s, c, j)] = torch.cuda.Event()
-                ev_f[(s, c, j)].record(stream)
-            elif d == A.ARB_B:
-                src = b_source(s, c)
-                if src is None:
-                    inp = dys[j]
-                else:
-                    inp = dx[(src[0], src[1], j)]
-                    stream.wait_event(ev_b[(src[0], src[1], j)])
-                dx[(s, c, j)] = torch.empty_like(inp)
-                R.stage_B(st.handle, j, inp, dx[(s, c, j)], stream)
-                ev_b[(s, c, j)] = torch.cuda.Event()
-                ev_b[(s, c, j)].record(stream)
-            else:
-                R.stage_W(st.handle, j, stream)
-
-        while True:
-            for s in range(N):
-                if running[s] is not None and running[s][1] <= t:
-                    task, t_end = running[s]
-                    running[s] = None
-                    A.arbiter_complete(self.arbiters[s], task)
-                    d, j, c = task
+                    store = y if d == A.ARB_F else dx
+                    if src_s < 0:
+                        inp = xs[j] if d == A.ARB_F else dys[j]
+                    else:
+                        inp = store[(src_s, src_c, j)]
+                        stream.wait_event(ev[(d, src_s, src_c, j)])
+                    out = torch.empty_like(inp)
+                    store[(s, c, j)] = out
+                    if t0 is not None:
+                        t0.record(stream)
                     if d == A.ARB_F:
-                        if s + 1 < N:
-                            heapq.heappush(arrivals, (t_end + latency, seq, s + 1, A.ARB_F, j, c)); seq += 1
-                        elif c + 1 < C:
-                            heapq.heappush(arrivals, (t_end + latency, seq, 0, A.ARB_F, j, c + 1)); seq += 1
-                    elif d == A.ARB_B:
-                        if s > 0:
-                            heapq.heappush(arrivals, (t_end + latency, seq, s - 1, A.ARB_B, j, c)); seq += 1
-                        elif c > 0:
-                            heapq.heappush(arrivals, (t_end + latency, seq, N - 1, A.ARB_B, j, c - 1)); seq += 1
-            while arrivals and arrivals[0][0] <= t:
-                _, _, s, d, j, c = heapq.heappop(arrivals)
-                A.arbiter_post_ready(self.arbiters[s], d, j, c)
-            all_done = True
-            for s in range(N):
-                if running[s] is not None:
-                    all_done = False
-                    continue
-                rc, task = A.arbiter_next(self.arbiters[s])
-                if rc == A.ARB_TASK:
-                    d, j, c = task
-                    p = float(duration(d, s, j, c))
-                    enqueue(s, d, j, c)
-                    running[s] = (task, t + p)
-                    trace.append((s, d, j, c, t, t + p))
-                    all_done = False
-                elif rc != A.ARB_DONE:
-                    all_done = False
-            if all_done:
-                break
-            nxt = [r[1] for r in running if r is not None] + ([arrivals[0][0]] if arrivals else [])
-            if not nxt:
-                raise RuntimeError("pipeline stalled: no task in flight and no message pending")
-            t = min(nxt)
+                        R.stage_F(st.handle, j, inp, self.cus[j], out, stream)
+                    else:
+                        R.stage_B(st.handle, j, inp, out, stream)
+                if t1 is not None:
+                    t1.record(stream)
+                    t1.synchronize()
+                    seconds = t0.elapsed_time(t1) * 1e-3
+                else:
+                    seconds = float(duration(d, s, j, c))
+                delay, end = A.rrfp_pipe_set_duration(pipe, seconds)
+                if d != A.ARB_W:
+                    if delay > 0.0:      # the device-side sleep sits behind the task, before its "sent" event
+                        A.rrfp_delay(min(delay, 1.0), stream)
+                    e = torch.cuda.Event()
+                    e.record(stream)
+                    ev[(d, s, c, j)] = e
+                self.delays.append((s, d, j, c, seconds, delay))
+                trace.append((s, d, j, c, start, end))
+        finally:
+            A.rrfp_pipe_destroy(pipe)
         for s in range(N):
             for c in range(C):
                 R.stage_grad_reduce(self.stages[s][c].handle, self.stages[s][c].grad_out, self.streams[s])

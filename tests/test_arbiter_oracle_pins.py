@@ -239,6 +239,55 @@ def test_backpressure_rule_on_hand_worked_states():
     assert a.next() == (A.F, 2, 0)
 
 
+def test_interleaved_backpressure_drain_order_on_the_papers_example():
+    # App. C.2, interleaved schedules, the paper's own example: C = 4 local chunks; a microbatch that
+    # has completed F_0, F_1, F_2 while F_3 has not arrived -> the stage waits for F_3 (it does not
+    # skip to other ready work), after F_3 it waits for B_3, then B_2, B_1, B_0; microbatches are
+    # scanned from index 0 upward, so the next microbatch is touched only when the first is drained.
+    C, M = 4, 3
+    a = A.StageArbiter(M=M, C=C, hint=A.HINT_BF, limit=3)
+    # normal mode: F_0, F_1, F_2 of microbatch 0 (forward prefers the smaller chunk, App. A)
+    for c in range(3):
+        a.Lf.add((0, c))
+        t = a.next(); assert t == (A.F, 0, c); a.complete(t)
+    assert a.n_f - a.n_b == 3 and a.in_backpressure()
+    # ready work of LATER microbatches and a later task of microbatch 0 must not be taken
+    a.Lf |= {(1, 0), (2, 0)}
+    assert a.next() is None                      # waits for F_3 of microbatch 0
+    a.Lf.add((0, 3))
+    t = a.next(); assert t == (A.F, 0, 3); a.complete(t)
+    assert a.n_f - a.n_b == 4                    # overshoot: at most limit + C (corollary of App. C.3)
+    a.Lb.add((0, 1))                             # B_1 arrives early: not the next required task
+    assert a.next() is None                      # waits for B_3
+    want = [3, 2, 1]
+    a.Lb |= {(0, 3), (0, 2)}
+    for c in want:                               # B_3, B_2, B_1: after B_1 D = 4 - 3 = 1 < limit, mode ends
+        t = a.next(); assert t == (A.B, 0, c), (t, c); a.complete(t)
+        assert a.in_backpressure() == (a.n_f - a.n_b >= 3)
+    assert not a.in_backpressure()
+    # back in readiness order (BF round: backward first, none ready -> forward, smallest chunk, smallest microbatch)
+    assert a.next() == (A.F, 1, 0)
+
+    # scan order: with two unfinished microbatches under backpressure the LOWER index is served first
+    # even when only the higher one has its required task ready
+    a = A.StageArbiter(M=2, C=2, hint=A.HINT_BF, limit=2)
+    for j in (0, 1):
+        a.Lf.add((j, 0))
+        t = a.next(); assert t == (A.F, j, 0); a.complete(t)
+    assert a.in_backpressure()
+    a.Lf.add((1, 1))                             # microbatch 1 could go on, microbatch 0 cannot
+    assert a.next() is None
+    a.Lf.add((0, 1))
+    t = a.next(); assert t == (A.F, 0, 1); a.complete(t)
+    a.Lb |= {(1, 1), (0, 0)}                     # neither is microbatch 0's next required task (B_1)
+    assert a.next() is None
+    a.Lb.add((0, 1))
+    t = a.next(); assert t == (A.B, 0, 1); a.complete(t)
+    assert a.in_backpressure()                   # D = 3 - 1 = 2
+    t = a.next(); assert t == (A.B, 0, 0); a.complete(t)
+    assert not a.in_backpressure()               # D = 1
+
+
 def test_bfw_weight_task_rule_on_hand_worked_states():
     # W becomes ready when its B completes and runs only when neither B nor F is ready (Sec. 7.1)
     a = _arb(A.HINT_BFW, M=2)

@@ -209,3 +209,41 @@ def test_jitter_injector_matches_oracle_bit_for_bit():
             A.jitter_destroy(nat)
     with pytest.raises(A.ArbiterError):
         A.jitter_create(1.5, 0.0, 1.0, 0, 0, 4)
+
+
+@pytest.mark.parametrize("N,M,C,limit,jit", [(3, 6, 1, 0, None), (3, 6, 1, 2, (0.3, 0.5, 1.0, 9)), (2, 6, 2, 1, None),
+                                            (4, 9, 3, 2, (0.2, 0.1, 0.7, 3)), (1, 4, 1, 0, None)])
+def test_pipe_event_loop_one_dispatch_at_a_time_matches_oracle(N, M, C, limit, jit):
+    # the resumable form of the event loop (rrfp_pipe_*), durations supplied task by task: trace, times and
+    # delays identical to the oracle simulator; the named producer of every input is the routing rule of
+    # Sec. 4.1 (neighbour stage, or the other end of the pipeline when the microbatch changes chunk)
+    rng = random.Random(N * 100 + M)
+    tab = {(d, s, c, j): rng.uniform(0.2, 3.0) for d in (0, 1, 2) for s in range(N) for c in range(C) for j in range(M)}
+    pipe = A.rrfp_pipe_create(N, M, C, A.ARB_HINT_BFW, limit, 0.1, jit or (0.0, 0.0, 0.0, 0))
+    tr = []
+    while True:
+        rc, d = A.rrfp_pipe_next(pipe)
+        if rc == A.ARB_DONE:
+            break
+        s, dd, j, c, ss, sc, start = d
+        if dd == A.ARB_F:
+            want = (s - 1, c) if s > 0 else ((N - 1, c - 1) if c > 0 else (-1, -1))
+        elif dd == A.ARB_B:
+            want = (s + 1, c) if s + 1 < N else ((0, c + 1) if c + 1 < C else (-1, -1))
+        else:
+            want = (-1, -1)
+        assert (ss, sc) == want
+        with pytest.raises(A.ArbiterError):
+            A.rrfp_pipe_next(pipe)                      # the duration is still owed
+        delay, end = A.rrfp_pipe_set_duration(pipe, tab[(dd, s, c, j)])
+        assert (delay > 0.0) <= (jit is not None and dd != A.ARB_W)
+        tr.append((s, dd, j, c, start, end))
+    with pytest.raises(A.ArbiterError):
+        A.rrfp_pipe_set_duration(pipe, 1.0)             # nothing waits for a duration
+    assert A.rrfp_pipe_next(pipe)[0] == A.ARB_DONE
+    A.rrfp_pipe_destroy(pipe)
+    ref = O.simulate(N, M, lambda d, s, c, j: tab[(d, s, c, j)], C=C, hint=O.HINT_BFW, limit=limit, latency=0.1,
+                     jitter=O.Jitter(*jit) if jit else None)
+    assert [[(d, j, c, t0, t1) for (s_, d, j, c, t0, t1) in tr if s_ == s] for s in range(N)] == ref.trace
+    with pytest.raises(A.ArbiterError):
+        A.rrfp_pipe_create(0, 4)

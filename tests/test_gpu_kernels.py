@@ -137,3 +137,76 @@ def test_mfma_gemm_short_tile_tail():
         _say(f"[kernel] columns {lo}:{hi}: rel err {err:.3e}")
         assert err <= 1e-2
     assert torch.all(dC[M:] == 7.0), "rows past M were written"
+
+
+@pytest.mark.parametrize("T,H,dtype", [(777, 512, "bf16"), (130, 256, "fp32"), (1030, 4096, "bf16"), (9, 1280, "bf16"),
+                                       (65, 200, "fp32")])
+def test_rmsnorm_kernels_against_oracle(T, H, dtype):
+    """RMSNorm forward and backward (rows + gain gradient) through their own entry points, against the fp64
+    oracle on the same rounded inputs; T spans several row chunks with a ragged tail."""
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+    from oracle import stage_oracle as O
+    from tests.helpers import max_norm_rel_err
+    name = f"rmsnorm T{T} H{H} {dtype}"
+    _say(f"[kernel] {name}")
+    eps = 1e-5
+    x = SI.make_tensor(3, name + "x", (T, H), 1.0, "fp32")
+    g = SI.make_tensor(3, name + "g", (H,), 0.02, dtype, mean=1.0)
+    dh = SI.make_tensor(3, name + "dh", (T, H), 1.0, "fp32")
+    add = SI.make_tensor(3, name + "add", (T, H), 1.0, "fp32")
+    h_ref, xhat, r_ref = O.rmsnorm_fwd(x.f64, g.f64, eps)
+    dx_ref, dg_ref = O.rmsnorm_bwd(dh.f64, xhat, r_ref, g.f64)
+    dx_ref = dx_ref + add.f64
+    dt = R.STAGE_DTYPE_FP32 if dtype == "fp32" else R.STAGE_DTYPE_BF16
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    dx_, ddh, dadd = (Hn.to_device(t.storage, "fp32") for t in (x, dh, add))
+    dgain = Hn.to_device(g.storage, dtype)
+    h = torch.full((T, H), float("nan"), dtype=tdt, device="cuda:0")
+    r = torch.full((T,), float("nan"), dtype=torch.float32, device="cuda:0")
+    R.rrfp_rmsnorm_fwd(dx_, dgain, h, r, T, H, eps, dt)
+    ws_bytes = R.rrfp_rmsnorm_bwd_workspace(T, H, dt)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    out32 = torch.full((T, H), float("nan"), dtype=torch.float32, device="cuda:0")
+    out_t = torch.full((T, H), float("nan"), dtype=tdt, device="cuda:0")
+    dg = torch.full((H,), float("nan"), dtype=torch.float32, device="cuda:0")
+    R.rrfp_rmsnorm_bwd(ddh, dx_, r, dgain, dadd, out32, out_t, dg, ws, ws_bytes, T, H, dt)
+    torch.cuda.synchronize()
+    tol_f32, tol_t = 2e-5, (2e-5 if dtype == "fp32" else 8e-3)     # fp32 arithmetic; bf16 storage rounds once (2^-9)
+    errs = {"h": (max_norm_rel_err(Hn.to_f64(h), h_ref), tol_t),
+            "r": (max_norm_rel_err(Hn.to_f64(r), r_ref.reshape(-1)), tol_f32),
+            "dx fp32": (max_norm_rel_err(Hn.to_f64(out32), dx_ref), tol_f32),
+            "dx storage": (max_norm_rel_err(Hn.to_f64(out_t), dx_ref), tol_t),
+            "dg": (max_norm_rel_err(Hn.to_f64(dg), dg_ref), tol_f32)}
+    for k, (e, tol) in errs.items():
+        _say(f"[kernel] {name} {k}: {e:.3e} (tol {tol})")
+        assert e <= tol, (name, k)
+    with pytest.raises(R.StageError):
+        R.rrfp_rmsnorm_bwd(ddh, dx_, r, dgain, dadd, out32, out_t, dg, ws, ws_bytes - 4, T, H, dt)
+
+
+def test_grad_reduce_kernel_is_the_index_ordered_sum():
+    """rrfp_grad_reduce against the oracle's grad_reduce (fp64: 1e-6 tolerance) and, bit for bit, against the
+    fp32 sum in index order formed with torch on the device, including values that make the order matter."""
+    import torch
+    import paper_2605_18750_amd as R
+    from oracle import stage_oracle as O
+    M, n, stride = 5, 4 * 100003, 4 * 100010
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(3)
+    slots = torch.empty(M * stride, dtype=torch.float32, device="cuda:0").normal_(0, 1, generator=g)
+    slots[0:stride:7] *= 1e8                     # large first terms: ((a + b) + c) != (a + (b + c)) in fp32
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda:0")
+    R.rrfp_grad_reduce(slots, stride, M, out, n)
+    torch.cuda.synchronize()
+    acc = slots[0:n].clone()
+    for j in range(1, M):
+        acc += slots[j * stride: j * stride + n]
+    assert torch.equal(acc.view(torch.int32), out.view(torch.int32))
+    per_mb = [[{"w": slots[j * stride: j * stride + n].cpu().double().numpy()}] for j in range(M)]
+    ref = O.grad_reduce(per_mb)[0]["w"]
+    err = float(np.max(np.abs(out.cpu().double().numpy() - ref)) / np.max(np.abs(ref)))
+    _say(f"[kernel] grad_reduce vs oracle: {err:.3e}")
+    assert err <= 1e-6
