@@ -71,6 +71,19 @@ int rrfp_rmsnorm_bwd(const float* dh, const float* x, const float* r, const void
  * All device fp32; n and slot_stride multiples of 4, pointers 16-byte aligned. */
 int rrfp_grad_reduce(const float* slots, size_t slot_stride, int M, float* out, size_t n, void* stream);
 
+/* rrfp_rmsnorm_bwd for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results (bit for
+ * bit) as rrfp_rmsnorm_bwd minus the workspace: the partial gain-gradient rows go to a 16 MiB array that lives
+ * in the library's device image (one copy per GPU, held until the process ends).  Calls no allocating routine.
+ * STAGE_ENOMEM when rrfp_rmsnorm_bwd_workspace(T, H, dtype) exceeds rrfp_rmsnorm_bwd_static_limit() (16 MiB:
+ * T * H up to 32 Mi elements for the fused kernel, e.g. 8192 x 4096); STAGE_EINVAL / STAGE_EHIP as the other
+ * entry points.  All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ * (different streams without ordering) race and give undefined dg; calls ordered on one stream, or by events,
+ * are safe, and nothing needs clearing between them (every row read is written first by the same call). */
+size_t rrfp_rmsnorm_bwd_static_limit(void);
+int rrfp_rmsnorm_bwd_static(const float* dh, const float* x, const float* r, const void* g, const float* add_in,
+                            float* out32, void* out_t, float* dg, int T, int H, int dtype, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -65,6 +65,10 @@ def lib() -> C.CDLL:
         L.rrfp_rmsnorm_bwd_workspace.restype = sz
         L.rrfp_rmsnorm_bwd.argtypes = [vp] * 9 + [sz, C.c_int, C.c_int, C.c_int, vp]
         L.rrfp_rmsnorm_bwd.restype = C.c_int
+        L.rrfp_rmsnorm_bwd_static_limit.argtypes = []
+        L.rrfp_rmsnorm_bwd_static_limit.restype = sz
+        L.rrfp_rmsnorm_bwd_static.argtypes = [vp] * 8 + [C.c_int, C.c_int, C.c_int, vp]
+        L.rrfp_rmsnorm_bwd_static.restype = C.c_int
         L.rrfp_grad_reduce.argtypes = [vp, sz, C.c_int, vp, sz, vp]
         L.rrfp_grad_reduce.restype = C.c_int
         for f in ("stage_query", "stage_param_layout", "stage_create", "stage_create_dry", "stage_F",
@@ -202,6 +206,18 @@ def rrfp_rmsnorm_bwd(dh, x, r, g, add_in, out32, out_t, dg, workspace, workspace
                      stream=None):
     _kcheck(lib().rrfp_rmsnorm_bwd(_ptr(dh), _ptr(x), _ptr(r), _ptr(g), _ptr(add_in), _ptr(out32), _ptr(out_t), _ptr(dg),
                                    _ptr(workspace), workspace_bytes, T, H, dtype, _stream(stream)), "rrfp_rmsnorm_bwd")
+
+
+def rrfp_rmsnorm_bwd_static_limit() -> int:
+    return lib().rrfp_rmsnorm_bwd_static_limit()
+
+
+def rrfp_rmsnorm_bwd_static(dh, x, r, g, add_in, out32, out_t, dg, T: int, H: int, dtype: int, stream=None):
+    rc = lib().rrfp_rmsnorm_bwd_static(_ptr(dh), _ptr(x), _ptr(r), _ptr(g), _ptr(add_in), _ptr(out32), _ptr(out_t), _ptr(dg),
+                                       T, H, dtype, _stream(stream))
+    if rc == STAGE_ENOMEM:
+        raise StageError(rc, "rrfp_rmsnorm_bwd_static: shape needs more than the library's static scratch")
+    _kcheck(rc, "rrfp_rmsnorm_bwd_static")
 
 
 def rrfp_grad_reduce(slots, slot_stride: int, M: int, out, n: int, stream=None):
