@@ -22,9 +22,17 @@
  *     stage_last_error();
  *   - "host" / "device" is stated for every pointer.  The library never allocates or
  *     frees device memory and never synchronises the device; every task call only
- *     enqueues work on the given HIP stream and returns;
+ *     enqueues work on the given HIP stream and returns.  One exception: stage_F copies the
+ *     attention tile lists of the microbatch from a pinned host buffer owned by the slot;
+ *     if the copy the SAME slot enqueued in the previous iteration has not completed yet,
+ *     stage_F waits for that one copy on the host first (it precedes all kernels of that
+ *     earlier task on its stream, so in steady state the wait returns at once);
  *   - all argument validation and all dependency checks happen BEFORE the first HIP call
- *     of an entry point; a call that fails validation has no side effect;
+ *     of an entry point; a call that fails validation (STAGE_EINVAL, STAGE_ENOTREADY,
+ *     STAGE_ENOMEM) has no side effect.  A HIP runtime failure (STAGE_EHIP) in the middle of
+ *     a task is different: part of the task may already be enqueued, so the slot is marked
+ *     POISONED and every later task on it (and stage_grad_reduce) returns STAGE_EHIP, with
+ *     the reason in stage_last_error, until the stage is destroyed;
  *   - calls on one stage_t must come from one host thread at a time (the arbiter thread).
  *     Tasks of different microbatches may be put on different streams; the device-side
  *     order F_j -> B_j -> W_j -> grad_reduce is enforced with library-owned events;

@@ -331,9 +331,7 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __re
 
 constexpr int BQ_KV = 64;      // query rows per step of the dK/dV kernel
 constexpr int WK = 32;         // keys per wavefront of the dK/dV kernel
-#ifndef DKV_VALU_PER_MFMA
-#define DKV_VALU_PER_MFMA 8    // vector instructions of the P / dS arithmetic issued after each MFMA of a group
-#endif
+constexpr int DKV_VALU_PER_MFMA = 8;    // vector instructions of the P / dS arithmetic issued after each MFMA of a group
 
 // N_MFMA times (one MFMA, N_VALU vector instructions) in the instruction scheduler's order.
 template <int N_MFMA, int N_VALU>
@@ -604,12 +602,9 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
 template <int D>
 hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
   auto kkv = attn_dkv_mfma_kernel<D>;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kkv, hipFuncAttributeMaxDynamicSharedMemorySize, DkvCfg<D>::SMEM);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::once_flag once;
+  static hipError_t once_status = hipSuccess;
+  if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kkv, DkvCfg<D>::SMEM); e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)D);
   hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((a.T * a.nq + 15) / 16), dim3(256), 0, s, (const bf16_t*)a.o,
                      a.o32, (const bf16_t*)a.d_o, a.delta, a.T, a.nq);
@@ -625,12 +620,9 @@ hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
   constexpr int NT = FWD_Q_ROWS / (32 * FWD_NIB) * 64;
   using C = FwdCfg<D, NT>;
   auto kern = attn_fwd_mfma_kernel<D, FWD_NIB>;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::once_flag once;
+  static hipError_t once_status = hipSuccess;
+  if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kern, C::SMEM); e != hipSuccess) return e;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(NT), C::SMEM, s, (const bf16_t*)a.qkv, (bf16_t*)a.o, a.o32, a.lse,
                      a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale_log2e);

@@ -177,12 +177,9 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
 template <int D>
 hipError_t dq_launch(const AttnArgs& a, hipStream_t s) {
   auto kq = attn_dq_mfma_kernel<D, DQ_NIB>;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kq, hipFuncAttributeMaxDynamicSharedMemorySize, DqCfg<D>::SMEM);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::once_flag once;
+  static hipError_t once_status = hipSuccess;
+  if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kq, DqCfg<D>::SMEM); e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)D);
   hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(FWD_Q_ROWS / (32 * DQ_NIB) * 64), DqCfg<D>::SMEM, s, (const bf16_t*)a.qkv,
                      (const bf16_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale);

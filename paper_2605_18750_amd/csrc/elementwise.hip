@@ -449,7 +449,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void headnorm_bwd_kernel(T* __restrict__ dy, int ld, int nq, int n_heads, int d,
                                                            const T* __restrict__ gq, const T* __restrict__ gk,
                                                            const T* __restrict__ xhat, const float* __restrict__ r_in,
-                                                           float* __restrict__ partial_q, float* __restrict__ partial_k, int Tn) {
+                                                           float* __restrict__ partial_q, float* __restrict__ partial_k, int Tn,
+                                                           float* __restrict__ dk32) {
   __shared__ float red[4][128];
   const int kind = blockIdx.y, nh = kind == 0 ? nq : n_heads - nq, h0 = kind == 0 ? 0 : nq;
   const T* g = kind == 0 ? gq : gk;
@@ -482,7 +483,13 @@ __global__ __launch_bounds__(256) void headnorm_bwd_kernel(T* __restrict__ dy, i
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int c = lane + u * WAVE;
-      if (c < d) p[c] = from_float<T>(rr * (w[u] - xh[u] * dot));
+      if (c < d) {
+        const float dxv = rr * (w[u] - xh[u] * dot);
+        p[c] = from_float<T>(dxv);
+        // un-rounded copy of the key-head gradients [Tn, nk * d]: their column sum (the key bias gradient) is a
+        // small remainder of cancelling terms and would lose its leading digits to the storage rounding
+        if (dk32 && kind == 1) dk32[((size_t)t * nh + (hd - h0)) * d + c] = dxv;
+      }
     }
   }
 #pragma unroll
@@ -577,12 +584,9 @@ hipError_t launch_bwd_fused(const float* dh, const float* x, const float* r, con
                             float* out32, void* out_t, float* dg_partial, int Tn, int H, hipStream_t s) {
   auto kern = rmsnorm_bwd_fused_kernel<T, NV>;
   const size_t smem = (size_t)4 * H * sizeof(float);
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * NV * WAVE * Vec<T>::N * 4);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::once_flag once;
+  static hipError_t once_status = hipSuccess;
+  if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kern, 4 * NV * WAVE * Vec<T>::N * 4); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((Tn + FUSED_ROWS - 1) / FUSED_ROWS), dim3(256), smem, s, dh, x, r, (const T*)g, add_in, out32,
                      (T*)out_t, dg_partial, Tn, H);
   return hipGetLastError();
@@ -629,11 +633,12 @@ hipError_t launch_headnorm_fwd(void* x, int ld, int nq, int n_heads, int d, cons
 }
 
 hipError_t launch_headnorm_bwd(void* dy, int ld, int nq, int n_heads, int d, const void* gq, const void* gk, const void* xhat,
-                               const float* r_in, float* partial_q, float* partial_k, int Tn, int dtype, hipStream_t s) {
+                               const float* r_in, float* partial_q, float* partial_k, int Tn, int dtype, hipStream_t s,
+                               float* dk32) {
   if (d > 128) return hipErrorInvalidValue;
   const int nb = std::max(headnorm_partials(Tn, nq), headnorm_partials(Tn, n_heads - nq));
   DISPATCH_T(dtype, hipLaunchKernelGGL(headnorm_bwd_kernel<T>, dim3(nb, 2), dim3(256), 0, s, (T*)dy, ld, nq, n_heads, d,
-                                       (const T*)gq, (const T*)gk, (const T*)xhat, r_in, partial_q, partial_k, Tn));
+                                       (const T*)gq, (const T*)gk, (const T*)xhat, r_in, partial_q, partial_k, Tn, dk32));
   return hipGetLastError();
 }
 

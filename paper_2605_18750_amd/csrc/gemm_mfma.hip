@@ -33,11 +33,6 @@
 #include "kernels.h"
 #include "numeric.h"
 
-#ifndef RRFP_WM_KC
-#define RRFP_WM_KC 2
-#define RRFP_WN_KC 4
-#endif
-
 namespace rrfp {
 namespace {
 
@@ -671,8 +666,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   };
   Pre pre[2][SW];
   if (ACT != ACT_SWIGLU_FWD) prefetch(pre[0], 0);
+  // The lanes of a wavefront exchange values through the wavefront's own scratch: write in the accumulator
+  // layout, read back row-contiguous, overwrite with the next chunk.  The hardware executes one wavefront's
+  // LDS instructions in order; these wavefront-scope fences keep the compiler from reordering the three phases.
+  auto wave_sync = [] {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
+    wave_sync();        // read-back of chunk i-1 precedes the writes of chunk i
     if constexpr (M32) {
 #pragma unroll
       for (int j = 0; j < NB; ++j)
@@ -688,6 +692,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
           *reinterpret_cast<float4*>(scratch + (h * 16 + li) * PITCH + j * 16 + hq * 4) =
               make_float4(acc[2 * i + h][j][0], acc[2 * i + h][j][1], acc[2 * i + h][j][2], acc[2 * i + h][j][3]);
     }
+    wave_sync();        // the writes of chunk i precede its read-back
     if (ACT == ACT_SWIGLU_FWD) {
       // scratch columns 0..31 = gate, 32..63 = up of features f0 .. f0+31; 4 lanes per row, 16 rows per sweep
       const int F = N >> 1;
@@ -900,13 +905,10 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
                        g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, 0, (const bf16_t*)g.bias);
     return hipGetLastError();
   }
-  static bool configured = false;   // per instantiation; the attribute is process-wide for the function
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::once_flag once;       // per instantiation; the attribute is process-wide for the function
+  static hipError_t once_status = hipSuccess;
+  if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>, SMEM_BYTES);
+      e != hipSuccess) return e;
   hipLaunchKernelGGL((gemm_mfma_kernel<A_KC, B_KC, TO, HAS_R>), dim3(tiles_m * tiles_n), dim3(NTHREADS), SMEM_BYTES, s,
                      (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb,
                      g.ldc, g.ldr, tiles_m, tiles_n);

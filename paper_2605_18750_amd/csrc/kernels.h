@@ -4,11 +4,20 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 namespace rrfp {
 
 enum DType : int { F32 = 0, BF16 = 1 };
 
 static inline size_t dtype_size(int dt) { return dt == F32 ? 4 : 2; }
+
+// Raises a kernel's dynamic LDS limit once per process, safely under concurrent first calls from several
+// host threads.  `flag` and `status` are statics of the calling launcher (one pair per kernel instantiation).
+static inline hipError_t set_max_dynamic_lds_once(std::once_flag& flag, hipError_t& status, const void* kernel, int bytes) {
+  std::call_once(flag, [&] { status = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); });
+  return status;
+}
 
 // C[M,N] = A(m,k) * B(k,n) (+ R[M,N]), fp32 accumulation.  R, when present, is always fp32 (the
 // residual stream is kept in fp32 between layers whatever the storage type).
@@ -116,7 +125,8 @@ int headnorm_partials(int T, int n_heads_of_kind);
 hipError_t launch_headnorm_fwd(void* x, int ld, int nq, int n_heads, int d, const void* gq, const void* gk, void* xhat,
                                float* r_out, int T, float eps, int dtype, hipStream_t s);
 hipError_t launch_headnorm_bwd(void* dy, int ld, int nq, int n_heads, int d, const void* gq, const void* gk, const void* xhat,
-                               const float* r_in, float* partial_q, float* partial_k, int T, int dtype, hipStream_t s);
+                               const float* r_in, float* partial_q, float* partial_k, int T, int dtype, hipStream_t s,
+                               float* dk32 = nullptr);   // optional fp32 copy [T, n_key_heads * d] of the rewritten key-head gradients
 // Per-chunk column sums of a [T, N] tensor of the storage type into partial [colsum_chunks(T), N] (bias gradients).
 hipError_t launch_colsum_rows(const void* src, int ld, float* partial, int T, int N, int dtype, hipStream_t s);
 

@@ -50,6 +50,7 @@ struct Plan {
   size_t param_elems;
   std::vector<LayerStash> layer;
   size_t t_dm, t_dh, t_do, t_delta, t_dgp, t_dbp, t_qtiles, t_kvtiles;  // per-microbatch temporaries
+  size_t t_dk32;                    // fp32 key-head gradients behind the head norm (QK-norm with biases only)
   int max_tiles;
   size_t mb_bytes;                  // one microbatch region
   size_t slots_off;                 // start of the M gradient slots
@@ -146,6 +147,7 @@ int make_plan(const stage_config* c, Plan* p) {
   size_t dbp = (c->norm_kind == 1 || c->bias) ? (size_t)colsum_chunks((int)T) * wide * 4 : 0;
   if (c->qk_norm) dbp = std::max(dbp, (size_t)headnorm_partials((int)T, (int)nkv) * d * 4);
   p->t_dbp = dbp ? take(dbp) : 0;
+  p->t_dk32 = (c->qk_norm && c->bias) ? take(T * nkv * d * 4) : 0;
   const int tile = std::min(ATTN_TILE_Q, ATTN_TILE_KV);
   p->max_tiles = (int)((T + tile - 1) / tile) + c->max_segments;
   p->t_qtiles = take((size_t)p->max_tiles * sizeof(AttnTile));
@@ -156,7 +158,9 @@ int make_plan(const stage_config* c, Plan* p) {
   return STAGE_OK;
 }
 
-enum MbState { MB_FREE = 0, MB_F = 1, MB_B = 2, MB_W = 3 };
+// MB_POISONED: a HIP call failed in the middle of a task of this slot, so part of the task is enqueued and the
+// slot's memory is in an unknown state; every later task on the slot is refused until the stage is destroyed.
+enum MbState { MB_FREE = 0, MB_F = 1, MB_B = 2, MB_W = 3, MB_POISONED = 4 };
 
 struct MbSlot {
   int state = MB_FREE;
@@ -189,14 +193,20 @@ void set_error(stage_t* st, const char* fmt, ...) {
   va_end(ap);
 }
 
+// A HIP failure inside a task body: the slot named by the enclosing scope's `poison` (an int*, or nullptr
+// outside task bodies) is marked poisoned, because kernels of the task may already be enqueued.
 #define HIP_TRY(st, expr)                                                              \
   do {                                                                                 \
     hipError_t e_ = (expr);                                                            \
     if (e_ != hipSuccess) {                                                            \
-      set_error(st, "%s failed: %s", #expr, hipGetErrorString(e_));                    \
+      set_error(st, "%s failed: %s%s", #expr, hipGetErrorString(e_),                   \
+                poison ? "; the microbatch slot is poisoned: its tasks are refused until stage_destroy" : ""); \
+      if (poison) *poison = MB_POISONED;                                               \
       return STAGE_EHIP;                                                               \
     }                                                                                  \
   } while (0)
+
+int refuse_poisoned(stage_t* st, int mb, const char* task);
 
 // Tiles of `rows` rows carved inside each segment, heaviest first (more keys first under a
 // causal mask) so that long tiles start early.  A pure function of cu_seqlens.
@@ -211,6 +221,11 @@ int build_tiles(const int32_t* cu, int n_seg, int rows, bool causal, bool kv_sid
   };
   std::stable_sort(out, out + n, [&](const AttnTile& a, const AttnTile& b) { return work(a) > work(b); });
   return n;
+}
+
+int refuse_poisoned(stage_t* st, int mb, const char* task) {
+  set_error(st, "%s(%d): the slot is poisoned by an earlier HIP failure in one of its tasks; destroy the stage", task, mb);
+  return STAGE_EHIP;
 }
 
 char* mb_base(stage_t* st, int mb) { return st->arena + st->plan.mb_bytes * (size_t)mb; }
@@ -360,6 +375,7 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
   if (T > c.max_tokens) { set_error(st, "T = %d exceeds max_tokens = %d", T, c.max_tokens); return STAGE_EINVAL; }
   if (!st->dry && (!x_dev || !y_dev)) { set_error(st, "x_dev and y_dev must not be NULL"); return STAGE_EINVAL; }
   MbSlot& m = st->mb[mb];
+  if (m.state == MB_POISONED) return refuse_poisoned(st, mb, "F");
   if (m.state != MB_FREE) { set_error(st, "F(%d): slot is busy until stage_grad_reduce", mb); return STAGE_ENOTREADY; }
 
   m.T = T;
@@ -368,8 +384,11 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     m.state = MB_F;
     return STAGE_OK;
   }
+  int* poison = &m.state;
   hipStream_t s = (hipStream_t)stream;
-  // The pinned tile lists of this slot may still be the source of the previous iteration's copy.
+  // The pinned tile lists of this slot may still be the source of the previous iteration's copy: the one
+  // place where a task call can wait on the host (documented in the header).  The copy was enqueued before
+  // the previous iteration's kernels of this slot, so in steady state it has long completed.
   if (m.copy_pending) { HIP_TRY(st, hipEventSynchronize(m.ev_copy)); m.copy_pending = false; }
   AttnTile* qt = m.staging;
   AttnTile* kt = m.staging + P.max_tiles;
@@ -458,11 +477,13 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
   const stage_config& c = P.c;
   if (!st->dry && (!dy_dev || !dx_dev)) { set_error(st, "dy_dev and dx_dev must not be NULL"); return STAGE_EINVAL; }
   MbSlot& m = st->mb[mb];
+  if (m.state == MB_POISONED) return refuse_poisoned(st, mb, "B");
   if (m.state != MB_F) {
     set_error(st, m.state == MB_FREE ? "B(%d) before F(%d)" : "B(%d) already issued", mb, mb);
     return STAGE_ENOTREADY;
   }
   if (st->dry) { m.state = MB_B; return STAGE_OK; }
+  int* poison = &m.state;
   hipStream_t s = (hipStream_t)stream;
   HIP_TRY(st, hipStreamWaitEvent(s, m.ev_F, 0));
   char* base = mb_base(st, mb);
@@ -543,11 +564,20 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     if (c.qk_norm) {   // gradients w.r.t. the normalised heads -> w.r.t. the projection outputs, gain gradients to the slot
       HIP_TRY(st, launch_headnorm_bwd(base + L.dqkv, P.n_qkv, c.n_q_heads, c.n_q_heads + c.n_kv_heads, c.head_dim,
                                       param_ptr(st, l, STAGE_P_GQ), param_ptr(st, l, STAGE_P_GK), base + L.qk_hat,
-                                      (const float*)(base + L.qk_r), (float*)(base + P.t_dgp), (float*)(base + P.t_dbp), T, dt, s));
+                                      (const float*)(base + L.qk_r), (float*)(base + P.t_dgp), (float*)(base + P.t_dbp), T, dt, s,
+                                      c.bias ? (float*)(base + P.t_dk32) : nullptr));
       HIP_TRY(st, launch_colsum((const float*)(base + P.t_dgp), headnorm_partials(T, c.n_q_heads), c.head_dim, slot + P.p_off[l][STAGE_P_GQ], s));
       HIP_TRY(st, launch_colsum((const float*)(base + P.t_dbp), headnorm_partials(T, c.n_kv_heads), c.head_dim, slot + P.p_off[l][STAGE_P_GK], s));
     }
-    if (c.bias) { rc = bias_grad(base + L.dqkv, P.n_qkv, P.p_off[l][STAGE_P_BQKV]); if (rc) return rc; }
+    if (c.bias) {
+      rc = bias_grad(base + L.dqkv, P.n_qkv, P.p_off[l][STAGE_P_BQKV]);
+      if (rc) return rc;
+      if (c.qk_norm) {   // the key block again, from the un-rounded gradients (a sum of cancelling terms)
+        const int nk = c.n_kv_heads * c.head_dim;
+        HIP_TRY(st, launch_colsum_rows(base + P.t_dk32, nk, (float*)(base + P.t_dbp), T, nk, F32, s));
+        HIP_TRY(st, launch_colsum((const float*)(base + P.t_dbp), n_chunk, nk, slot + P.p_off[l][STAGE_P_BQKV] + c.n_q_heads * c.head_dim, s));
+      }
+    }
     // dh1 = [dq|dk|dv] Wqkv^T
     g.A = base + L.dqkv; g.lda = P.n_qkv; g.B = param_ptr(st, l, STAGE_P_WQKV); g.ldb = P.n_qkv;
     g.C = base + P.t_dh; g.ldc = H; g.N = H; g.K = P.n_qkv; g.out_dtype = F32;
@@ -567,11 +597,13 @@ int stage_W(stage_t* st, int mb, void* stream) {
   const Plan& P = st->plan;
   const stage_config& c = P.c;
   MbSlot& m = st->mb[mb];
+  if (m.state == MB_POISONED) return refuse_poisoned(st, mb, "W");
   if (m.state != MB_B) {
     set_error(st, m.state == MB_W ? "W(%d) already issued" : "W(%d) before B(%d)", mb, mb);
     return STAGE_ENOTREADY;
   }
   if (st->dry) { m.state = MB_W; return STAGE_OK; }
+  int* poison = &m.state;
   hipStream_t s = (hipStream_t)stream;
   HIP_TRY(st, hipStreamWaitEvent(s, m.ev_B, 0));
   char* base = mb_base(st, mb);
@@ -604,9 +636,12 @@ int stage_grad_reduce(stage_t* st, void* grad_out_dev, void* stream) {
   if (!st) { set_tls_error("stage handle is NULL"); return STAGE_EINVAL; }
   const Plan& P = st->plan;
   if (!st->dry && !grad_out_dev) { set_error(st, "grad_out_dev is NULL"); return STAGE_EINVAL; }
-  for (int j = 0; j < P.c.n_microbatches; ++j)
+  for (int j = 0; j < P.c.n_microbatches; ++j) {
+    if (st->mb[j].state == MB_POISONED) return refuse_poisoned(st, j, "grad_reduce: slot");
     if (st->mb[j].state != MB_W) { set_error(st, "grad_reduce: W(%d) not issued", j); return STAGE_ENOTREADY; }
+  }
   if (!st->dry) {
+    int* poison = &st->mb[0].state;   // a failed reduce leaves grad_out undefined: the iteration cannot be completed
     hipStream_t s = (hipStream_t)stream;
     for (auto& m : st->mb) HIP_TRY(st, hipStreamWaitEvent(s, m.ev_W, 0));
     HIP_TRY(st, launch_grad_reduce(slot_base(st, 0), align_up(P.slot_floats * 4) / 4, P.c.n_microbatches,

@@ -447,6 +447,27 @@ def test_bias_variant_reduces_to_plain_layer_at_zero_bias():
     np.testing.assert_array_equal(ya, yb)
 
 
+def test_key_bias_gradient_vanishes_without_rope_or_head_norm():
+    # Adding the same vector to every key of a segment moves all scores of a query row by one constant, which
+    # the softmax removes: the loss does not depend on the key bias, so its gradient is exactly zero in exact
+    # arithmetic (fp64 round-off here), while the other projection biases have ordinary gradients.
+    cfg = _cfg(mlp_kind="gelu", causal=True, n_kv_heads=2, bias=True)
+    rng = np.random.default_rng(3)
+    T, cu = 9, [0, 4, 9]
+    params = _rand_params(cfg, rng)
+    x, dy = rng.standard_normal((T, cfg.hidden)), rng.standard_normal((T, cfg.hidden))
+    _, caches = O.stage_F(x, params, cu, cfg)
+    _, grads = O.stage_backward_unsplit(dy, caches, params, cfg)
+    for g in grads:
+        assert np.max(np.abs(g["bk"])) < 1e-12 * np.max(np.abs(g["bq"]))
+        assert np.max(np.abs(g["bv"])) > 1e-3
+    # with the rotary embedding the bias is rotated per position and the invariance is gone
+    cfg_r = _cfg(mlp_kind="gelu", causal=True, n_kv_heads=2, bias=True, rope=True)
+    _, caches = O.stage_F(x, params, cu, cfg_r)
+    _, grads = O.stage_backward_unsplit(dy, caches, params, cfg_r)
+    assert all(np.max(np.abs(g["bk"])) > 1e-6 for g in grads)
+
+
 def test_qk_norm_makes_scores_independent_of_the_projection_scale():
     # with head normalisation (eps = 0) scaling Wq or Wk by a positive constant changes nothing
     rng = np.random.default_rng(10)
