@@ -9,8 +9,13 @@ the stage plus stage_grad_reduce, inputs resident in HBM.  Prints ONE JSON line.
 value     = algorithmic TFLOP of the step / wall time (GEMM 2*T*P per layer per task kind,
             attention forward 4*d*n_q*pairs with pairs = s^2/2 causal or s^2 bidirectional,
             attention backward counted as twice the forward, no recompute, no elementwise flops).
-roofline  = the dominant kernel (the bf16 MFMA GEMM, timed alone on its largest forward shape
-            with HIP events on its stream) against the dense bf16 MFMA peak of 2.5 PFLOP/s.
+roofline  = the kernel with the largest share of the step time in the form the step launches it (the
+            bf16 MFMA GEMM in its weight-gradient form on the up projection, fp32 output: one call of the
+            W task), timed alone with HIP events on its stream, against the dense bf16 MFMA peak of
+            2.5 PFLOP/s.
+hbm_kernels = the HBM-bound kernels of the step timed alone through their own entry points (RMSNorm
+            forward and backward at [T, hidden], the gradient reduction), algorithmic bytes per call
+            against 8 TB/s, beside the rate of a plain device copy on the same box.
 cpu_baseline = the fp64 oracle, as it stands, timed on this machine's host cores on a bounded
             sample of the same workload.
 """
@@ -118,17 +123,77 @@ def gemm_roofline(shape, T, Bw, s, gen, n_launch=20, form="nn"):
     g_ms = g0.elapsed_time(g1) / n_launch
     g_fl = 2.0 * dims[0] * dims[1] * dims[2]
     ach = g_fl / (g_ms * 1e-3) / 1e12
-    traffic = None
+    # HBM traffic per call: a recorded rocprofv3 counter value (profiles/gemm_mfma_traffic.json names the
+    # counter summary it comes from), not a measurement of this run.
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "gemm_mfma_traffic.json")
-    if form == "nn" and os.path.exists(tpath):
+    if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(f"{T}x{N_up}x{shape.hidden}")
+            rec = json.load(open(tpath))
+            traffic = rec.get(f"{form}:{dims[0]}x{dims[1]}x{dims[2]}")
+            traffic_source = rec.get("source") if traffic is not None else None
         except Exception:
             traffic = None
-    label = "(one call: 256-row tiles + 128-row tail launch)" if form == "nn" else "(fp32 out)"
+    label = {"nn": "(one call: 256-row tiles + 128-row tail launch)", "nt": "(fp32 out)",
+             "tn": "(weight-gradient form of the W task, fp32 out)"}[form]
     return {"bound": "mfma", "kernel": f"gemm_mfma_dl_kernel {form.upper()} {dims[0]}x{dims[1]}x{dims[2]} bf16 {label}", "achieved": round(ach, 1),
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-            "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic}
+            "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic,
+            "traffic_source": traffic_source}
+
+
+def hbm_kernels(shape, T, M, grad_floats, s, gen, n_launch=20):
+    """The HBM-bound kernels alone, HIP events on the launch stream.  Algorithmic bytes (storage type bf16):
+    RMSNorm forward 2 * T * H * 2 B, RMSNorm backward 4 * T * H * 2 B (three reads, one write), gradient
+    reduction (M + 1) * P * 4 B.  `moved` is what the kernel really reads and writes (the residual stream and
+    the GEMM output it consumes are fp32 in this build)."""
+    import torch
+    import paper_2605_18750_amd as R
+    H = shape.hidden
+    dev = "cuda:0"
+    dt = R.STAGE_DTYPE_BF16
+    x = torch.empty((T, H), dtype=torch.float32, device=dev).normal_(0.0, 1.0, generator=gen)
+    dh = torch.empty((T, H), dtype=torch.float32, device=dev).normal_(0.0, 1.0, generator=gen)
+    add = torch.empty((T, H), dtype=torch.float32, device=dev).normal_(0.0, 1.0, generator=gen)
+    g = torch.ones(H, dtype=torch.bfloat16, device=dev)
+    h = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
+    r = torch.empty(T, dtype=torch.float32, device=dev)
+    out32 = torch.empty((T, H), dtype=torch.float32, device=dev)
+    out_t = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
+    dg = torch.empty(H, dtype=torch.float32, device=dev)
+    nb = R.rrfp_rmsnorm_bwd_workspace(T, H, dt)
+    ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+    n_red = min(grad_floats, 1 << 28) // 4 * 4
+    slots = torch.empty(M * n_red, dtype=torch.float32, device=dev).normal_(0.0, 1.0, generator=gen)
+    red = torch.empty(n_red, dtype=torch.float32, device=dev)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    cases = [
+        ("rmsnorm_fwd", lambda: R.rrfp_rmsnorm_fwd(x, g, h, r, T, H, 1e-5, dt, s), 2 * T * H * 2, T * H * (4 + 2)),
+        ("rmsnorm_bwd (+ gain gradient)", lambda: R.rrfp_rmsnorm_bwd(dh, x, r, g, add, out32, out_t, dg, ws, nb, T, H, dt, s),
+         4 * T * H * 2, T * H * (4 * 3 + 4 + 2)),
+        ("grad_reduce", lambda: R.rrfp_grad_reduce(slots, n_red, M, red, n_red, s), (M + 1) * n_red * 4, (M + 1) * n_red * 4),
+        ("device copy (torch, 1 GiB)", lambda: dst.copy_(src, non_blocking=True), 2 << 30, 2 << 30),
+    ]
+    out = []
+    with torch.cuda.stream(s):
+        for name, fn, alg, moved in cases:
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s)
+            for _ in range(n_launch):
+                fn()
+            e1.record(s)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / n_launch
+            gbs = alg / (ms * 1e-3) / 1e9
+            out.append({"kernel": name, "shape": f"T={T}, hidden={H}" if "rmsnorm" in name else
+                        (f"{M} slots x {n_red} fp32" if name == "grad_reduce" else "1 GiB"),
+                        "avg_launch_us": round(ms * 1e3, 2), "algorithmic_bytes": alg, "GB/s": round(gbs, 1),
+                        "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "moved_bytes": moved,
+                        "moved_GB/s": round(moved / (ms * 1e-3) / 1e9, 1)})
+    return out
 
 
 def pipeline_study(shape, cus, per_mb, n_stages, with_oracle):
@@ -190,8 +255,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="language")
     ap.add_argument("--streams", type=int, default=1, help="streams the tasks are dealt to (B/F/W order)")
-    ap.add_argument("--gemm-form", default="nn", choices=["nn", "nt", "tn"],
-                    help="with --only gemm: operand orientation (forward, input-gradient or weight-gradient form of the up projection)")
+    ap.add_argument("--gemm-form", default=None, choices=["nn", "nt", "tn"],
+                    help="operand orientation of the roofline GEMM (forward, input-gradient or weight-gradient form of the "
+                         "up projection); default: tn, the form with the largest share of the step")
     ap.add_argument("--only", default="step", choices=["step", "gemm", "copy", "pipeline"],
                     help="gemm: launch only the roofline GEMM (for counter runs); copy: a 2 GiB device copy, the "
                          "calibration of the FETCH_SIZE / WRITE_SIZE counters; pipeline: measure the per-microbatch "
@@ -242,7 +308,7 @@ def main():
         N_up = (2 if shape.mlp_kind == "swiglu" else 1) * shape.ffn
         Bw = torch.empty((shape.hidden, N_up), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, shape.w_std, generator=gen)
         print(json.dumps({"only": "gemm", "roofline": gemm_roofline(shape, T, Bw, torch.cuda.Stream(), gen, n_launch=args.steps,
-                                                                    form=args.gemm_form)}))
+                                                                    form=args.gemm_form or "tn")}))
         return
     M = shape.n_microbatches
     cus = [SI.default_cu_seqlens(shape, j) for j in range(M)]
@@ -347,16 +413,19 @@ def main():
     red_gbs = (M + 1) * gb / (red_ms * 1e-3) / 1e9
     grad_reduce = {"ms": round(red_ms, 4), "GB/s": round(red_gbs, 1), "frac_of_hbm_peak": round(red_gbs / PEAK_HBM_GBS, 4),
                    "bytes": (M + 1) * gb}
-    # Roofline of the dominant kernel: the MFMA GEMM on the largest forward shape of this stage
-    # (the MLP up projection), timed alone with HIP events on its stream.
-    roof = None
+    # Roofline of the dominant kernel: the weight-gradient GEMM of the up projection ([hidden, N_up] with
+    # K = tokens, fp32 out), the single launch with the largest share of the step and the form (both operands
+    # K-strided) that takes the largest share of the step overall; timed alone with HIP events on its stream.
+    roof, hbm = None, None
     if shape.dtype == "bf16":
         off, (r, c) = R.stage_param_layout(cfg, 0, R.STAGE_P_WUP)
-        roof = gemm_roofline(shape, T_max, params[off:off + r * c].view(r, c), streams[0], gen)
+        roof = gemm_roofline(shape, T_max, params[off:off + r * c].view(r, c), streams[0], gen, form=args.gemm_form or "tn")
 
     torch.cuda.synchronize()
     R.stage_destroy(st)
     del arena
+    if shape.dtype == "bf16":
+        hbm = hbm_kernels(shape, T_max, M, gb // 4, streams[0], gen)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -378,6 +447,7 @@ def main():
         "tasks": tasks,
         "grad_reduce": grad_reduce,
         "roofline": roof,
+        "hbm_kernels": hbm,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -39,7 +39,13 @@
  *   - tensors are row-major.  Activations are [T, hidden] with the T tokens of a
  *     microbatch packed; segment s is rows cu_seqlens[s] .. cu_seqlens[s+1]-1 and attention
  *     never crosses a segment boundary.  Storage dtype is fp32 or bf16 (config); every
- *     gradient slot and grad_out are fp32.
+ *     gradient slot and grad_out are fp32;
+ *   - on the bf16 path the library keeps its OWN copies of the forward activations that lead into
+ *     the attention scores (first norm output, q, k, v) and of Wqkv as IEEE halves (11-bit
+ *     significand), because the softmax amplifies their rounding error; interface tensors,
+ *     parameters and gradients stay bf16.  The half copy of Wqkv is refreshed by the first
+ *     stage_F after stage_create / stage_grad_reduce: the caller may change the parameters only
+ *     between stage_grad_reduce and the next stage_F.
  */
 #ifndef RRFP_STAGE_H
 #define RRFP_STAGE_H
@@ -179,7 +185,7 @@ int stage_grad_slot(stage_t* st, int mb, void** slot_dev /*host*/);
 enum {
   STAGE_T_X = 0,      /* fp32 [T, hidden]   layer input (residual stream)           */
   STAGE_T_H1 = 1,     /* storage [T, hidden] first RMSNorm output                   */
-  STAGE_T_QKV = 2,    /* storage [T, (n_q + 2 n_kv) d]                              */
+  STAGE_T_QKV = 2,    /* [T, (n_q + 2 n_kv) d]; fp32 path: fp32; bf16 path: IEEE half */
   STAGE_T_O = 3,      /* storage [T, n_q d]  attention output                       */
   STAGE_T_X1 = 4,     /* fp32 [T, hidden]   x + o Wo                                */
   STAGE_T_H2 = 5,     /* storage [T, hidden] second RMSNorm output                  */
@@ -190,7 +196,8 @@ enum {
   STAGE_T_DX1 = 10,   /* storage [T, hidden] gradient w.r.t. x1                     */
   STAGE_T_DQKV = 11,  /* storage, shape of STAGE_T_QKV                              */
   STAGE_T_LSE = 12,   /* fp32 [n_q, T]      log-sum-exp of the attention scores     */
-  STAGE_T_COUNT = 13
+  STAGE_T_H1_HALF = 13, /* bf16 path only: IEEE half [T, hidden], the first norm output as the QKV projection reads it */
+  STAGE_T_COUNT = 14
 };
 
 /* Device pointer of intermediate tensor `which` (STAGE_T_*) of `layer` for microbatch mb; valid to

@@ -156,7 +156,7 @@ def stage_grad_slot(st, mb: int) -> int:
 
 
 (STAGE_T_X, STAGE_T_H1, STAGE_T_QKV, STAGE_T_O, STAGE_T_X1, STAGE_T_H2, STAGE_T_UP, STAGE_T_M, STAGE_T_DY,
- STAGE_T_DUP, STAGE_T_DX1, STAGE_T_DQKV, STAGE_T_LSE, STAGE_T_COUNT) = range(14)
+ STAGE_T_DUP, STAGE_T_DX1, STAGE_T_DQKV, STAGE_T_LSE, STAGE_T_H1_HALF, STAGE_T_COUNT) = range(15)
 
 
 def stage_intermediate(st, mb: int, layer: int, which: int) -> int:

@@ -1,14 +1,15 @@
-// bf16 MFMA attention for gfx950: tiled online-softmax forward over packed segments with GQA,
-// causal or bidirectional masks and head_dim 64 / 80 / 128.
+// MFMA attention for gfx950 (the bf16 storage path of the stage): tiled online-softmax forward over packed
+// segments with GQA, causal or bidirectional masks and head_dim 64 / 80 / 128.  q, k, v (and dO in the
+// backward) arrive as IEEE halves, the output and dq, dk, dv leave as bf16: see attn_mfma_common.h.
 //
 // Forward.  A workgroup (8 wavefronts, two per SIMD) owns one query tile (up to 256 rows inside one
 // segment) of one query head; each wavefront owns 32 query rows and stays under 256 registers, so
 // that the softmax arithmetic of one wavefront runs under the MFMAs of the other one on its SIMD.
 // Keys and values stream through LDS in
 // steps of 64 rows with two stages (global loads of step k+1 are in flight while step k runs).
-// Scores are computed TRANSPOSED, S^T[key, query] = K Q^T with v_mfma_f32_32x32x16_bf16, so
+// Scores are computed TRANSPOSED, S^T[key, query] = K Q^T with v_mfma_f32_32x32x16_f16, so
 // that a lane holds one query column: the softmax row statistics are lane-local except one
-// exchange between the two halves of the wavefront, and the probabilities, rounded to bf16, are
+// exchange between the two halves of the wavefront, and the probabilities, converted to halves, are
 // already in the B-operand layout of the second product O^T[d, query] += V^T P^T.  V stays in
 // LDS in its memory orientation and its fragments come from the LDS transpose read.
 // Exponentials are base 2 (scores pre-multiplied by log2 e / sqrt(d)); the saved log-sum-exp
@@ -40,7 +41,7 @@ using KvRegs = uint4[FwdCfg<D, NT>::PER_THREAD];
 
 template <int D, int NT>
 __device__ __forceinline__ void kv_load(KvRegs<D, NT>& rk, KvRegs<D, NT>& rv,
-                                        const bf16_t* __restrict__ qkv, int ld, int kcol, int vcol, int k0, int k_end) {
+                                        const el_t* __restrict__ qkv, int ld, int kcol, int vcol, int k0, int k_end) {
   using C = FwdCfg<D, NT>;
 #pragma unroll
   for (int i = 0; i < C::PER_THREAD; ++i) {
@@ -49,7 +50,7 @@ __device__ __forceinline__ void kv_load(KvRegs<D, NT>& rk, KvRegs<D, NT>& rv,
     const int q = min(i * NT + (int)threadIdx.x, C::NCHUNK - 1);
     const int row = q / C::CH, c = q - row * C::CH;
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-    const bf16_t* p = qkv + (size_t)min(k0 + row, k_end - 1) * ld + c * 8;
+    const el_t* p = qkv + (size_t)min(k0 + row, k_end - 1) * ld + c * 8;
     rk[i] = __builtin_bit_cast(uint4, *reinterpret_cast<const u32x4*>(p + kcol));
     rv[i] = __builtin_bit_cast(uint4, *reinterpret_cast<const u32x4*>(p + vcol));
   }
@@ -78,7 +79,7 @@ __device__ __forceinline__ void kv_store(const KvRegs<D, NT>& rk, const KvRegs<D
 }
 
 template <int D, int NIB>
-__global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+__global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_kernel(const el_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                             float* __restrict__ o32, float* __restrict__ lse,
                                                             const AttnTile* __restrict__ tiles,
                                                             int Tn, int nq, int nkv, int causal, float scale_log2e) {
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
   const bool wave_has_rows = wq0 < tl.r1;
 
   // Q fragments (B operand): column = query wq0 + ib*32 + li, k = ds*16 + h*8 .. +8.
-  bf16x8 qf[NIB][NDS];
+  frag_t qf[NIB][NDS];
 #pragma unroll
   for (int ib = 0; ib < NIB; ++ib) {
     const int i = wq0 + ib * 32 + li;
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
     for (int ds = 0; ds < NDS; ++ds) {
       uint4 v = make_uint4(0, 0, 0, 0);
       if (i < tl.r1) v = *reinterpret_cast<const uint4*>(qkv + (size_t)i * ld + qcol + ds * 16 + h * 8);
-      qf[ib][ds] = __builtin_bit_cast(bf16x8, v);
+      qf[ib][ds] = __builtin_bit_cast(frag_t, v);
     }
   }
 
@@ -156,18 +157,18 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
     floatx16 s[2][NIB];
 #pragma unroll
     for (int jb = 0; jb < 2; ++jb) {
-      bf16x8 kfr[NDS];
+      frag_t kfr[NDS];
 #pragma unroll
       for (int ds = 0; ds < NDS; ++ds) {
         const uint4 kv4 = *reinterpret_cast<const uint4*>(sk + (jb * 32 + li) * C::KP + (ds * 2 + h) * 16);
-        kfr[ds] = __builtin_bit_cast(bf16x8, kv4);
+        kfr[ds] = __builtin_bit_cast(frag_t, kv4);
       }
 #pragma unroll
       for (int ib = 0; ib < NIB; ++ib) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[jb][ib][e] = 0.f;
 #pragma unroll
-        for (int ds = 0; ds < NDS; ++ds) s[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ds], qf[ib][ds], s[jb][ib], 0, 0, 0);
+        for (int ds = 0; ds < NDS; ++ds) s[jb][ib] = mfma16(kfr[ds], qf[ib][ds], s[jb][ib]);
       }
     }
     const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
           for (int e = 0; e < 16; ++e) oacc[db][ib][e] *= alpha;
       }
     }
-    bf16x8 pf[NIB][2][2];   // [ib][jb][u]: probabilities of 16 keys as a B operand
+    frag_t pf[NIB][2][2];   // [ib][jb][u]: probabilities of 16 keys as a B operand
 #pragma unroll
     for (int ib = 0; ib < NIB; ++ib) {
       float ps = 0.f;
@@ -238,14 +239,14 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
     for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        bf16x8 vfr[NDB];
+        frag_t vfr[NDB];
 #pragma unroll
         for (int db = 0; db < NDB; ++db) vfr[db] = frag_cols_tr(sv, C::VP, jb * 32 + u * 16, db * 32, lane);
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
           for (int ib = 0; ib < NIB; ++ib)
-            oacc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[db], pf[ib][jb][u], oacc[db][ib], 0, 0, 0);
+            oacc[db][ib] = mfma16(vfr[db], pf[ib][jb][u], oacc[db][ib]);
       }
     io_end(st);
     return true;
@@ -302,7 +303,7 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
 
 template <int D>
 __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __restrict__ o, const float* __restrict__ o32,
-                                                              const bf16_t* __restrict__ d_o, float* __restrict__ delta,
+                                                              const el_t* __restrict__ d_o, float* __restrict__ delta,
                                                               int Tn, int nq) {
   // 16 lanes per (token, head) pair, 8 elements per lane.
   const int pair = blockIdx.x * 16 + (threadIdx.x >> 4);
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16_t* __re
     } else {
       load_vec<bf16_t>(o + (size_t)pair * D + c * 8, x);
     }
-    load_vec<bf16_t>(d_o + (size_t)pair * D + c * 8, y);
+    load_vec<el_t>(d_o + (size_t)pair * D + c * 8, y);
 #pragma unroll
     for (int e = 0; e < 8; ++e) s += x[e] * y[e];
   }
@@ -353,7 +354,7 @@ struct DkvCfg {
 };
 
 template <int D>
-__global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+__global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restrict__ qkv, const el_t* __restrict__ d_o,
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
                                                             bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
                                                             int Tn, int nq, int nkv, int causal, float scale) {
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
   const bool wave_has_keys = wj0 < tl.r1;
   const float scale_log2e = scale * LOG2E;
 
-  bf16x8 kf[NDS], vf[NDS];
+  frag_t kf[NDS], vf[NDS];
 #pragma unroll
   for (int ds = 0; ds < NDS; ++ds) {
     uint4 v = make_uint4(0, 0, 0, 0), w = v;
@@ -381,8 +382,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
       v = *reinterpret_cast<const uint4*>(qkv + (size_t)j * ld + kcol + ds * 16 + h * 8);
       w = *reinterpret_cast<const uint4*>(qkv + (size_t)j * ld + vcol + ds * 16 + h * 8);
     }
-    kf[ds] = __builtin_bit_cast(bf16x8, v);
-    vf[ds] = __builtin_bit_cast(bf16x8, w);
+    kf[ds] = __builtin_bit_cast(frag_t, v);
+    vf[ds] = __builtin_bit_cast(frag_t, w);
     // MFMA operands only from here on: keep them in the accumulation half of the register file, which has
     // room, so that the fragment sets and the tile in flight fit in the other half without spilling
     asm volatile("" : "+a"(kf[ds]), "+a"(vf[ds]));
@@ -432,7 +433,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
   // MASK is a compile-time flag so that each variant of the step is one basic block.
   constexpr int NH0 = (NDS + 1) / 2, NH1 = NDS - NH0;      // head-dimension slices of 16 in the two halves
   constexpr int FS = NH0 > NDB ? NH0 : NDB;
-  struct FragSet { bf16x8 a[FS], b[FS]; };                // (Q, dO) row fragments or (dO^T, Q^T) transposed ones
+  struct FragSet { frag_t a[FS], b[FS]; };                // (Q, dO) row fragments or (dO^T, Q^T) transposed ones
   FragSet fx;                                              // carried from step to step: rows of block 0, first half
   auto load_rows = [&](const char* sq, const char* sd, int ib, int half, FragSet& f) {
 #pragma unroll
@@ -445,7 +446,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
                           char* next_stage, auto mask_tag) {
     constexpr bool MASK = decltype(mask_tag)::value;
     floatx16 sacc[2], dpacc[2];
-    bf16x8 pf[2][2], dsf[2][2];
+    frag_t pf[2][2], dsf[2][2];
     FragSet fy;
     auto load_tr = [&](int ib, int u, FragSet& f) {
 #pragma unroll
@@ -461,8 +462,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
       }
 #pragma unroll
       for (int i = 0; i < (half ? NH1 : NH0); ++i) {
-        sacc[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], kf[half * NH0 + i], sacc[ib], 0, 0, 0);
-        dpacc[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[i], vf[half * NH0 + i], dpacc[ib], 0, 0, 0);
+        sacc[ib] = mfma16(f.a[i], kf[half * NH0 + i], sacc[ib]);
+        dpacc[ib] = mfma16(f.b[i], vf[half * NH0 + i], dpacc[ib]);
       }
     };
     auto arith = [&](int ib, int u) {
@@ -493,8 +494,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const bf16_t* __rest
     auto dvdk = [&](int ib, int u, const FragSet& f) {
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
-        dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[db], pf[ib][u], dv[db], 0, 0, 0);
-        dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[db], dsf[ib][u], dk[db], 0, 0, 0);
+        dv[db] = mfma16(f.a[db], pf[ib][u], dv[db]);
+        dk[db] = mfma16(f.b[db], dsf[ib][u], dk[db]);
       }
     };
     // Order inside a group: the LDS reads first, then one MFMA per handful of vector instructions.
@@ -607,9 +608,9 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
   if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kkv, DkvCfg<D>::SMEM); e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)D);
   hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((a.T * a.nq + 15) / 16), dim3(256), 0, s, (const bf16_t*)a.o,
-                     a.o32, (const bf16_t*)a.d_o, a.delta, a.T, a.nq);
-  hipLaunchKernelGGL(kkv, dim3(a.nkv, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const bf16_t*)a.qkv,
-                     (const bf16_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale);
+                     a.o32, (const el_t*)a.d_o, a.delta, a.T, a.nq);
+  hipLaunchKernelGGL(kkv, dim3(a.nkv, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const el_t*)a.qkv,
+                     (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return launch_attn_dq_mfma(a, s);
@@ -624,7 +625,7 @@ hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
   static hipError_t once_status = hipSuccess;
   if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kern, C::SMEM); e != hipSuccess) return e;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(NT), C::SMEM, s, (const bf16_t*)a.qkv, (bf16_t*)a.o, a.o32, a.lse,
+  hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(NT), C::SMEM, s, (const el_t*)a.qkv, (bf16_t*)a.o, a.o32, a.lse,
                      a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale_log2e);
   return hipGetLastError();
 }

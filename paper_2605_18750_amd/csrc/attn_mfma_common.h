@@ -1,5 +1,12 @@
-// Pieces shared by the bf16 MFMA attention kernels (attn_mfma.hip, attn_mfma_dq.hip): vector types,
+// Pieces shared by the MFMA attention kernels (attn_mfma.hip, attn_mfma_dq.hip): vector types,
 // fragment reads from LDS tiles, and the global -> register -> LDS tile movers.
+//
+// Element types.  q, k, v and the kernels' copy of dO are IEEE halves (el_t), and so are the probabilities
+// and dS formed in registers: every matrix product here is a v_mfma_f32_32x32x16_f16.  The score S = q k^T
+// feeds an exponential, so a relative error e in q or k becomes an error |S| e in log-probability; with
+// bf16 operands (e = 2^-9) that is what dominated the error of the whole stage, with halves (2^-12) it does
+// not.  The attention OUTPUT and the gradients dq, dk, dv are written in bf16 (they feed bf16 GEMMs against
+// bf16 weights and bf16 gradients).
 #pragma once
 
 #include "kernels.h"
@@ -10,16 +17,22 @@
 namespace rrfp {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef f16_t el_t;                                            // element type of q, k, v, dO
+typedef _Float16 frag_t __attribute__((ext_vector_type(8)));   // eight of them: one MFMA operand fragment per lane
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
 
-__device__ __forceinline__ bf16x8 pack8(const float* p) {
+// Eight fp32 values (probabilities or dS, in range by construction) -> one operand fragment; one conversion
+// instruction per pair (truncating: a relative error below 2^-11, a quarter of bf16's rounding error).
+__device__ __forceinline__ frag_t pack8(const float* p) {
   uint4 w;
-  w.x = pack_bf16x2(p[0], p[1]); w.y = pack_bf16x2(p[2], p[3]);
-  w.z = pack_bf16x2(p[4], p[5]); w.w = pack_bf16x2(p[6], p[7]);
-  return __builtin_bit_cast(bf16x8, w);
+  w.x = pack_f16x2_rtz(p[0], p[1]); w.y = pack_f16x2_rtz(p[2], p[3]);
+  w.z = pack_f16x2_rtz(p[4], p[5]); w.w = pack_f16x2_rtz(p[6], p[7]);
+  return __builtin_bit_cast(frag_t, w);
+}
+__device__ __forceinline__ floatx16 mfma16(frag_t a, frag_t b, floatx16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
 constexpr int BKV = 64;        // keys per step
@@ -29,18 +42,18 @@ constexpr int FWD_NIB = 1;                // 32-query blocks per wavefront: 8 wa
 constexpr int DQ_NIB = 1;
 
 // Fragment of a tile stored [row][k] (pitch bytes): lane gets row row0 + (lane & 31), k = ks*16 + h*8 .. +8.
-__device__ __forceinline__ bf16x8 frag_rows(const char* tile, int pitch, int row0, int ks, int lane) {
+__device__ __forceinline__ frag_t frag_rows(const char* tile, int pitch, int row0, int ks, int lane) {
   const uint4 v = *reinterpret_cast<const uint4*>(tile + (row0 + (lane & 31)) * pitch + (ks * 2 + (lane >> 5)) * 16);
-  return __builtin_bit_cast(bf16x8, v);
+  return __builtin_bit_cast(frag_t, v);
 }
 
 // Transposed fragment of a tile stored [k][col] (pitch bytes): lane gets column col0 + (lane & 31) and
 // the eight k values kstart + {0..3} and kstart + 8 + {0..3}, kstart = k0 + (lane >> 5) * 4.  This is the
 // k order in which a 32x32 accumulator block, packed to bf16, serves as the other MFMA operand.
-__device__ __forceinline__ bf16x8 frag_cols_tr(const char* tile, int pitch, int k0, int col0, int lane) {
+__device__ __forceinline__ frag_t frag_cols_tr(const char* tile, int pitch, int k0, int col0, int lane) {
   const int krow = k0 + (lane >> 5) * 4 + ((lane & 15) >> 2);
   const int col = col0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  union { short4v hh[2]; bf16x8 v; } f;
+  union { short4v hh[2]; frag_t v; } f;
   f.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + krow * pitch + col * 2));
   f.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(tile + (krow + 8) * pitch + col * 2));
   return f.v;
@@ -54,7 +67,7 @@ template <int D, int ROWS, int NT = 256>
 using TileArr = uint4[TileRegs<D, ROWS, NT>::N];
 
 template <int D, int ROWS, int NT = 256>
-__device__ __forceinline__ void tile_load(TileArr<D, ROWS, NT>& r, const bf16_t* __restrict__ base, int ld,
+__device__ __forceinline__ void tile_load(TileArr<D, ROWS, NT>& r, const el_t* __restrict__ base, int ld,
                                           int row0, int row_end) {
   constexpr int CH = D / 8;
 #pragma unroll
@@ -71,7 +84,7 @@ __device__ __forceinline__ void tile_load(TileArr<D, ROWS, NT>& r, const bf16_t*
 // whose chunk lies past the tile re-reads the tile's last chunk (tile_store drops it).  For tiles whose
 // rows past the end only ever meet zero weights.
 template <int D, int ROWS, int NT = 256>
-__device__ __forceinline__ void tile_load_clamped(TileArr<D, ROWS, NT>& r, const bf16_t* __restrict__ base, int ld,
+__device__ __forceinline__ void tile_load_clamped(TileArr<D, ROWS, NT>& r, const el_t* __restrict__ base, int ld,
                                                   int row0, int row_end) {
   constexpr int CH = D / 8;
 #pragma unroll

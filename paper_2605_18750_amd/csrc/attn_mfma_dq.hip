@@ -1,4 +1,4 @@
-// dQ kernel of the bf16 MFMA attention backward (see attn_mfma.hip for the scheme).  It lives in its own
+// dQ kernel of the MFMA attention backward (see attn_mfma.hip for the scheme).  It lives in its own
 // translation unit because it is compiled with a different instruction-scheduling strategy than the other
 // attention kernels (the build passes -mllvm -amdgpu-sched-strategy=iterative-ilp for this file: measured
 // 8-10 % faster for this kernel, slower for the dK/dV kernel, neutral for the forward).
@@ -19,7 +19,7 @@ struct DqCfg {
 };
 
 template <int D, int NIB>
-__global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+__global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_kernel(const el_t* __restrict__ qkv, const el_t* __restrict__ d_o,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
                                                            int Tn, int nq, int nkv, int causal, float scale) {
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
   const bool wave_has_rows = wq0 < tl.r1;
   const float scale_log2e = scale * LOG2E;
 
-  bf16x8 qf[NIB][NDS], dof[NIB][NDS];
+  frag_t qf[NIB][NDS], dof[NIB][NDS];
   float lse2[NIB], dl[NIB];
 #pragma unroll
   for (int ib = 0; ib < NIB; ++ib) {
@@ -55,8 +55,8 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
         v = *reinterpret_cast<const uint4*>(qkv + (size_t)i * ld + qcol + ds * 16 + h * 8);
         w = *reinterpret_cast<const uint4*>(d_o + (size_t)i * nq * D + qcol + ds * 16 + h * 8);
       }
-      qf[ib][ds] = __builtin_bit_cast(bf16x8, v);
-      dof[ib][ds] = __builtin_bit_cast(bf16x8, w);
+      qf[ib][ds] = __builtin_bit_cast(frag_t, v);
+      dof[ib][ds] = __builtin_bit_cast(frag_t, w);
     }
   }
   floatx16 acc[NDB][NIB];
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
       floatx16 s[2], dp[2];
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb) {
-        bf16x8 kfr[NDS], vfr[NDS];      // all fragments of the 32-key block before its MFMAs
+        frag_t kfr[NDS], vfr[NDS];      // all fragments of the 32-key block before its MFMAs
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds) {
           kfr[ds] = frag_rows(sk, C::KP, jb * 32, ds, lane);
@@ -116,8 +116,8 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
         for (int e = 0; e < 16; ++e) { s[jb][e] = 0.f; dp[jb][e] = 0.f; }
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds) {
-          s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ds], qf[ib][ds], s[jb], 0, 0, 0);
-          dp[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[ds], dof[ib][ds], dp[jb], 0, 0, 0);
+          s[jb] = mfma16(kfr[ds], qf[ib][ds], s[jb]);
+          dp[jb] = mfma16(vfr[ds], dof[ib][ds], dp[jb]);
         }
       }
 #pragma unroll
@@ -139,13 +139,13 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-          const bf16x8 dsf = pack8(dsv + u * 8);
-          bf16x8 ktr[NDB];
+          const frag_t dsf = pack8(dsv + u * 8);
+          frag_t ktr[NDB];
 #pragma unroll
           for (int db = 0; db < NDB; ++db) ktr[db] = frag_cols_tr(sk, C::KP, jb * 32 + u * 16, db * 32, lane);
 #pragma unroll
           for (int db = 0; db < NDB; ++db)
-            acc[db][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr[db], dsf, acc[db][ib], 0, 0, 0);
+            acc[db][ib] = mfma16(ktr[db], dsf, acc[db][ib]);
         }
       }
     }
@@ -181,8 +181,8 @@ hipError_t dq_launch(const AttnArgs& a, hipStream_t s) {
   static hipError_t once_status = hipSuccess;
   if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kq, DqCfg<D>::SMEM); e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)D);
-  hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(FWD_Q_ROWS / (32 * DQ_NIB) * 64), DqCfg<D>::SMEM, s, (const bf16_t*)a.qkv,
-                     (const bf16_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale);
+  hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(FWD_Q_ROWS / (32 * DQ_NIB) * 64), DqCfg<D>::SMEM, s, (const el_t*)a.qkv,
+                     (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale);
   return hipGetLastError();
 }
 

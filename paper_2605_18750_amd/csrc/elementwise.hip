@@ -49,10 +49,12 @@ __global__ __launch_bounds__(256) void widen_kernel(const T* __restrict__ src, f
 // ---------------------------------------------------------------- RMSNorm forward
 // One wavefront per row; 4 rows per workgroup.  Two sweeps over the row (the second is
 // served by cache): sum of squares, then scale.  x is the fp32 residual stream.
+// h16, when given (bf16 storage only), receives the same values rounded to IEEE half: the copy the QKV
+// projection reads (the bf16 one then serves the weight-gradient GEMM, whose other operand is a bf16 gradient).
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restrict__ x, const T* __restrict__ g,
                                                           T* __restrict__ h, float* __restrict__ r_out,
-                                                          int Tn, int H, float eps) {
+                                                          int Tn, int H, float eps, f16_t* __restrict__ h16) {
   constexpr int V = Vec<T>::N;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
@@ -82,9 +84,16 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restric
 #pragma unroll
       for (int i = 0; i < V; ++i) v[i] = v[i] * r * gv[i];
       store_vec<T>(hr + c, v);
+      if constexpr (V == 8) {
+        if (h16) store_vec<f16_t>(h16 + (size_t)row * H + c, v);
+      }
     }
   } else {
-    for (int c = lane; c < H; c += WAVE) hr[c] = from_float<T>(xr[c] * r * to_float(g[c]));
+    for (int c = lane; c < H; c += WAVE) {
+      const float v = xr[c] * r * to_float(g[c]);
+      hr[c] = from_float<T>(v);
+      if (h16) h16[(size_t)row * H + c] = from_float<f16_t>(v);
+    }
   }
 }
 
@@ -342,7 +351,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const float* __restrict__ x, const T* __restrict__ g,
                                                             const T* __restrict__ b, T* __restrict__ h,
                                                             float* __restrict__ r_out, float* __restrict__ mu_out,
-                                                            int Tn, int H, float eps) {
+                                                            int Tn, int H, float eps, f16_t* __restrict__ h16) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= Tn) return;
@@ -355,7 +364,11 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const float* __restr
   const float r = 1.0f / sqrtf(wave_sum(ss) / (float)H + eps);
   if (lane == 0) { r_out[row] = r; mu_out[row] = mu; }
   T* hr = h + (size_t)row * H;
-  for (int c = lane; c < H; c += WAVE) hr[c] = from_float<T>((xr[c] - mu) * r * to_float(g[c]) + to_float(b[c]));
+  for (int c = lane; c < H; c += WAVE) {
+    const float v = (xr[c] - mu) * r * to_float(g[c]) + to_float(b[c]);
+    hr[c] = from_float<T>(v);
+    if (h16) h16[(size_t)row * H + c] = from_float<f16_t>(v);
+  }
 }
 
 // dx = add_in + r * (w - mean(w) - xhat * mean(w * xhat)),  w = dh * g,  xhat = (x - mu) * r.
@@ -421,16 +434,17 @@ __global__ __launch_bounds__(256) void colsum_rows_kernel(const T* __restrict__ 
 // RMSNorm over head_dim of every (token, head) d-vector of the first n_heads heads of a [T, ld] tensor, in
 // place: x <- xhat * g, with xhat = x * r saved (storage type) and r saved (fp32) for the backward.
 // Heads [0, nq) use gq, heads [nq, n_heads) use gk.  One wavefront per (token, head).
-template <typename T>
+// TP = type of the gains (the parameter storage type); T = type of the tensor and of the saved xhat.
+template <typename T, typename TP>
 __global__ __launch_bounds__(256) void headnorm_fwd_kernel(T* __restrict__ x, int ld, int nq, int n_heads, int d,
-                                                           const T* __restrict__ gq, const T* __restrict__ gk,
+                                                           const TP* __restrict__ gq, const TP* __restrict__ gk,
                                                            T* __restrict__ xhat, float* __restrict__ r_out, int Tn, float eps) {
   const size_t pair = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (pair >= (size_t)Tn * n_heads) return;
   const int t = (int)(pair / n_heads), hd = (int)(pair - (size_t)t * n_heads);
   T* p = x + (size_t)t * ld + hd * d;
-  const T* g = hd < nq ? gq : gk;
+  const TP* g = hd < nq ? gq : gk;
   float ss = 0.f;
   for (int c = lane; c < d; c += WAVE) { const float v = to_float(p[c]); ss += v * v; }
   const float r = 1.0f / sqrtf(wave_sum(ss) / (float)d + eps);
@@ -445,10 +459,11 @@ __global__ __launch_bounds__(256) void headnorm_fwd_kernel(T* __restrict__ x, in
 // Backward, in place on the gradient tensor: dx = r * (w - xhat * mean(w * xhat)), w = dy * g.  A workgroup
 // handles 64 consecutive (token, head) pairs of ONE kind (grid y = 0: query heads, 1: key heads) and writes
 // one partial row of the gain gradient, sum over its pairs (ascending, wavefronts combined in order) of dy * xhat.
-template <typename T>
+// TX = type of the saved xhat (the forward's tensor type); T = type of the gradient tensor and of the gains.
+template <typename T, typename TX>
 __global__ __launch_bounds__(256) void headnorm_bwd_kernel(T* __restrict__ dy, int ld, int nq, int n_heads, int d,
                                                            const T* __restrict__ gq, const T* __restrict__ gk,
-                                                           const T* __restrict__ xhat, const float* __restrict__ r_in,
+                                                           const TX* __restrict__ xhat, const float* __restrict__ r_in,
                                                            float* __restrict__ partial_q, float* __restrict__ partial_k, int Tn,
                                                            float* __restrict__ dk32) {
   __shared__ float red[4][128];
@@ -559,6 +574,15 @@ inline int grid_for(size_t n, int cap = 256 * 32) {
   if ((dtype) == F32) { using T = float; __VA_ARGS__; } \
   else { using T = bf16_t; __VA_ARGS__; }
 
+// bf16 -> IEEE half, element by element (exact except below half's normal range; saturating).
+__global__ __launch_bounds__(256) void bf16_to_f16_kernel(const bf16_t* __restrict__ src, f16_t* __restrict__ dst, size_t n8) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    float v[8];
+    load_vec<bf16_t>(src + i * 8, v);
+    store_vec<f16_t>(dst + i * 8, v);
+  }
+}
+
 hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s) {
   DISPATCH_T(dtype, hipLaunchKernelGGL(widen_kernel<T>, dim3(grid_for(n / Vec<T>::N + 1)), dim3(256), 0, s, (const T*)src, dst, n));
   return hipGetLastError();
@@ -567,15 +591,20 @@ hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStr
 hipError_t launch_rope(void* x, const AttnTile* q_tiles, int n_q_tiles, int n_heads, int d, int ld, float base,
                        float sign, int dtype, hipStream_t s) {
   if (n_q_tiles < 1 || n_heads < 1 || (d & 1) || !(base > 1.0f)) return hipErrorInvalidValue;
+  if (dtype == F16) {
+    hipLaunchKernelGGL(rope_kernel<f16_t>, dim3(n_q_tiles, n_heads), dim3(256), 0, s, (f16_t*)x, q_tiles, d, ld, log2((double)base), sign);
+    return hipGetLastError();
+  }
   DISPATCH_T(dtype, hipLaunchKernelGGL(rope_kernel<T>, dim3(n_q_tiles, n_heads), dim3(256), 0, s, (T*)x, q_tiles, d, ld,
                                        log2((double)base), sign));
   return hipGetLastError();
 }
 
 hipError_t launch_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_out, int Tn, int H, float eps,
-                              int dtype, hipStream_t s) {
+                              int dtype, hipStream_t s, void* h16) {
+  if (h16 && dtype != BF16) return hipErrorInvalidValue;
   DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_fwd_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, x, (const T*)g, (T*)h,
-                                       r_out, Tn, H, eps));
+                                       r_out, Tn, H, eps, (f16_t*)h16));
   return hipGetLastError();
 }
 
@@ -627,17 +656,28 @@ hipError_t launch_headnorm_fwd(void* x, int ld, int nq, int n_heads, int d, cons
                                float* r_out, int Tn, float eps, int dtype, hipStream_t s) {
   if (d > 128) return hipErrorInvalidValue;
   const size_t pairs = (size_t)Tn * n_heads;
-  DISPATCH_T(dtype, hipLaunchKernelGGL(headnorm_fwd_kernel<T>, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s, (T*)x, ld, nq,
+  if (dtype == F16) {   // half tensor, bf16 gains
+    hipLaunchKernelGGL((headnorm_fwd_kernel<f16_t, bf16_t>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s, (f16_t*)x, ld, nq,
+                       n_heads, d, (const bf16_t*)gq, (const bf16_t*)gk, (f16_t*)xhat, r_out, Tn, eps);
+    return hipGetLastError();
+  }
+  DISPATCH_T(dtype, hipLaunchKernelGGL((headnorm_fwd_kernel<T, T>), dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, s, (T*)x, ld, nq,
                                        n_heads, d, (const T*)gq, (const T*)gk, (T*)xhat, r_out, Tn, eps));
   return hipGetLastError();
 }
 
 hipError_t launch_headnorm_bwd(void* dy, int ld, int nq, int n_heads, int d, const void* gq, const void* gk, const void* xhat,
                                const float* r_in, float* partial_q, float* partial_k, int Tn, int dtype, hipStream_t s,
-                               float* dk32) {
+                               float* dk32, int xhat_dtype) {
   if (d > 128) return hipErrorInvalidValue;
   const int nb = std::max(headnorm_partials(Tn, nq), headnorm_partials(Tn, n_heads - nq));
-  DISPATCH_T(dtype, hipLaunchKernelGGL(headnorm_bwd_kernel<T>, dim3(nb, 2), dim3(256), 0, s, (T*)dy, ld, nq, n_heads, d,
+  if (xhat_dtype == F16) {
+    if (dtype != BF16) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((headnorm_bwd_kernel<bf16_t, f16_t>), dim3(nb, 2), dim3(256), 0, s, (bf16_t*)dy, ld, nq, n_heads, d,
+                       (const bf16_t*)gq, (const bf16_t*)gk, (const f16_t*)xhat, r_in, partial_q, partial_k, Tn, dk32);
+    return hipGetLastError();
+  }
+  DISPATCH_T(dtype, hipLaunchKernelGGL((headnorm_bwd_kernel<T, T>), dim3(nb, 2), dim3(256), 0, s, (T*)dy, ld, nq, n_heads, d,
                                        (const T*)gq, (const T*)gk, (const T*)xhat, r_in, partial_q, partial_k, Tn, dk32));
   return hipGetLastError();
 }
@@ -645,9 +685,10 @@ hipError_t launch_headnorm_bwd(void* dy, int ld, int nq, int n_heads, int d, con
 int colsum_chunks(int Tn) { return (Tn + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS; }
 
 hipError_t launch_layernorm_fwd(const float* x, const void* g, const void* b, void* h, float* r_out, float* mu_out,
-                                int Tn, int H, float eps, int dtype, hipStream_t s) {
+                                int Tn, int H, float eps, int dtype, hipStream_t s, void* h16) {
+  if (h16 && dtype != BF16) return hipErrorInvalidValue;
   DISPATCH_T(dtype, hipLaunchKernelGGL(layernorm_fwd_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, x, (const T*)g,
-                                       (const T*)b, (T*)h, r_out, mu_out, Tn, H, eps));
+                                       (const T*)b, (T*)h, r_out, mu_out, Tn, H, eps, (f16_t*)h16));
   return hipGetLastError();
 }
 
@@ -705,6 +746,12 @@ hipError_t launch_gelu_bwd(const float* dm, const void* u, void* du, int Tn, int
     const size_t nv = (size_t)Tn * F / Vec<T>::N;
     hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for(nv)), dim3(256), 0, s, dm, (const T*)u, (T*)du, nv);
   });
+  return hipGetLastError();
+}
+
+hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s) {
+  if (n % 8 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bf16_to_f16_kernel, dim3(grid_for(n / 8)), dim3(256), 0, s, (const bf16_t*)src, (f16_t*)dst, n / 8);
   return hipGetLastError();
 }
 

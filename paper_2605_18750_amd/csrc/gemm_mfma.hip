@@ -29,6 +29,7 @@
 // the choice of 128-row tiles and the split-K factor depend only on the shape and on the device's CU
 // count, never on what else is running, so a given call always sums in the same order.
 #include <algorithm>
+#include <type_traits>
 
 #include "kernels.h"
 #include "numeric.h"
@@ -398,12 +399,20 @@ struct Frags { bf16x8 alo[MA], ahi[MA], b[2][NF]; };
 
 // acc[i0 + i][j] += A block i x B block j.  The B fragment is the first operand: a lane's four accumulator
 // values are four consecutive columns of one row of C.
-template <int MA, int NF, int MI16>
+// F16: the 16-bit operands are IEEE halves (v_mfma_f32_16x16x32_f16; same rate, same fragment layout).
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+template <int MA, int NF, int MI16, bool F16 = false>
 __device__ __forceinline__ void mfma_blocks(floatx4 (&acc)[MI16][NF], const bf16x8 (&a)[MA], const bf16x8 (&b)[NF], int i0) {
 #pragma unroll
   for (int i = 0; i < MA; ++i)
 #pragma unroll
-    for (int j = 0; j < NF; ++j) acc[i0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i0 + i][j], 0, 0, 0);
+    for (int j = 0; j < NF; ++j) {
+      if constexpr (F16)
+        acc[i0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, b[j]), __builtin_bit_cast(halfx8, a[i]),
+                                                                acc[i0 + i][j], 0, 0, 0);
+      else
+        acc[i0 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i0 + i][j], 0, 0, 0);
+    }
 }
 
 // 32x32x16 path (both operands K-strided): fragments of one 16-wide k-step, MI row blocks of A and NB column
@@ -466,7 +475,9 @@ __device__ __forceinline__ void unpack4(uint2 w, float* v) {
 
 // BMT = rows of the C tile: 256, or 128 for the short tiles that finish a GEMM whose tile count is
 // not a multiple of the CU count (A K-contiguous only).  tn0 = first tile column of this launch.
-template <bool A_KC, bool B_KC, typename TO, bool HAS_R, int WM, int WN, int ACT, int BMT = 256>
+// F16IN: A and B hold IEEE halves instead of bf16 (forms with a K-contiguous operand only); TO may be float,
+// bf16_t or f16_t.
+template <bool A_KC, bool B_KC, typename TO, bool HAS_R, int WM, int WN, int ACT, int BMT = 256, bool F16IN = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                TO* __restrict__ C, const float* __restrict__ R, int M,
                                                                int N, int K, int lda, int ldb, int ldc, int ldr,
@@ -498,6 +509,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   const int wm = (wave / WN) * WAVE_M, wn = (wave % WN) * WAVE_N;
 
   constexpr bool M32 = dl_m32(A_KC, B_KC);          // 32x32x16 accumulators (acc32) instead of 16x16x32 ones (acc)
+  static_assert(!(M32 && F16IN), "half inputs are built for the 16x16x32 forms only");
   constexpr int MI16 = 2 * MI, NF = 2 * NB, MA = MI;   // 16-row / 16-column blocks per wavefront; A blocks per half
   floatx4 acc[M32 ? 1 : MI16][M32 ? 1 : NF];
   floatx16 acc32[M32 ? MI : 1][M32 ? NB : 1];
@@ -559,7 +571,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
       interleave_ds_vm_mfma<2 * (MI + NB), MI * NB, (PAR == 0 ? NQ3 : NQ1)>();                           \
     } else {                                                                                             \
       load_blocks<A_KC, MA>(fr.ahi, b0, off_ahi);                                                        \
-      mfma_blocks<MA, NF, MI16>(acc, fr.alo, fr.b[PAR], 0);                                              \
+      mfma_blocks<MA, NF, MI16, F16IN>(acc, fr.alo, fr.b[PAR], 0);                                       \
       interleave_ds_vm_mfma<DS_A, N_MFMA, (PAR == 0 ? NQ3 : NQ1)>();                                     \
     }                                                                                                    \
     if (!GUARD || (tt) + 1 < nk) {                                                                       \
@@ -575,7 +587,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
       }                                                                                                  \
     }                                                                                                    \
     if constexpr (M32) mfma32<MI, NB>(acc32, fy);                                                        \
-    else mfma_blocks<MA, NF, MI16>(acc, fr.ahi, fr.b[PAR], MA);                                          \
+    else mfma_blocks<MA, NF, MI16, F16IN>(acc, fr.ahi, fr.b[PAR], MA);                                   \
     if (!GUARD) {                                                                                        \
       if constexpr (M32) interleave_ds_vm_mfma<2 * (MI + NB), MI * NB, (PAR == 0 ? NQ0 : NQ2)>();        \
       else interleave_ds_vm_mfma<DS_A + DS_B, N_MFMA, (PAR == 0 ? NQ0 : NQ2)>();                         \
@@ -779,7 +791,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
             *reinterpret_cast<float4*>(crow + 4) = make_float4(v[4], v[5], v[6], v[7]);
           }
         } else {
-          if (ok) store_vec<bf16_t>((bf16_t*)C + (size_t)m * ldc + n, v);
+          using T16 = std::conditional_t<sizeof(TO) == 2, TO, bf16_t>;    // bf16_t or f16_t
+          if (ok) store_vec<T16>((T16*)C + (size_t)m * ldc + n, v);
         }
       }
     }
@@ -807,6 +820,16 @@ RRFP_INST(true, false, bf16_t, false, ACT_SWIGLU_FWD) RRFP_INST(true, false, bf1
 RRFP_INST(true, true, bf16_t, false, ACT_SWIGLU_BWD) RRFP_INST(true, true, bf16_t, false, ACT_GELU_BWD)
 #undef RRFP_INST4
 #undef RRFP_INST
+// Half-precision forms of the attention-input path: the QKV projection (half in, half out) and the gradient
+// of the attention output, dO = dx1 Wo^T (bf16 in, half out), each with its 128-row tile variant.
+template __global__ void gemm_mfma_dl_kernel<true, false, f16_t, false, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 256, true>(
+    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+template __global__ void gemm_mfma_dl_kernel<true, false, f16_t, false, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 128, true>(
+    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+template __global__ void gemm_mfma_dl_kernel<true, true, f16_t, false, dl_wm(true, true), dl_wn(true, true), ACT_NONE, 256, false>(
+    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+template __global__ void gemm_mfma_dl_kernel<true, true, f16_t, false, dl_wm(true, true), dl_wn(true, true), ACT_NONE, 128, false>(
+    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
 
 // True when the direct-to-LDS kernel can take the call (else the register-staged one does).
 inline bool direct_ok(const GemmArgs& g) {
@@ -859,18 +882,18 @@ inline int splitk_factor(int t, int K, int n_cu) {
 }
 
 // Launch of the direct-to-LDS kernel for the forms with A K-contiguous, per the cut above.
-template <bool B_KC, typename TO, bool HAS_R, int ACT>
+template <bool B_KC, typename TO, bool HAS_R, int ACT, bool F16IN = false>
 hipError_t launch_a_kc(const GemmArgs& g, hipStream_t s) {
   constexpr int WMv = dl_wm(true, B_KC), WNv = dl_wn(true, B_KC);
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   const int cn = full_tile_columns(tiles_m, tiles_n, cu_count());
   if (cn > 0)
-    hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT>), dim3(tiles_m * cn), dim3(WMv * WNv * 64),
+    hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT, 256, F16IN>), dim3(tiles_m * cn), dim3(WMv * WNv * 64),
                        0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc,
                        g.ldr, tiles_m, cn, (bf16_t*)g.E, g.lde, 0, 0, (const bf16_t*)g.bias);
   if (cn < tiles_n) {
     const int tiles_m2 = (g.M + 127) / 128;
-    hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT, 128>), dim3(tiles_m2 * (tiles_n - cn)),
+    hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT, 128, F16IN>), dim3(tiles_m2 * (tiles_n - cn)),
                        dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K,
                        g.lda, g.ldb, g.ldc, g.ldr, tiles_m2, tiles_n - cn, (bf16_t*)g.E, g.lde, cn, 0, (const bf16_t*)g.bias);
   }
@@ -976,7 +999,13 @@ GemmPlan gemm_mfma_plan(const GemmArgs& g, int n_cu, bool have_scratch) {
 }
 
 bool gemm_mfma_supports(const GemmArgs& g) {
-  if (g.in_dtype != BF16) return false;
+  if (g.in_dtype != BF16 && g.in_dtype != F16) return false;
+  if (g.in_dtype == F16 || g.out_dtype == F16) {
+    // half forms: QKV projection (half x half -> half, NN) and dO (bf16 x bf16 -> half, NT); direct-load kernel only
+    const bool qkv_form = g.in_dtype == F16 && g.out_dtype == F16 && !g.transA && !g.transB;
+    const bool do_form = g.in_dtype == BF16 && g.out_dtype == F16 && !g.transA && g.transB;
+    if (!(qkv_form || do_form) || g.R || g.act != ACT_NONE || !direct_ok(g)) return false;
+  }
   if (g.bias && (!direct_ok(g) || ((uintptr_t)g.bias & 15))) return false;   // bias lives in the direct-load kernel's epilogue
   if (g.M < 1 || g.N < 1 || g.K < 1) return false;
   if ((g.lda | g.ldb | g.ldc) & 7) return false;
@@ -1001,6 +1030,8 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     }
   }
   const bool a_kc = !g.transA, b_kc = g.transB;
+  if (g.in_dtype == F16) return launch_a_kc<false, f16_t, false, ACT_NONE, true>(g, s);
+  if (g.out_dtype == F16) return launch_a_kc<true, f16_t, false, ACT_NONE, false>(g, s);
   if (a_kc && !b_kc) return launch_orient<true, false>(g, s);
   if (a_kc && b_kc) return launch_orient<true, true>(g, s);
   if (!a_kc && !b_kc) return launch_orient<false, false>(g, s);

@@ -8,7 +8,9 @@
 
 namespace rrfp {
 
-enum DType : int { F32 = 0, BF16 = 1 };
+// F16 (IEEE half) is internal: the library's own copies of forward activations on the path into the
+// attention scores.  It never appears at the C interface (STAGE_DTYPE_* has fp32 and bf16 only).
+enum DType : int { F32 = 0, BF16 = 1, F16 = 2 };
 
 static inline size_t dtype_size(int dt) { return dt == F32 ? 4 : 2; }
 
@@ -64,7 +66,8 @@ constexpr int ATTN_TILE_Q = 256;   // rows per query tile (forward and dQ kernel
 constexpr int ATTN_TILE_KV = 128;  // rows per key tile (dK/dV kernel)
 
 struct AttnArgs {
-  const void* qkv;      // [T, (nq + 2 nkv) d]: Q heads, K heads, V heads
+  const void* qkv;      // [T, (nq + 2 nkv) d]: Q heads, K heads, V heads.  dtype BF16 (the MFMA kernels): IEEE halves,
+                        // and so is d_o; the outputs o and dqkv are bf16.  dtype F32: everything fp32.
   void* o;              // [T, nq d]
   float* o32;           // [T, nq d] fp32 copy of o before rounding (bf16 MFMA path; else null): the
                         // backward forms delta from it so that rounding o does not break sum_j dS_ij = 0
@@ -94,8 +97,11 @@ hipError_t launch_rope(void* x, const AttnTile* q_tiles, int n_q_tiles, int n_he
                        float sign, int dtype, hipStream_t s);
 
 // h = x * r * g, r = rsqrt(mean(x^2) + eps); x fp32, r_out [T] fp32, g and h storage type.
+// h16 (optional, bf16 storage only): the same output rounded to IEEE half instead of bf16, [T, H].
 hipError_t launch_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_out,
-                              int T, int H, float eps, int dtype, hipStream_t s);
+                              int T, int H, float eps, int dtype, hipStream_t s, void* h16 = nullptr);
+// dst[i] = (half)src[i] for n bf16 values (n a multiple of 8, 16-byte aligned pointers); saturating.
+hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t s);
 
 constexpr int NORM_BWD_ROWS = 64;  // rows per partial of the gain-gradient column sum (unfused kernels)
 // Number of partial rows launch_rmsnorm_bwd writes for this shape (a pure function of shape and dtype:
@@ -113,7 +119,7 @@ hipError_t launch_colsum(const float* partial, int n_partial, int H, float* out,
 // the per-chunk partial sums of the gain and bias gradients ([colsum_chunks(T), H] each, for launch_colsum).
 int colsum_chunks(int T);
 hipError_t launch_layernorm_fwd(const float* x, const void* g, const void* b, void* h, float* r_out, float* mu_out,
-                                int T, int H, float eps, int dtype, hipStream_t s);
+                                int T, int H, float eps, int dtype, hipStream_t s, void* h16 = nullptr);
 hipError_t launch_layernorm_bwd(const float* dh, const float* x, const float* r, const float* mu, const void* g,
                                 const float* add_in, float* out32, void* out_t, float* partial_g, float* partial_b,
                                 int T, int H, int dtype, hipStream_t s);
@@ -126,7 +132,8 @@ hipError_t launch_headnorm_fwd(void* x, int ld, int nq, int n_heads, int d, cons
                                float* r_out, int T, float eps, int dtype, hipStream_t s);
 hipError_t launch_headnorm_bwd(void* dy, int ld, int nq, int n_heads, int d, const void* gq, const void* gk, const void* xhat,
                                const float* r_in, float* partial_q, float* partial_k, int T, int dtype, hipStream_t s,
-                               float* dk32 = nullptr);   // optional fp32 copy [T, n_key_heads * d] of the rewritten key-head gradients
+                               float* dk32 = nullptr,    // optional fp32 copy [T, n_key_heads * d] of the rewritten key-head gradients
+                               int xhat_dtype = -1);     // type of the saved xhat when it differs from dtype (F16: forward ran on a half tensor)
 // Per-chunk column sums of a [T, N] tensor of the storage type into partial [colsum_chunks(T), N] (bias gradients).
 hipError_t launch_colsum_rows(const void* src, int ld, float* partial, int T, int N, int dtype, hipStream_t s);
 

@@ -39,6 +39,7 @@ struct LayerStash {
   size_t o32;                                         // written by F: attention output before rounding (bf16 path)
   size_t mu1, mu2;                                    // written by F: row means (LayerNorm variant)
   size_t qk_hat, qk_r;                                // written by F: normalised q, k heads and their 1/rms (QK-norm variant)
+  size_t h1_16;                                       // written by F (bf16 path): first norm output as IEEE halves, operand of the QKV projection
 };
 
 struct Plan {
@@ -55,6 +56,7 @@ struct Plan {
   size_t mb_bytes;                  // one microbatch region
   size_t slots_off;                 // start of the M gradient slots
   size_t slot_floats;               // floats per slot (= param_elems)
+  size_t w16_off[64];               // bf16 path: IEEE-half copy of every layer's Wqkv (byte offsets in the arena), refreshed once per iteration
   size_t arena_bytes;
 };
 
@@ -134,6 +136,7 @@ int make_plan(const stage_config* c, Plan* p) {
     s.mu2 = c->norm_kind == 1 ? take(T * 4) : 0;
     s.qk_hat = c->qk_norm ? take(T * (nq + nkv) * d * e) : 0;
     s.qk_r = c->qk_norm ? take(T * (nq + nkv) * 4) : 0;
+    s.h1_16 = c->dtype == STAGE_DTYPE_BF16 ? take(T * H * 2) : 0;
   }
   p->t_dm = take(T * F * 4);     // fp32: GEMM outputs that only an elementwise kernel consumes are not rounded
   p->t_dh = take(T * H * 4);
@@ -155,6 +158,10 @@ int make_plan(const stage_config* c, Plan* p) {
   p->mb_bytes = o;
   p->slots_off = p->mb_bytes * (size_t)c->n_microbatches;
   p->arena_bytes = p->slots_off + align_up(p->slot_floats * 4) * (size_t)c->n_microbatches;
+  for (int l = 0; l < c->n_layers; ++l) {
+    p->w16_off[l] = p->arena_bytes;
+    if (c->dtype == STAGE_DTYPE_BF16) p->arena_bytes += align_up(H * (size_t)p->n_qkv * 2);
+  }
   return STAGE_OK;
 }
 
@@ -181,6 +188,8 @@ struct stage_s {
   std::vector<MbSlot> mb;
   hipEvent_t ev_reduce = nullptr;
   bool reduce_recorded = false;
+  hipEvent_t ev_w16 = nullptr;      // the half copies of Wqkv of this iteration are complete
+  bool w16_valid = false;           // false from stage_create / stage_grad_reduce until the next stage_F
   char err[512] = "";
 };
 
@@ -313,6 +322,7 @@ int stage_create(const stage_config* cfg, const void* params_dev, void* arena_de
     if (e == hipSuccess) e = hipHostMalloc((void**)&m.staging, 2 * (size_t)st->plan.max_tiles * sizeof(AttnTile), hipHostMallocDefault);
   }
   if (e == hipSuccess) e = hipEventCreateWithFlags(&st->ev_reduce, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&st->ev_w16, hipEventDisableTiming);
   if (e != hipSuccess) {
     set_tls_error("HIP set-up failed: %s", hipGetErrorString(e));
     stage_destroy(st);
@@ -333,6 +343,7 @@ int stage_destroy(stage_t* st) {
       if (m.staging) (void)hipHostFree(m.staging);
     }
     if (st->ev_reduce) (void)hipEventDestroy(st->ev_reduce);
+    if (st->ev_w16) (void)hipEventDestroy(st->ev_w16);
   }
   delete st;
   return STAGE_OK;
@@ -356,7 +367,11 @@ int stage_intermediate(stage_t* st, int mb, int layer, int which, void** ptr_dev
     return STAGE_EINVAL;
   }
   const LayerStash& L = st->plan.layer[layer];
-  const size_t off[STAGE_T_COUNT] = {L.x, L.h1, L.qkv, L.o, L.x1, L.h2, L.up, L.m, L.dy, L.dup, L.dx1, L.dqkv, L.lse};
+  const size_t off[STAGE_T_COUNT] = {L.x, L.h1, L.qkv, L.o, L.x1, L.h2, L.up, L.m, L.dy, L.dup, L.dx1, L.dqkv, L.lse, L.h1_16};
+  if (which == STAGE_T_H1_HALF && st->plan.c.dtype != STAGE_DTYPE_BF16) {
+    set_error(st, "stage_intermediate: the half copy of h1 exists on the bf16 path only");
+    return STAGE_EINVAL;
+  }
   *ptr_dev = st->dry ? nullptr : (void*)(mb_base(st, mb) + off[which]);
   return STAGE_OK;
 }
@@ -397,12 +412,27 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
 
   char* base = mb_base(st, mb);
   if (st->reduce_recorded) HIP_TRY(st, hipStreamWaitEvent(s, st->ev_reduce, 0));
+  if (c.dtype == STAGE_DTYPE_BF16) {
+    // The QKV projection runs on IEEE-half operands.  The first F of an iteration converts every layer's Wqkv
+    // (the caller may have changed the parameters since the last stage_grad_reduce) on its own stream, behind
+    // the previous reduce and so behind every earlier reader of the copies; every F waits for that conversion.
+    if (!st->w16_valid) {
+      for (int l = 0; l < c.n_layers; ++l)
+        HIP_TRY(st, launch_bf16_to_f16(param_ptr(st, l, STAGE_P_WQKV), st->arena + P.w16_off[l], (size_t)c.hidden * P.n_qkv, s));
+      HIP_TRY(st, hipEventRecord(st->ev_w16, s));
+      st->w16_valid = true;
+    } else {
+      HIP_TRY(st, hipStreamWaitEvent(s, st->ev_w16, 0));
+    }
+  }
   HIP_TRY(st, hipMemcpyAsync(base + P.t_qtiles, qt, (size_t)m.n_q_tiles * sizeof(AttnTile), hipMemcpyHostToDevice, s));
   HIP_TRY(st, hipMemcpyAsync(base + P.t_kvtiles, kt, (size_t)m.n_kv_tiles * sizeof(AttnTile), hipMemcpyHostToDevice, s));
   HIP_TRY(st, hipEventRecord(m.ev_copy, s));
   m.copy_pending = true;
 
   const int H = c.hidden, F = c.ffn, dt = c.dtype, nqd = c.n_q_heads * c.head_dim;
+  const bool half_path = dt == BF16;            // h1 -> QKV projection -> attention run on IEEE halves
+  const int qdt = half_path ? (int)F16 : dt;    // element type of the q|k|v stash
   HIP_TRY(st, launch_widen(x_dev, (float*)(base + P.layer[0].x), (size_t)T * H, dt, s));
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerStash& L = P.layer[l];
@@ -410,22 +440,25 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     void* y_out = last ? y_dev : (void*)(base + P.layer[l + 1].x);
     if (c.norm_kind == 1)
       HIP_TRY(st, launch_layernorm_fwd((const float*)(base + L.x), param_ptr(st, l, STAGE_P_G1), param_ptr(st, l, STAGE_P_B1), base + L.h1,
-                                       (float*)(base + L.r1), (float*)(base + L.mu1), T, H, c.norm_eps, dt, s));
+                                       (float*)(base + L.r1), (float*)(base + L.mu1), T, H, c.norm_eps, dt, s, half_path ? base + L.h1_16 : nullptr));
     else
-      HIP_TRY(st, launch_rmsnorm_fwd((const float*)(base + L.x), param_ptr(st, l, STAGE_P_G1), base + L.h1, (float*)(base + L.r1), T, H, c.norm_eps, dt, s));
+      HIP_TRY(st, launch_rmsnorm_fwd((const float*)(base + L.x), param_ptr(st, l, STAGE_P_G1), base + L.h1, (float*)(base + L.r1), T, H, c.norm_eps, dt, s,
+                                     half_path ? base + L.h1_16 : nullptr));
     GemmArgs g{};
     g.in_dtype = dt; g.out_dtype = dt; g.transA = false; g.transB = false; g.M = T;
     g.A = base + L.h1; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WQKV); g.ldb = P.n_qkv;
+    if (half_path) { g.in_dtype = F16; g.out_dtype = F16; g.A = base + L.h1_16; g.B = st->arena + P.w16_off[l]; }
     g.C = base + L.qkv; g.ldc = P.n_qkv; g.R = nullptr; g.N = P.n_qkv; g.K = H;
     g.bias = c.bias ? param_ptr(st, l, STAGE_P_BQKV) : nullptr;
     HIP_TRY(st, launch_gemm(g, s));
+    g.in_dtype = dt; g.out_dtype = dt;
     if (c.qk_norm)   // normalise every q and k head in place (before the rotation)
       HIP_TRY(st, launch_headnorm_fwd(base + L.qkv, P.n_qkv, c.n_q_heads, c.n_q_heads + c.n_kv_heads, c.head_dim,
                                       param_ptr(st, l, STAGE_P_GQ), param_ptr(st, l, STAGE_P_GK), base + L.qk_hat,
-                                      (float*)(base + L.qk_r), T, c.norm_eps, dt, s));
+                                      (float*)(base + L.qk_r), T, c.norm_eps, qdt, s));
     if (c.rope)   // rotate q and k in place: the stash then holds what the attention (and its backward) reads
       HIP_TRY(st, launch_rope(base + L.qkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,
-                              c.head_dim, P.n_qkv, c.rope_base, 1.0f, dt, s));
+                              c.head_dim, P.n_qkv, c.rope_base, 1.0f, qdt, s));
     AttnArgs a{};
     a.qkv = base + L.qkv; a.o = base + L.o; a.lse = (float*)(base + L.lse);
     a.o32 = dt == BF16 ? (float*)(base + L.o32) : nullptr;
@@ -548,8 +581,10 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     if (c.bias) { rc = bias_grad(base + L.dx1, H, P.p_off[l][STAGE_P_BO]); if (rc) return rc; }
     // do = dx1 Wo^T
     g.A = base + L.dx1; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WO); g.ldb = H;
-    g.C = base + P.t_do; g.ldc = nqd; g.N = nqd; g.K = H; g.out_dtype = dt;
+    g.C = base + P.t_do; g.ldc = nqd; g.N = nqd; g.K = H;
+    g.out_dtype = dt == BF16 ? (int)F16 : dt;      // bf16 path: the attention backward reads dO as IEEE halves, like q, k, v
     HIP_TRY(st, launch_gemm(g, s));
+    g.out_dtype = dt;
     AttnArgs a{};
     a.qkv = base + L.qkv; a.o = base + L.o; a.lse = (float*)(base + L.lse);
     a.o32 = dt == BF16 ? (float*)(base + L.o32) : nullptr;
@@ -565,7 +600,7 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
       HIP_TRY(st, launch_headnorm_bwd(base + L.dqkv, P.n_qkv, c.n_q_heads, c.n_q_heads + c.n_kv_heads, c.head_dim,
                                       param_ptr(st, l, STAGE_P_GQ), param_ptr(st, l, STAGE_P_GK), base + L.qk_hat,
                                       (const float*)(base + L.qk_r), (float*)(base + P.t_dgp), (float*)(base + P.t_dbp), T, dt, s,
-                                      c.bias ? (float*)(base + P.t_dk32) : nullptr));
+                                      c.bias ? (float*)(base + P.t_dk32) : nullptr, dt == BF16 ? (int)F16 : -1));
       HIP_TRY(st, launch_colsum((const float*)(base + P.t_dgp), headnorm_partials(T, c.n_q_heads), c.head_dim, slot + P.p_off[l][STAGE_P_GQ], s));
       HIP_TRY(st, launch_colsum((const float*)(base + P.t_dbp), headnorm_partials(T, c.n_kv_heads), c.head_dim, slot + P.p_off[l][STAGE_P_GK], s));
     }
@@ -650,6 +685,7 @@ int stage_grad_reduce(stage_t* st, void* grad_out_dev, void* stream) {
     st->reduce_recorded = true;
   }
   for (auto& m : st->mb) m.state = MB_FREE;
+  st->w16_valid = false;    // the caller may change the parameters now: the next F converts Wqkv again
   return STAGE_OK;
 }
 

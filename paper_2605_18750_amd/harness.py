@@ -153,14 +153,17 @@ class Stage:
         nup = (2 if c.mlp_kind == R.STAGE_MLP_SWIGLU else 1) * c.ffn
         cols = {R.STAGE_T_X: c.hidden, R.STAGE_T_H1: c.hidden, R.STAGE_T_QKV: nqkv, R.STAGE_T_O: c.n_q_heads * c.head_dim,
                 R.STAGE_T_X1: c.hidden, R.STAGE_T_H2: c.hidden, R.STAGE_T_UP: nup, R.STAGE_T_M: c.ffn,
-                R.STAGE_T_DY: c.hidden, R.STAGE_T_DUP: nup, R.STAGE_T_DX1: c.hidden, R.STAGE_T_DQKV: nqkv}
+                R.STAGE_T_DY: c.hidden, R.STAGE_T_DUP: nup, R.STAGE_T_DX1: c.hidden, R.STAGE_T_DQKV: nqkv,
+                R.STAGE_T_H1_HALF: c.hidden}
         off = R.stage_intermediate(self.handle, mb, layer, which) - self.arena.data_ptr()
         if which == R.STAGE_T_LSE:
             return self.arena[off:off + 4 * c.n_q_heads * T].view(torch.float32).view(c.n_q_heads, T)
         f32 = which in (R.STAGE_T_X, R.STAGE_T_X1) or self.dtype == "fp32"
+        half = not f32 and which in (R.STAGE_T_QKV, R.STAGE_T_H1_HALF)     # IEEE-half copies of the bf16 path
         esz = 4 if f32 else 2
         n = T * cols[which]
-        return self.arena[off:off + esz * n].view(torch.float32 if f32 else torch.bfloat16).view(T, cols[which])
+        tdt = torch.float32 if f32 else (torch.float16 if half else torch.bfloat16)
+        return self.arena[off:off + esz * n].view(tdt).view(T, cols[which])
 
     def close(self):
         if self.handle is not None:
