@@ -108,9 +108,12 @@ def gemm_roofline(shape, T, Bw, s, gen, n_launch=20, form="nn"):
         else:
             Cc = torch.empty((H, N_up), dtype=torch.float32, device=Bw.device)
             dims = (H, N_up, T)
+            ws_bytes = T * shape.ffn * 4            # the scratch the W task hands to this call (B's idle fp32 temporary)
+            ws = torch.empty(ws_bytes, dtype=torch.uint8, device=Bw.device)
 
             def launch():
-                R.rrfp_gemm(A, G, Cc, None, H, N_up, T, H, N_up, N_up, N_up, 1, 0, 1, 0, R.RRFP_GEMM_MFMA, s)
+                R.rrfp_gemm(A, G, Cc, None, H, N_up, T, H, N_up, N_up, N_up, 1, 0, 1, 0, R.RRFP_GEMM_MFMA, s,
+                            workspace=ws, workspace_bytes=ws_bytes)
     with torch.cuda.stream(s):
         for _ in range(3):
             launch()
@@ -135,7 +138,7 @@ def gemm_roofline(shape, T, Bw, s, gen, n_launch=20, form="nn"):
         except Exception:
             traffic = None
     label = {"nn": "(one call: 256-row tiles + 128-row tail launch)", "nt": "(fp32 out)",
-             "tn": "(weight-gradient form of the W task, fp32 out)"}[form]
+             "tn": "(weight-gradient form of the W task, fp32 out; one call: plain launch + split-K tail launch + its reduce)"}[form]
     return {"bound": "mfma", "kernel": f"gemm_mfma_dl_kernel {form.upper()} {dims[0]}x{dims[1]}x{dims[2]} bf16 {label}", "achieved": round(ach, 1),
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
             "flops_per_launch": g_fl, "avg_launch_ms": round(g_ms, 4), "traffic": traffic,

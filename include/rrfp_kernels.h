@@ -33,13 +33,25 @@ int rrfp_gemm(const void* A, const void* B, void* C, const void* R, int M, int N
               int ldb, int ldc, int ldr, int trans_a, int trans_b, int in_dtype, int out_dtype,
               int family, void* stream);
 
+/* rrfp_gemm with a caller-owned device workspace (256-byte aligned, contents undefined afterwards), as the W task
+ * calls it: with a workspace the weight-gradient form (bf16 inputs, trans_a = 1, trans_b = 0, fp32 output, no
+ * residual) may split the contraction into ranges that write partial planes into the workspace and are added in
+ * range order (rrfp_gemm_plan with have_scratch = 1 tells which shapes do).  A workspace too small for a shape's
+ * split simply disables the split.  The result is bit-identical from call to call for a given shape, workspace
+ * size class and device. */
+int rrfp_gemm_ws(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
+                 int ldc, int ldr, int trans_a, int trans_b, int in_dtype, int out_dtype, int family,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
 /* How the bf16 MFMA GEMM cuts a shape into launches on a device with n_cu compute units: host logic only
  * (no GPU call, no pointers; operands are taken as 16-byte aligned).  The cut is a pure function of the
  * shape and n_cu, which is what keeps the summation order of a call fixed (the bit-exactness requirement
  * behind readiness-driven reordering, paper Section 7.1).  out[0] = kernel (0 the MFMA family refuses the
  * shape, 1 direct-to-LDS, 2 register-staged), out[1] = wavefronts per workgroup, out[2] = workgroups of
- * the 256-row-tile launch, out[3] = workgroups of the 128-row-tile launch that finishes a grid whose last
- * round would be nearly empty, out[4] = split-K ranges (weight-gradient form with scratch; 1 = none).
+ * the 256-row-tile launch, out[3] = workgroups of the second launch that finishes a grid whose last round
+ * would be nearly empty (128-row tiles when A is K-contiguous; for the weight-gradient form with scratch the
+ * trailing tile columns split along K into out[4] ranges), out[4] = split-K ranges (weight-gradient form with
+ * scratch: of the whole grid when out[3] = 0, of the tail launch otherwise; 1 = none).
  * Returns STAGE_OK or STAGE_EINVAL. */
 int rrfp_gemm_plan(int M, int N, int K, int lda, int ldb, int ldc, int trans_a, int trans_b, int out_dtype,
                    int have_scratch, int n_cu, int32_t out[5]);

@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
         L.stage_last_error.restype = C.c_char_p
         L.rrfp_gemm.argtypes = [vp, vp, vp, vp] + [C.c_int] * 12 + [vp]
         L.rrfp_gemm.restype = C.c_int
+        L.rrfp_gemm_ws.argtypes = [vp, vp, vp, vp] + [C.c_int] * 12 + [vp, sz, vp]
+        L.rrfp_gemm_ws.restype = C.c_int
         L.rrfp_gemm_plan.argtypes = [C.c_int] * 11 + [C.POINTER(C.c_int32)]
         L.rrfp_gemm_plan.restype = C.c_int
         L.rrfp_rmsnorm_fwd.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_float, C.c_int, vp]
@@ -169,9 +171,14 @@ RRFP_GEMM_AUTO, RRFP_GEMM_SIMT, RRFP_GEMM_MFMA = 0, 1, 2
 
 
 def rrfp_gemm(A, B, Cout, R, M, N, K, lda, ldb, ldc, ldr, trans_a, trans_b, in_dtype, out_dtype,
-              family=RRFP_GEMM_AUTO, stream=None):
-    rc = lib().rrfp_gemm(_ptr(A), _ptr(B), _ptr(Cout), _ptr(R), M, N, K, lda, ldb, ldc, ldr,
-                         int(trans_a), int(trans_b), in_dtype, out_dtype, family, _stream(stream))
+              family=RRFP_GEMM_AUTO, stream=None, workspace=None, workspace_bytes=0):
+    """workspace given: rrfp_gemm_ws (the weight-gradient form may then split along K)."""
+    if workspace is not None:
+        rc = lib().rrfp_gemm_ws(_ptr(A), _ptr(B), _ptr(Cout), _ptr(R), M, N, K, lda, ldb, ldc, ldr, int(trans_a), int(trans_b),
+                                in_dtype, out_dtype, family, _ptr(workspace), workspace_bytes, _stream(stream))
+    else:
+        rc = lib().rrfp_gemm(_ptr(A), _ptr(B), _ptr(Cout), _ptr(R), M, N, K, lda, ldb, ldc, ldr,
+                             int(trans_a), int(trans_b), in_dtype, out_dtype, family, _stream(stream))
     if rc != STAGE_OK:
         raise StageError(rc, "rrfp_gemm rejected its arguments" if rc == STAGE_EINVAL else "HIP launch failed")
 

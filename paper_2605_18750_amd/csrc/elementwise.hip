@@ -34,16 +34,22 @@ __device__ inline void store_f32(float* p, const float* in) {
 }
 
 // ---------------------------------------------------------------- storage type -> fp32 copy
+// copy, when given, also receives the values unchanged (one read of src serves both outputs).
 template <typename T>
-__global__ __launch_bounds__(256) void widen_kernel(const T* __restrict__ src, float* __restrict__ dst, size_t n) {
+__global__ __launch_bounds__(256) void widen_kernel(const T* __restrict__ src, float* __restrict__ dst, size_t n,
+                                                    T* __restrict__ copy) {
   constexpr int V = Vec<T>::N;
   const size_t nv = n / V;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
     float v[V];
     load_vec<T>(src + i * V, v);
     store_f32<V>(dst + i * V, v);
+    if (copy) store_vec<T>(copy + i * V, v);     // widening and rounding back is the identity
   }
-  for (size_t i = nv * V + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = to_float(src[i]);
+  for (size_t i = nv * V + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    dst[i] = to_float(src[i]);
+    if (copy) copy[i] = src[i];
+  }
 }
 
 // ---------------------------------------------------------------- RMSNorm forward
@@ -583,8 +589,8 @@ __global__ __launch_bounds__(256) void bf16_to_f16_kernel(const bf16_t* __restri
   }
 }
 
-hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s) {
-  DISPATCH_T(dtype, hipLaunchKernelGGL(widen_kernel<T>, dim3(grid_for(n / Vec<T>::N + 1)), dim3(256), 0, s, (const T*)src, dst, n));
+hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s, void* copy) {
+  DISPATCH_T(dtype, hipLaunchKernelGGL(widen_kernel<T>, dim3(grid_for(n / Vec<T>::N + 1)), dim3(256), 0, s, (const T*)src, dst, n, (T*)copy));
   return hipGetLastError();
 }
 

@@ -873,6 +873,40 @@ inline int full_tile_columns(int tiles_m, int tiles_n, int n_cu) {
   return (removes_round && tail_fits) ? tiles_n - ct : tiles_n;
 }
 
+// Sum of S partial planes [M, ldw] (plane stride M * ldw floats) in plane order into the column block
+// out[m, 0 .. width) of a matrix with row pitch ldo: the fixed-order finish of a split-K tail launch.
+__global__ __launch_bounds__(256) void splitk_tail_reduce_kernel(const float* __restrict__ ws, int S, int M, int ldw,
+                                                                 float* __restrict__ out, int ldo, int width) {
+  const int w4 = width >> 2;
+  const size_t n = (size_t)M * w4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const int m = (int)(i / w4), c = (int)(i - (size_t)m * w4) * 4;
+    float4 acc = *reinterpret_cast<const float4*>(ws + (size_t)m * ldw + c);
+    for (int p = 1; p < S; ++p) {
+      const float4 v = *reinterpret_cast<const float4*>(ws + ((size_t)p * M + m) * ldw + c);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *reinterpret_cast<float4*>(out + (size_t)m * ldo + c) = acc;
+  }
+}
+
+// Weight-gradient form on a grid of more than one round: when the last round would be nearly empty and carving
+// the trailing tile columns off removes it (the rule of full_tile_columns), those columns are a second launch
+// whose tiles are split along K into TAIL_SPLIT ranges (so the tail fills the CUs for half a round instead of a
+// fraction of them for a whole one); each range writes its own compact partial plane into the scratch and the
+// planes are added in range order.  Returns the tile columns of the plain launch (tiles_n = no tail).
+constexpr int TAIL_SPLIT = 2;
+inline int wgrad_full_tile_columns(const GemmArgs& g, int tiles_m, int tiles_n, int n_cu, bool have_scratch) {
+  if (!have_scratch || g.R || g.out_dtype != F32) return tiles_n;
+  const int cn = full_tile_columns(tiles_m, tiles_n, n_cu);
+  if (cn <= 0 || cn >= tiles_n) return tiles_n;
+  const int steps = (g.K + DBK - 1) / DBK;
+  const int width = g.N - cn * BN;
+  if (steps < 16 * TAIL_SPLIT || (width & 3) || (g.ldc & 3)) return tiles_n;
+  return cn;
+}
+inline size_t wgrad_tail_scratch_bytes(const GemmArgs& g, int cn) { return (size_t)TAIL_SPLIT * g.M * (g.N - cn * BN) * 4; }
+
 // Split-K factor for a grid of t tiles and a contraction of K: as many ranges as fit the CUs, each at
 // least 16 steps deep, at most 16 ranges; 1 = no split.  A pure function of the shape and the device.
 inline int splitk_factor(int t, int K, int n_cu) {
@@ -920,6 +954,25 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         return launch_grad_reduce((const float*)g.ws, (size_t)g.M * g.N, S_eff, (float*)g.C, (size_t)g.M * g.N, s);
+      }
+      const int cn = wgrad_full_tile_columns(g, tiles_m, tiles_n, cu_count(), g.ws != nullptr);
+      if (cn < tiles_n && wgrad_tail_scratch_bytes(g, cn) <= g.ws_bytes && ((uintptr_t)g.ws & 15) == 0) {
+        constexpr int WMv = dl_wm(A_KC, B_KC), WNv = dl_wn(A_KC, B_KC);
+        const int ct = tiles_n - cn, width = g.N - cn * BN;
+        const int steps = (g.K + DBK - 1) / DBK, k_split = (steps + TAIL_SPLIT - 1) / TAIL_SPLIT * DBK;
+        hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, WMv, WNv, ACT_NONE>), dim3(tiles_m * cn), dim3(WMv * WNv * 64), 0,
+                           s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, g.ldr,
+                           tiles_m, cn, (bf16_t*)nullptr, 0, 0, 0, (const bf16_t*)nullptr);
+        // the tail's planes are compact ([M, width]); the kernel addresses columns by their index in C, so the
+        // plane pointer is moved left by the tail's first column (never dereferenced outside the planes)
+        float* ws_shifted = (float*)g.ws - (size_t)cn * BN;
+        hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, WMv, WNv, ACT_NONE>), dim3(tiles_m * ct, TAIL_SPLIT),
+                           dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)ws_shifted, g.R, g.M, g.N, g.K,
+                           g.lda, g.ldb, width, g.ldr, tiles_m, ct, (bf16_t*)nullptr, 0, cn, k_split, (const bf16_t*)nullptr);
+        const size_t n4 = (size_t)g.M * (width / 4);
+        hipLaunchKernelGGL(splitk_tail_reduce_kernel, dim3((unsigned)std::min<size_t>((n4 + 255) / 256, 8192)), dim3(256), 0, s,
+                           (const float*)g.ws, TAIL_SPLIT, g.M, width, (float*)g.C + (size_t)cn * BN, g.ldc, width);
+        return hipGetLastError();
       }
     }
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
@@ -988,11 +1041,18 @@ GemmPlan gemm_mfma_plan(const GemmArgs& g, int n_cu, bool have_scratch) {
     return p;
   }
   p.main_workgroups = tiles_m * tiles_n;
-  if (!b_kc && !g.R && g.out_dtype == F32 && have_scratch && g.ldc == g.N && ((size_t)g.M * g.N) % 4 == 0) {
-    const int S = splitk_factor(tiles_m * tiles_n, g.K, n_cu);
+  if (!b_kc && !g.R && g.out_dtype == F32 && have_scratch) {
+    const int S = (g.ldc == g.N && ((size_t)g.M * g.N) % 4 == 0) ? splitk_factor(tiles_m * tiles_n, g.K, n_cu) : 1;
     if (S > 1) {
       const int steps = (g.K + DBK - 1) / DBK, k_split = (steps + S - 1) / S * DBK;
       p.split_k = (g.K + k_split - 1) / k_split;
+    } else {
+      const int cn = wgrad_full_tile_columns(g, tiles_m, tiles_n, n_cu, true);
+      if (cn < tiles_n) {   // plain launch over cn tile columns + a tail launch split along K
+        p.main_workgroups = tiles_m * cn;
+        p.short_workgroups = tiles_m * (tiles_n - cn) * TAIL_SPLIT;
+        p.split_k = TAIL_SPLIT;
+      }
     }
   }
   return p;

@@ -9,7 +9,14 @@ using namespace rrfp;
 extern "C" int rrfp_gemm(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
                          int ldc, int ldr, int trans_a, int trans_b, int in_dtype, int out_dtype, int family,
                          void* stream) {
+  return rrfp_gemm_ws(A, B, C, R, M, N, K, lda, ldb, ldc, ldr, trans_a, trans_b, in_dtype, out_dtype, family, nullptr, 0, stream);
+}
+
+extern "C" int rrfp_gemm_ws(const void* A, const void* B, void* C, const void* R, int M, int N, int K, int lda, int ldb,
+                            int ldc, int ldr, int trans_a, int trans_b, int in_dtype, int out_dtype, int family,
+                            void* workspace, size_t workspace_bytes, void* stream) {
   if (!A || !B || !C || M < 1 || N < 1 || K < 1) return STAGE_EINVAL;
+  if (workspace && ((uintptr_t)workspace & 255)) return STAGE_EINVAL;
   if (in_dtype != F32 && in_dtype != BF16) return STAGE_EINVAL;
   if (out_dtype != F32 && !(out_dtype == BF16 && in_dtype == BF16)) return STAGE_EINVAL;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N || (R && ldr < N)) return STAGE_EINVAL;
@@ -17,6 +24,7 @@ extern "C" int rrfp_gemm(const void* A, const void* B, void* C, const void* R, i
   g.A = A; g.B = B; g.C = C; g.R = (const float*)R; g.M = M; g.N = N; g.K = K;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ldr = ldr;
   g.transA = trans_a != 0; g.transB = trans_b != 0; g.in_dtype = in_dtype; g.out_dtype = out_dtype;
+  g.ws = workspace; g.ws_bytes = workspace ? workspace_bytes : 0;
   hipError_t e;
   if (family == RRFP_GEMM_AUTO) e = launch_gemm(g, (hipStream_t)stream);
   else if (family == RRFP_GEMM_SIMT) e = launch_gemm_simt(g, (hipStream_t)stream);

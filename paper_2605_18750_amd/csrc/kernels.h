@@ -89,7 +89,8 @@ hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s);
 bool attn_mfma_supports(const AttnArgs& a);
 
 // dst[i] = (float)src[i]: storage type -> fp32 (entry of the residual stream).
-hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s);
+// copy (optional): also receives src unchanged, in the storage type.
+hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s, void* copy = nullptr);
 // Rotary embedding, in place, on the first n_heads heads (head_dim d, even) of every row of a [T, ld]
 // tensor: pair (x_i, x_{i+d/2}) turns by sign * pos * base^(-2i/d), pos = row - segment start, rows and
 // segment starts taken from the query tile list (the tiles partition the rows).

@@ -522,10 +522,10 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
   char* base = mb_base(st, mb);
   float* slot = slot_base(st, mb);
   const int T = m.T, H = c.hidden, F = c.ffn, dt = c.dtype, nqd = c.n_q_heads * c.head_dim;
-  const size_t e = P.esz;
   const int n_part = norm_bwd_partials(T, H, dt);
-  HIP_TRY(st, hipMemcpyAsync(base + P.layer[c.n_layers - 1].dy, dy_dev, (size_t)T * H * e, hipMemcpyDeviceToDevice, s));
-  HIP_TRY(st, launch_widen(dy_dev, (float*)(base + P.layer[c.n_layers - 1].dy32), (size_t)T * H, dt, s));
+  // one pass over dy: the fp32 head of the residual-gradient chain and the library's own copy for the GEMMs and W
+  HIP_TRY(st, launch_widen(dy_dev, (float*)(base + P.layer[c.n_layers - 1].dy32), (size_t)T * H, dt, s,
+                           base + P.layer[c.n_layers - 1].dy));
   const int n_chunk = colsum_chunks(T);
   // bias gradient = column sum of a projection's output-gradient (storage type), in a fixed order
   auto bias_grad = [&](const void* src, int n, size_t slot_off) -> int {

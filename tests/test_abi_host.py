@@ -156,8 +156,17 @@ def test_gemm_launch_plan_is_a_pure_function_of_shape_and_cu_count():
     assert R.rrfp_gemm_plan(T, H, F2, 0, 1, F32) == dict(kernel=1, wavefronts=8, main_workgroups=256, short_workgroups=0, split_k=1)
     assert R.rrfp_gemm_plan(T, Q, H, 0, 0, BF)["main_workgroups"] == 768   # 3 full rounds: no tail launch
     assert R.rrfp_gemm_plan(T, Q, H, 0, 0, BF)["short_workgroups"] == 0
+    # weight gradient of the up projection: 16 x 86 = 1376 tiles = 5.4 rounds; the 6 trailing tile columns (96
+    # tiles) become a tail launch split along K into 2 ranges (192 workgroups, half a round) when scratch exists
     wg = R.rrfp_gemm_plan(H, F2, T, 1, 0, F32, have_scratch=True)
-    assert wg == dict(kernel=1, wavefronts=4, main_workgroups=1376, short_workgroups=0, split_k=1)
+    assert wg == dict(kernel=1, wavefronts=4, main_workgroups=1280, short_workgroups=192, split_k=2)
+    assert R.rrfp_gemm_plan(H, F2, T, 1, 0, F32, have_scratch=False) == dict(kernel=1, wavefronts=4, main_workgroups=1376,
+                                                                            short_workgroups=0, split_k=1)
+    # down projection (43 x 16 = 688 tiles): the 176 left-over tiles do not fit a split tail: one plain launch
+    assert R.rrfp_gemm_plan(11008, H, T, 1, 0, F32, have_scratch=True) == dict(kernel=1, wavefronts=4, main_workgroups=688,
+                                                                              short_workgroups=0, split_k=1)
+    # whole rounds (QKV: 768 tiles) are left alone
+    assert R.rrfp_gemm_plan(H, Q, T, 1, 0, F32, have_scratch=True)["short_workgroups"] == 0
     # vision stage: dW of the output projection, 1280 x 1280 with K = 6272 tokens: 25 tiles -> split along K
     small = R.rrfp_gemm_plan(1280, 1280, 6272, 1, 0, F32, have_scratch=True)
     assert small["main_workgroups"] == 25 and 1 < small["split_k"] <= 16

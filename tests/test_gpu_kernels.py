@@ -210,3 +210,38 @@ def test_grad_reduce_kernel_is_the_index_ordered_sum():
     err = float(np.max(np.abs(out.cpu().double().numpy() - ref)) / np.max(np.abs(ref)))
     _say(f"[kernel] grad_reduce vs oracle: {err:.3e}")
     assert err <= 1e-6
+
+
+@pytest.mark.parametrize("M,N,K", [(4096, 22016, 1024), (4096, 5640, 1056), (1280, 1280, 2080)])
+def test_weight_gradient_gemm_with_workspace_split_forms(M, N, K):
+    """The weight-gradient form with a workspace, every element against the fp64 definition: a grid whose last
+    round is nearly empty (16 x 86 tiles, the up-projection shape: plain launch + tail launch split along K),
+    the same with a ragged last tile column and a ragged K, and a small grid split along K as a whole."""
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+    from tests.helpers import max_norm_rel_err
+    plan = R.rrfp_gemm_plan(M, N, K, 1, 0, R.STAGE_DTYPE_FP32, have_scratch=True)
+    _say(f"[kernel] wgrad with workspace M{M} N{N} K{K}: plan {plan}")
+    assert plan["split_k"] > 1
+    A = SI.make_tensor(4, f"wsA{M}", (K, M), 1.0, "bf16")
+    B = SI.make_tensor(4, f"wsB{N}", (K, N), 1.0, "bf16")
+    dA, dB = Hn.to_device(A.storage, "bf16"), Hn.to_device(B.storage, "bf16")
+    ws_bytes = 16 * M * N * 4 if plan["short_workgroups"] == 0 else 2 * M * 2048 * 4
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    dC = torch.full((M + 8, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    dC[M:] = 7.0
+    R.rrfp_gemm(dA, dB, dC, None, M, N, K, M, N, N, N, 1, 0, 1, 0, R.RRFP_GEMM_MFMA, workspace=ws, workspace_bytes=ws_bytes)
+    torch.cuda.synchronize()
+    got = dC[:M].cpu().to(torch.float64).numpy()
+    assert np.all(np.isfinite(got))
+    ref = A.f64.T @ B.f64
+    err = max_norm_rel_err(got, ref)
+    _say(f"[kernel] wgrad with workspace: rel err {err:.3e}")
+    assert err <= 2e-5
+    assert torch.all(dC[M:] == 7.0), "rows past M were written"
+    # same call again: bit-identical (fixed summation order)
+    dC2 = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
+    R.rrfp_gemm(dA, dB, dC2, None, M, N, K, M, N, N, N, 1, 0, 1, 0, R.RRFP_GEMM_MFMA, workspace=ws, workspace_bytes=ws_bytes)
+    torch.cuda.synchronize()
+    assert torch.equal(dC2.view(torch.int32), dC[:M].view(torch.int32))
