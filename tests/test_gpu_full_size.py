@@ -120,24 +120,6 @@ def test_vision_stage_full_size_sampled_microbatch():
     _say(f"[full] vision: worst rel err {worst:.3e}")
 
 
-def test_wide_gqa_full_width_one_layer():
-    """Wide GQA stage at full width (hidden 8192, 64 q / 8 kv heads, FFN 28672), one layer, T=1024."""
-    shape = SI.WIDE_GQA.replace(n_layers=1, name="wide_gqa_bf16/one_layer")
-    _say("[full] wide GQA, 1 layer, T=1024")
-    got, ref = _run_one_mb(shape, np.array([0, 1024], dtype=np.int32), 2, 1)
-    worst = Hp.compare(got, ref, 2e-2, "wide gqa full width")
-    _say(f"[full] wide: worst rel err {worst:.3e}")
-
-
-def test_multimodal_ragged_full_width_one_layer():
-    """Language-width layer with a ragged packed microbatch: two causal segments, odd lengths."""
-    shape = SI.MULTIMODAL.replace(n_layers=1, name="multimodal_varlen_bf16/one_layer")
-    _say("[full] multimodal ragged, 1 layer, segments 777 + 1301")
-    got, ref = _run_one_mb(shape, np.array([0, 777, 2078], dtype=np.int32), 2, 0)
-    worst = Hp.compare(got, ref, 2e-2, "multimodal ragged full width")
-    _say(f"[full] multimodal: worst rel err {worst:.3e}")
-
-
 def _order_and_reduce_properties(shape, cu, order_seed):
     """All microbatches of a workload at full size (device-generated inputs, as in bench.py): a seeded random
     ready order on 3 streams gives y, dx, slots and grad_out bit-identical to the canonical order on one
