@@ -80,7 +80,7 @@ __device__ __forceinline__ void kv_store(const KvRegs<D, NT>& rk, const KvRegs<D
 
 template <int D, int NIB>
 __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_kernel(const el_t* __restrict__ qkv, bf16_t* __restrict__ o,
-                                                            float* __restrict__ o32, float* __restrict__ lse,
+                                                            float* __restrict__ o32, el_t* __restrict__ o16, float* __restrict__ lse,
                                                             const AttnTile* __restrict__ tiles,
                                                             int Tn, int nq, int nkv, int causal, float scale_log2e) {
   constexpr int NT = FWD_Q_ROWS / (32 * NIB) * 64;   // threads: one wavefront per 32 * NIB query rows
@@ -285,6 +285,11 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
         w.y = pack_bf16x2(v2, v3);
         *reinterpret_cast<uint2*>(orow + dd) = w;
         if (o32) *reinterpret_cast<float4*>(o32 + (size_t)i * nq * D + qcol + dd) = make_float4(v0, v1, v2, v3);
+        if (o16) {     // the copy the output projection reads (halves); the bf16 one above serves the weight gradient
+          w.x = pack_f16x2(v0, v1);
+          w.y = pack_f16x2(v2, v3);
+          *reinterpret_cast<uint2*>(o16 + (size_t)i * nq * D + qcol + dd) = w;
+        }
       }
   }
 }
@@ -625,7 +630,7 @@ hipError_t fwd_launch(const AttnArgs& a, hipStream_t s) {
   static hipError_t once_status = hipSuccess;
   if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kern, C::SMEM); e != hipSuccess) return e;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(NT), C::SMEM, s, (const el_t*)a.qkv, (bf16_t*)a.o, a.o32, a.lse,
+  hipLaunchKernelGGL(kern, dim3(a.nq, a.n_q_tiles), dim3(NT), C::SMEM, s, (const el_t*)a.qkv, (bf16_t*)a.o, a.o32, (el_t*)a.o16, a.lse,
                      a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale_log2e);
   return hipGetLastError();
 }

@@ -820,12 +820,17 @@ RRFP_INST(true, false, bf16_t, false, ACT_SWIGLU_FWD) RRFP_INST(true, false, bf1
 RRFP_INST(true, true, bf16_t, false, ACT_SWIGLU_BWD) RRFP_INST(true, true, bf16_t, false, ACT_GELU_BWD)
 #undef RRFP_INST4
 #undef RRFP_INST
-// Half-precision forms of the attention-input path: the QKV projection (half in, half out) and the gradient
-// of the attention output, dO = dx1 Wo^T (bf16 in, half out), each with its 128-row tile variant.
+// Half-precision forms of the attention path: the QKV projection (half in, half out), the output projection
+// (half in, fp32 out with the residual) and the gradient of the attention output, dO = dx1 Wo^T (bf16 in, half
+// out), each with its 128-row tile variant.
 template __global__ void gemm_mfma_dl_kernel<true, false, f16_t, false, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 256, true>(
     const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
 template __global__ void gemm_mfma_dl_kernel<true, false, f16_t, false, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 128, true>(
     const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+template __global__ void gemm_mfma_dl_kernel<true, false, float, true, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 256, true>(
+    const bf16_t*, const bf16_t*, float*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+template __global__ void gemm_mfma_dl_kernel<true, false, float, true, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 128, true>(
+    const bf16_t*, const bf16_t*, float*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
 template __global__ void gemm_mfma_dl_kernel<true, true, f16_t, false, dl_wm(true, true), dl_wn(true, true), ACT_NONE, 256, false>(
     const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
 template __global__ void gemm_mfma_dl_kernel<true, true, f16_t, false, dl_wm(true, true), dl_wn(true, true), ACT_NONE, 128, false>(
@@ -1061,10 +1066,12 @@ GemmPlan gemm_mfma_plan(const GemmArgs& g, int n_cu, bool have_scratch) {
 bool gemm_mfma_supports(const GemmArgs& g) {
   if (g.in_dtype != BF16 && g.in_dtype != F16) return false;
   if (g.in_dtype == F16 || g.out_dtype == F16) {
-    // half forms: QKV projection (half x half -> half, NN) and dO (bf16 x bf16 -> half, NT); direct-load kernel only
-    const bool qkv_form = g.in_dtype == F16 && g.out_dtype == F16 && !g.transA && !g.transB;
-    const bool do_form = g.in_dtype == BF16 && g.out_dtype == F16 && !g.transA && g.transB;
-    if (!(qkv_form || do_form) || g.R || g.act != ACT_NONE || !direct_ok(g)) return false;
+    // half forms: QKV projection (half x half -> half, NN), output projection (half x half -> fp32 + residual, NN)
+    // and dO (bf16 x bf16 -> half, NT); direct-load kernel only
+    const bool qkv_form = g.in_dtype == F16 && g.out_dtype == F16 && !g.transA && !g.transB && !g.R;
+    const bool wo_form = g.in_dtype == F16 && g.out_dtype == F32 && !g.transA && !g.transB && g.R;
+    const bool do_form = g.in_dtype == BF16 && g.out_dtype == F16 && !g.transA && g.transB && !g.R;
+    if (!(qkv_form || wo_form || do_form) || g.act != ACT_NONE || !direct_ok(g)) return false;
   }
   if (g.bias && (!direct_ok(g) || ((uintptr_t)g.bias & 15))) return false;   // bias lives in the direct-load kernel's epilogue
   if (g.M < 1 || g.N < 1 || g.K < 1) return false;
@@ -1090,6 +1097,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     }
   }
   const bool a_kc = !g.transA, b_kc = g.transB;
+  if (g.in_dtype == F16 && g.out_dtype == F32) return launch_a_kc<false, float, true, ACT_NONE, true>(g, s);
   if (g.in_dtype == F16) return launch_a_kc<false, f16_t, false, ACT_NONE, true>(g, s);
   if (g.out_dtype == F16) return launch_a_kc<true, f16_t, false, ACT_NONE, false>(g, s);
   if (a_kc && !b_kc) return launch_orient<true, false>(g, s);

@@ -71,6 +71,7 @@ struct AttnArgs {
   void* o;              // [T, nq d]
   float* o32;           // [T, nq d] fp32 copy of o before rounding (bf16 MFMA path; else null): the
                         // backward forms delta from it so that rounding o does not break sum_j dS_ij = 0
+  void* o16;            // [T, nq d] optional copy of o as IEEE halves (MFMA path): operand of the output projection
   float* lse;           // [nq, T]   log-sum-exp of the scaled, masked scores (natural log)
   const AttnTile* q_tiles; int n_q_tiles;     // device pointers to the tile lists
   const AttnTile* kv_tiles; int n_kv_tiles;

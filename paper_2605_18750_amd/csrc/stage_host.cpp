@@ -40,6 +40,7 @@ struct LayerStash {
   size_t mu1, mu2;                                    // written by F: row means (LayerNorm variant)
   size_t qk_hat, qk_r;                                // written by F: normalised q, k heads and their 1/rms (QK-norm variant)
   size_t h1_16;                                       // written by F (bf16 path): first norm output as IEEE halves, operand of the QKV projection
+  size_t o16;                                         // written by F (bf16 path): attention output as IEEE halves, operand of the output projection
 };
 
 struct Plan {
@@ -57,6 +58,7 @@ struct Plan {
   size_t slots_off;                 // start of the M gradient slots
   size_t slot_floats;               // floats per slot (= param_elems)
   size_t w16_off[64];               // bf16 path: IEEE-half copy of every layer's Wqkv (byte offsets in the arena), refreshed once per iteration
+  size_t w16o_off[64];              // the same for Wo
   size_t arena_bytes;
 };
 
@@ -137,6 +139,7 @@ int make_plan(const stage_config* c, Plan* p) {
     s.qk_hat = c->qk_norm ? take(T * (nq + nkv) * d * e) : 0;
     s.qk_r = c->qk_norm ? take(T * (nq + nkv) * 4) : 0;
     s.h1_16 = c->dtype == STAGE_DTYPE_BF16 ? take(T * H * 2) : 0;
+    s.o16 = c->dtype == STAGE_DTYPE_BF16 ? take(T * nq * d * 2) : 0;
   }
   p->t_dm = take(T * F * 4);     // fp32: GEMM outputs that only an elementwise kernel consumes are not rounded
   p->t_dh = take(T * H * 4);
@@ -161,6 +164,8 @@ int make_plan(const stage_config* c, Plan* p) {
   for (int l = 0; l < c->n_layers; ++l) {
     p->w16_off[l] = p->arena_bytes;
     if (c->dtype == STAGE_DTYPE_BF16) p->arena_bytes += align_up(H * (size_t)p->n_qkv * 2);
+    p->w16o_off[l] = p->arena_bytes;
+    if (c->dtype == STAGE_DTYPE_BF16) p->arena_bytes += align_up(nq * d * H * 2);
   }
   return STAGE_OK;
 }
@@ -413,12 +418,16 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
   char* base = mb_base(st, mb);
   if (st->reduce_recorded) HIP_TRY(st, hipStreamWaitEvent(s, st->ev_reduce, 0));
   if (c.dtype == STAGE_DTYPE_BF16) {
-    // The QKV projection runs on IEEE-half operands.  The first F of an iteration converts every layer's Wqkv
-    // (the caller may have changed the parameters since the last stage_grad_reduce) on its own stream, behind
-    // the previous reduce and so behind every earlier reader of the copies; every F waits for that conversion.
+    // The QKV and output projections run on IEEE-half operands.  The first F of an iteration converts every
+    // layer's Wqkv and Wo (the caller may have changed the parameters since the last stage_grad_reduce) on its own
+    // stream, behind the previous reduce and so behind every earlier reader of the copies; every F waits for
+    // that conversion.
     if (!st->w16_valid) {
-      for (int l = 0; l < c.n_layers; ++l)
+      for (int l = 0; l < c.n_layers; ++l) {
         HIP_TRY(st, launch_bf16_to_f16(param_ptr(st, l, STAGE_P_WQKV), st->arena + P.w16_off[l], (size_t)c.hidden * P.n_qkv, s));
+        HIP_TRY(st, launch_bf16_to_f16(param_ptr(st, l, STAGE_P_WO), st->arena + P.w16o_off[l],
+                                       (size_t)c.n_q_heads * c.head_dim * c.hidden, s));
+      }
       HIP_TRY(st, hipEventRecord(st->ev_w16, s));
       st->w16_valid = true;
     } else {
@@ -462,16 +471,18 @@ int stage_F(stage_t* st, int mb, const void* x_dev, const int32_t* cu, int n_seg
     AttnArgs a{};
     a.qkv = base + L.qkv; a.o = base + L.o; a.lse = (float*)(base + L.lse);
     a.o32 = dt == BF16 ? (float*)(base + L.o32) : nullptr;
+    a.o16 = half_path ? base + L.o16 : nullptr;
     a.q_tiles = (const AttnTile*)(base + P.t_qtiles); a.n_q_tiles = m.n_q_tiles;
     a.kv_tiles = (const AttnTile*)(base + P.t_kvtiles); a.n_kv_tiles = m.n_kv_tiles;
     a.T = T; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.d = c.head_dim; a.causal = c.causal; a.dtype = dt;
     HIP_TRY(st, launch_attn_fwd(a, s));
     g.A = base + L.o; g.lda = nqd; g.B = param_ptr(st, l, STAGE_P_WO); g.ldb = H;
+    if (half_path) { g.in_dtype = F16; g.A = base + L.o16; g.B = st->arena + P.w16o_off[l]; }
     g.C = base + L.x1; g.ldc = H; g.R = (const float*)(base + L.x); g.ldr = H; g.N = H; g.K = nqd;
     g.out_dtype = F32;                       // x1 stays in the fp32 residual stream
     g.bias = c.bias ? param_ptr(st, l, STAGE_P_BO) : nullptr;
     HIP_TRY(st, launch_gemm(g, s));
-    g.out_dtype = dt;
+    g.out_dtype = dt; g.in_dtype = dt;
     if (c.norm_kind == 1)
       HIP_TRY(st, launch_layernorm_fwd((const float*)(base + L.x1), param_ptr(st, l, STAGE_P_G2), param_ptr(st, l, STAGE_P_B2), base + L.h2,
                                        (float*)(base + L.r2), (float*)(base + L.mu2), T, H, c.norm_eps, dt, s));
