@@ -362,7 +362,8 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restrict__ qkv, const el_t* __restrict__ d_o,
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
                                                             bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
-                                                            int Tn, int nq, int nkv, int causal, float scale) {
+                                                            int Tn, int nq, int nkv, int causal, float scale,
+                                                            const float* __restrict__ grad_scale) {
   using C = DkvCfg<D>;
   constexpr int NDS = D / 16, NDB = C::DP / 32;
   constexpr float LOG2E = 1.4426950408889634f;
@@ -586,6 +587,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
     t = run_steps(t, nq_steps, st, std::true_type{});
   }
   if (j < tl.r1) {
+    const float inv_s = grad_scale ? grad_scale[1] : 1.0f;     // d_o held s * dO: undo it (a power of two: exact)
+    scale *= inv_s;
     bf16_t* krow = dqkv + (size_t)j * ld + kcol;
     bf16_t* vrow = dqkv + (size_t)j * ld + vcol;
 #pragma unroll
@@ -598,8 +601,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
         w.x = pack_bf16x2(dk[db][g * 4 + 0] * scale, dk[db][g * 4 + 1] * scale);
         w.y = pack_bf16x2(dk[db][g * 4 + 2] * scale, dk[db][g * 4 + 3] * scale);
         *reinterpret_cast<uint2*>(krow + dd) = w;
-        w.x = pack_bf16x2(dv[db][g * 4 + 0], dv[db][g * 4 + 1]);
-        w.y = pack_bf16x2(dv[db][g * 4 + 2], dv[db][g * 4 + 3]);
+        w.x = pack_bf16x2(dv[db][g * 4 + 0] * inv_s, dv[db][g * 4 + 1] * inv_s);
+        w.y = pack_bf16x2(dv[db][g * 4 + 2] * inv_s, dv[db][g * 4 + 3] * inv_s);
         *reinterpret_cast<uint2*>(vrow + dd) = w;
       }
   }
@@ -615,7 +618,7 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((a.T * a.nq + 15) / 16), dim3(256), 0, s, (const bf16_t*)a.o,
                      a.o32, (const el_t*)a.d_o, a.delta, a.T, a.nq);
   hipLaunchKernelGGL(kkv, dim3(a.nkv, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const el_t*)a.qkv,
-                     (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale);
+                     (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale, a.grad_scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return launch_attn_dq_mfma(a, s);

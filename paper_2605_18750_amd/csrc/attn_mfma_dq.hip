@@ -22,7 +22,8 @@ template <int D, int NIB>
 __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_kernel(const el_t* __restrict__ qkv, const el_t* __restrict__ d_o,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
-                                                           int Tn, int nq, int nkv, int causal, float scale) {
+                                                           int Tn, int nq, int nkv, int causal, float scale,
+                                                           const float* __restrict__ grad_scale) {
   constexpr int NT = FWD_Q_ROWS / (32 * NIB) * 64;   // threads: one wavefront per 32 * NIB query rows
   constexpr int WQ = 32 * NIB;
   using C = DqCfg<D>;
@@ -159,6 +160,7 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
   for (int ib = 0; ib < NIB; ++ib) {
     const int i = wq0 + ib * 32 + li;
     if (i >= tl.r1) continue;
+    const float out_scale = scale * (grad_scale ? grad_scale[1] : 1.0f);    // d_o held s * dO: undo it (a power of two: exact)
     bf16_t* row = dqkv + (size_t)i * ld + qcol;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
@@ -167,8 +169,8 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
         const int dd = db * 32 + g * 8 + h * 4;
         if (dd >= D) continue;
         uint2 w;
-        w.x = pack_bf16x2(acc[db][ib][g * 4 + 0] * scale, acc[db][ib][g * 4 + 1] * scale);
-        w.y = pack_bf16x2(acc[db][ib][g * 4 + 2] * scale, acc[db][ib][g * 4 + 3] * scale);
+        w.x = pack_bf16x2(acc[db][ib][g * 4 + 0] * out_scale, acc[db][ib][g * 4 + 1] * out_scale);
+        w.y = pack_bf16x2(acc[db][ib][g * 4 + 2] * out_scale, acc[db][ib][g * 4 + 3] * out_scale);
         *reinterpret_cast<uint2*>(row + dd) = w;
       }
   }
@@ -182,7 +184,7 @@ hipError_t dq_launch(const AttnArgs& a, hipStream_t s) {
   if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kq, DqCfg<D>::SMEM); e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)D);
   hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(FWD_Q_ROWS / (32 * DQ_NIB) * 64), DqCfg<D>::SMEM, s, (const el_t*)a.qkv,
-                     (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale);
+                     (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale, a.grad_scale);
   return hipGetLastError();
 }
 

@@ -52,6 +52,51 @@ __global__ __launch_bounds__(256) void widen_kernel(const T* __restrict__ src, f
   }
 }
 
+// ---------------------------------------------------------------- gradient scale
+// max |v| over the tensor in two steps (per-workgroup maxima, then one workgroup): a maximum has no summation
+// order, so the result does not depend on how the work was cut.
+template <typename T>
+__global__ __launch_bounds__(256) void absmax_partial_kernel(const T* __restrict__ src, size_t n, float* __restrict__ partial) {
+  constexpr int V = Vec<T>::N;
+  __shared__ float red[4];
+  float mx = 0.f;
+  const size_t nv = n / V;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
+    float v[V];
+    load_vec<T>(src + i * V, v);
+#pragma unroll
+    for (int e = 0; e < V; ++e) mx = fmaxf(mx, fabsf(v[e]));      // fmaxf drops NaNs: a NaN in dy shows in the results, not here
+  }
+  for (size_t i = nv * V + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) mx = fmaxf(mx, fabsf(to_float(src[i])));
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+__global__ __launch_bounds__(256) void grad_scale_kernel(const float* __restrict__ partial, int n_partial, float* __restrict__ scale) {
+  __shared__ float red[4];
+  float mx = 0.f;
+  for (int i = threadIdx.x; i < n_partial; i += 256) mx = fmaxf(mx, partial[i]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float s = 1.0f;
+    if (mx > 0.f && mx < INFINITY) {
+      int ex;
+      frexpf(mx, &ex);                               // mx = f * 2^ex, f in [0.5, 1)
+      ex = max(-100, min(100, ex - 1));              // 2^ex <= mx < 2^(ex+1)
+      s = ldexpf(1.0f, -ex);                         // s * mx in [1, 2)
+    }
+    scale[0] = s;
+    scale[1] = 1.0f / s;                             // exact: s is a power of two
+  }
+}
+
 // ---------------------------------------------------------------- RMSNorm forward
 // One wavefront per row; 4 rows per workgroup.  Two sweeps over the row (the second is
 // served by cache): sum of squares, then scale.  x is the fp32 residual stream.
@@ -752,6 +797,15 @@ hipError_t launch_gelu_bwd(const float* dm, const void* u, void* du, int Tn, int
     const size_t nv = (size_t)Tn * F / Vec<T>::N;
     hipLaunchKernelGGL(gelu_bwd_kernel<T>, dim3(grid_for(nv)), dim3(256), 0, s, dm, (const T*)u, (T*)du, nv);
   });
+  return hipGetLastError();
+}
+
+int grad_scale_partials(size_t n) { return grid_for(n / 8 + 1, 1024); }
+
+hipError_t launch_grad_scale(const void* dy, size_t n, int dtype, float* partial, float* scale, hipStream_t s) {
+  const int nb = grad_scale_partials(n);
+  DISPATCH_T(dtype, hipLaunchKernelGGL(absmax_partial_kernel<T>, dim3(nb), dim3(256), 0, s, (const T*)dy, n, partial));
+  hipLaunchKernelGGL(grad_scale_kernel, dim3(1), dim3(256), 0, s, (const float*)partial, nb, scale);
   return hipGetLastError();
 }
 

@@ -482,7 +482,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
                                                                TO* __restrict__ C, const float* __restrict__ R, int M,
                                                                int N, int K, int lda, int ldb, int ldc, int ldr,
                                                                int tiles_m, int tiles_n, bf16_t* __restrict__ E, int lde,
-                                                               int tn0, int k_split, const bf16_t* __restrict__ bias) {
+                                                               int tn0, int k_split, const bf16_t* __restrict__ bias,
+                                                               const float* __restrict__ out_scale) {
   constexpr int NW = WM * WN;
   // Split-K launches (grid y = split): this workgroup contracts k in [y * k_split, min(K, (y+1) * k_split))
   // and writes its partial tile into the y-th [M, ldc] plane of C.
@@ -666,6 +667,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
   const int n_ld = min(n_col, N - 8);
   float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (ACT != ACT_SWIGLU_FWD && bias) load_vec<bf16_t>(bias + n_ld, bv);
+  // out_scale (plain 16-bit outputs only): a device scalar, a power of two, multiplied into the result before it
+  // is rounded -- brings a gradient tensor into the range of IEEE halves whatever the scale of the loss
+  const float oscale = (ACT == ACT_NONE && !HAS_R && sizeof(TO) == 2 && out_scale) ? *out_scale : 1.0f;
   struct Pre { float rv[8]; uint4 e0, e1; };
   auto prefetch = [&](Pre (&pre)[SW], int i) {
 #pragma unroll
@@ -792,6 +796,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
           }
         } else {
           using T16 = std::conditional_t<sizeof(TO) == 2, TO, bf16_t>;    // bf16_t or f16_t
+          if constexpr (ACT == ACT_NONE && !HAS_R) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= oscale;
+          }
           if (ok) store_vec<T16>((T16*)C + (size_t)m * ldc + n, v);
         }
       }
@@ -802,10 +810,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
 // Explicit instantiations of every variant the launcher can pick.
 #define RRFP_INST(AKC, BKC, TO, HR, ACT)                                                                     \
   template __global__ void gemm_mfma_dl_kernel<AKC, BKC, TO, HR, dl_wm(AKC, BKC), dl_wn(AKC, BKC), ACT>(      \
-      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*, const float*);
 #define RRFP_INST_SHORT(BKC, TO, HR, ACT)                                                                    \
   template __global__ void gemm_mfma_dl_kernel<true, BKC, TO, HR, dl_wm(true, BKC), dl_wn(true, BKC), ACT, 128>( \
-      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+      const bf16_t*, const bf16_t*, TO*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*, const float*);
 #define RRFP_INST_SHORT4(BKC) RRFP_INST_SHORT(BKC, float, true, ACT_NONE) RRFP_INST_SHORT(BKC, float, false, ACT_NONE) \
                               RRFP_INST_SHORT(BKC, bf16_t, true, ACT_NONE) RRFP_INST_SHORT(BKC, bf16_t, false, ACT_NONE)
 RRFP_INST_SHORT4(false) RRFP_INST_SHORT4(true)
@@ -824,17 +832,17 @@ RRFP_INST(true, true, bf16_t, false, ACT_SWIGLU_BWD) RRFP_INST(true, true, bf16_
 // (half in, fp32 out with the residual) and the gradient of the attention output, dO = dx1 Wo^T (bf16 in, half
 // out), each with its 128-row tile variant.
 template __global__ void gemm_mfma_dl_kernel<true, false, f16_t, false, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 256, true>(
-    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*, const float*);
 template __global__ void gemm_mfma_dl_kernel<true, false, f16_t, false, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 128, true>(
-    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*, const float*);
 template __global__ void gemm_mfma_dl_kernel<true, false, float, true, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 256, true>(
-    const bf16_t*, const bf16_t*, float*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+    const bf16_t*, const bf16_t*, float*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*, const float*);
 template __global__ void gemm_mfma_dl_kernel<true, false, float, true, dl_wm(true, false), dl_wn(true, false), ACT_NONE, 128, true>(
-    const bf16_t*, const bf16_t*, float*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+    const bf16_t*, const bf16_t*, float*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*, const float*);
 template __global__ void gemm_mfma_dl_kernel<true, true, f16_t, false, dl_wm(true, true), dl_wn(true, true), ACT_NONE, 256, false>(
-    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*, const float*);
 template __global__ void gemm_mfma_dl_kernel<true, true, f16_t, false, dl_wm(true, true), dl_wn(true, true), ACT_NONE, 128, false>(
-    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*);
+    const bf16_t*, const bf16_t*, f16_t*, const float*, int, int, int, int, int, int, int, int, int, bf16_t*, int, int, int, const bf16_t*, const float*);
 
 // True when the direct-to-LDS kernel can take the call (else the register-staged one does).
 inline bool direct_ok(const GemmArgs& g) {
@@ -929,12 +937,12 @@ hipError_t launch_a_kc(const GemmArgs& g, hipStream_t s) {
   if (cn > 0)
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT, 256, F16IN>), dim3(tiles_m * cn), dim3(WMv * WNv * 64),
                        0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc,
-                       g.ldr, tiles_m, cn, (bf16_t*)g.E, g.lde, 0, 0, (const bf16_t*)g.bias);
+                       g.ldr, tiles_m, cn, (bf16_t*)g.E, g.lde, 0, 0, (const bf16_t*)g.bias, g.out_scale);
   if (cn < tiles_n) {
     const int tiles_m2 = (g.M + 127) / 128;
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<true, B_KC, TO, HAS_R, WMv, WNv, ACT, 128, F16IN>), dim3(tiles_m2 * (tiles_n - cn)),
                        dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K,
-                       g.lda, g.ldb, g.ldc, g.ldr, tiles_m2, tiles_n - cn, (bf16_t*)g.E, g.lde, cn, 0, (const bf16_t*)g.bias);
+                       g.lda, g.ldb, g.ldc, g.ldr, tiles_m2, tiles_n - cn, (bf16_t*)g.E, g.lde, cn, 0, (const bf16_t*)g.bias, g.out_scale);
   }
   return hipGetLastError();
 }
@@ -955,7 +963,7 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
         hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
                            dim3(tiles_m * tiles_n, S_eff), dim3(dl_wm(A_KC, B_KC) * dl_wn(A_KC, B_KC) * 64), 0,
                            s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.ws, g.R, g.M, g.N, g.K, g.lda,
-                           g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, k_split, (const bf16_t*)nullptr);
+                           g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, k_split, (const bf16_t*)nullptr, (const float*)nullptr);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         return launch_grad_reduce((const float*)g.ws, (size_t)g.M * g.N, S_eff, (float*)g.C, (size_t)g.M * g.N, s);
@@ -967,13 +975,13 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
         const int steps = (g.K + DBK - 1) / DBK, k_split = (steps + TAIL_SPLIT - 1) / TAIL_SPLIT * DBK;
         hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, WMv, WNv, ACT_NONE>), dim3(tiles_m * cn), dim3(WMv * WNv * 64), 0,
                            s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, g.ldr,
-                           tiles_m, cn, (bf16_t*)nullptr, 0, 0, 0, (const bf16_t*)nullptr);
+                           tiles_m, cn, (bf16_t*)nullptr, 0, 0, 0, (const bf16_t*)nullptr, (const float*)nullptr);
         // the tail's planes are compact ([M, width]); the kernel addresses columns by their index in C, so the
         // plane pointer is moved left by the tail's first column (never dereferenced outside the planes)
         float* ws_shifted = (float*)g.ws - (size_t)cn * BN;
         hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, WMv, WNv, ACT_NONE>), dim3(tiles_m * ct, TAIL_SPLIT),
                            dim3(WMv * WNv * 64), 0, s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)ws_shifted, g.R, g.M, g.N, g.K,
-                           g.lda, g.ldb, width, g.ldr, tiles_m, ct, (bf16_t*)nullptr, 0, cn, k_split, (const bf16_t*)nullptr);
+                           g.lda, g.ldb, width, g.ldr, tiles_m, ct, (bf16_t*)nullptr, 0, cn, k_split, (const bf16_t*)nullptr, (const float*)nullptr);
         const size_t n4 = (size_t)g.M * (width / 4);
         hipLaunchKernelGGL(splitk_tail_reduce_kernel, dim3((unsigned)std::min<size_t>((n4 + 255) / 256, 8192)), dim3(256), 0, s,
                            (const float*)g.ws, TAIL_SPLIT, g.M, width, (float*)g.C + (size_t)cn * BN, g.ldc, width);
@@ -983,7 +991,7 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
     hipLaunchKernelGGL((gemm_mfma_dl_kernel<A_KC, B_KC, TO, HAS_R, dl_wm(A_KC, B_KC), dl_wn(A_KC, B_KC), ACT_NONE>),
                        dim3(tiles_m * tiles_n), dim3(dl_wm(A_KC, B_KC) * dl_wn(A_KC, B_KC) * 64), 0,
                        s, (const bf16_t*)g.A, (const bf16_t*)g.B, (TO*)g.C, g.R, g.M, g.N, g.K, g.lda,
-                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, 0, (const bf16_t*)g.bias);
+                       g.ldb, g.ldc, g.ldr, tiles_m, tiles_n, (bf16_t*)nullptr, 0, 0, 0, (const bf16_t*)g.bias, g.out_scale);
     return hipGetLastError();
   }
   static std::once_flag once;       // per instantiation; the attribute is process-wide for the function

@@ -48,6 +48,7 @@ struct GemmArgs {
   void* ws;        // optional scratch for split-K partial results (fp32), else null
   size_t ws_bytes;
   const void* bias; // optional [N] vector of the storage type added to every row before residual / activation
+  const float* out_scale;  // optional device scalar (a power of two) multiplied into a plain 16-bit output before rounding
 };
 bool gemm_act_supported(const GemmArgs& g);   // true if launch_gemm can run g.act fused for this shape
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);       // picks the kernel family
@@ -80,6 +81,8 @@ struct AttnArgs {
   const void* d_o;      // [T, nq d]
   void* dqkv;           // [T, (nq + 2 nkv) d]
   float* delta;         // [nq, T]   rowsum(dO * O)
+  const float* grad_scale;  // MFMA path, optional: device pair {s, 1/s}; d_o holds s * dO (s a power of two that keeps
+                            // the half copy of dO in range), the kernels multiply dq, dk, dv by 1/s before rounding
 };
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
@@ -92,6 +95,10 @@ bool attn_mfma_supports(const AttnArgs& a);
 // dst[i] = (float)src[i]: storage type -> fp32 (entry of the residual stream).
 // copy (optional): also receives src unchanged, in the storage type.
 hipError_t launch_widen(const void* src, float* dst, size_t n, int dtype, hipStream_t s, void* copy = nullptr);
+// Gradient scale of a microbatch from its output gradient dy [n] (storage type): scale[0] = s = 2^-floor(log2 max|dy|)
+// (1 if dy is all zero or not finite), scale[1] = 1/s.  partial: device scratch of grad_scale_partials(n) floats.
+int grad_scale_partials(size_t n);
+hipError_t launch_grad_scale(const void* dy, size_t n, int dtype, float* partial, float* scale, hipStream_t s);
 // Rotary embedding, in place, on the first n_heads heads (head_dim d, even) of every row of a [T, ld]
 // tensor: pair (x_i, x_{i+d/2}) turns by sign * pos * base^(-2i/d), pos = row - segment start, rows and
 // segment starts taken from the query tile list (the tiles partition the rows).

@@ -53,6 +53,7 @@ struct Plan {
   std::vector<LayerStash> layer;
   size_t t_dm, t_dh, t_do, t_delta, t_dgp, t_dbp, t_qtiles, t_kvtiles;  // per-microbatch temporaries
   size_t t_dk32;                    // fp32 key-head gradients behind the head norm (QK-norm with biases only)
+  size_t t_gscale, t_gpart;         // bf16 path: {s, 1/s} of the microbatch's gradient scale, and the partial maxima behind it
   int max_tiles;
   size_t mb_bytes;                  // one microbatch region
   size_t slots_off;                 // start of the M gradient slots
@@ -154,6 +155,8 @@ int make_plan(const stage_config* c, Plan* p) {
   if (c->qk_norm) dbp = std::max(dbp, (size_t)headnorm_partials((int)T, (int)nkv) * d * 4);
   p->t_dbp = dbp ? take(dbp) : 0;
   p->t_dk32 = (c->qk_norm && c->bias) ? take(T * nkv * d * 4) : 0;
+  p->t_gscale = take(256);
+  p->t_gpart = take((size_t)grad_scale_partials(T * H) * 4);
   const int tile = std::min(ATTN_TILE_Q, ATTN_TILE_KV);
   p->max_tiles = (int)((T + tile - 1) / tile) + c->max_segments;
   p->t_qtiles = take((size_t)p->max_tiles * sizeof(AttnTile));
@@ -537,6 +540,13 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
   // one pass over dy: the fp32 head of the residual-gradient chain and the library's own copy for the GEMMs and W
   HIP_TRY(st, launch_widen(dy_dev, (float*)(base + P.layer[c.n_layers - 1].dy32), (size_t)T * H, dt, s,
                            base + P.layer[c.n_layers - 1].dy));
+  // bf16 path: the attention backward keeps its copy of dO as IEEE halves; s = 2^-floor(log2 max|dy|) brings it
+  // into their range whatever the scale of the loss (dO is linear in dy), and dq, dk, dv are multiplied by 1/s
+  const float* gscale = nullptr;
+  if (dt == BF16) {
+    HIP_TRY(st, launch_grad_scale(dy_dev, (size_t)T * H, dt, (float*)(base + P.t_gpart), (float*)(base + P.t_gscale), s));
+    gscale = (const float*)(base + P.t_gscale);
+  }
   const int n_chunk = colsum_chunks(T);
   // bias gradient = column sum of a projection's output-gradient (storage type), in a fixed order
   auto bias_grad = [&](const void* src, int n, size_t slot_off) -> int {
@@ -593,9 +603,10 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     // do = dx1 Wo^T
     g.A = base + L.dx1; g.lda = H; g.B = param_ptr(st, l, STAGE_P_WO); g.ldb = H;
     g.C = base + P.t_do; g.ldc = nqd; g.N = nqd; g.K = H;
-    g.out_dtype = dt == BF16 ? (int)F16 : dt;      // bf16 path: the attention backward reads dO as IEEE halves, like q, k, v
+    g.out_dtype = dt == BF16 ? (int)F16 : dt;      // bf16 path: the attention backward reads s * dO as IEEE halves
+    g.out_scale = gscale;
     HIP_TRY(st, launch_gemm(g, s));
-    g.out_dtype = dt;
+    g.out_dtype = dt; g.out_scale = nullptr;
     AttnArgs a{};
     a.qkv = base + L.qkv; a.o = base + L.o; a.lse = (float*)(base + L.lse);
     a.o32 = dt == BF16 ? (float*)(base + L.o32) : nullptr;
@@ -603,6 +614,7 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     a.kv_tiles = (const AttnTile*)(base + P.t_kvtiles); a.n_kv_tiles = m.n_kv_tiles;
     a.T = T; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.d = c.head_dim; a.causal = c.causal; a.dtype = dt;
     a.d_o = base + P.t_do; a.dqkv = base + L.dqkv; a.delta = (float*)(base + P.t_delta);
+    a.grad_scale = gscale;
     HIP_TRY(st, launch_attn_bwd(a, s));
     if (c.rope)   // gradients w.r.t. the rotated q, k -> w.r.t. the projection outputs (inverse rotation)
       HIP_TRY(st, launch_rope(base + L.dqkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,

@@ -147,3 +147,46 @@ def test_second_iteration_reuses_slots_and_matches():
         for k in la:
             assert np.array_equal(la[k], lb[k]), k
     stage.close()
+
+
+@pytest.mark.parametrize("log2_scale", [-24, 18])
+def test_backward_is_exactly_homogeneous_in_the_output_gradient(log2_scale):
+    """B and W are linear in dy.  The bf16 path keeps its attention-internal copy of dO as IEEE halves behind a
+    per-microbatch power-of-two scale taken from max|dy|, so multiplying dy by 2^k (exact in bf16) must multiply
+    dx and every gradient by 2^k EXACTLY: with gradients of order 1e-7 (an un-scaled mean loss) or 1e+5 the half
+    copy would otherwise lose its digits or overflow.  The scaled run is also compared with the oracle."""
+    import torch
+    import paper_2605_18750_amd as R
+    from paper_2605_18750_amd import harness as Hn
+    shape, cus = SMALL["bf16_ragged_causal_gqa"]
+    w = Hp.Workload(shape, cus)
+    cfg = Hn.make_config(shape, 333, 2, n_microbatches=w.M)
+    stage = Hn.Stage(cfg, Hn.pack_params(cfg, w.layers))
+    xs = [Hn.to_device(t.storage, shape.dtype) for t in w.x]
+    factor = 2.0 ** log2_scale
+    runs = []
+    for f in (1.0, factor):
+        dys = [Hn.to_device(t.storage, shape.dtype) * f for t in w.dy]      # exact: a power of two
+        ys = [torch.empty_like(x) for x in xs]
+        dxs = [torch.empty_like(x) for x in xs]
+        _say(f"[homogeneous] dy x 2^{0 if f == 1.0 else log2_scale}")
+        for j in range(w.M):
+            R.stage_F(stage.handle, j, xs[j], w.cus[j], ys[j])
+        for j in range(w.M):
+            R.stage_B(stage.handle, j, dys[j], dxs[j])
+            R.stage_W(stage.handle, j)
+        R.stage_grad_reduce(stage.handle, stage.grad_out)
+        torch.cuda.synchronize()
+        runs.append(([d.float().cpu() for d in dxs], stage.grad_out.cpu().clone()))
+    (dx1, g1), (dx2, g2) = runs
+    for a, b in zip(dx1, dx2):
+        assert torch.equal(a * factor, b), "dx is not exactly homogeneous in dy"
+    assert torch.equal(g1 * factor, g2), "the gradients are not exactly homogeneous in dy"
+    assert float(g1.abs().max()) > 0
+    # and the scaled run against the oracle (linear in dy as well)
+    ref = Hp.run_oracle(w)
+    got_red = Hn.unpack_grads(cfg, (g2 / factor).numpy())
+    worst = Hp.compare({"y": [], "dx": [Hn.to_f64(d / factor) for d in dx2], "grads": [], "reduced": got_red},
+                       {"y": [], "dx": ref["dx"], "grads": [], "reduced": ref["reduced"]}, 2e-2, f"dy x 2^{log2_scale}")
+    _say(f"[homogeneous] 2^{log2_scale}: exact; against the oracle {worst:.3e}")
+    stage.close()
