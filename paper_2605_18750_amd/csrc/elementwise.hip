@@ -817,7 +817,9 @@ hipError_t launch_bf16_to_f16(const void* src, void* dst, size_t n, hipStream_t 
 
 hipError_t launch_grad_reduce(const float* slots, size_t slot_stride, int M, float* out, size_t n, hipStream_t s) {
   if (n % 4 || slot_stride % 4) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(grad_reduce_kernel, dim3(grid_for(n / 4)), dim3(256), 0, s, (const f32x4*)slots, slot_stride / 4,
+  // one 16-byte element per thread where the grid allows it: measured 5.3 TB/s against 4.6 TB/s for a grid-stride
+  // loop over 8192 workgroups (8 slots of 1 GiB; a pure read of the same bytes runs at 5.7 TB/s on this chip)
+  hipLaunchKernelGGL(grad_reduce_kernel, dim3(grid_for(n / 4, 1 << 24)), dim3(256), 0, s, (const f32x4*)slots, slot_stride / 4,
                      M, (f32x4*)out, n / 4);
   return hipGetLastError();
 }
