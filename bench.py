@@ -81,7 +81,7 @@ def cpu_baseline(shape, T_sample: int):
                       f"{dt:.1f} s wall"}
 
 
-def gemm_roofline(shape, T, Bw, s, gen, n_launch=20, form="nn"):
+def gemm_roofline(shape, T, Bw, s, gen, n_launch=40, form="nn"):
     """The bf16 MFMA GEMM of the up projection alone, HIP events on the launch stream.  form "nn": the
     forward [T, hidden] x [hidden, N_up] (the roofline kernel of the step bench); "nt": its input
     gradient [T, N_up] x [hidden, N_up]^T -> fp32 [T, hidden]; "tn": its weight gradient
@@ -115,7 +115,9 @@ def gemm_roofline(shape, T, Bw, s, gen, n_launch=20, form="nn"):
                 R.rrfp_gemm(A, G, Cc, None, H, N_up, T, H, N_up, N_up, N_up, 1, 0, 1, 0, R.RRFP_GEMM_MFMA, s,
                             workspace=ws, workspace_bytes=ws_bytes)
     with torch.cuda.stream(s):
-        for _ in range(3):
+        # the tensors above were just made: the chip has been idle, and its clock takes some tens of launches to
+        # settle under the GEMM again (the step timed before ran with a settled clock)
+        for _ in range(max(3, n_launch)):
             launch()
         g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         g0.record(s)
