@@ -339,13 +339,28 @@ constexpr int BQ_KV = 64;      // query rows per step of the dK/dV kernel
 constexpr int WK = 32;         // keys per wavefront of the dK/dV kernel
 constexpr int DKV_VALU_PER_MFMA = 8;    // vector instructions of the P / dS arithmetic issued after each MFMA of a group
 
-// N_MFMA times (one MFMA, N_VALU vector instructions) in the instruction scheduler's order.
-template <int N_MFMA, int N_VALU>
+// N_MFMA times (one MFMA, a share of the N_READS LDS reads, of the N_VMEM global loads and of the N_WRITES LDS
+// writes, N_VALU vector instructions) in the instruction scheduler's order.  A wavefront issues in order, so
+// whatever it issues in a run holds its MFMAs back: reads in one run fill its 16 outstanding-LDS-operation slots
+// and then wait for the LDS, global loads in one run wait for the texture path (16 cycles per 1 KB instruction, and
+// the four wavefronts of the workgroup arrive together).  One or two under each MFMA cost nothing.  The reads
+// (fragments of the NEXT group) go under the first N_MFMA - 2 MFMAs.
+template <int N_MFMA, int N_VALU, int N_READS, int N_VMEM = 0, int N_WRITES = 0, int I = 0>
 __device__ __forceinline__ void interleave_mfma_valu() {
-  if constexpr (N_MFMA > 0) {
+  if constexpr (I < N_MFMA) {
+    // with LDS writes in the group (which the compiler must keep behind the reads: it cannot tell the two LDS
+    // stages apart), the reads take the first half of the MFMAs and the writes the second
+    constexpr int SPREAD = N_WRITES > 0 ? N_MFMA / 2 : (N_MFMA > 2 ? N_MFMA - 2 : 1);
+    constexpr int R = I < SPREAD ? ((I + 1) * N_READS) / SPREAD - (I * N_READS) / SPREAD : 0;
+    constexpr int G = ((I + 1) * N_VMEM) / N_MFMA - (I * N_VMEM) / N_MFMA;
+    constexpr int WS = N_MFMA - SPREAD;
+    constexpr int W = (N_WRITES > 0 && I >= SPREAD) ? ((I - SPREAD + 1) * N_WRITES) / WS - ((I - SPREAD) * N_WRITES) / WS : 0;
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (R > 0) __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
+    if constexpr (G > 0) __builtin_amdgcn_sched_group_barrier(0x020, G, 0);
+    if constexpr (W > 0) __builtin_amdgcn_sched_group_barrier(0x200, W, 0);
     if constexpr (N_VALU > 0) __builtin_amdgcn_sched_group_barrier(0x002, N_VALU, 0);
-    interleave_mfma_valu<N_MFMA - 1, N_VALU>();
+    interleave_mfma_valu<N_MFMA, N_VALU, N_READS, N_VMEM, N_WRITES, I + 1>();
   }
 }
 
@@ -407,16 +422,21 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
   float r_stat = 0.f;
 
   // Rows past the end of the segment repeat its last row (finite values): P and dS are exactly zero there.
-  auto fetch = [&](int step) {
+  auto fetch_q = [&](int step) {
     const int a = b * G + step / nq_steps;
     const int q0 = q_begin + (step % nq_steps) * BQ_KV;
     tile_load_clamped<D, BQ_KV>(rq, qkv + a * D, ld, q0, tl.s1);
+  };
+  auto fetch_d = [&](int step) {
+    const int a = b * G + step / nq_steps;
+    const int q0 = q_begin + (step % nq_steps) * BQ_KV;
     tile_load_clamped<D, BQ_KV>(rd, d_o + a * D, nq * D, q0, tl.s1);
     // row statistics: threads 0..63 bring lse, 64..127 delta, the upper half of the workgroup the same again
     const int i = min(q0 + (int)(threadIdx.x & (BQ_KV - 1)), tl.s1 - 1);
     const bool is_dl = (threadIdx.x & BQ_KV) != 0;
     r_stat = (is_dl ? delta : lse)[(size_t)a * Tn + i];       // used (scaled) only in commit: no wait for it here
   };
+  auto fetch = [&](int step) { fetch_q(step); fetch_d(step); };
   auto commit = [&](char* stage) {
     tile_store<D, BQ_KV, C::QP, C::DP, 256, true>(rq, stage);
     tile_store<D, BQ_KV, C::QP, C::DP, 256, true>(rd, stage + C::T_BYTES);
@@ -433,9 +453,9 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
   // wavefront per SIMD, so nothing but this wavefront's own instruction stream can fill the MFMA pipe:
   // every group issues the LDS fragment reads of the NEXT group before its own MFMAs (two fragment sets
   // alive, used in turn), and the P / dS arithmetic of a 16-row half (quarter-rate exponentials
-  // included) issues between the MFMAs of a group that does not depend on it.  The next tile goes to
-  // LDS before the sixth group; the step's one barrier sits between the last two groups, under MFMAs in
-  // flight; the last group reads the first fragments of the step after, from the other LDS stage.
+  // included) issues between the MFMAs of a group that does not depend on it.  The next tile's global loads
+  // are issued one under each MFMA of the first two groups and go to LDS under the MFMAs of the seventh; the
+  // step's one barrier sits between the last two groups, under MFMAs in flight; the last group reads the first fragments of the step after, from the other LDS stage.
   // MASK is a compile-time flag so that each variant of the step is one basic block.
   constexpr int NH0 = (NDS + 1) / 2, NH1 = NDS - NH0;      // head-dimension slices of 16 in the two halves
   constexpr int FS = NH0 > NDB ? NH0 : NDB;
@@ -472,15 +492,26 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
         dpacc[ib] = mfma16(f.b[i], vf[half * NH0 + i], dpacc[ib]);
       }
     };
-    auto arith = [&](int ib, int u) {
+    // Row statistics of a 16-row half: read one group ahead of the arithmetic that uses them (LDS reads return in
+    // order, so a read issued behind a group's fragment reads would make the arithmetic wait for all of those).
+    struct Stats { float4 l[2], d[2]; };
+    Stats sx, sy;
+    auto stat_load = [&](int ib, int u, Stats& st) {
+#pragma unroll
+      for (int gg = 0; gg < 2; ++gg) {
+        const int il = ib * 32 + (u * 2 + gg) * 8 + h * 4;
+        st.l[gg] = *reinterpret_cast<const float4*>(s_lse + il);
+        st.d[gg] = *reinterpret_cast<const float4*>(s_dl + il);
+      }
+    };
+    auto arith = [&](int ib, int u, const Stats& st) {
       // accumulator value e belongs to row ib*32 + (e/4)*8 + h*4 + e%4; half u holds e = 8u .. 8u+7
       float pv[8], dsv[8];
 #pragma unroll
       for (int gg = 0; gg < 2; ++gg) {
         const int g = u * 2 + gg;
         const int il = ib * 32 + g * 8 + h * 4;
-        const float4 l4 = *reinterpret_cast<const float4*>(s_lse + il);
-        const float4 d4 = *reinterpret_cast<const float4*>(s_dl + il);
+        const float4 l4 = st.l[gg], d4 = st.d[gg];
         const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -504,50 +535,56 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
         dk[db] = mfma16(f.b[db], dsf[ib][u], dk[db]);
       }
     };
-    // Order inside a group: the LDS reads first, then one MFMA per handful of vector instructions.
-    auto group_order = [&](auto n_reads, auto n_mfma, auto n_valu) {
-      __builtin_amdgcn_sched_group_barrier(0x100, decltype(n_reads)::value, 0);
-      interleave_mfma_valu<decltype(n_mfma)::value, decltype(n_valu)::value>();
+    // Order inside a group: one MFMA, a few LDS reads, a handful of vector instructions, and again.
+    auto group_order = [&](auto n_reads, auto n_mfma, auto n_valu, auto n_vmem, auto n_writes) {
+      interleave_mfma_valu<decltype(n_mfma)::value, decltype(n_valu)::value, decltype(n_reads)::value, decltype(n_vmem)::value,
+                           decltype(n_writes)::value>();
       __builtin_amdgcn_sched_barrier(0);
     };
     constexpr int V = DKV_VALU_PER_MFMA;
 #define RRFP_IC(x) std::integral_constant<int, (x)>{}
-    // S,dP of block 0; the next tile's global loads (after the last step: the same tile again, never used)
-    fetch(min(next_step, nsteps - 1));
+    constexpr int NLD = TileRegs<D, BQ_KV>::N;       // global loads per thread and tile (Q, dO alike)
+    // S,dP of block 0; the next tile's global loads (after the last step: the same tile again, never used), one
+    // under each MFMA
+    fetch_q(min(next_step, nsteps - 1));
     load_rows(sq, sd, 0, 1, fy);
     sdp(0, 0, fx);
-    group_order(RRFP_IC(2 * NH1), RRFP_IC(2 * NH0), RRFP_IC(0));
+    group_order(RRFP_IC(2 * NH1), RRFP_IC(2 * NH0), RRFP_IC(0), RRFP_IC(NLD), RRFP_IC(0));
+    fetch_d(min(next_step, nsteps - 1));
     load_rows(sq, sd, 1, 0, fx);
+    stat_load(0, 0, sx);
     sdp(0, 1, fy);
-    group_order(RRFP_IC(2 * NH0), RRFP_IC(2 * NH1), RRFP_IC(0));
+    group_order(RRFP_IC(2 * NH0 + 4), RRFP_IC(2 * NH1), RRFP_IC(0), RRFP_IC(NLD + 1), RRFP_IC(0));
     // S,dP of block 1 with the arithmetic of block 0
     load_rows(sq, sd, 1, 1, fy);
+    stat_load(0, 1, sy);
     sdp(1, 0, fx);
-    arith(0, 0);
-    group_order(RRFP_IC(2 * NH1 + 4), RRFP_IC(2 * NH0), RRFP_IC(V));
+    arith(0, 0, sx);
+    group_order(RRFP_IC(2 * NH1 + 4), RRFP_IC(2 * NH0), RRFP_IC(V), RRFP_IC(0), RRFP_IC(0));
     load_tr(0, 0, fx);
+    stat_load(1, 0, sx);
     sdp(1, 1, fy);
-    arith(0, 1);
-    group_order(RRFP_IC(4 * NDB + 4), RRFP_IC(2 * NH1), RRFP_IC(V));
+    arith(0, 1, sy);
+    group_order(RRFP_IC(4 * NDB + 4), RRFP_IC(2 * NH1), RRFP_IC(V), RRFP_IC(0), RRFP_IC(0));
     // dV,dK of block 0 with the arithmetic of block 1
     load_tr(0, 1, fy);
+    stat_load(1, 1, sy);
     dvdk(0, 0, fx);
-    arith(1, 0);
-    group_order(RRFP_IC(4 * NDB + 4), RRFP_IC(2 * NDB), RRFP_IC(V));
-    commit(next_stage);
-    __builtin_amdgcn_sched_barrier(0);
+    arith(1, 0, sx);
+    group_order(RRFP_IC(4 * NDB + 4), RRFP_IC(2 * NDB), RRFP_IC(V), RRFP_IC(0), RRFP_IC(0));
     load_tr(1, 0, fx);
     dvdk(0, 1, fy);
-    arith(1, 1);
-    group_order(RRFP_IC(4 * NDB + 4), RRFP_IC(2 * NDB), RRFP_IC(V));
-    // dV,dK of block 1
+    arith(1, 1, sy);
+    group_order(RRFP_IC(4 * NDB), RRFP_IC(2 * NDB), RRFP_IC(V), RRFP_IC(0), RRFP_IC(0));
+    // dV,dK of block 1; the next tile goes to LDS under the MFMAs of its first half
     load_tr(1, 1, fy);
+    commit(next_stage);
     dvdk(1, 0, fx);
-    group_order(RRFP_IC(4 * NDB), RRFP_IC(2 * NDB), RRFP_IC(0));
+    group_order(RRFP_IC(4 * NDB), RRFP_IC(2 * NDB), RRFP_IC(0), RRFP_IC(0), RRFP_IC(2 * NLD + 1));
     __syncthreads();
     load_rows(next_stage, next_stage + C::T_BYTES, 0, 0, fx);   // stale data after the last step: read, never used
     dvdk(1, 1, fy);
-    group_order(RRFP_IC(2 * NH0), RRFP_IC(2 * NDB), RRFP_IC(0));
+    group_order(RRFP_IC(2 * NH0), RRFP_IC(2 * NDB), RRFP_IC(0), RRFP_IC(0), RRFP_IC(0));
 #undef RRFP_IC
   };
 
