@@ -147,6 +147,47 @@ def gemm_roofline(shape, T, Bw, s, gen, n_launch=40, form="nn"):
             "traffic_source": traffic_source}
 
 
+def gemm_sweep(s, n_launch=200):
+    """One bf16 GEMM [M, K] x [K, 4096] per row, M = 4096 / 2048 / 1024 (256, 128, 64 tiles of 256 x 256) and
+    K = 2048 / 4096 / 8192, in the weight-gradient (tn, fp32 out), input-gradient (nt, fp32 and bf16 out) and forward
+    (nn, bf16 out) forms; HIP events over n_launch launches after n_launch warm-up launches.  The slope against K is
+    the main-loop time of one tile, the intercept what a launch costs besides (launch, pipeline fill, the output
+    burst).  With fewer tiles than CUs the forms with a K-contiguous A cut M into 128-row tiles."""
+    import torch
+    import paper_2605_18750_amd as R
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    BF, F32 = R.STAGE_DTYPE_BF16, R.STAGE_DTYPE_FP32
+    N = 4096
+    rows = []
+    for form, out in (("tn", F32), ("nt", F32), ("nt", BF), ("nn", BF)):
+        ta, tb = {"tn": (1, 0), "nt": (0, 1), "nn": (0, 0)}[form]
+        for M in (4096, 2048, 1024):
+            us = []
+            for K in (2048, 4096, 8192):
+                A = torch.empty((K, M) if ta else (M, K), dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=gen)
+                B = torch.empty((N, K) if tb else (K, N), dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0 if form == "tn" else 0.02,
+                                                                                                       generator=gen)
+                C = torch.empty((M, N), dtype=torch.float32 if out == F32 else torch.bfloat16, device=dev)
+                call = lambda: R.rrfp_gemm(A, B, C, None, M, N, K, A.shape[1], B.shape[1], N, 0, ta, tb, BF, out, stream=s)
+                with torch.cuda.stream(s):
+                    for _ in range(n_launch):
+                        call()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(s)
+                    for _ in range(n_launch):
+                        call()
+                    e1.record(s)
+                torch.cuda.synchronize()
+                us.append(e0.elapsed_time(e1) / n_launch * 1e3)
+            slope = (us[2] - us[0]) / 6.0
+            rows.append({"form": form, "out": "fp32" if out == F32 else "bf16", "M": M, "tiles_256": (M // 256) * (N // 256),
+                         "us_at_K_2048_4096_8192": [round(u, 1) for u in us], "us_per_1024_K": round(slope, 2),
+                         "intercept_us": round(us[0] - 2 * slope, 1)})
+    return rows
+
+
 def hbm_kernels(shape, T, M, grad_floats, s, gen, n_launch=20):
     """The HBM-bound kernels alone, HIP events on the launch stream.  Algorithmic bytes (storage type bf16):
     RMSNorm forward 2 * T * H * 2 B, RMSNorm backward 4 * T * H * 2 B (three reads, one write), gradient
@@ -263,11 +304,14 @@ def main():
     ap.add_argument("--gemm-form", default=None, choices=["nn", "nt", "tn"],
                     help="operand orientation of the roofline GEMM (forward, input-gradient or weight-gradient form of the "
                          "up projection); default: tn, the form with the largest share of the step")
-    ap.add_argument("--only", default="step", choices=["step", "gemm", "copy", "pipeline"],
-                    help="gemm: launch only the roofline GEMM (for counter runs); copy: a 2 GiB device copy, the "
+    ap.add_argument("--only", default="step", choices=["step", "gemm", "gemm_sweep", "copy", "pipeline"],
+                    help="gemm: launch only the roofline GEMM (for counter runs); gemm_sweep: time of the GEMM forms against "
+                         "K with a full, a half and a quarter round of 256 x 256 tiles (main-loop rate and fixed cost per "
+                         "launch, with and without every CU busy); copy: a 2 GiB device copy, the "
                          "calibration of the FETCH_SIZE / WRITE_SIZE counters; pipeline: measure the per-microbatch "
                          "task times of the workload and replay them through the native pipeline simulator "
                          "(fixed 1F1B against readiness-driven dispatch, jitter levels J0-J3)")
+    ap.add_argument("--sweep-launches", type=int, default=200, help="timed (and warm-up) launches per row of --only gemm_sweep")
     ap.add_argument("--pipeline-stages", type=int, default=8)
     ap.add_argument("--rope", action="store_true", help="turn on the rotary-embedding variant of the layer (off in the headline workload)")
     ap.add_argument("--qk-norm", action="store_true", help="turn on the QK-norm variant of the layer (off in the headline workload)")
@@ -297,6 +341,10 @@ def main():
         shape = shape.replace(qk_norm=True, name=shape.name + "+qknorm")
     if args.layernorm_bias:
         shape = shape.replace(norm_kind="layer", bias=True, name=shape.name + "+layernorm+bias")
+    if args.only == "gemm_sweep":
+        torch.cuda.set_device(0)
+        print(json.dumps({"only": "gemm_sweep", "rows": gemm_sweep(torch.cuda.Stream(), n_launch=args.sweep_launches)}))
+        return
     if args.only in ("gemm", "copy"):
         torch.cuda.set_device(0)
         gen = torch.Generator(device="cuda:0")
