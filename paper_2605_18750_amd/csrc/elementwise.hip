@@ -148,6 +148,51 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restric
   }
 }
 
+// The same for rows of up to NV * 64 vectors (H % Vec<T>::N == 0): the row is read once, all its loads issued
+// before the first use, and stays in registers between the two sweeps.  Same arithmetic in the same order as the
+// kernel above (bit-identical results).
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_rows_kernel(const float* __restrict__ x, const T* __restrict__ g,
+                                                               T* __restrict__ h, float* __restrict__ r_out,
+                                                               int Tn, int H, float eps, f16_t* __restrict__ h16) {
+  constexpr int V = Vec<T>::N;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= Tn) return;
+  const float* xr = x + (size_t)row * H;
+  float a[NV][V];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int c = (v * WAVE + lane) * V;
+    if (c < H) load_f32<V>(xr + c, a[v]);
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    if ((v * WAVE + lane) * V < H) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) ss += a[v][i] * a[v][i];
+    }
+  }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)H + eps);
+  if (lane == 0) r_out[row] = r;
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int c = (v * WAVE + lane) * V;
+    if (c < H) {
+      float gv[V];
+      load_vec<T>(g + c, gv);
+#pragma unroll
+      for (int i = 0; i < V; ++i) a[v][i] = a[v][i] * r * gv[i];
+      store_vec<T>(h + (size_t)row * H + c, a[v]);
+      if constexpr (V == 8) {
+        if (h16) store_vec<f16_t>(h16 + (size_t)row * H + c, a[v]);
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------- RMSNorm backward, rows
 // dx = add_in + r * (w - xhat * mean(w * xhat)),  w = dh * g,  xhat = x * r.
 // dh (a GEMM output consumed only here), x and add_in (residual stream) are fp32.  dx goes to out32 (fp32, next link of the residual-gradient
@@ -697,6 +742,18 @@ hipError_t launch_rope(void* x, const AttnTile* q_tiles, int n_q_tiles, int n_he
 hipError_t launch_rmsnorm_fwd(const float* x, const void* g, void* h, float* r_out, int Tn, int H, float eps,
                               int dtype, hipStream_t s, void* h16) {
   if (h16 && dtype != BF16) return hipErrorInvalidValue;
+  const int V = dtype == F32 ? 4 : 8;
+  if ((H % V) == 0) {
+    const int nv = (H + WAVE * V - 1) / (WAVE * V);
+#define RRFP_ROWS(NVV)                                                                                              \
+  if (nv <= NVV) {                                                                                                  \
+    DISPATCH_T(dtype, hipLaunchKernelGGL((rmsnorm_fwd_rows_kernel<T, NVV>), dim3((Tn + 3) / 4), dim3(256), 0, s, x, \
+                                         (const T*)g, (T*)h, r_out, Tn, H, eps, (f16_t*)h16));                      \
+    return hipGetLastError();                                                                                       \
+  }
+    RRFP_ROWS(1) RRFP_ROWS(2) RRFP_ROWS(4) RRFP_ROWS(8) RRFP_ROWS(16)
+#undef RRFP_ROWS
+  }
   DISPATCH_T(dtype, hipLaunchKernelGGL(rmsnorm_fwd_kernel<T>, dim3((Tn + 3) / 4), dim3(256), 0, s, x, (const T*)g, (T*)h,
                                        r_out, Tn, H, eps, (f16_t*)h16));
   return hipGetLastError();
