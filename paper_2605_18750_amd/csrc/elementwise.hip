@@ -386,7 +386,16 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ p
   const int p0 = grp * per, p1 = min(p0 + per, n_partial);
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (c + 3 < H && (H & 3) == 0) {
-    for (int p = p0; p < p1; ++p) {
+    // eight loads in flight at a time, added in row order (the loop is bound by the latency of its loads)
+    int p = p0;
+    for (; p + 8 <= p1; p += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(partial + (size_t)(p + u) * H + c);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { acc[0] += v[u].x; acc[1] += v[u].y; acc[2] += v[u].z; acc[3] += v[u].w; }
+    }
+    for (; p < p1; ++p) {
       const float4 v = *reinterpret_cast<const float4*>(partial + (size_t)p * H + c);
       acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
     }
