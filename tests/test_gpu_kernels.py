@@ -140,7 +140,8 @@ def test_mfma_gemm_short_tile_tail():
 
 
 @pytest.mark.parametrize("T,H,dtype", [(777, 512, "bf16"), (130, 256, "fp32"), (1030, 4096, "bf16"), (9, 1280, "bf16"),
-                                       (65, 200, "fp32"), (300, 8192, "bf16"), (70, 2048, "fp32"), (33, 3000, "bf16")])
+                                       (65, 200, "fp32"), (300, 8192, "bf16"), (70, 2048, "fp32"), (33, 3000, "bf16"),
+                                       (20, 4096, "fp32"), (12, 8192, "fp32"), (7, 1001, "fp32"), (5, 16384, "bf16")])
 def test_rmsnorm_kernels_against_oracle(T, H, dtype):
     """RMSNorm forward and backward (rows + gain gradient) through their own entry points, against the fp64
     oracle on the same rounded inputs; T spans several row chunks with a ragged tail."""
