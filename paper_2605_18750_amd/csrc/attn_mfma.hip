@@ -451,11 +451,12 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
   //   S,dP(0) halves | S,dP(1) halves + arithmetic(0) | dV,dK(0) halves + arithmetic(1) | dV,dK(1) halves
   // (S,dP halved over the head dimension, dV,dK over the 16-row halves of the block).  There is one
   // wavefront per SIMD, so nothing but this wavefront's own instruction stream can fill the MFMA pipe:
-  // every group issues the LDS fragment reads of the NEXT group before its own MFMAs (two fragment sets
+  // every group issues the LDS fragment reads of the NEXT group under its own MFMAs (two fragment sets
   // alive, used in turn), and the P / dS arithmetic of a 16-row half (quarter-rate exponentials
   // included) issues between the MFMAs of a group that does not depend on it.  The next tile's global loads
   // are issued one under each MFMA of the first two groups and go to LDS under the MFMAs of the seventh; the
-  // step's one barrier sits between the last two groups, under MFMAs in flight; the last group reads the first fragments of the step after, from the other LDS stage.
+  // step's one barrier sits between the last two groups, under MFMAs in flight; the last group reads the
+  // first fragments of the step after, from the other LDS stage.
   // MASK is a compile-time flag so that each variant of the step is one basic block.
   constexpr int NH0 = (NDS + 1) / 2, NH1 = NDS - NH0;      // head-dimension slices of 16 in the two halves
   constexpr int FS = NH0 > NDB ? NH0 : NDB;
