@@ -17,10 +17,8 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
 
 
-# Per-file additions to FLAGS.  The dQ attention kernel is scheduled with the iterative-ilp strategy
-# (measured: 8-10 % faster for that kernel; slower for the dK/dV kernel, neutral for the attention forward
-# and, in the stage step, for the GEMMs, which keep the default).
-EXTRA_FLAGS = {"attn_mfma_dq.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"]}
+# Per-file additions to FLAGS (none at present: every kernel is built with the default scheduling strategy).
+EXTRA_FLAGS = {}
 
 
 def sources():

@@ -296,14 +296,20 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
 
 
 // ------------------------------------------------------------------------------------------
-// Backward.  Three kernels, no atomics:
+// Backward.  Three kernels, no atomics; P and dS are formed once:
 //   delta:  delta[a][i] = sum_d dO[i,a,d] * O[i,a,d]
-//   dQ:     same tiling as the forward; per key step recompute S^T and dP^T = V dO^T, form
-//           dS^T = P^T * (dP^T - delta) in registers (already a B operand), dQ^T += K^T dS^T.
 //   dK/dV:  a workgroup owns 128 keys of one KV head (32 per wavefront, K and V fragments held
 //           in registers) and walks the query heads of its group and the query rows in ascending
 //           order; S = Q K^T and dP = dO V^T are computed UNtransposed so that a lane holds one
-//           key column and P, dS are B operands of dV^T += dO^T P and dK^T += Q^T dS.
+//           key column and P, dS are B operands of dV^T += dO^T P and dK^T += Q^T dS.  The dS
+//           operand (IEEE halves, exactly what the dK product consumed) also goes to a scratch.
+//   dQ:     (attn_mfma_dq.hip) streams that scratch: dQ^T += K^T dS^T, no recomputation.
+// The scratch is block-linear: the 32 keys x 64 queries a wavefront handles in one step are one 4 KB block, written as
+// four 1 KB stores, one per 16-row quarter (32-row half ib, 16-row half u) of the step: lane l stores 16 bytes, the dS
+// of key l % 32 for the query rows 16u + 4 (l / 32) + {0..3} and 16u + 8 + 4 (l / 32) + {0..3} of half ib.  Blocks are
+// indexed [query head][32-key block row][64-query step], rows and steps counted from the segment start (rows offset by
+// the tile's kb0).  Every block a dQ wavefront reads has been written in full: masked entries hold the zeros the dK
+// product saw.
 // ------------------------------------------------------------------------------------------
 
 template <int D>
@@ -378,7 +384,8 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
                                                             bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
                                                             int Tn, int nq, int nkv, int causal, float scale,
-                                                            const float* __restrict__ grad_scale) {
+                                                            const float* __restrict__ grad_scale, el_t* __restrict__ ds,
+                                                            int ds_rows, int ds_nqs) {
   using C = DkvCfg<D>;
   constexpr int NDS = D / 16, NDB = C::DP / 32;
   constexpr float LOG2E = 1.4426950408889634f;
@@ -394,6 +401,9 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
   const int j = wj0 + li;                       // this lane's key column
   const bool wave_has_keys = wj0 < tl.r1;
   const float scale_log2e = scale * LOG2E;
+  // dS scratch: this wavefront's block row; the block of a step and the query head are added per step
+  const int ds_krow = tl.kb0 + ((wj0 - tl.s0) >> 5);
+  el_t* ds_head = ds;
 
   frag_t kf[NDS], vf[NDS];
 #pragma unroll
@@ -472,6 +482,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
   auto compute_step = [&](const char* sq, const char* sd, const float* s_lse, const float* s_dl, int q0, int next_step,
                           char* next_stage, auto mask_tag) {
     constexpr bool MASK = decltype(mask_tag)::value;
+    el_t* ds_block = ds_head + ((size_t)ds_krow * ds_nqs + ((q0 - tl.s0) >> 6)) * 2048 + lane * 8;
     floatx16 sacc[2], dpacc[2];
     frag_t pf[2][2], dsf[2][2];
     FragSet fy;
@@ -528,6 +539,10 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
       }
       pf[ib][u] = pack8(pv);
       dsf[ib][u] = pack8(dsv);
+      // the dQ kernel's copy: 16 bytes per lane = this key's dS for query rows 16u + h*4 .. +3 and 16u + 8 + h*4 .. +3
+      // of half ib; streamed past the caches (read once, by another kernel)
+      typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+      __builtin_nontemporal_store(__builtin_bit_cast(u32x4, dsf[ib][u]), reinterpret_cast<u32x4*>(ds_block + (ib * 2 + u) * 512));
     };
     auto dvdk = [&](int ib, int u, const FragSet& f) {
 #pragma unroll
@@ -612,6 +627,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
   };
   int st = 0;
   for (int ah = 0; ah < G; ++ah) {
+    ds_head = ds + (size_t)(b * G + ah) * ds_rows * ds_nqs * 2048;
     int t = 0;
     for (; t < n_skip; ++t, ++st) {
       if (st + 1 < nsteps) { fetch(st + 1); commit(smem + ((st + 1) & 1) * C::STAGE); }
@@ -656,7 +672,8 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((a.T * a.nq + 15) / 16), dim3(256), 0, s, (const bf16_t*)a.o,
                      a.o32, (const el_t*)a.d_o, a.delta, a.T, a.nq);
   hipLaunchKernelGGL(kkv, dim3(a.nkv, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const el_t*)a.qkv,
-                     (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale, a.grad_scale);
+                     (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale, a.grad_scale,
+                     (el_t*)a.ds, a.ds_rows, a.ds_nqs);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return launch_attn_dq_mfma(a, s);
@@ -690,7 +707,7 @@ hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
-  if (!attn_mfma_supports(a) || a.n_kv_tiles < 1) return hipErrorInvalidValue;
+  if (!attn_mfma_supports(a) || a.n_kv_tiles < 1 || !a.ds || a.ds_rows < 1 || a.ds_nqs < 5) return hipErrorInvalidValue;
   if (a.d == 64) return bwd_launch<64>(a, s);
   if (a.d == 80) return bwd_launch<80>(a, s);
   return bwd_launch<128>(a, s);

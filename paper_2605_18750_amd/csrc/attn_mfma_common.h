@@ -36,10 +36,9 @@ __device__ __forceinline__ floatx16 mfma16(frag_t a, frag_t b, floatx16 c) {
 }
 
 constexpr int BKV = 64;        // keys per step
-constexpr int FWD_Q_ROWS = ATTN_TILE_Q;   // query rows per workgroup of the forward and dQ kernels
+constexpr int FWD_Q_ROWS = ATTN_TILE_Q;   // query rows per workgroup of the forward kernel (the dQ kernel uses the same tiles)
 constexpr int FWD_NIB = 1;                // 32-query blocks per wavefront: 8 wavefronts, two per SIMD, so that one
                                           // wavefront's softmax arithmetic runs under the other's MFMAs
-constexpr int DQ_NIB = 1;
 
 // Fragment of a tile stored [row][k] (pitch bytes): lane gets row row0 + (lane & 31), k = ks*16 + h*8 .. +8.
 __device__ __forceinline__ frag_t frag_rows(const char* tile, int pitch, int row0, int ks, int lane) {

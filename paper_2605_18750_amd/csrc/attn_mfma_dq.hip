@@ -1,165 +1,153 @@
-// dQ kernel of the MFMA attention backward (see attn_mfma.hip for the scheme).  It lives in its own
-// translation unit because it is compiled with a different instruction-scheduling strategy than the other
-// attention kernels (the build passes -mllvm -amdgpu-sched-strategy=iterative-ilp for this file: measured
-// 8-10 % faster for this kernel, slower for the dK/dV kernel, neutral for the forward).
+// dQ kernel of the MFMA attention backward (see attn_mfma.hip for the scheme): dQ^T += K^T dS^T, with dS read back
+// from the scratch the dK/dV kernel filled, so that neither the scores nor dP are formed a second time.
+//
+// A workgroup (8 wavefronts) owns one query tile (up to 256 rows inside one segment) of one query head; a wavefront
+// owns 32 query rows = one 32-row half of a 64-query step of the scratch.  Keys advance in steps of 128: the K tile of
+// a step goes through LDS (shared by the wavefronts, two stages), the wavefront's own dS -- four blocks of 32 keys, 2 KB
+// each, contiguous in the scratch -- through a private LDS area, and both operands of an MFMA come from the LDS
+// transpose read: the scratch holds, per key, four consecutive queries in 8 bytes, which is the unit that read
+// transposes.  Under a causal mask a wavefront contracts only over the 32-key blocks that hold a key at or before its
+// last query; those are exactly the blocks the dK/dV kernel wrote for its query step, zeros included, so nothing is
+// masked here.  The kernel is bound by the stream of dS out of memory (no reuse: it is read past the caches); loads
+// run two steps ahead in two register sets.
 #include "attn_mfma_common.h"
 
 namespace rrfp {
 namespace {
 
+constexpr int DQ_BK = 128;       // keys per step
+
 template <int D>
 struct DqCfg {
   static constexpr int DP = (D + 31) / 32 * 32;
-  static constexpr int KP = 304;                     // K tile: row fragments AND transposed fragments.  304 = 48 (mod 256):
-                                                     // 16 rows x 16 B and 4 rows x 32 B both land on distinct banks
-  static constexpr int VP = D * 2 + 16;              // V tile: row fragments only
-  static constexpr int K_BYTES = BKV * KP;
-  static constexpr int STAGE = (K_BYTES + BKV * VP + 255) / 256 * 256;
-  static constexpr int SMEM = 2 * STAGE;
+  static constexpr int KP = 304;                        // K tile row pitch in bytes; 304 = 48 (mod 256): the four rows of 32 B a
+                                                        // transposed read touches land on distinct banks
+  static constexpr int K_STAGE = (DQ_BK * KP + 255) / 256 * 256;
+  static constexpr int DS_HALF = 512 + 64;              // 32 lanes x 16 B of a scratch store, then 64 B of padding so that the
+                                                        // two halves of a store land on different banks
+  static constexpr int DS_PAIR = 2 * DS_HALF;           // one 1 KB store of the dK/dV kernel
+  static constexpr int DS_BLOCK = 2 * DS_PAIR;          // this wavefront's 32 queries of one 32-key block
+  static constexpr int DS_WAVE = (DQ_BK / 32) * DS_BLOCK;
+  static constexpr int SMEM = 2 * K_STAGE + 8 * DS_WAVE;
 };
 
-template <int D, int NIB>
-__global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_kernel(const el_t* __restrict__ qkv, const el_t* __restrict__ d_o,
-                                                           const float* __restrict__ lse, const float* __restrict__ delta,
+template <int D>
+__global__ __launch_bounds__(512) void attn_dq_mfma_kernel(const el_t* __restrict__ qkv, const el_t* __restrict__ ds,
                                                            bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
-                                                           int Tn, int nq, int nkv, int causal, float scale,
-                                                           const float* __restrict__ grad_scale) {
-  constexpr int NT = FWD_Q_ROWS / (32 * NIB) * 64;   // threads: one wavefront per 32 * NIB query rows
-  constexpr int WQ = 32 * NIB;
+                                                           int nq, int nkv, int causal, float scale,
+                                                           const float* __restrict__ grad_scale, int ds_rows, int ds_nqs) {
   using C = DqCfg<D>;
-  constexpr int NDS = D / 16, NDB = C::DP / 32;
-  constexpr float LOG2E = 1.4426950408889634f;
+  constexpr int NT = 512, NDB = C::DP / 32, NBLK = DQ_BK / 32;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const AttnTile tl = tiles[blockIdx.y];
   const int a = blockIdx.x, b = a / (nq / nkv);
   const int ld = (nq + 2 * nkv) * D;
-  const int qcol = a * D, kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
+  const int qcol = a * D, kcol = (nq + b) * D;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: wave-level branches stay uniform
   const int h = lane >> 5, li = lane & 31;
-  const int wq0 = tl.r0 + wave * WQ;
+  const int wq0 = tl.r0 + wave * 32;
   const bool wave_has_rows = wq0 < tl.r1;
-  const float scale_log2e = scale * LOG2E;
+  const int kv_end = causal ? tl.r1 : tl.s1;
+  const int nsteps = (kv_end - tl.s0 + DQ_BK - 1) / DQ_BK;
+  // 32-key blocks this wavefront contracts over: all that hold a key, under a causal mask those with a key at or
+  // before its last query (wq0 - s0 is a multiple of 32)
+  const int nblk_all = (kv_end - tl.s0 + 31) / 32;
+  const int nblk = !wave_has_rows ? 0 : (causal ? min(nblk_all, ((wq0 - tl.s0) >> 5) + 1) : nblk_all);
+  // this lane's 16 bytes of the first store of block row 0; the second store is 1 KB on, the next block row
+  // ds_nqs blocks on
+  const el_t* ds_wave = ds + (((size_t)a * ds_rows + tl.kb0) * ds_nqs + ((wq0 - tl.s0) >> 6)) * 2048 +
+                        (((wq0 - tl.s0) >> 5) & 1) * 1024 + lane * 8;
+  const size_t ds_row_stride = (size_t)ds_nqs * 2048;
 
-  frag_t qf[NIB][NDS], dof[NIB][NDS];
-  float lse2[NIB], dl[NIB];
-#pragma unroll
-  for (int ib = 0; ib < NIB; ++ib) {
-    const int i = wq0 + ib * 32 + li;
-    const bool ok = i < tl.r1;
-    lse2[ib] = ok ? lse[(size_t)a * Tn + i] * LOG2E : 0.f;
-    dl[ib] = ok ? delta[(size_t)a * Tn + i] : 0.f;
-#pragma unroll
-    for (int ds = 0; ds < NDS; ++ds) {
-      uint4 v = make_uint4(0, 0, 0, 0), w = v;
-      if (ok) {
-        v = *reinterpret_cast<const uint4*>(qkv + (size_t)i * ld + qcol + ds * 16 + h * 8);
-        w = *reinterpret_cast<const uint4*>(d_o + (size_t)i * nq * D + qcol + ds * 16 + h * 8);
-      }
-      qf[ib][ds] = __builtin_bit_cast(frag_t, v);
-      dof[ib][ds] = __builtin_bit_cast(frag_t, w);
-    }
-  }
-  floatx16 acc[NDB][NIB];
+  floatx16 acc[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
-    for (int ib = 0; ib < NIB; ++ib)
+    for (int e = 0; e < 16; ++e) acc[db][e] = 0.f;
+
+  // two register sets: the loads of steps st + 1 and st + 2 are in flight while step st is computed
+  struct Regs { uint4 rk[TileRegs<D, DQ_BK, NT>::N]; uint4 rd[NBLK][2]; };
+  Regs ra, rb;
+  char* dsw = smem + 2 * C::K_STAGE + wave * C::DS_WAVE;
+  auto fetch = [&](int st, Regs& r) {
+    tile_load<D, DQ_BK, NT>(r.rk, qkv + kcol, ld, tl.s0 + st * DQ_BK, kv_end);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[db][ib][e] = 0.f;
-
-  const int kv_end = causal ? tl.r1 : tl.s1;
-  const int nsteps = (kv_end - tl.s0 + BKV - 1) / BKV;
-  uint4 rk[TileRegs<D, BKV, NT>::N], rv[TileRegs<D, BKV, NT>::N];
-  tile_load<D, BKV, NT>(rk, qkv + kcol, ld, tl.s0, kv_end);
-  tile_load<D, BKV, NT>(rv, qkv + vcol, ld, tl.s0, kv_end);
-  tile_store<D, BKV, C::KP, C::DP, NT>(rk, smem);
-  tile_store<D, BKV, C::VP, D, NT>(rv, smem + C::K_BYTES);
-  __syncthreads();
-
-  // Leading steps in which this wavefront has unmasked keys; the rest only move data.  The dQ
-  // accumulators are touched in the first loop alone and unconditionally (they stay in place).
-  const int n_active = !wave_has_rows ? 0 : (causal ? min(nsteps, (wq0 + WQ - 1 - tl.s0) / BKV + 1) : nsteps);
-  auto io_begin = [&](int st) {
-    if (st + 1 < nsteps) {
-      tile_load<D, BKV, NT>(rk, qkv + kcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
-      tile_load<D, BKV, NT>(rv, qkv + vcol, ld, tl.s0 + (st + 1) * BKV, kv_end);
+    for (int blk = 0; blk < NBLK; ++blk) {
+      // no branch: a block past this wavefront's last one re-reads that one (never used)
+      const int kb = min(st * NBLK + blk, max(nblk - 1, 0));
+      typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+      const el_t* p = ds_wave + (size_t)kb * ds_row_stride;
+      r.rd[blk][0] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)));
+      r.rd[blk][1] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 512)));
     }
   };
-  auto io_end = [&](int st) {
-    if (st + 1 < nsteps) {
-      char* nk = smem + ((st + 1) & 1) * C::STAGE;
-      tile_store<D, BKV, C::KP, C::DP, NT>(rk, nk);
-      tile_store<D, BKV, C::VP, D, NT>(rv, nk + C::K_BYTES);
-    }
-    __syncthreads();
-  };
-  int st = 0;
-  for (; st < n_active; ++st) {
-    const int k0 = tl.s0 + st * BKV;
-    const char* sk = smem + (st & 1) * C::STAGE;
-    const char* sv = sk + C::K_BYTES;
-    io_begin(st);
-    const bool need_mask = (causal && k0 + BKV - 1 > wq0) || (k0 + BKV > kv_end);
+  auto commit = [&](int st, const Regs& r) {
+    tile_store<D, DQ_BK, C::KP, C::DP, NT>(r.rk, smem + (st & 1) * C::K_STAGE);
 #pragma unroll
-    for (int ib = 0; ib < NIB; ++ib) {
-      const int i = wq0 + ib * 32 + li;
-      floatx16 s[2], dp[2];
+    for (int blk = 0; blk < NBLK; ++blk) {
+      if (st * NBLK + blk < nblk) {
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb) {
-        frag_t kfr[NDS], vfr[NDS];      // all fragments of the 32-key block before its MFMAs
-#pragma unroll
-        for (int ds = 0; ds < NDS; ++ds) {
-          kfr[ds] = frag_rows(sk, C::KP, jb * 32, ds, lane);
-          vfr[ds] = frag_rows(sv, C::VP, jb * 32, ds, lane);
-        }
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { s[jb][e] = 0.f; dp[jb][e] = 0.f; }
-#pragma unroll
-        for (int ds = 0; ds < NDS; ++ds) {
-          s[jb] = mfma16(kfr[ds], qf[ib][ds], s[jb]);
-          dp[jb] = mfma16(vfr[ds], dof[ib][ds], dp[jb]);
-        }
+        for (int u = 0; u < 2; ++u)
+          *reinterpret_cast<uint4*>(dsw + blk * C::DS_BLOCK + u * C::DS_PAIR + h * C::DS_HALF + li * 16) = r.rd[blk][u];
       }
+    }
+  };
+  // The private dS area is written and read by this wavefront alone, and the hardware executes one wavefront's LDS
+  // instructions in order; these wavefront-scope fences keep the compiler from moving the next step's writes above
+  // this step's reads.
+  auto wave_sync = [] {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  // The dS^T fragment (B operand: column = query, k = keys) by the LDS transpose read, with the lane roles of
+  // frag_cols_tr: a lane names the 8-byte unit (key row, four queries) it contributes.  Query group qg = queries
+  // 4 qg .. 4 qg + 3 of the wavefront's 32 sits in store qg / 4, half qg % 2 of the lanes, bytes 8 ((qg / 2) % 2) .. of the
+  // lane's 16.
+  const int tr_krow = h * 4 + ((lane & 15) >> 2);
+  const int tr_qg = ((lane >> 4) & 1) * 4 + (lane & 3);
+  const int tr_off = (tr_qg >> 2) * C::DS_PAIR + (tr_qg & 1) * C::DS_HALF + ((tr_qg >> 1) & 1) * 8 + tr_krow * 16;
+  auto compute = [&](int st) {
+    const char* sk = smem + (st & 1) * C::K_STAGE;
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb) {
-        float dsv[16];
+    for (int blk = 0; blk < NBLK; ++blk) {
+      if (st * NBLK + blk < nblk) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[jb][e], scale_log2e, -lse2[ib]));
-          dsv[e] = p * (dp[jb][e] - dl[ib]);
-        }
-        if (need_mask) {
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int j = k0 + jb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-            float v = (j >= kv_end || (causal && j > i)) ? 0.f : dsv[e];
-            asm volatile("" : "+v"(v));   // pins the select inside this (wave-uniform) branch
-            dsv[e] = v;
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const frag_t dsf = pack8(dsv + u * 8);
+        for (int s2 = 0; s2 < 2; ++s2) {          // 16 keys each
+          const char* p = dsw + blk * C::DS_BLOCK + tr_off + s2 * 256;
+          union { short4v hh[2]; frag_t v; } f;
+          f.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)p);
+          f.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p + 128));
           frag_t ktr[NDB];
 #pragma unroll
-          for (int db = 0; db < NDB; ++db) ktr[db] = frag_cols_tr(sk, C::KP, jb * 32 + u * 16, db * 32, lane);
+          for (int db = 0; db < NDB; ++db) ktr[db] = frag_cols_tr(sk, C::KP, blk * 32 + s2 * 16, db * 32, lane);
 #pragma unroll
-          for (int db = 0; db < NDB; ++db)
-            acc[db][ib] = mfma16(ktr[db], dsf, acc[db][ib]);
+          for (int db = 0; db < NDB; ++db) acc[db] = mfma16(ktr[db], f.v, acc[db]);
         }
       }
     }
-    io_end(st);
+    wave_sync();
+  };
+  fetch(0, ra);
+  commit(0, ra);
+  __syncthreads();
+  if (1 < nsteps) fetch(1, ra);
+  if (2 < nsteps) fetch(2, rb);
+  for (int st = 0; st < nsteps; st += 2) {
+    compute(st);
+    if (st + 1 < nsteps) commit(st + 1, ra);
+    __syncthreads();
+    if (st + 3 < nsteps) fetch(st + 3, ra);
+    if (st + 1 < nsteps) {
+      compute(st + 1);
+      if (st + 2 < nsteps) commit(st + 2, rb);
+      __syncthreads();
+      if (st + 4 < nsteps) fetch(st + 4, rb);
+    }
   }
-  for (; st < nsteps; ++st) {
-    io_begin(st);
-    io_end(st);
-  }
-#pragma unroll
-  for (int ib = 0; ib < NIB; ++ib) {
-    const int i = wq0 + ib * 32 + li;
-    if (i >= tl.r1) continue;
+  const int i = wq0 + li;
+  if (i < tl.r1) {
     const float out_scale = scale * (grad_scale ? grad_scale[1] : 1.0f);    // d_o held s * dO: undo it (a power of two: exact)
     bf16_t* row = dqkv + (size_t)i * ld + qcol;
 #pragma unroll
@@ -169,8 +157,8 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
         const int dd = db * 32 + g * 8 + h * 4;
         if (dd >= D) continue;
         uint2 w;
-        w.x = pack_bf16x2(acc[db][ib][g * 4 + 0] * out_scale, acc[db][ib][g * 4 + 1] * out_scale);
-        w.y = pack_bf16x2(acc[db][ib][g * 4 + 2] * out_scale, acc[db][ib][g * 4 + 3] * out_scale);
+        w.x = pack_bf16x2(acc[db][g * 4 + 0] * out_scale, acc[db][g * 4 + 1] * out_scale);
+        w.y = pack_bf16x2(acc[db][g * 4 + 2] * out_scale, acc[db][g * 4 + 3] * out_scale);
         *reinterpret_cast<uint2*>(row + dd) = w;
       }
   }
@@ -178,20 +166,21 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_dq_mfma_ker
 
 template <int D>
 hipError_t dq_launch(const AttnArgs& a, hipStream_t s) {
-  auto kq = attn_dq_mfma_kernel<D, DQ_NIB>;
+  auto kq = attn_dq_mfma_kernel<D>;
   static std::once_flag once;
   static hipError_t once_status = hipSuccess;
   if (hipError_t e = set_max_dynamic_lds_once(once, once_status, (const void*)kq, DqCfg<D>::SMEM); e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)D);
-  hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(FWD_Q_ROWS / (32 * DQ_NIB) * 64), DqCfg<D>::SMEM, s, (const el_t*)a.qkv,
-                     (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.q_tiles, a.T, a.nq, a.nkv, a.causal, scale, a.grad_scale);
+  hipLaunchKernelGGL(kq, dim3(a.nq, a.n_q_tiles), dim3(512), DqCfg<D>::SMEM, s, (const el_t*)a.qkv, (const el_t*)a.ds,
+                     (bf16_t*)a.dqkv, a.q_tiles, a.nq, a.nkv, a.causal, scale, a.grad_scale, a.ds_rows, a.ds_nqs);
   return hipGetLastError();
 }
 
 }  // namespace
 
-// Needs a.delta (the delta kernel) on the same stream before it; writes the dq columns of a.dqkv.
+// Needs the dK/dV kernel (which fills a.ds) on the same stream before it; writes the dq columns of a.dqkv.
 hipError_t launch_attn_dq_mfma(const AttnArgs& a, hipStream_t s) {
+  if (!a.ds) return hipErrorInvalidValue;
   if (a.d == 64) return dq_launch<64>(a, s);
   if (a.d == 80) return dq_launch<80>(a, s);
   if (a.d == 128) return dq_launch<128>(a, s);

@@ -60,8 +60,9 @@ bool gemm_mfma_supports(const GemmArgs& g);                     // alignment / d
 struct GemmPlan { int kernel, wavefronts, main_workgroups, short_workgroups, split_k; };
 GemmPlan gemm_mfma_plan(const GemmArgs& g, int n_cu, bool have_scratch);
 
-// One attention work item: a tile of rows [r0, r1) inside the segment [s0, s1).
-struct AttnTile { int32_t r0, r1, s0, s1; };
+// One attention work item: a tile of rows [r0, r1) inside the segment [s0, s1).  kb0 = number of 32-key blocks in
+// the segments before this one (each segment rounded up): the segment's first block row in the dS scratch.
+struct AttnTile { int32_t r0, r1, s0, s1, kb0; };
 
 constexpr int ATTN_TILE_Q = 256;   // rows per query tile (forward and dQ kernels)
 constexpr int ATTN_TILE_KV = 128;  // rows per key tile (dK/dV kernel)
@@ -83,7 +84,14 @@ struct AttnArgs {
   float* delta;         // [nq, T]   rowsum(dO * O)
   const float* grad_scale;  // MFMA path, optional: device pair {s, 1/s}; d_o holds s * dO (s a power of two that keeps
                             // the half copy of dO in range), the kernels multiply dq, dk, dv by 1/s before rounding
+  void* ds;                 // MFMA path: scratch of attn_ds_bytes(...) bytes.  The dK/dV kernel leaves dS there (IEEE halves,
+                            // one 4 KB block per 32 keys x 64 queries of a head) and the dQ kernel contracts it with K
+  int ds_rows, ds_nqs;      // its shape: 32-key block rows per head, 64-query steps per block row
 };
+// Shape of the dS scratch for up to T tokens in up to n_seg segments, and its size for nq query heads.
+inline int attn_ds_rows(int T, int n_seg) { return (T + 31) / 32 + n_seg; }
+inline int attn_ds_nqs(int T) { return (T + 63) / 64 + 4; }
+inline size_t attn_ds_bytes(int T, int n_seg, int nq) { return (size_t)nq * attn_ds_rows(T, n_seg) * attn_ds_nqs(T) * 4096; }
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_fwd_simt(const AttnArgs& a, hipStream_t s);

@@ -52,6 +52,8 @@ struct Plan {
   size_t param_elems;
   std::vector<LayerStash> layer;
   size_t t_dm, t_dh, t_do, t_delta, t_dgp, t_dbp, t_qtiles, t_kvtiles;  // per-microbatch temporaries
+  size_t t_ds;               // dS scratch of the MFMA attention backward (0 when that path cannot run)
+  int ds_rows, ds_nqs;
   size_t t_dk32;                    // fp32 key-head gradients behind the head norm (QK-norm with biases only)
   size_t t_gscale, t_gpart;         // bf16 path: {s, 1/s} of the microbatch's gradient scale, and the partial maxima behind it
   int max_tiles;
@@ -161,6 +163,15 @@ int make_plan(const stage_config* c, Plan* p) {
   p->max_tiles = (int)((T + tile - 1) / tile) + c->max_segments;
   p->t_qtiles = take((size_t)p->max_tiles * sizeof(AttnTile));
   p->t_kvtiles = take((size_t)p->max_tiles * sizeof(AttnTile));
+  // The MFMA attention backward forms dS once, in the dK/dV kernel, and hands it to the dQ kernel through this
+  // scratch (per microbatch: B tasks of different microbatches may run side by side on different streams).
+  {
+    AttnArgs probe{};
+    probe.dtype = c->dtype; probe.d = c->head_dim; probe.n_q_tiles = 1;
+    p->ds_rows = attn_ds_rows((int)T, c->max_segments);
+    p->ds_nqs = attn_ds_nqs((int)T);
+    p->t_ds = attn_mfma_supports(probe) ? take(attn_ds_bytes((int)T, c->max_segments, (int)nq)) : 0;
+  }
   p->mb_bytes = o;
   p->slots_off = p->mb_bytes * (size_t)c->n_microbatches;
   p->arena_bytes = p->slots_off + align_up(p->slot_floats * 4) * (size_t)c->n_microbatches;
@@ -228,10 +239,12 @@ int refuse_poisoned(stage_t* st, int mb, const char* task);
 // Tiles of `rows` rows carved inside each segment, heaviest first (more keys first under a
 // causal mask) so that long tiles start early.  A pure function of cu_seqlens.
 int build_tiles(const int32_t* cu, int n_seg, int rows, bool causal, bool kv_side, AttnTile* out) {
-  int n = 0;
-  for (int s = 0; s < n_seg; ++s)
+  int n = 0, kb0 = 0;
+  for (int s = 0; s < n_seg; ++s) {
     for (int r = cu[s]; r < cu[s + 1]; r += rows)
-      out[n++] = AttnTile{r, std::min(r + rows, cu[s + 1]), cu[s], cu[s + 1]};
+      out[n++] = AttnTile{r, std::min(r + rows, cu[s + 1]), cu[s], cu[s + 1], kb0};
+    kb0 += (cu[s + 1] - cu[s] + 31) / 32;
+  }
   auto work = [&](const AttnTile& t) {
     if (!causal) return t.s1 - t.s0;
     return kv_side ? t.s1 - t.r0 : t.r1 - t.s0;
@@ -615,6 +628,7 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     a.T = T; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.d = c.head_dim; a.causal = c.causal; a.dtype = dt;
     a.d_o = base + P.t_do; a.dqkv = base + L.dqkv; a.delta = (float*)(base + P.t_delta);
     a.grad_scale = gscale;
+    a.ds = P.t_ds ? base + P.t_ds : nullptr; a.ds_rows = P.ds_rows; a.ds_nqs = P.ds_nqs;
     HIP_TRY(st, launch_attn_bwd(a, s));
     if (c.rope)   // gradients w.r.t. the rotated q, k -> w.r.t. the projection outputs (inverse rotation)
       HIP_TRY(st, launch_rope(base + L.dqkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,
