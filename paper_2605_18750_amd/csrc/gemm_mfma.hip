@@ -739,6 +739,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_dl_kernel(const bf16_t
           store_vec<bf16_t>(E + (size_t)m * lde + f0 + fc, mm);
         }
       }
+    } else if (sizeof(TO) == 4 && ACT == ACT_NONE && !HAS_R && !bias) {
+      // plain fp32 tile: 16 bytes per lane with the lanes of a row side by side, so that every store instruction
+      // writes whole 128-byte lines (with 32 bytes per lane each of the two stores would write half of every line)
+      constexpr int LPR4 = NBC / 4, RPS4 = 64 / LPR4, SW4 = 32 / RPS4;
+      const int c4 = (lane % LPR4) * 4, r4 = lane / LPR4;
+      const int n = n0 + wn + c4;
+#pragma unroll
+      for (int rr = 0; rr < SW4; ++rr) {
+        const int row = rr * RPS4 + r4;
+        const int m = m0 + wm + i * 32 + row;
+        const float4 v = *reinterpret_cast<const float4*>(scratch + row * PITCH + c4);
+        if (m < M && n < N) *reinterpret_cast<float4*>((float*)C + (size_t)m * ldc + n) = v;   // N is a multiple of 8
+      }
     } else {
       if (i + 1 < MI) prefetch(pre[(i + 1) & 1], i + 1);
       const Pre (&cur)[SW] = pre[i & 1];
