@@ -263,34 +263,33 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
     io_end(st);
   }
 
-  // Finalise: the two halves of the wavefront hold disjoint key subsets of every query column.
+  // Finalise: the two halves of the wavefront hold disjoint key subsets of every query column.  The K/V stages are free
+  // (every wavefront is past the last barrier): the output goes through this wavefront's part of them, see emit_block_rows.
+  float* stage_out = reinterpret_cast<float*>(smem + wave * OUT_STAGE_BYTES);
 #pragma unroll
   for (int ib = 0; ib < NIB; ++ib) {
     const int i = wq0 + ib * 32 + li;
     const float l_tot = l_run[ib] + __shfl_xor(l_run[ib], 32, 64);
-    if (i >= tl.r1) continue;
-    const float inv = 1.0f / l_tot;
-    if (h == 0) lse[(size_t)a * Tn + i] = (m_run[ib] + log2f(l_tot)) * 0.69314718055994531f;
-    bf16_t* orow = o + (size_t)i * nq * D + qcol;
+    const float inv = 1.0f / l_tot;       // rows past the tile: never stored
+    if (i < tl.r1 && h == 0) lse[(size_t)a * Tn + i] = (m_run[ib] + log2f(l_tot)) * 0.69314718055994531f;
+    const int i_base = wq0 + ib * 32;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int dd = db * 32 + g * 8 + h * 4;
-        if (dd >= D) continue;
-        const float v0 = oacc[db][ib][g * 4 + 0] * inv, v1 = oacc[db][ib][g * 4 + 1] * inv;
-        const float v2 = oacc[db][ib][g * 4 + 2] * inv, v3 = oacc[db][ib][g * 4 + 3] * inv;
+      emit_block_rows(stage_out, oacc[db][ib], inv, lane, [&](int row, int c, float4 v) {
+        const int ir = i_base + row, dd = db * 32 + c;
+        if (ir >= tl.r1 || dd >= D) return;
+        const size_t off = (size_t)ir * nq * D + qcol + dd;
         uint2 w;
-        w.x = pack_bf16x2(v0, v1);
-        w.y = pack_bf16x2(v2, v3);
-        *reinterpret_cast<uint2*>(orow + dd) = w;
-        if (o32) *reinterpret_cast<float4*>(o32 + (size_t)i * nq * D + qcol + dd) = make_float4(v0, v1, v2, v3);
+        w.x = pack_bf16x2(v.x, v.y);
+        w.y = pack_bf16x2(v.z, v.w);
+        *reinterpret_cast<uint2*>(o + off) = w;
+        if (o32) *reinterpret_cast<float4*>(o32 + off) = v;
         if (o16) {     // the copy the output projection reads (halves); the bf16 one above serves the weight gradient
-          w.x = pack_f16x2(v0, v1);
-          w.y = pack_f16x2(v2, v3);
-          *reinterpret_cast<uint2*>(o16 + (size_t)i * nq * D + qcol + dd) = w;
+          w.x = pack_f16x2(v.x, v.y);
+          w.y = pack_f16x2(v.z, v.w);
+          *reinterpret_cast<uint2*>(o16 + off) = w;
         }
-      }
+      });
   }
 }
 
@@ -640,25 +639,26 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
     t = run_steps(t, max(t, t_tail_begin), st, std::false_type{});
     t = run_steps(t, nq_steps, st, std::true_type{});
   }
-  if (j < tl.r1) {
+  {
     const float inv_s = grad_scale ? grad_scale[1] : 1.0f;     // d_o held s * dO: undo it (a power of two: exact)
     scale *= inv_s;
-    bf16_t* krow = dqkv + (size_t)j * ld + kcol;
-    bf16_t* vrow = dqkv + (size_t)j * ld + vcol;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int dd = db * 32 + g * 8 + h * 4;
-        if (dd >= D) continue;
+    __syncthreads();      // nobody reads the tile stages any more: they stage the output (emit_block_rows)
+    float* st = reinterpret_cast<float*>(smem + wave * OUT_STAGE_BYTES);
+    auto put = [&](const floatx16& acc, float mul, int col, int db) {
+      emit_block_rows(st, acc, mul, lane, [&](int row, int c, float4 v) {
+        const int jr = wj0 + row, dd = db * 32 + c;
+        if (jr >= tl.r1 || dd >= D) return;
         uint2 w;
-        w.x = pack_bf16x2(dk[db][g * 4 + 0] * scale, dk[db][g * 4 + 1] * scale);
-        w.y = pack_bf16x2(dk[db][g * 4 + 2] * scale, dk[db][g * 4 + 3] * scale);
-        *reinterpret_cast<uint2*>(krow + dd) = w;
-        w.x = pack_bf16x2(dv[db][g * 4 + 0] * inv_s, dv[db][g * 4 + 1] * inv_s);
-        w.y = pack_bf16x2(dv[db][g * 4 + 2] * inv_s, dv[db][g * 4 + 3] * inv_s);
-        *reinterpret_cast<uint2*>(vrow + dd) = w;
-      }
+        w.x = pack_bf16x2(v.x, v.y);
+        w.y = pack_bf16x2(v.z, v.w);
+        *reinterpret_cast<uint2*>(dqkv + (size_t)jr * ld + col + dd) = w;
+      });
+    };
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      put(dk[db], scale, kcol, db);
+      put(dv[db], inv_s, vcol, db);
+    }
   }
 }
 

@@ -115,5 +115,37 @@ __device__ __forceinline__ void tile_store(const TileArr<D, ROWS, NT>& r, char* 
   }
 }
 
+
+// Output of a transposed accumulator block.  A 32x32 accumulator of the kernels here holds 32 consecutive head-dimension
+// values (rows) of 32 output rows (one per lane of a half-wavefront): stored from there, every lane writes to a row of
+// its own, 8 or 16 bytes at a time, and one store instruction becomes up to 64 separate write requests.  Instead the
+// wavefront passes the block through a private LDS area and reads it back with 8 lanes side by side on each output row
+// (4 values per lane, 8 rows per sweep), so that a store instruction writes 64 or 128 contiguous bytes per row.
+// st: this wavefront's area of OUT_STAGE_BYTES; v = the block times mul; emit(row 0..31, first of 4 head-dimension
+// values 0..28, the 4 values).  The area is private to the wavefront and the hardware runs one wavefront's LDS instructions
+// in order: the wavefront-scope fences only keep the compiler from reordering the phases.
+constexpr int OUT_PITCH = 36;                       // floats per staged row: 32 values + a 16-byte skew
+constexpr int OUT_STAGE_BYTES = 32 * OUT_PITCH * 4;
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+template <typename Emit>
+__device__ __forceinline__ void emit_block_rows(float* st, const floatx16& acc, float mul, int lane, Emit&& emit) {
+  const int h = lane >> 5, li = lane & 31;
+  wave_lds_sync();       // the read-back of the block before precedes these writes
+#pragma unroll
+  for (int g = 0; g < 4; ++g)
+    *reinterpret_cast<float4*>(st + li * OUT_PITCH + g * 8 + h * 4) =
+        make_float4(acc[g * 4 + 0] * mul, acc[g * 4 + 1] * mul, acc[g * 4 + 2] * mul, acc[g * 4 + 3] * mul);
+  wave_lds_sync();
+#pragma unroll
+  for (int sw = 0; sw < 4; ++sw) {
+    const int row = sw * 8 + (lane >> 3), c = (lane & 7) * 4;
+    emit(row, c, *reinterpret_cast<const float4*>(st + row * OUT_PITCH + c));
+  }
+}
+
 }  // namespace
 }  // namespace rrfp

@@ -146,22 +146,20 @@ __global__ __launch_bounds__(512) void attn_dq_mfma_kernel(const el_t* __restric
       if (st + 4 < nsteps) fetch(st + 4, rb);
     }
   }
-  const int i = wq0 + li;
-  if (i < tl.r1) {
-    const float out_scale = scale * (grad_scale ? grad_scale[1] : 1.0f);    // d_o held s * dO: undo it (a power of two: exact)
-    bf16_t* row = dqkv + (size_t)i * ld + qcol;
+  // the K stages are free (every wavefront is past the last barrier): the output goes through this wavefront's part
+  // of them, see emit_block_rows
+  const float out_scale = scale * (grad_scale ? grad_scale[1] : 1.0f);    // d_o held s * dO: undo it (a power of two: exact)
+  float* st = reinterpret_cast<float*>(smem + wave * OUT_STAGE_BYTES);
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int dd = db * 32 + g * 8 + h * 4;
-        if (dd >= D) continue;
-        uint2 w;
-        w.x = pack_bf16x2(acc[db][g * 4 + 0] * out_scale, acc[db][g * 4 + 1] * out_scale);
-        w.y = pack_bf16x2(acc[db][g * 4 + 2] * out_scale, acc[db][g * 4 + 3] * out_scale);
-        *reinterpret_cast<uint2*>(row + dd) = w;
-      }
-  }
+  for (int db = 0; db < NDB; ++db)
+    emit_block_rows(st, acc[db], out_scale, lane, [&](int row, int c, float4 v) {
+      const int ir = wq0 + row, dd = db * 32 + c;
+      if (ir >= tl.r1 || dd >= D) return;
+      uint2 w;
+      w.x = pack_bf16x2(v.x, v.y);
+      w.y = pack_bf16x2(v.z, v.w);
+      *reinterpret_cast<uint2*>(dqkv + (size_t)ir * ld + qcol + dd) = w;
+    });
 }
 
 template <int D>
