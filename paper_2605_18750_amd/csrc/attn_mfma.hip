@@ -133,10 +133,10 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
   // The running maximum is a REFERENCE point only: the result is exact for any reference as long as
   // exp2(score - reference) stays in range.  A "fast" step keeps the reference fixed and never touches
   // the output accumulators except through MFMAs, so they stay in place in the accumulator registers;
-  // it gives up (before changing any state) when some score of the step exceeds the reference by more
-  // than 2^TAU.  A "slow" step moves the reference to the new maximum and rescales.  The first step of
-  // a wavefront is slow; with typical data nearly all the others are fast.
-  constexpr float TAU = 12.0f;
+  // it gives up (before changing any state) when a lane's sum of exp2(score - reference) over the step exceeds
+  // LIMIT, which bounds every single one of them.  A "slow" step moves the reference to the new maximum and
+  // rescales.  The first step of a wavefront is slow; with typical data nearly all the others are fast.
+  constexpr float LIMIT = 4096.0f;
   // number of leading steps in which this wavefront has unmasked keys (the rest only move data)
   const int n_active = !wave_has_rows ? 0 : (causal ? min(nsteps, (wq0 + WQ - 1 - tl.s0) / BKV + 1) : nsteps);
 
@@ -187,26 +187,16 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
           }
       }
     }
-    float m_cand[NIB];
-#pragma unroll
-    for (int ib = 0; ib < NIB; ++ib) {
-      float mx = -INFINITY;   // maximum of the raw scores (the scale is positive)
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[jb][ib][e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      m_cand[ib] = mx * scale_log2e;
-    }
-    if (!RESCALE) {
-      bool over = false;
-#pragma unroll
-      for (int ib = 0; ib < NIB; ++ib) over = over || (m_cand[ib] > m_run[ib] + TAU);
-      if (__any(over)) return false;
-    } else {
+    if constexpr (RESCALE) {
 #pragma unroll
       for (int ib = 0; ib < NIB; ++ib) {
-        const float m_new = fmaxf(m_run[ib], m_cand[ib]);
+        float mx = -INFINITY;   // maximum of the raw scores (the scale is positive)
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[jb][ib][e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run[ib], mx * scale_log2e);
         const float alpha = __builtin_amdgcn_exp2f(m_run[ib] - m_new);
         m_run[ib] = m_new;
         l_run[ib] *= alpha;
@@ -217,22 +207,32 @@ __global__ __launch_bounds__(FWD_Q_ROWS / (32 * NIB) * 64) void attn_fwd_mfma_ke
       }
     }
     frag_t pf[NIB][2][2];   // [ib][jb][u]: probabilities of 16 keys as a B operand
+    float ps[NIB];
 #pragma unroll
     for (int ib = 0; ib < NIB; ++ib) {
-      float ps = 0.f;
+      ps[ib] = 0.f;
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb) {
         float p[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           p[e] = __builtin_amdgcn_exp2f(fmaf(s[jb][ib][e], scale_log2e, -m_run[ib]));
-          ps += p[e];
+          ps[ib] += p[e];
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) pf[ib][jb][u] = pack8(p + u * 8);
       }
-      l_run[ib] += ps;
     }
+    if constexpr (!RESCALE) {
+      // The lane's sum bounds each of its terms, and it is needed anyway: no maximum over the scores and no exchange
+      // between the halves of the wavefront on this path.
+      bool over = false;
+#pragma unroll
+      for (int ib = 0; ib < NIB; ++ib) over = over || !(ps[ib] <= LIMIT);
+      if (__any(over)) return false;
+    }
+#pragma unroll
+    for (int ib = 0; ib < NIB; ++ib) l_run[ib] += ps[ib];
     // O^T[db][ib] += V^T P^T.  B-operand slot s of half h is key 16u + (s/4)*8 + h*4 + s%4 of the
     // 32-key block, so the matching V fragment is two transpose reads starting at keys h*4 and 8 + h*4.
 #pragma unroll
