@@ -384,13 +384,17 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
                                                             bf16_t* __restrict__ dqkv, const AttnTile* __restrict__ tiles,
                                                             int Tn, int nq, int nkv, int causal, float scale,
                                                             const float* __restrict__ grad_scale, el_t* __restrict__ ds,
-                                                            int ds_rows, int ds_nqs) {
+                                                            int ds_rows, int ds_nqs, int n_sub, float* __restrict__ part) {
   using C = DkvCfg<D>;
   constexpr int NDS = D / 16, NDB = C::DP / 32;
   constexpr float LOG2E = 1.4426950408889634f;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const AttnTile tl = tiles[blockIdx.y];
-  const int b = blockIdx.x, G = nq / nkv;
+  // n_sub > 1: the query heads of a KV head are dealt to n_sub workgroups (few KV heads and long causal tiles leave
+  // the chip half empty otherwise); each writes its sums as an fp32 partial plane and dkv_combine_kernel adds the planes
+  // in subset order.  G = query heads this workgroup walks, a0 = the first of them.
+  const int b = blockIdx.x / n_sub, sub = blockIdx.x - b * n_sub;
+  const int G = nq / nkv / n_sub, a0 = b * (nq / nkv) + sub * G;
   const int ld = (nq + 2 * nkv) * D;
   const int kcol = (nq + b) * D, vcol = (nq + nkv + b) * D;
   const int lane = threadIdx.x & 63;
@@ -432,12 +436,12 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
 
   // Rows past the end of the segment repeat its last row (finite values): P and dS are exactly zero there.
   auto fetch_q = [&](int step) {
-    const int a = b * G + step / nq_steps;
+    const int a = a0 + step / nq_steps;
     const int q0 = q_begin + (step % nq_steps) * BQ_KV;
     tile_load_clamped<D, BQ_KV>(rq, qkv + a * D, ld, q0, tl.s1);
   };
   auto fetch_d = [&](int step) {
-    const int a = b * G + step / nq_steps;
+    const int a = a0 + step / nq_steps;
     const int q0 = q_begin + (step % nq_steps) * BQ_KV;
     tile_load_clamped<D, BQ_KV>(rd, d_o + a * D, nq * D, q0, tl.s1);
     // row statistics: threads 0..63 bring lse, 64..127 delta, the upper half of the workgroup the same again
@@ -626,7 +630,7 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
   };
   int st = 0;
   for (int ah = 0; ah < G; ++ah) {
-    ds_head = ds + (size_t)(b * G + ah) * ds_rows * ds_nqs * 2048;
+    ds_head = ds + (size_t)(a0 + ah) * ds_rows * ds_nqs * 2048;
     int t = 0;
     for (; t < n_skip; ++t, ++st) {
       if (st + 1 < nsteps) { fetch(st + 1); commit(smem + ((st + 1) & 1) * C::STAGE); }
@@ -654,12 +658,67 @@ __global__ __launch_bounds__(256) void attn_dkv_mfma_kernel(const el_t* __restri
         *reinterpret_cast<uint2*>(dqkv + (size_t)jr * ld + col + dd) = w;
       });
     };
+    // partial plane [tensor][subset][token][KV head * D + d], unscaled (dkv_combine_kernel scales the sum)
+    auto put_part = [&](const floatx16& acc, int tensor, int db) {
+      float* plane = part + ((size_t)(tensor * n_sub + sub) * Tn) * (nkv * D);
+      emit_block_rows(st, acc, 1.0f, lane, [&](int row, int c, float4 v) {
+        const int jr = wj0 + row, dd = db * 32 + c;
+        if (jr >= tl.r1 || dd >= D) return;
+        *reinterpret_cast<float4*>(plane + (size_t)jr * (nkv * D) + b * D + dd) = v;
+      });
+    };
+    if (n_sub > 1) {
 #pragma unroll
-    for (int db = 0; db < NDB; ++db) {
-      put(dk[db], scale, kcol, db);
-      put(dv[db], inv_s, vcol, db);
+      for (int db = 0; db < NDB; ++db) {
+        put_part(dk[db], 0, db);
+        put_part(dv[db], 1, db);
+      }
+    } else {
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        put(dk[db], scale, kcol, db);
+        put(dv[db], inv_s, vcol, db);
+      }
     }
   }
+}
+
+// dk, dv = the sum of the n_sub partial planes in subset order, scaled, rounded to bf16 into the K and V columns of dqkv.
+// One thread per 4 values of a [T, nkv * D] plane.
+__global__ __launch_bounds__(256) void dkv_combine_kernel(const float* __restrict__ part, bf16_t* __restrict__ dqkv, int Tn, int nq,
+                                                          int nkv, int D, int n_sub, float scale, const float* __restrict__ grad_scale) {
+  const int W = nkv * D;
+  const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (idx >= (size_t)Tn * W) return;
+  const int j = (int)(idx / W), c = (int)(idx - (size_t)j * W);
+  const float inv_s = grad_scale ? grad_scale[1] : 1.0f;
+  const int ld = (nq + 2 * nkv) * D;
+#pragma unroll
+  for (int tensor = 0; tensor < 2; ++tensor) {
+    float4 acc = *reinterpret_cast<const float4*>(part + ((size_t)(tensor * n_sub) * Tn) * W + idx);
+    for (int sub = 1; sub < n_sub; ++sub) {
+      const float4 v = *reinterpret_cast<const float4*>(part + ((size_t)(tensor * n_sub + sub) * Tn) * W + idx);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const float mul = tensor == 0 ? scale * inv_s : inv_s;
+    uint2 w;
+    w.x = pack_bf16x2(acc.x * mul, acc.y * mul);
+    w.y = pack_bf16x2(acc.z * mul, acc.w * mul);
+    *reinterpret_cast<uint2*>(dqkv + (size_t)j * ld + (nq + tensor * nkv) * D + c) = w;
+  }
+}
+
+// Compute units of the current device (cached per device id; 256 if the query fails).
+inline int attn_cu_count() {
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 256;
+    cached[dev] = v;
+  }
+  return cached[dev];
 }
 
 template <int D>
@@ -671,9 +730,15 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)D);
   hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((a.T * a.nq + 15) / 16), dim3(256), 0, s, (const bf16_t*)a.o,
                      a.o32, (const el_t*)a.d_o, a.delta, a.T, a.nq);
-  hipLaunchKernelGGL(kkv, dim3(a.nkv, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const el_t*)a.qkv,
+  const int n_sub = a.dkv_part ? attn_dkv_subsets(a.nq, a.nkv, a.n_kv_tiles, attn_cu_count()) : 1;
+  hipLaunchKernelGGL(kkv, dim3(a.nkv * n_sub, a.n_kv_tiles), dim3(256), DkvCfg<D>::SMEM, s, (const el_t*)a.qkv,
                      (const el_t*)a.d_o, a.lse, a.delta, (bf16_t*)a.dqkv, a.kv_tiles, a.T, a.nq, a.nkv, a.causal, scale, a.grad_scale,
-                     (el_t*)a.ds, a.ds_rows, a.ds_nqs);
+                     (el_t*)a.ds, a.ds_rows, a.ds_nqs, n_sub, a.dkv_part);
+  if (n_sub > 1) {
+    const size_t n4 = (size_t)a.T * a.nkv * D / 4;
+    hipLaunchKernelGGL(dkv_combine_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, a.dkv_part, (bf16_t*)a.dqkv, a.T, a.nq,
+                       a.nkv, D, n_sub, scale, a.grad_scale);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return launch_attn_dq_mfma(a, s);

@@ -87,11 +87,34 @@ struct AttnArgs {
   void* ds;                 // MFMA path: scratch of attn_ds_bytes(...) bytes.  The dK/dV kernel leaves dS there (IEEE halves,
                             // one 4 KB block per 32 keys x 64 queries of a head) and the dQ kernel contracts it with K
   int ds_rows, ds_nqs;      // its shape: 32-key block rows per head, 64-query steps per block row
+  float* dkv_part;          // MFMA path with grouped query heads (nq > nkv): attn_dkv_part_bytes(...) bytes for the partial dK / dV
+                            // planes of the head subsets (see attn_dkv_subsets); null = one workgroup walks the whole group
 };
 // Shape of the dS scratch for up to T tokens in up to n_seg segments, and its size for nq query heads.
 inline int attn_ds_rows(int T, int n_seg) { return (T + 31) / 32 + n_seg; }
 inline int attn_ds_nqs(int T) { return (T + 63) / 64 + 4; }
 inline size_t attn_ds_bytes(int T, int n_seg, int nq) { return (size_t)nq * attn_ds_rows(T, n_seg) * attn_ds_nqs(T) * 4096; }
+// Head subsets of the dK/dV kernel (a pure function of shape and CU count).  A workgroup of that kernel owns 128 keys of a
+// KV head and walks all query heads of its group; with few KV heads the grid nkv x n_kv_tiles is about one workgroup per CU
+// and, under a causal mask, the longest of them sets the time.  The group is then dealt to the smallest number of subsets
+// (a divisor of the group size, at most ATTN_DKV_MAX_SUBSETS) that gives two workgroups per CU, each subset summing into
+// an fp32 partial plane; the planes are added in subset order.
+constexpr int ATTN_DKV_MAX_SUBSETS = 4;
+inline int attn_dkv_subsets(int nq, int nkv, int n_kv_tiles, int n_cu) {
+  const int G = nq / nkv;
+  int best = 1;
+  for (int s = 1; s <= G && s <= ATTN_DKV_MAX_SUBSETS; ++s) {
+    if (G % s) continue;
+    best = s;
+    if ((long long)nkv * n_kv_tiles * s >= 2LL * n_cu) break;
+  }
+  return best;
+}
+// Bytes of AttnArgs::dkv_part for up to T tokens: room for the most subsets the rule above can pick; 0 without grouped heads.
+inline size_t attn_dkv_part_bytes(int T, int nq, int nkv, int d) {
+  if (nq == nkv) return 0;
+  return (size_t)2 * attn_dkv_subsets(nq, nkv, 1, 1 << 30) * T * nkv * d * 4;
+}
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_bwd(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_fwd_simt(const AttnArgs& a, hipStream_t s);

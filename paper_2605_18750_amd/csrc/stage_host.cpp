@@ -54,6 +54,7 @@ struct Plan {
   size_t t_dm, t_dh, t_do, t_delta, t_dgp, t_dbp, t_qtiles, t_kvtiles;  // per-microbatch temporaries
   size_t t_ds;               // dS scratch of the MFMA attention backward (0 when that path cannot run)
   int ds_rows, ds_nqs;
+  size_t t_dkvp;             // partial dK / dV planes of its head subsets (0 without grouped query heads)
   size_t t_dk32;                    // fp32 key-head gradients behind the head norm (QK-norm with biases only)
   size_t t_gscale, t_gpart;         // bf16 path: {s, 1/s} of the microbatch's gradient scale, and the partial maxima behind it
   int max_tiles;
@@ -171,6 +172,8 @@ int make_plan(const stage_config* c, Plan* p) {
     p->ds_rows = attn_ds_rows((int)T, c->max_segments);
     p->ds_nqs = attn_ds_nqs((int)T);
     p->t_ds = attn_mfma_supports(probe) ? take(attn_ds_bytes((int)T, c->max_segments, (int)nq)) : 0;
+    const size_t part = attn_dkv_part_bytes((int)T, (int)nq, (int)nkv, (int)d);
+    p->t_dkvp = (attn_mfma_supports(probe) && part) ? take(part) : 0;
   }
   p->mb_bytes = o;
   p->slots_off = p->mb_bytes * (size_t)c->n_microbatches;
@@ -629,6 +632,7 @@ int stage_B(stage_t* st, int mb, const void* dy_dev, void* dx_dev, void* stream)
     a.d_o = base + P.t_do; a.dqkv = base + L.dqkv; a.delta = (float*)(base + P.t_delta);
     a.grad_scale = gscale;
     a.ds = P.t_ds ? base + P.t_ds : nullptr; a.ds_rows = P.ds_rows; a.ds_nqs = P.ds_nqs;
+    a.dkv_part = P.t_dkvp ? (float*)(base + P.t_dkvp) : nullptr;
     HIP_TRY(st, launch_attn_bwd(a, s));
     if (c.rope)   // gradients w.r.t. the rotated q, k -> w.r.t. the projection outputs (inverse rotation)
       HIP_TRY(st, launch_rope(base + L.dqkv, (const AttnTile*)(base + P.t_qtiles), m.n_q_tiles, c.n_q_heads + c.n_kv_heads,
