@@ -56,6 +56,16 @@ int rrfp_gemm_ws(const void* A, const void* B, void* C, const void* R, int M, in
 int rrfp_gemm_plan(int M, int N, int K, int lda, int ldb, int ldc, int trans_a, int trans_b, int out_dtype,
                    int have_scratch, int n_cu, int32_t out[5]);
 
+/* Launch plan of the attention backward's dK/dV kernel, pure host logic (no HIP call): the number of workgroups that
+ * share the query heads of one KV head.  A workgroup of that kernel owns 128 keys of a KV head; with grouped query
+ * heads (n_q_heads > n_kv_heads) and few KV heads the grid n_kv_heads x n_kv_tiles under-fills the chip and, under a
+ * causal mask, its longest workgroup sets the time, so the group is dealt to the smallest divisor of the group size
+ * (at most 4) that gives two workgroups per CU; their partial sums are added in subset order (a pure function of
+ * shape and n_cu: the summation order of a call is fixed, paper Section 7.1).  n_kv_tiles = key tiles of 128 rows over
+ * all segments.  Returns the count (>= 1), or STAGE_EINVAL for non-positive arguments or n_q_heads not a multiple of
+ * n_kv_heads. */
+int rrfp_attn_dkv_subsets(int n_q_heads, int n_kv_heads, int n_kv_tiles, int n_cu);
+
 /* ---- HBM-bound kernels of the tasks, one by one (steps a1, a10 and a13 of the F and B tasks and of the
  * gradient reduction; paper Section 3.1 for the tasks, Section 7.1 for the requirement that the result must
  * not depend on the order tasks ran in, which is why every sum here has one fixed order). ---------------- */

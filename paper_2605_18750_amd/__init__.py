@@ -61,6 +61,8 @@ def lib() -> C.CDLL:
         L.rrfp_gemm_ws.restype = C.c_int
         L.rrfp_gemm_plan.argtypes = [C.c_int] * 11 + [C.POINTER(C.c_int32)]
         L.rrfp_gemm_plan.restype = C.c_int
+        L.rrfp_attn_dkv_subsets.argtypes = [C.c_int] * 4
+        L.rrfp_attn_dkv_subsets.restype = C.c_int
         L.rrfp_rmsnorm_fwd.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_float, C.c_int, vp]
         L.rrfp_rmsnorm_fwd.restype = C.c_int
         L.rrfp_rmsnorm_bwd_workspace.argtypes = [C.c_int, C.c_int, C.c_int]
@@ -181,6 +183,14 @@ def rrfp_gemm(A, B, Cout, R, M, N, K, lda, ldb, ldc, ldr, trans_a, trans_b, in_d
                              int(trans_a), int(trans_b), in_dtype, out_dtype, family, _stream(stream))
     if rc != STAGE_OK:
         raise StageError(rc, "rrfp_gemm rejected its arguments" if rc == STAGE_EINVAL else "HIP launch failed")
+
+
+def rrfp_attn_dkv_subsets(n_q_heads, n_kv_heads, n_kv_tiles, n_cu=256):
+    """Workgroups that share the query heads of one KV head in the dK/dV kernel (pure host logic)."""
+    rc = lib().rrfp_attn_dkv_subsets(n_q_heads, n_kv_heads, n_kv_tiles, n_cu)
+    if rc < 1:
+        raise StageError(rc, "rrfp_attn_dkv_subsets rejected its arguments")
+    return rc
 
 
 def rrfp_gemm_plan(M, N, K, trans_a, trans_b, out_dtype, n_cu=256, have_scratch=False, lda=None, ldb=None, ldc=None):

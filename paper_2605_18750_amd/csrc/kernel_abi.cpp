@@ -54,6 +54,11 @@ extern "C" int rrfp_rmsnorm_fwd(const float* x, const void* g, void* h, float* r
   return launch_rmsnorm_fwd(x, g, h, r_out, T, H, eps, dtype, (hipStream_t)stream) == hipSuccess ? STAGE_OK : STAGE_EHIP;
 }
 
+extern "C" int rrfp_attn_dkv_subsets(int n_q_heads, int n_kv_heads, int n_kv_tiles, int n_cu) {
+  if (n_q_heads < 1 || n_kv_heads < 1 || n_kv_tiles < 1 || n_cu < 1 || n_q_heads % n_kv_heads) return STAGE_EINVAL;
+  return attn_dkv_subsets(n_q_heads, n_kv_heads, n_kv_tiles, n_cu);
+}
+
 extern "C" size_t rrfp_rmsnorm_bwd_workspace(int T, int H, int dtype) {
   if (T < 1 || H < 1 || (dtype != F32 && dtype != BF16)) return 0;
   return (size_t)norm_bwd_partials(T, H, dtype) * (size_t)H * sizeof(float);

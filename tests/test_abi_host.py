@@ -178,3 +178,18 @@ def test_gemm_launch_plan_is_a_pure_function_of_shape_and_cu_count():
     # K not a multiple of 32 with a K-contiguous operand: register-staged kernel; N not a multiple of 8: refused
     assert R.rrfp_gemm_plan(264, 520, 200, 0, 0, BF)["kernel"] == 2
     assert R.rrfp_gemm_plan(264, 516, 256, 0, 0, BF)["kernel"] == 0
+
+
+def test_dkv_head_subsets_are_a_pure_function_of_shape():
+    # one query head per KV head: never split (the language stage)
+    assert R.rrfp_attn_dkv_subsets(32, 32, 32) == 1
+    # wide-GQA stage: 8 KV heads x 32 key tiles = one workgroup per CU -> two subsets give two per CU
+    assert R.rrfp_attn_dkv_subsets(64, 8, 32) == 2
+    # enough key tiles already: no split; very few: the largest divisor of the group size up to 4
+    assert R.rrfp_attn_dkv_subsets(64, 8, 64) == 1
+    assert R.rrfp_attn_dkv_subsets(64, 8, 4) == 4
+    assert R.rrfp_attn_dkv_subsets(4, 2, 3) == 2
+    assert R.rrfp_attn_dkv_subsets(4, 1, 2) == 4
+    assert R.rrfp_attn_dkv_subsets(6, 2, 1) == 3 and R.rrfp_attn_dkv_subsets(16, 2, 1) == 4 and R.rrfp_attn_dkv_subsets(10, 2, 1) == 1
+    assert R.rrfp_attn_dkv_subsets(64, 8, 32, n_cu=128) == 1
+    _expect(R.STAGE_EINVAL, R.rrfp_attn_dkv_subsets, 6, 4, 1)
